@@ -1,0 +1,172 @@
+/*
+ * omniconv -- batched-lowering convolution for one MI355X (gfx950), C ABI.
+ *
+ * The library computes a convolution layer the way the paper's single-node engine does
+ * (Omnivore, arXiv 1606.04487, Sec. III-B "Batching and Data Parallelism" and App. C
+ * "Convolution by Lowering and GEMM"): the WHOLE mini-batch is lowered into one matrix
+ * D-hat and each pass of the layer is ONE dense matrix product on the matrix cores.
+ *
+ * Conventions for every entry point
+ *   - Pointers named X, W, Y, dX, dY, dW, bias, workspace, ... are DEVICE pointers owned by the
+ *     caller (for example a torch tensor's data_ptr()).  The library never allocates, frees or
+ *     keeps them.  Descriptors, shape outputs and the pointer tables of omni_sgd_momentum_step
+ *     are HOST memory.
+ *   - Tensors are dense and contiguous: X [N][C][H][W], W [F][C][kh][kw], Y [N][F][Ho][Wo].
+ *     `dtype` is the storage type of X, W, Y, dY, dX and of D-hat; products are accumulated in
+ *     fp32 on the matrix cores and rounded to nearest-even once on store.  bias, dW, dbias and
+ *     the optimizer state are always fp32.
+ *   - Outputs are overwritten, never accumulated into.  Results are deterministic: no floating
+ *     point atomics are used, so equal inputs give bit-identical outputs.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the null
+ *     stream) and return; nothing synchronises with the device.
+ *   - Device pointers must be 16-byte aligned (OMNI_MISALIGNED otherwise).
+ *   - Return value: OMNI_OK (0) or a negative omni_status.  Argument checks are done on the
+ *     host before anything is launched; a failed call launches nothing.
+ */
+#ifndef OMNICONV_H
+#define OMNICONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    OMNI_OK = 0,
+    OMNI_INVALID_ARGUMENT = -1,    /* null required pointer, non-positive extent, empty output  */
+    OMNI_UNSUPPORTED = -2,         /* unknown dtype or flag, extents beyond 32-bit indexing     */
+    OMNI_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes below omni_conv_workspace_bytes()         */
+    OMNI_MISALIGNED = -4,          /* a device pointer is not 16-byte aligned                   */
+    OMNI_HIP_ERROR = -5            /* the HIP runtime refused a launch                           */
+} omni_status;
+
+typedef enum { OMNI_F32 = 0, OMNI_BF16 = 1 } omni_dtype;
+
+typedef enum {
+    OMNI_PASS_FORWARD = 0,
+    OMNI_PASS_BACKWARD_DATA = 1,
+    OMNI_PASS_BACKWARD_WEIGHTS = 2
+} omni_pass;
+
+/* omni_conv_desc.flags */
+#define OMNI_FLAG_RELU 1u        /* forward: store max(0, .) (ReLU fused into the GEMM epilogue) */
+#define OMNI_FLAG_DHAT_CACHED 2u /* backward_weights: the workspace still holds D-hat written by
+                                    omni_conv_forward for the same descriptor and the same X, so
+                                    the lowering pass is skipped (the paper's b_p = b: with 288 GB
+                                    of HBM every layer's D-hat can stay resident)                */
+
+/*
+ * A convolution layer (Sec. III-A, Eq. (conv_full); App. C adds stride and zero padding):
+ *   Y[n,f,oy,ox] = bias[f] + sum_{c,ky,kx} X[n,c,oy*stride_h-pad_h+ky,ox*stride_w-pad_w+kx] * W[f,c,ky,kx]
+ * with X read as zero outside the image, no kernel flip, Ho = (H+2*pad_h-kh)/stride_h + 1
+ * (integer division; windows that do not fit are dropped), Wo likewise.  Groups and dilation
+ * are fixed at 1 (the paper removes grouping from its networks).
+ */
+typedef struct {
+    int32_t N, C, H, W;
+    int32_t F, kh, kw;
+    int32_t stride_h, stride_w, pad_h, pad_w;
+    int32_t dtype;   /* omni_dtype */
+    uint32_t flags;  /* OMNI_FLAG_* */
+} omni_conv_desc;
+
+/* Host only.  Writes Ho, Wo.  OMNI_INVALID_ARGUMENT if any extent is non-positive, padding is
+ * negative or the window does not fit the padded image. */
+int omni_conv_output_dims(const omni_conv_desc *desc, int32_t *Ho, int32_t *Wo);
+
+/* Host only.  Leading dimension (in elements) of D-hat inside the workspace: N*Ho*Wo rounded up
+ * to a multiple of 8.  omni_lower / omni_col2im take the leading dimension as an argument. */
+int omni_conv_dhat_ld(const omni_conv_desc *desc, int64_t *ld);
+
+/* Host only.  Bytes of scratch the given pass (omni_pass) needs.  The forward and
+ * backward-weights workspaces both begin with D-hat ([C*kh*kw][ld], desc->dtype), which is what
+ * makes OMNI_FLAG_DHAT_CACHED possible when the same buffer is passed to both. */
+int omni_conv_workspace_bytes(const omni_conv_desc *desc, int pass, size_t *bytes);
+
+/*
+ * Forward pass (Sec. III-B: lower all N images, then a single GEMM; App. C: lifting is pure
+ * addressing and costs no copy).  Steps: batched lowering of X into the workspace, reshaping of
+ * W into a padded K-hat, one MFMA GEMM Y-hat[F x M] = K-hat[F x K] * D-hat[K x M] whose epilogue adds
+ * bias (nullable, fp32[F]), applies ReLU if OMNI_FLAG_RELU and stores straight into Y [N][F][Ho][Wo].
+ */
+int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, const float *bias,
+                      void *Y, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Data gradient (Sec. II-B: BW maps the gradient w.r.t. the layer's output to the gradient
+ * w.r.t. its input).  Steps: dY is packed into the matrix dY-hat [F][ld]; one MFMA GEMM
+ * dD-hat[K x M] = K-hat^T[K x F] * dY-hat[F x M]; col2im sums the entries of dD-hat that were copies
+ * of the same input pixel into dX [N][C][H][W] (gather form, fixed summation order).
+ */
+int omni_conv_backward_data(const omni_conv_desc *desc, const void *dY, const void *W, void *dX,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Model gradient, summed over the batch with no 1/N (Sec. II-B: "gradients from each tuple are
+ * summed").  Steps: lowering of X (skipped with OMNI_FLAG_DHAT_CACHED), packing of dY, one MFMA
+ * GEMM dK-hat[F x K] = dY-hat[F x M] * D-hat^T[M x K] split along M over the chip with a second,
+ * ordered reduction stage.  dW is fp32 [F][C][kh][kw]; dbias (nullable) is fp32 [F] and receives
+ * the plain sum of dY over images and pixels.
+ */
+int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const void *dY, float *dW,
+                               float *dbias, void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
+
+/*
+ * Momentum SGD over a list of parameter tensors in one launch sequence
+ * (Sec. II-B, Eq. (update2) then Eq. (update1)):
+ *     V <- momentum * V - lr * (G + weight_decay * W);    W <- W + V
+ * W, V, G and W_shadow are HOST arrays of n_tensors DEVICE pointers; counts (host) holds each
+ * tensor's element count.  W and V are updated in place, G is read.  W_shadow is nullable, and
+ * so is each of its entries; where given, the updated W is also stored there as bf16 (the copy
+ * the bf16 forward pass reads).  n_tensors == 0 is a no-op; counts[i] == 0 skips tensor i.
+ */
+int omni_sgd_momentum_step(int32_t n_tensors, float *const *W, float *const *V,
+                           const float *const *G, const int64_t *counts, void *const *W_shadow,
+                           float lr, float momentum, float weight_decay, void *hip_stream);
+
+/*
+ * The two data-movement steps on their own (App. C, lowering phase, and its transpose), in the
+ * canonical layout D-hat row-major [C*kh*kw][ld], row (c*kh+ky)*kw+kx, column (n*Ho+oy)*Wo+ox,
+ * ld >= N*Ho*Wo (columns beyond N*Ho*Wo are written as zero by omni_lower and ignored by
+ * omni_col2im).  Lowering is a pure copy: every entry is bit-identical to an element of X or +0.
+ * col2im adds, for each pixel, its contributing entries in ascending (ky, kx) order in fp32.
+ */
+int omni_lower(const omni_conv_desc *desc, const void *X, void *Dhat, int64_t ld, void *hip_stream);
+int omni_col2im(const omni_conv_desc *desc, const void *dDhat, int64_t ld, void *dX,
+                void *hip_stream);
+
+/*
+ * Layers between the convolutions of the paper's networks (named in App. C, "Data Parallelism in
+ * non-GEMM Kernels").  `dtype` is an omni_dtype; `count` is in elements.
+ *   relu_forward : y = max(0, x)                      (in place allowed)
+ *   relu_backward: dx = (y > 0) ? dy : 0, y being the ReLU's output (or input)   (in place allowed)
+ *   maxpool_forward : k x k window, stride s, no padding, over `planes` = N*C planes of H x W;
+ *       ceil_mode != 0 keeps a last border-clipped window.  The first maximum in (ky, kx) scan
+ *       order wins.  argmax (uint8 per output, nullable) receives ky*k+kx of the winner.
+ *   maxpool_backward: dx [planes][H][W] (overwritten) receives each dy at its window's winner.
+ * omni_pool_output_dim is host only and returns the pooled extent or a negative status.
+ */
+int omni_relu_forward(int32_t dtype, int64_t count, const void *x, void *y, void *hip_stream);
+int omni_relu_backward(int32_t dtype, int64_t count, const void *y, const void *dy, void *dx,
+                       void *hip_stream);
+int omni_pool_output_dim(int32_t in, int32_t k, int32_t stride, int32_t ceil_mode);
+int omni_maxpool_forward(int32_t dtype, int64_t planes, int32_t H, int32_t W, int32_t k,
+                         int32_t stride, int32_t ceil_mode, const void *x, void *y, uint8_t *argmax,
+                         void *hip_stream);
+int omni_maxpool_backward(int32_t dtype, int64_t planes, int32_t H, int32_t W, int32_t k,
+                          int32_t stride, int32_t ceil_mode, const void *dy, const uint8_t *argmax,
+                          void *dx, void *hip_stream);
+
+/* Host only.  Static string for a status code. */
+const char *omni_status_string(int status);
+
+/* Host only.  Library version, "major.minor". */
+const char *omni_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OMNICONV_H */

@@ -1,0 +1,265 @@
+"""ctypes binding over libomniconv.so -- argument marshalling only.
+
+Every function here has the name of the C entry point it calls (minus the `omni_` prefix),
+takes torch tensors that live on the GPU, passes their `data_ptr()` and the current torch
+stream to the library, and raises `OmniError` on a non-zero status.  torch is used for device
+memory and streams; no arithmetic of the method happens in Python.
+
+The library must have been built (`python -m paper_1606_04487_amd.build` or
+`__graft_entry__.build()`); importing this module without it raises ImportError -- there is no
+fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+from typing import Optional, Sequence
+
+import torch
+
+_LIB_PATH = Path(__file__).resolve().parent / "libomniconv.so"
+if not _LIB_PATH.exists():
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_1606_04487_amd.build`")
+_lib = ctypes.CDLL(str(_LIB_PATH))
+
+F32, BF16 = 0, 1
+PASS_FORWARD, PASS_BACKWARD_DATA, PASS_BACKWARD_WEIGHTS = 0, 1, 2
+FLAG_RELU, FLAG_DHAT_CACHED = 1, 2
+
+SYMBOLS = [
+    "omni_conv_output_dims", "omni_conv_dhat_ld", "omni_conv_workspace_bytes", "omni_conv_forward",
+    "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
+    "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
+    "omni_maxpool_forward", "omni_maxpool_backward", "omni_status_string", "omni_version",
+]
+
+
+class ConvDesc(ctypes.Structure):
+    """Mirror of `omni_conv_desc`."""
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("N", "C", "H", "W", "F", "kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w", "dtype")
+                ] + [("flags", ctypes.c_uint32)]
+
+    def with_flags(self, flags: int) -> "ConvDesc":
+        d = ConvDesc.from_buffer_copy(self)
+        d.flags = flags
+        return d
+
+
+class OmniError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"omniconv status {status}: {status_string(status)}")
+
+
+_vp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+_dp = ctypes.POINTER(ConvDesc)
+_lib.omni_status_string.restype = ctypes.c_char_p
+_lib.omni_status_string.argtypes = [ctypes.c_int]
+_lib.omni_version.restype = ctypes.c_char_p
+_lib.omni_conv_output_dims.argtypes = [_dp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+_lib.omni_conv_dhat_ld.argtypes = [_dp, ctypes.POINTER(_i64)]
+_lib.omni_conv_workspace_bytes.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(_sz)]
+_lib.omni_conv_forward.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.omni_conv_backward_data.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.omni_conv_backward_weights.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.omni_sgd_momentum_step.argtypes = [_i32, _vp, _vp, _vp, _vp, _vp, ctypes.c_float, ctypes.c_float,
+                                        ctypes.c_float, _vp]
+_lib.omni_lower.argtypes = [_dp, _vp, _vp, _i64, _vp]
+_lib.omni_col2im.argtypes = [_dp, _vp, _i64, _vp, _vp]
+_lib.omni_relu_forward.argtypes = [_i32, _i64, _vp, _vp, _vp]
+_lib.omni_relu_backward.argtypes = [_i32, _i64, _vp, _vp, _vp, _vp]
+_lib.omni_pool_output_dim.argtypes = [_i32, _i32, _i32, _i32]
+_lib.omni_maxpool_forward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
+_lib.omni_maxpool_backward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
+
+
+def raw():
+    """The ctypes library handle (for tests of the error paths)."""
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return _lib.omni_status_string(int(status)).decode()
+
+
+def version() -> str:
+    return _lib.omni_version().decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise OmniError(status)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _p(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous and live on the GPU")
+    return t.data_ptr()
+
+
+def torch_dtype(dtype: int):
+    return torch.bfloat16 if dtype == BF16 else torch.float32
+
+
+def dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    raise ValueError(f"unsupported dtype {t}")
+
+
+def conv_desc(N, C, H, W, F, kh, kw=None, stride=1, pad=0, dtype=F32, flags=0) -> ConvDesc:
+    kw = kh if kw is None else kw
+    sh, sw = (stride, stride) if isinstance(stride, int) else stride
+    ph, pw = (pad, pad) if isinstance(pad, int) else pad
+    return ConvDesc(N, C, H, W, F, kh, kw, sh, sw, ph, pw, dtype, flags)
+
+
+def conv_output_dims(desc: ConvDesc):
+    ho, wo = _i32(), _i32()
+    _check(_lib.omni_conv_output_dims(ctypes.byref(desc), ctypes.byref(ho), ctypes.byref(wo)))
+    return ho.value, wo.value
+
+
+def conv_dhat_ld(desc: ConvDesc) -> int:
+    ld = _i64()
+    _check(_lib.omni_conv_dhat_ld(ctypes.byref(desc), ctypes.byref(ld)))
+    return ld.value
+
+
+def conv_workspace_bytes(desc: ConvDesc, which_pass: int) -> int:
+    b = _sz()
+    _check(_lib.omni_conv_workspace_bytes(ctypes.byref(desc), which_pass, ctypes.byref(b)))
+    return b.value
+
+
+def alloc_workspace(desc: ConvDesc, which_pass: int, device="cuda") -> torch.Tensor:
+    return torch.empty(conv_workspace_bytes(desc, which_pass), dtype=torch.uint8, device=device)
+
+
+def conv_forward(desc: ConvDesc, X, W, bias=None, Y=None, workspace=None):
+    """omni_conv_forward: lowering of the whole batch, one GEMM, epilogue into Y [N][F][Ho][Wo]."""
+    ho, wo = conv_output_dims(desc)
+    if Y is None:
+        Y = torch.empty((desc.N, desc.F, ho, wo), dtype=torch_dtype(desc.dtype), device=X.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, PASS_FORWARD, X.device)
+    _check(_lib.omni_conv_forward(ctypes.byref(desc), _p(X), _p(W), _p(bias), _p(Y), _p(workspace),
+                                  workspace.numel(), _stream()))
+    return Y
+
+
+def conv_backward_data(desc: ConvDesc, dY, W, dX=None, workspace=None):
+    """omni_conv_backward_data: dY-hat packing, one GEMM, col2im into dX [N][C][H][W]."""
+    if dX is None:
+        dX = torch.empty((desc.N, desc.C, desc.H, desc.W), dtype=torch_dtype(desc.dtype), device=dY.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, PASS_BACKWARD_DATA, dY.device)
+    _check(_lib.omni_conv_backward_data(ctypes.byref(desc), _p(dY), _p(W), _p(dX), _p(workspace),
+                                        workspace.numel(), _stream()))
+    return dX
+
+
+def conv_backward_weights(desc: ConvDesc, X, dY, dW=None, dbias=None, workspace=None, want_dbias=True):
+    """omni_conv_backward_weights: fp32 dW [F][C][kh][kw] (and dbias [F]) summed over the batch."""
+    if dW is None:
+        dW = torch.empty((desc.F, desc.C, desc.kh, desc.kw), dtype=torch.float32, device=dY.device)
+    if dbias is None and want_dbias:
+        dbias = torch.empty((desc.F,), dtype=torch.float32, device=dY.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, PASS_BACKWARD_WEIGHTS, dY.device)
+    _check(_lib.omni_conv_backward_weights(ctypes.byref(desc), _p(X), _p(dY), _p(dW), _p(dbias),
+                                           _p(workspace), workspace.numel(), _stream()))
+    return dW, dbias
+
+
+def sgd_momentum_step(W: Sequence[torch.Tensor], V: Sequence[torch.Tensor], G: Sequence[torch.Tensor],
+                      lr: float, momentum: float, weight_decay: float = 0.0,
+                      W_shadow: Optional[Sequence[Optional[torch.Tensor]]] = None) -> None:
+    """omni_sgd_momentum_step: V <- mu V - lr (G + lambda W); W <- W + V, in place, all tensors at once."""
+    n = len(W)
+    if not (len(V) == n and len(G) == n and (W_shadow is None or len(W_shadow) == n)):
+        raise ValueError("W, V, G (and W_shadow) must have equal length")
+    for t in list(W) + list(V) + list(G):
+        if t.dtype != torch.float32:
+            raise ValueError("W, V and G must be float32")
+    arr = _vp * max(n, 1)
+    cnt = (_i64 * max(n, 1))(*[w.numel() for w in W])
+    pw, pv, pg = arr(*[_p(t) for t in W]), arr(*[_p(t) for t in V]), arr(*[_p(t) for t in G])
+    ps = None
+    if W_shadow is not None:
+        for t in W_shadow:
+            if t is not None and t.dtype != torch.bfloat16:
+                raise ValueError("W_shadow tensors must be bfloat16")
+        ps = arr(*[_p(t) for t in W_shadow])
+    _check(_lib.omni_sgd_momentum_step(n, pw, pv, pg, cnt, ps, lr, momentum, weight_decay, _stream()))
+
+
+def lower(desc: ConvDesc, X, Dhat=None, ld: Optional[int] = None):
+    """omni_lower: D-hat [C*kh*kw][ld] in the canonical layout (ld defaults to N*Ho*Wo)."""
+    ho, wo = conv_output_dims(desc)
+    M = desc.N * ho * wo
+    ld = M if ld is None else ld
+    if Dhat is None:
+        Dhat = torch.empty((desc.C * desc.kh * desc.kw, ld), dtype=torch_dtype(desc.dtype), device=X.device)
+    _check(_lib.omni_lower(ctypes.byref(desc), _p(X), _p(Dhat), ld, _stream()))
+    return Dhat
+
+
+def col2im(desc: ConvDesc, dDhat, dX=None, ld: Optional[int] = None):
+    """omni_col2im: sums a D-hat-shaped matrix back into dX [N][C][H][W]."""
+    ld = dDhat.shape[1] if ld is None else ld
+    if dX is None:
+        dX = torch.empty((desc.N, desc.C, desc.H, desc.W), dtype=torch_dtype(desc.dtype), device=dDhat.device)
+    _check(_lib.omni_col2im(ctypes.byref(desc), _p(dDhat), ld, _p(dX), _stream()))
+    return dX
+
+
+def relu_forward(x, y=None):
+    y = torch.empty_like(x) if y is None else y
+    _check(_lib.omni_relu_forward(dtype_code(x.dtype), x.numel(), _p(x), _p(y), _stream()))
+    return y
+
+
+def relu_backward(y, dy, dx=None):
+    dx = torch.empty_like(dy) if dx is None else dx
+    _check(_lib.omni_relu_backward(dtype_code(y.dtype), y.numel(), _p(y), _p(dy), _p(dx), _stream()))
+    return dx
+
+
+def pool_output_dim(n: int, k: int = 3, stride: int = 2, ceil_mode: bool = True) -> int:
+    o = _lib.omni_pool_output_dim(n, k, stride, int(ceil_mode))
+    if o < 0:
+        raise OmniError(o)
+    return o
+
+
+def maxpool_forward(x, k: int = 3, stride: int = 2, ceil_mode: bool = True, y=None, argmax=None):
+    """omni_maxpool_forward over the last two axes; returns (y, argmax uint8 = ky*k+kx of the winner)."""
+    H, W = x.shape[-2:]
+    planes = x.numel() // (H * W)
+    ho, wo = pool_output_dim(H, k, stride, ceil_mode), pool_output_dim(W, k, stride, ceil_mode)
+    if y is None:
+        y = torch.empty(tuple(x.shape[:-2]) + (ho, wo), dtype=x.dtype, device=x.device)
+    if argmax is None:
+        argmax = torch.empty(tuple(x.shape[:-2]) + (ho, wo), dtype=torch.uint8, device=x.device)
+    _check(_lib.omni_maxpool_forward(dtype_code(x.dtype), planes, H, W, k, stride, int(ceil_mode), _p(x), _p(y),
+                                     _p(argmax), _stream()))
+    return y, argmax
+
+
+def maxpool_backward(dy, argmax, H: int, W: int, k: int = 3, stride: int = 2, ceil_mode: bool = True, dx=None):
+    planes = dy.numel() // (dy.shape[-1] * dy.shape[-2])
+    if dx is None:
+        dx = torch.empty(tuple(dy.shape[:-2]) + (H, W), dtype=dy.dtype, device=dy.device)
+    _check(_lib.omni_maxpool_backward(dtype_code(dy.dtype), planes, H, W, k, stride, int(ceil_mode), _p(dy),
+                                      _p(argmax), _p(dx), _stream()))
+    return dx

@@ -1,0 +1,333 @@
+// C ABI of the library: argument checks, workspace carving and the launch sequence of each pass.
+// Everything before the first launch is plain host code, so every error path can be exercised on a
+// machine without a GPU.
+#include "common.h"
+
+namespace omni {
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int make_geom(const omni_conv_desc *d, ConvGeom *g)
+{
+    if (d == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->F <= 0 || d->kh <= 0 || d->kw <= 0 ||
+        d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
+        return OMNI_INVALID_ARGUMENT;
+    int64_t eh = (int64_t)d->H + 2 * (int64_t)d->pad_h - d->kh;
+    int64_t ew = (int64_t)d->W + 2 * (int64_t)d->pad_w - d->kw;
+    if (eh < 0 || ew < 0) return OMNI_INVALID_ARGUMENT;  // the window does not fit: empty output
+    if (d->dtype != OMNI_F32 && d->dtype != OMNI_BF16) return OMNI_UNSUPPORTED;
+    if (d->flags & ~(OMNI_FLAG_RELU | OMNI_FLAG_DHAT_CACHED)) return OMNI_UNSUPPORTED;
+    int64_t Ho = eh / d->stride_h + 1, Wo = ew / d->stride_w + 1;
+    int64_t M = (int64_t)d->N * Ho * Wo;
+    int64_t K = (int64_t)d->C * d->kh * d->kw;
+    const int64_t lim = 0x7fffffffll - 4096;  // indices are decoded with 32-bit multiply-high divisions
+    if (M > lim || K > lim || (int64_t)d->H * d->W > lim || (int64_t)d->N * d->C > lim ||
+        (int64_t)d->N * d->F > lim || d->F > 65535 || (int64_t)d->pad_h + d->H > lim ||
+        (int64_t)d->pad_w + d->W > lim)
+        return OMNI_UNSUPPORTED;
+    g->N = d->N; g->C = d->C; g->H = d->H; g->W = d->W; g->F = d->F;
+    g->kh = d->kh; g->kw = d->kw; g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
+    g->Ho = (int32_t)Ho; g->Wo = (int32_t)Wo; g->K = (int32_t)K; g->M = (int32_t)M; g->HoWo = (int32_t)(Ho * Wo);
+    g->div_Wo = FastDiv((uint32_t)Wo);
+    g->div_HoWo = FastDiv((uint32_t)(Ho * Wo));
+    g->div_kw = FastDiv((uint32_t)d->kw);
+    g->div_khkw = FastDiv((uint32_t)(d->kh * d->kw));
+    g->div_W = FastDiv((uint32_t)d->W);
+    g->div_HW = FastDiv((uint32_t)(d->H * d->W));
+    return OMNI_OK;
+}
+
+static size_t align256(size_t b) { return (b + 255) / 256 * 256; }
+
+void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w)
+{
+    size_t e = elem_size(dtype);
+    w->ld = dhat_ld(g);
+    w->Fp = g.F;
+    w->Kp = round_up(g.K, 8);
+    w->dhat = 0;
+    w->khat = align256((size_t)g.K * w->ld * e);
+    w->total = w->khat + align256((size_t)w->Fp * w->Kp * e);
+}
+
+void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w)
+{
+    size_t e = elem_size(dtype);
+    w->ld = dhat_ld(g);
+    w->Kp = g.K;
+    w->Fp = round_up(g.F, 8);
+    w->ddhat = 0;
+    w->dyhat = align256((size_t)g.K * w->ld * e);
+    w->khat_t = w->dyhat + align256((size_t)g.F * w->ld * e);
+    w->total = w->khat_t + align256((size_t)w->Kp * w->Fp * e);
+}
+
+void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w)
+{
+    size_t e = elem_size(dtype);
+    w->ld = dhat_ld(g);
+    // Split the long reduction (M = N*Ho*Wo) so that about four workgroups per compute unit exist,
+    // each with at least four LDS steps of work.
+    int64_t bk = gemm_red_tile(dtype);
+    int64_t tiles = ((g.F + 127) / 128) * (int64_t)((g.K + 127) / 128);
+    int64_t steps = (w->ld + bk - 1) / bk;
+    int64_t want = (1024 + tiles - 1) / tiles;
+    int64_t max_splits = steps / 4 > 0 ? steps / 4 : 1;
+    int64_t splits = want < max_splits ? want : max_splits;
+    if (splits < 1) splits = 1;
+    int64_t chunk = round_up((w->ld + splits - 1) / splits, bk);
+    splits = (w->ld + chunk - 1) / chunk;
+    w->splits = (int)splits;
+    w->chunk = chunk;
+    w->bias_blocks = pack_dyhat_blocks(g);
+    w->dhat = 0;
+    w->dyhat = align256((size_t)g.K * w->ld * e);
+    w->partials = w->dyhat + align256((size_t)g.F * w->ld * e);
+    w->bias_partials = w->partials + align256(splits > 1 ? (size_t)splits * g.F * g.K * sizeof(float) : 0);
+    w->total = w->bias_partials + align256((size_t)g.F * w->bias_blocks * sizeof(float));
+}
+
+}  // namespace omni
+
+using namespace omni;
+
+extern "C" {
+
+const char *omni_status_string(int status)
+{
+    switch (status) {
+    case OMNI_OK: return "ok";
+    case OMNI_INVALID_ARGUMENT: return "invalid argument";
+    case OMNI_UNSUPPORTED: return "unsupported dtype, flag or extent";
+    case OMNI_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case OMNI_MISALIGNED: return "device pointer not 16-byte aligned";
+    case OMNI_HIP_ERROR: return "HIP launch error";
+    default: return "unknown status";
+    }
+}
+
+const char *omni_version(void) { return "0.1"; }
+
+int omni_conv_output_dims(const omni_conv_desc *desc, int32_t *Ho, int32_t *Wo)
+{
+    if (Ho == nullptr || Wo == nullptr) return OMNI_INVALID_ARGUMENT;
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    *Ho = g.Ho;
+    *Wo = g.Wo;
+    return OMNI_OK;
+}
+
+int omni_conv_dhat_ld(const omni_conv_desc *desc, int64_t *ld)
+{
+    if (ld == nullptr) return OMNI_INVALID_ARGUMENT;
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    *ld = dhat_ld(g);
+    return OMNI_OK;
+}
+
+int omni_conv_workspace_bytes(const omni_conv_desc *desc, int pass, size_t *bytes)
+{
+    if (bytes == nullptr) return OMNI_INVALID_ARGUMENT;
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (pass == OMNI_PASS_FORWARD) {
+        ForwardWs w;
+        plan_forward(g, desc->dtype, &w);
+        *bytes = w.total;
+    } else if (pass == OMNI_PASS_BACKWARD_DATA) {
+        BwdDataWs w;
+        plan_backward_data(g, desc->dtype, &w);
+        *bytes = w.total;
+    } else if (pass == OMNI_PASS_BACKWARD_WEIGHTS) {
+        BwdWeightsWs w;
+        plan_backward_weights(g, desc->dtype, &w);
+        *bytes = w.total;
+    } else {
+        return OMNI_INVALID_ARGUMENT;
+    }
+    return OMNI_OK;
+}
+
+int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, const float *bias, void *Y,
+                      void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (X == nullptr || W == nullptr || Y == nullptr || workspace == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(workspace) || (bias && !aligned16(bias)))
+        return OMNI_MISALIGNED;
+    ForwardWs w;
+    plan_forward(g, desc->dtype, &w);
+    if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+    void *Dhat = ws + w.dhat, *Khat = ws + w.khat;
+
+    st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
+    if (st != OMNI_OK) return st;
+    st = launch_pack_khat(g, desc->dtype, W, Khat, w.Fp, w.Kp, s);
+    if (st != OMNI_OK) return st;
+    GemmFwdArgs a{Khat, w.Kp, Dhat, w.ld, bias, Y, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0};
+    return launch_gemm_forward(g, desc->dtype, a, s);
+}
+
+int omni_conv_backward_data(const omni_conv_desc *desc, const void *dY, const void *W, void *dX, void *workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (dY == nullptr || W == nullptr || dX == nullptr || workspace == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(dY) || !aligned16(W) || !aligned16(dX) || !aligned16(workspace)) return OMNI_MISALIGNED;
+    BwdDataWs w;
+    plan_backward_data(g, desc->dtype, &w);
+    if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+    void *dDhat = ws + w.ddhat, *dYhat = ws + w.dyhat, *KhatT = ws + w.khat_t;
+
+    st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, nullptr, 0, nullptr, s);
+    if (st != OMNI_OK) return st;
+    st = launch_pack_khat_t(g, desc->dtype, W, KhatT, w.Kp, w.Fp, s);
+    if (st != OMNI_OK) return st;
+    GemmDgradArgs a{KhatT, w.Fp, dYhat, w.ld, dDhat};
+    st = launch_gemm_dgrad(g, desc->dtype, a, s);
+    if (st != OMNI_OK) return st;
+    return launch_col2im(g, desc->dtype, dDhat, w.ld, dX, s);
+}
+
+int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const void *dY, float *dW, float *dbias,
+                               void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    bool cached = (desc->flags & OMNI_FLAG_DHAT_CACHED) != 0;
+    if ((X == nullptr && !cached) || dY == nullptr || dW == nullptr || workspace == nullptr)
+        return OMNI_INVALID_ARGUMENT;
+    if ((X && !aligned16(X)) || !aligned16(dY) || !aligned16(dW) || !aligned16(workspace) ||
+        (dbias && !aligned16(dbias)))
+        return OMNI_MISALIGNED;
+    BwdWeightsWs w;
+    plan_backward_weights(g, desc->dtype, &w);
+    if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+    void *Dhat = ws + w.dhat, *dYhat = ws + w.dyhat;
+    float *partials = (float *)(ws + w.partials), *bias_partials = (float *)(ws + w.bias_partials);
+
+    if (!cached) {
+        st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
+        if (st != OMNI_OK) return st;
+    }
+    st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, dbias ? bias_partials : nullptr, w.bias_blocks, dbias, s);
+    if (st != OMNI_OK) return st;
+    GemmWgradArgs a{dYhat, Dhat, w.ld, partials, w.splits, w.chunk, dW};
+    return launch_gemm_wgrad(g, desc->dtype, a, s);
+}
+
+int omni_sgd_momentum_step(int32_t n_tensors, float *const *W, float *const *V, const float *const *G,
+                           const int64_t *counts, void *const *W_shadow, float lr, float momentum, float weight_decay,
+                           void *hip_stream)
+{
+    if (n_tensors < 0) return OMNI_INVALID_ARGUMENT;
+    if (n_tensors == 0) return OMNI_OK;
+    if (W == nullptr || V == nullptr || G == nullptr || counts == nullptr) return OMNI_INVALID_ARGUMENT;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (counts[i] < 0) return OMNI_INVALID_ARGUMENT;
+        if (counts[i] == 0) continue;
+        if (W[i] == nullptr || V[i] == nullptr || G[i] == nullptr) return OMNI_INVALID_ARGUMENT;
+        if (!aligned16(W[i]) || !aligned16(V[i]) || !aligned16(G[i]) || (W_shadow && W_shadow[i] && !aligned16(W_shadow[i])))
+            return OMNI_MISALIGNED;
+    }
+    return launch_sgd(n_tensors, W, V, G, counts, W_shadow, lr, momentum, weight_decay, (hipStream_t)hip_stream);
+}
+
+int omni_lower(const omni_conv_desc *desc, const void *X, void *Dhat, int64_t ld, void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (X == nullptr || Dhat == nullptr || ld < g.M) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(X) || !aligned16(Dhat)) return OMNI_MISALIGNED;
+    return launch_lower(g, desc->dtype, X, Dhat, ld, (hipStream_t)hip_stream);
+}
+
+int omni_col2im(const omni_conv_desc *desc, const void *dDhat, int64_t ld, void *dX, void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (dDhat == nullptr || dX == nullptr || ld < g.M) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(dDhat) || !aligned16(dX)) return OMNI_MISALIGNED;
+    return launch_col2im(g, desc->dtype, dDhat, ld, dX, (hipStream_t)hip_stream);
+}
+
+static int check_dtype(int32_t dtype) { return (dtype == OMNI_F32 || dtype == OMNI_BF16) ? OMNI_OK : OMNI_UNSUPPORTED; }
+
+int omni_relu_forward(int32_t dtype, int64_t count, const void *x, void *y, void *hip_stream)
+{
+    if (check_dtype(dtype) != OMNI_OK) return OMNI_UNSUPPORTED;
+    if (count < 0) return OMNI_INVALID_ARGUMENT;
+    if (count == 0) return OMNI_OK;
+    if (x == nullptr || y == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(x) || !aligned16(y)) return OMNI_MISALIGNED;
+    return launch_relu(dtype, false, count, x, nullptr, y, (hipStream_t)hip_stream);
+}
+
+int omni_relu_backward(int32_t dtype, int64_t count, const void *y, const void *dy, void *dx, void *hip_stream)
+{
+    if (check_dtype(dtype) != OMNI_OK) return OMNI_UNSUPPORTED;
+    if (count < 0) return OMNI_INVALID_ARGUMENT;
+    if (count == 0) return OMNI_OK;
+    if (y == nullptr || dy == nullptr || dx == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(y) || !aligned16(dy) || !aligned16(dx)) return OMNI_MISALIGNED;
+    return launch_relu(dtype, true, count, y, dy, dx, (hipStream_t)hip_stream);
+}
+
+int omni_pool_output_dim(int32_t in, int32_t k, int32_t stride, int32_t ceil_mode)
+{
+    if (in <= 0 || k <= 0 || stride <= 0 || in < k) return OMNI_INVALID_ARGUMENT;
+    int32_t span = in - k;
+    return (ceil_mode ? (span + stride - 1) / stride : span / stride) + 1;
+}
+
+static int check_pool(int32_t dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride)
+{
+    if (check_dtype(dtype) != OMNI_OK) return OMNI_UNSUPPORTED;
+    if (planes < 0 || H <= 0 || W <= 0 || k <= 0 || stride <= 0 || H < k || W < k) return OMNI_INVALID_ARGUMENT;
+    if (k > 15) return OMNI_UNSUPPORTED;  // the winner's window position is stored in one byte
+    if ((int64_t)H * W > 0x7fffffffll - 4096) return OMNI_UNSUPPORTED;
+    return OMNI_OK;
+}
+
+int omni_maxpool_forward(int32_t dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride,
+                         int32_t ceil_mode, const void *x, void *y, uint8_t *argmax, void *hip_stream)
+{
+    int st = check_pool(dtype, planes, H, W, k, stride);
+    if (st != OMNI_OK) return st;
+    if (planes == 0) return OMNI_OK;
+    if (x == nullptr || y == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(x) || !aligned16(y)) return OMNI_MISALIGNED;
+    return launch_maxpool_fwd(dtype, planes, H, W, k, stride, ceil_mode, x, y, argmax, (hipStream_t)hip_stream);
+}
+
+int omni_maxpool_backward(int32_t dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride,
+                          int32_t ceil_mode, const void *dy, const uint8_t *argmax, void *dx, void *hip_stream)
+{
+    int st = check_pool(dtype, planes, H, W, k, stride);
+    if (st != OMNI_OK) return st;
+    if (planes == 0) return OMNI_OK;
+    if (dy == nullptr || argmax == nullptr || dx == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(dy) || !aligned16(dx)) return OMNI_MISALIGNED;
+    return launch_maxpool_bwd(dtype, planes, H, W, k, stride, ceil_mode, dy, argmax, dx, (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,125 @@
+// Internal declarations shared by the HIP sources of the library (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "omniconv.h"
+
+namespace omni {
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+
+// ---------------------------------------------------------------- bf16 <-> fp32, device side
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// Round to nearest, ties to even; NaN stays a (quiet) NaN.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float *p) { return *p; }
+    static __device__ __forceinline__ float to_f32(float v) { return v; }
+    static __device__ __forceinline__ float from_f32(float v) { return v; }
+};
+template <> struct Elem<bf16_t> {
+    static __device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
+    static __device__ __forceinline__ bf16_t from_f32(float v) { return f32_to_bf16(v); }
+};
+
+// ---------------------------------------------------------------- division by a run-time constant
+// q = n / d for 0 <= n < 2^31 and 1 <= d < 2^31 as a multiply-high, an add and a shift
+// (the round-up method of Granlund & Montgomery); the multiplier is computed once on the host.
+struct FastDiv {
+    uint32_t d, mul, shift;
+    FastDiv() : d(1), mul(0), shift(0) {}
+    explicit FastDiv(uint32_t div) : d(div)
+    {
+        shift = 0;
+        while ((1ull << shift) < div) ++shift;
+        mul = (uint32_t)((((1ull << shift) - div) << 32) / div + 1);
+    }
+    __host__ __device__ __forceinline__ uint32_t div(uint32_t n) const
+    {
+#if defined(__HIP_DEVICE_COMPILE__)
+        return (__umulhi(n, mul) + n) >> shift;
+#else
+        return (uint32_t)((((uint64_t)n * mul) >> 32) + n) >> shift;
+#endif
+    }
+    __host__ __device__ __forceinline__ void divmod(uint32_t n, uint32_t &q, uint32_t &r) const
+    {
+        q = div(n);
+        r = n - q * d;
+    }
+};
+
+// ---------------------------------------------------------------- geometry of one layer
+struct ConvGeom {
+    int32_t N, C, H, W, F, kh, kw, sh, sw, ph, pw, Ho, Wo;
+    int32_t K;     // C*kh*kw   rows of D-hat
+    int32_t M;     // N*Ho*Wo   columns of D-hat
+    int32_t HoWo;  // Ho*Wo
+    FastDiv div_Wo, div_HoWo, div_kw, div_khkw, div_W, div_HW;
+};
+
+inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+
+// Host-side checks; fill `g` from a descriptor.  Pure host code (no HIP calls).
+int make_geom(const omni_conv_desc *desc, ConvGeom *g);
+
+// Leading dimension of D-hat / dY-hat inside a workspace.
+inline int64_t dhat_ld(const ConvGeom &g) { return round_up(g.M, 8); }
+
+// ---------------------------------------------------------------- workspace carving
+struct ForwardWs { size_t dhat, khat, total; int64_t ld, Fp, Kp; };
+struct BwdDataWs { size_t ddhat, dyhat, khat_t, total; int64_t ld, Kp, Fp; };
+struct BwdWeightsWs { size_t dhat, dyhat, partials, bias_partials, total; int64_t ld; int splits; int64_t chunk; int bias_blocks; };
+void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w);
+void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w);
+void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w);
+
+inline size_t elem_size(int dtype) { return dtype == OMNI_BF16 ? 2 : 4; }
+
+#define OMNI_LAUNCH_CHECK()                                   \
+    do {                                                      \
+        if (hipGetLastError() != hipSuccess) return OMNI_HIP_ERROR; \
+    } while (0)
+
+// ---------------------------------------------------------------- launchers (one per source file)
+// lowering.hip
+int launch_lower(const ConvGeom &g, int dtype, const void *X, void *Dhat, int64_t ld, hipStream_t s);
+int launch_col2im(const ConvGeom &g, int dtype, const void *dDhat, int64_t ld, void *dX, hipStream_t s);
+int launch_pack_khat(const ConvGeom &g, int dtype, const void *W, void *Khat, int64_t Fp, int64_t Kp, hipStream_t s);
+int launch_pack_khat_t(const ConvGeom &g, int dtype, const void *W, void *KhatT, int64_t Kp, int64_t Fp, hipStream_t s);
+// dY [N][F][Ho][Wo] -> dY-hat [F][ld]; if bias_partials != null also writes per-block sums
+// [F][bias_blocks] and then reduces them into dbias.
+int launch_pack_dyhat(const ConvGeom &g, int dtype, const void *dY, void *dYhat, int64_t ld,
+                      float *bias_partials, int bias_blocks, float *dbias, hipStream_t s);
+int pack_dyhat_blocks(const ConvGeom &g);
+
+// gemm.hip
+struct GemmFwdArgs { const void *Khat; int64_t ldk; const void *Dhat; int64_t ldd; const float *bias; void *Y; int relu; };
+int launch_gemm_forward(const ConvGeom &g, int dtype, const GemmFwdArgs &a, hipStream_t s);
+struct GemmDgradArgs { const void *KhatT; int64_t ldk; const void *dYhat; int64_t ldd; void *dDhat; };
+int launch_gemm_dgrad(const ConvGeom &g, int dtype, const GemmDgradArgs &a, hipStream_t s);
+struct GemmWgradArgs { const void *dYhat; const void *Dhat; int64_t ldd; float *partials; int splits; int64_t chunk; float *dW; };
+int launch_gemm_wgrad(const ConvGeom &g, int dtype, const GemmWgradArgs &a, hipStream_t s);
+int gemm_red_tile(int dtype);  // reduction extent of one LDS tile (elements)
+
+// elementwise.hip
+int launch_sgd(int32_t n, float *const *W, float *const *V, const float *const *G, const int64_t *counts,
+               void *const *shadow, float lr, float mu, float wd, hipStream_t s);
+int launch_relu(int dtype, bool backward, int64_t count, const void *ref, const void *dy, void *out, hipStream_t s);
+int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
+                       const void *x, void *y, uint8_t *argmax, hipStream_t s);
+int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
+                       const void *dy, const uint8_t *argmax, void *dx, hipStream_t s);
+
+}  // namespace omni

@@ -1,0 +1,295 @@
+// Element-wise and window kernels (gfx950): the fused momentum-SGD update over a list of tensors,
+// ReLU, and 2-D max-pooling.  All are bound by HBM traffic; each thread moves 16 bytes where the
+// layout allows it and nothing uses floating point atomics.
+#include "common.h"
+
+namespace omni {
+
+// ------------------------------------------------------------------------------------------------
+// Momentum SGD (Sec. II-B, Eq. (update2) then Eq. (update1)), many tensors per launch:
+//   V <- mu*V - lr*(G + lambda*W);   W <- W + V;   optionally W_shadow <- bf16(W)
+// The tensor table travels in the kernel arguments, so no device memory is needed for it.
+// ------------------------------------------------------------------------------------------------
+constexpr int SGD_MAX_TENSORS = 24;
+constexpr int SGD_BLOCK_ELEMS = 256 * 4 * 4;  // 4 float4 per thread
+
+struct SgdTable {
+    float *W[SGD_MAX_TENSORS];
+    float *V[SGD_MAX_TENSORS];
+    const float *G[SGD_MAX_TENSORS];
+    bf16_t *S[SGD_MAX_TENSORS];
+    int64_t count[SGD_MAX_TENSORS];
+    int32_t first_block[SGD_MAX_TENSORS + 1];  // prefix sum of blocks per tensor
+    int32_t n;
+};
+
+__device__ __forceinline__ void sgd_one(float &w, float &v, float g, float lr, float mu, float wd)
+{
+    float step = g + wd * w;
+    v = mu * v - lr * step;
+    w = w + v;
+}
+
+__global__ __launch_bounds__(256) void sgd_kernel(SgdTable t, float lr, float mu, float wd)
+{
+    int b = blockIdx.x;
+    int ti = 0;
+    while (ti + 1 < t.n && b >= t.first_block[ti + 1]) ++ti;
+    int64_t base = (int64_t)(b - t.first_block[ti]) * SGD_BLOCK_ELEMS;
+    float *W = t.W[ti];
+    float *V = t.V[ti];
+    const float *G = t.G[ti];
+    bf16_t *S = t.S[ti];
+    int64_t count = t.count[ti];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        int64_t i = base + ((int64_t)q * 256 + threadIdx.x) * 4;
+        if (i + 4 <= count) {
+            float4 w = *reinterpret_cast<float4 *>(W + i);
+            float4 v = *reinterpret_cast<float4 *>(V + i);
+            float4 g = *reinterpret_cast<const float4 *>(G + i);
+            sgd_one(w.x, v.x, g.x, lr, mu, wd);
+            sgd_one(w.y, v.y, g.y, lr, mu, wd);
+            sgd_one(w.z, v.z, g.z, lr, mu, wd);
+            sgd_one(w.w, v.w, g.w, lr, mu, wd);
+            *reinterpret_cast<float4 *>(W + i) = w;
+            *reinterpret_cast<float4 *>(V + i) = v;
+            if (S != nullptr) {
+                uint2 p;
+                p.x = (uint32_t)f32_to_bf16(w.x) | ((uint32_t)f32_to_bf16(w.y) << 16);
+                p.y = (uint32_t)f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
+                *reinterpret_cast<uint2 *>(S + i) = p;
+            }
+        } else {
+            for (int64_t j = i; j < count; ++j) {
+                float w = W[j], v = V[j];
+                sgd_one(w, v, G[j], lr, mu, wd);
+                W[j] = w;
+                V[j] = v;
+                if (S != nullptr) S[j] = f32_to_bf16(w);
+            }
+        }
+    }
+}
+
+int launch_sgd(int32_t n, float *const *W, float *const *V, const float *const *G, const int64_t *counts,
+               void *const *shadow, float lr, float mu, float wd, hipStream_t s)
+{
+    int32_t done = 0;
+    while (done < n) {
+        SgdTable t;
+        t.n = 0;
+        t.first_block[0] = 0;
+        while (done < n && t.n < SGD_MAX_TENSORS) {
+            int64_t c = counts[done];
+            if (c > 0) {
+                int64_t blocks = (c + SGD_BLOCK_ELEMS - 1) / SGD_BLOCK_ELEMS;
+                if (t.first_block[t.n] + blocks > 0x7fffffff) {
+                    if (t.n == 0) return OMNI_UNSUPPORTED;
+                    break;  // launch what is collected so far; this tensor starts the next table
+                }
+                t.W[t.n] = W[done];
+                t.V[t.n] = V[done];
+                t.G[t.n] = G[done];
+                t.S[t.n] = shadow ? (bf16_t *)shadow[done] : nullptr;
+                t.count[t.n] = c;
+                t.first_block[t.n + 1] = t.first_block[t.n] + (int32_t)blocks;
+                ++t.n;
+            }
+            ++done;
+        }
+        if (t.n == 0) continue;
+        for (int i = t.n; i < SGD_MAX_TENSORS; ++i) {
+            t.W[i] = t.V[i] = nullptr;
+            t.G[i] = nullptr;
+            t.S[i] = nullptr;
+            t.count[i] = 0;
+            t.first_block[i + 1] = t.first_block[t.n];
+        }
+        hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)t.first_block[t.n]), dim3(256), 0, s, t, lr, mu, wd);
+        OMNI_LAUNCH_CHECK();
+    }
+    return OMNI_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// ReLU
+// ------------------------------------------------------------------------------------------------
+template <typename T, bool BACKWARD>
+__global__ __launch_bounds__(256) void relu_kernel(int64_t count, const T *ref, const T *dy, T *out)  // in place allowed: no restrict
+{
+    constexpr int VEC = 16 / sizeof(T);
+    int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * VEC;
+    if (i >= count) return;
+    if (i + VEC <= count) {
+        struct alignas(16) V { T v[VEC]; };
+        V r = *reinterpret_cast<const V *>(ref + i);
+        V o;
+        if constexpr (BACKWARD) {
+            V d = *reinterpret_cast<const V *>(dy + i);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) o.v[e] = Elem<T>::to_f32(r.v[e]) > 0.f ? d.v[e] : (T)0;
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) o.v[e] = Elem<T>::to_f32(r.v[e]) > 0.f ? r.v[e] : (T)0;
+        }
+        *reinterpret_cast<V *>(out + i) = o;
+    } else {
+        for (int64_t j = i; j < count; ++j) {
+            bool pos = Elem<T>::to_f32(ref[j]) > 0.f;
+            out[j] = pos ? (BACKWARD ? dy[j] : ref[j]) : (T)0;
+        }
+    }
+}
+
+int launch_relu(int dtype, bool backward, int64_t count, const void *ref, const void *dy, void *out, hipStream_t s)
+{
+    if (count == 0) return OMNI_OK;
+    int vec = dtype == OMNI_BF16 ? 8 : 4;
+    dim3 grid((unsigned)((count + 256 * (int64_t)vec - 1) / (256 * (int64_t)vec)));
+    if (dtype == OMNI_BF16) {
+        if (backward)
+            hipLaunchKernelGGL((relu_kernel<bf16_t, true>), grid, dim3(256), 0, s, count, (const bf16_t *)ref, (const bf16_t *)dy, (bf16_t *)out);
+        else
+            hipLaunchKernelGGL((relu_kernel<bf16_t, false>), grid, dim3(256), 0, s, count, (const bf16_t *)ref, (const bf16_t *)nullptr, (bf16_t *)out);
+    } else {
+        if (backward)
+            hipLaunchKernelGGL((relu_kernel<float, true>), grid, dim3(256), 0, s, count, (const float *)ref, (const float *)dy, (float *)out);
+        else
+            hipLaunchKernelGGL((relu_kernel<float, false>), grid, dim3(256), 0, s, count, (const float *)ref, (const float *)nullptr, (float *)out);
+    }
+    OMNI_LAUNCH_CHECK();
+    return OMNI_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Max-pool, k x k window, stride s, no padding, last window clipped at the border in ceil mode.
+// ------------------------------------------------------------------------------------------------
+struct PoolGeom {
+    int32_t H, W, Ho, Wo, k, s;
+    FastDiv div_Wo, div_HoWo, div_W, div_HW;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(PoolGeom g, int64_t plane0, uint32_t count,
+                                                          const T *__restrict__ x, T *__restrict__ y,
+                                                          uint8_t *__restrict__ argmax)
+{
+    // One launch covers `count` < 2^31 outputs starting at plane plane0.
+    uint32_t local = blockIdx.x * 256u + threadIdx.x;
+    if (local >= count) return;
+    uint32_t pl, o, oy, ox;
+    g.div_HoWo.divmod(local, pl, o);
+    g.div_Wo.divmod(o, oy, ox);
+    int64_t plane = plane0 + pl;
+    const T *src = x + plane * g.H * g.W;
+    int best = -1;
+    float bv = 0.f;
+    T braw = (T)0;
+    for (int ky = 0; ky < g.k; ++ky) {
+        int iy = (int)oy * g.s + ky;
+        if (iy >= g.H) break;
+        for (int kx = 0; kx < g.k; ++kx) {
+            int ix = (int)ox * g.s + kx;
+            if (ix >= g.W) break;
+            T raw = src[iy * g.W + ix];
+            float v = Elem<T>::to_f32(raw);
+            if (best < 0 || v > bv) {  // strict: the first maximum in scan order wins
+                best = ky * g.k + kx;
+                bv = v;
+                braw = raw;
+            }
+        }
+    }
+    int64_t out = plane * g.Ho * g.Wo + o;
+    y[out] = braw;
+    if (argmax != nullptr) argmax[out] = (uint8_t)best;
+}
+
+// Gather form: each input pixel collects the gradient of every window that elected it, in
+// ascending (oy, ox) order, in fp32.
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolGeom g, int64_t plane0, uint32_t count,
+                                                          const T *__restrict__ dy, const uint8_t *__restrict__ argmax,
+                                                          T *__restrict__ dx)
+{
+    uint32_t local = blockIdx.x * 256u + threadIdx.x;
+    if (local >= count) return;
+    uint32_t pl, p, iy, ix;
+    g.div_HW.divmod(local, pl, p);
+    g.div_W.divmod(p, iy, ix);
+    int64_t plane = plane0 + pl;
+    int oy_lo = (int)iy - g.k + 1;
+    oy_lo = oy_lo <= 0 ? 0 : (oy_lo + g.s - 1) / g.s;
+    int oy_hi = (int)iy / g.s;
+    if (oy_hi > g.Ho - 1) oy_hi = g.Ho - 1;
+    int ox_lo = (int)ix - g.k + 1;
+    ox_lo = ox_lo <= 0 ? 0 : (ox_lo + g.s - 1) / g.s;
+    int ox_hi = (int)ix / g.s;
+    if (ox_hi > g.Wo - 1) ox_hi = g.Wo - 1;
+    const int64_t obase = plane * g.Ho * g.Wo;
+    float acc = 0.f;
+    for (int oy = oy_lo; oy <= oy_hi; ++oy)
+        for (int ox = ox_lo; ox <= ox_hi; ++ox) {
+            int code = ((int)iy - oy * g.s) * g.k + ((int)ix - ox * g.s);
+            int64_t o = obase + (int64_t)oy * g.Wo + ox;
+            if (argmax[o] == (uint8_t)code) acc += Elem<T>::to_f32(dy[o]);
+        }
+    dx[plane * g.H * g.W + p] = Elem<T>::from_f32(acc);
+}
+
+static PoolGeom make_pool_geom(int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode)
+{
+    PoolGeom g;
+    g.H = H;
+    g.W = W;
+    g.k = k;
+    g.s = stride;
+    g.Ho = omni_pool_output_dim(H, k, stride, ceil_mode);
+    g.Wo = omni_pool_output_dim(W, k, stride, ceil_mode);
+    g.div_Wo = FastDiv((uint32_t)g.Wo);
+    g.div_HoWo = FastDiv((uint32_t)(g.Ho * g.Wo));
+    g.div_W = FastDiv((uint32_t)W);
+    g.div_HW = FastDiv((uint32_t)(H * W));
+    return g;
+}
+
+int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
+                       const void *x, void *y, uint8_t *argmax, hipStream_t s)
+{
+    PoolGeom g = make_pool_geom(H, W, k, stride, ceil_mode);
+    int64_t per = (int64_t)g.Ho * g.Wo;
+    int64_t planes_per_launch = (0x7fffffffll - 4096) / per;
+    for (int64_t p0 = 0; p0 < planes; p0 += planes_per_launch) {
+        int64_t np = planes - p0 < planes_per_launch ? planes - p0 : planes_per_launch;
+        uint32_t count = (uint32_t)(np * per);
+        dim3 grid((count + 255u) / 256u);
+        if (dtype == OMNI_BF16)
+            hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, grid, dim3(256), 0, s, g, p0, count, (const bf16_t *)x, (bf16_t *)y, argmax);
+        else
+            hipLaunchKernelGGL(maxpool_fwd_kernel<float>, grid, dim3(256), 0, s, g, p0, count, (const float *)x, (float *)y, argmax);
+        OMNI_LAUNCH_CHECK();
+    }
+    return OMNI_OK;
+}
+
+int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
+                       const void *dy, const uint8_t *argmax, void *dx, hipStream_t s)
+{
+    PoolGeom g = make_pool_geom(H, W, k, stride, ceil_mode);
+    int64_t per = (int64_t)H * W;
+    int64_t planes_per_launch = (0x7fffffffll - 4096) / per;
+    for (int64_t p0 = 0; p0 < planes; p0 += planes_per_launch) {
+        int64_t np = planes - p0 < planes_per_launch ? planes - p0 : planes_per_launch;
+        uint32_t count = (uint32_t)(np * per);
+        dim3 grid((count + 255u) / 256u);
+        if (dtype == OMNI_BF16)
+            hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, grid, dim3(256), 0, s, g, p0, count, (const bf16_t *)dy, argmax, (bf16_t *)dx);
+        else
+            hipLaunchKernelGGL(maxpool_bwd_kernel<float>, grid, dim3(256), 0, s, g, p0, count, (const float *)dy, argmax, (float *)dx);
+        OMNI_LAUNCH_CHECK();
+    }
+    return OMNI_OK;
+}
+
+}  // namespace omni

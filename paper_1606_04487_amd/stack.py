@@ -1,0 +1,125 @@
+"""A chain of convolution layers (conv -> ReLU -> optional 3x3/2 max-pool) run through the library.
+
+This is the thin harness the tests and the bench use for the paper's CIFAR-style and
+CaffeNet-style convolution phases (Sec. II-C: the "conv phase" of a CNN; Sec. IV-A: an engine is
+a list of layers run forward and then in reverse).  It only sequences calls of the binding and
+owns the device buffers; every arithmetic step runs in the library's kernels.
+
+Memory plan (sized for one MI355X's 288 GB): every layer keeps its own forward workspace, so the
+lowered matrix D-hat written by the forward pass is still there when the backward pass needs it
+for the model gradient (the paper's "b_p = b": lower the whole batch once, Sec. III-B).  The
+data-gradient workspace is shared by all layers.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+from .workloads import ConvLayer
+
+
+class ConvStack:
+    def __init__(self, layers: Sequence[ConvLayer], dtype: int = B.F32, ceil_mode: bool = True,
+                 skip_first_dgrad: bool = True, device: str = "cuda"):
+        self.layers = list(layers)
+        self.dtype = dtype
+        self.tdtype = B.torch_dtype(dtype)
+        self.ceil_mode = ceil_mode
+        self.skip_first_dgrad = skip_first_dgrad   # App. B: the first layer needs no data gradient
+        self.device = device
+        self.desc = [B.conv_desc(L.N, L.C, L.H, L.W, L.F, L.k, L.k, L.s, L.p, dtype, B.FLAG_RELU)
+                     for L in self.layers]
+        self.desc_cached = [d.with_flags(B.FLAG_DHAT_CACHED) for d in self.desc]
+        # parameters: fp32 masters, velocity, gradients; bf16 copies of W for the bf16 passes
+        self.W = [torch.zeros((L.F, L.C, L.k, L.k), dtype=torch.float32, device=device) for L in self.layers]
+        self.b = [torch.zeros((L.F,), dtype=torch.float32, device=device) for L in self.layers]
+        self.VW = [torch.zeros_like(w) for w in self.W]
+        self.Vb = [torch.zeros_like(b) for b in self.b]
+        self.dW = [torch.empty_like(w) for w in self.W]
+        self.db = [torch.empty_like(b) for b in self.b]
+        self.Wc = ([torch.zeros_like(w, dtype=torch.bfloat16) for w in self.W] if dtype == B.BF16 else self.W)
+        # workspaces
+        self.ws_layer = []
+        bwd_bytes = 0
+        for i, d in enumerate(self.desc):
+            nbytes = max(B.conv_workspace_bytes(d, B.PASS_FORWARD),
+                         B.conv_workspace_bytes(d, B.PASS_BACKWARD_WEIGHTS))
+            self.ws_layer.append(torch.empty(nbytes, dtype=torch.uint8, device=device))
+            if not (i == 0 and skip_first_dgrad):
+                bwd_bytes = max(bwd_bytes, B.conv_workspace_bytes(d, B.PASS_BACKWARD_DATA))
+        self.ws_bwd = torch.empty(max(bwd_bytes, 16), dtype=torch.uint8, device=device)
+        # activations
+        self.X: List[Optional[torch.Tensor]] = [None] * len(self.layers)
+        self.Y, self.P, self.A, self.dYc, self.dXl = [], [], [], [], []
+        for i, (L, d) in enumerate(zip(self.layers, self.desc)):
+            ho, wo = B.conv_output_dims(d)
+            self.Y.append(torch.empty((L.N, L.F, ho, wo), dtype=self.tdtype, device=device))
+            self.dYc.append(torch.empty((L.N, L.F, ho, wo), dtype=self.tdtype, device=device))
+            if L.pool_after:
+                po, pw = B.pool_output_dim(ho, 3, 2, ceil_mode), B.pool_output_dim(wo, 3, 2, ceil_mode)
+                self.P.append(torch.empty((L.N, L.F, po, pw), dtype=self.tdtype, device=device))
+                self.A.append(torch.empty((L.N, L.F, po, pw), dtype=torch.uint8, device=device))
+            else:
+                self.P.append(None)
+                self.A.append(None)
+            need_dx = not (i == 0 and skip_first_dgrad)
+            self.dXl.append(torch.empty((L.N, L.C, L.H, L.W), dtype=self.tdtype, device=device) if need_dx else None)
+
+    # ------------------------------------------------------------------ parameters
+    def set_parameters(self, Ws, bs) -> None:
+        for i, (w, b) in enumerate(zip(Ws, bs)):
+            self.W[i].copy_(torch.as_tensor(w, dtype=torch.float32))
+            self.b[i].copy_(torch.as_tensor(b, dtype=torch.float32))
+            if self.dtype == B.BF16:
+                self.Wc[i].copy_(self.W[i])       # plumbing: the inputs are bf16-representable already
+            self.VW[i].zero_()
+            self.Vb[i].zero_()
+
+    def output_shape(self):
+        last = self.P[-1] if self.P[-1] is not None else self.Y[-1]
+        return tuple(last.shape)
+
+    # ------------------------------------------------------------------ passes
+    def forward(self, X: torch.Tensor) -> torch.Tensor:
+        cur = X
+        for i, L in enumerate(self.layers):
+            self.X[i] = cur
+            B.conv_forward(self.desc[i], cur, self.Wc[i], self.b[i], self.Y[i], self.ws_layer[i])
+            cur = self.Y[i]
+            if L.pool_after:
+                B.maxpool_forward(cur, 3, 2, self.ceil_mode, self.P[i], self.A[i])
+                cur = self.P[i]
+        return cur
+
+    def backward(self, dOut: torch.Tensor) -> Optional[torch.Tensor]:
+        g = dOut
+        for i in reversed(range(len(self.layers))):
+            L, Y = self.layers[i], self.Y[i]
+            if L.pool_after:
+                B.maxpool_backward(g, self.A[i], Y.shape[-2], Y.shape[-1], 3, 2, self.ceil_mode, self.dYc[i])
+                B.relu_backward(Y, self.dYc[i], self.dYc[i])
+            else:
+                B.relu_backward(Y, g, self.dYc[i])
+            B.conv_backward_weights(self.desc_cached[i], self.X[i], self.dYc[i], self.dW[i], self.db[i],
+                                    self.ws_layer[i])
+            if self.dXl[i] is None:
+                return None
+            B.conv_backward_data(self.desc[i], self.dYc[i], self.Wc[i], self.dXl[i], self.ws_bwd)
+            g = self.dXl[i]
+        return g
+
+    def sgd_step(self, lr: float, momentum: float, weight_decay: float = 0.0) -> None:
+        shadow = None
+        if self.dtype == B.BF16:
+            shadow = list(self.Wc) + [None] * len(self.b)
+        B.sgd_momentum_step(self.W + self.b, self.VW + self.Vb, self.dW + self.db, lr, momentum,
+                            weight_decay, shadow)
+
+    def step(self, X: torch.Tensor, dOut: torch.Tensor, lr: float, momentum: float,
+             weight_decay: float = 0.0) -> torch.Tensor:
+        out = self.forward(X)
+        self.backward(dOut)
+        self.sgd_step(lr, momentum, weight_decay)
+        return out

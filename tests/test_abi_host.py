@@ -1,0 +1,120 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, answers the shape/workspace queries, and turns bad arguments into error codes
+before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "omniconv.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1606_04487_amd import binding
+    return binding
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(omni_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(B):
+    names = declared_symbols()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(B.raw(), n), n
+    assert sorted(B.SYMBOLS) == names
+    assert B.version() == "0.1"
+
+
+def test_output_dims_and_ld(B):
+    d = B.conv_desc(256, 3, 227, 227, 96, 11, 11, 4, 0)
+    assert B.conv_output_dims(d) == (55, 55)
+    assert B.conv_dhat_ld(d) == 256 * 55 * 55
+    d = B.conv_desc(3, 5, 13, 13, 7, 3, 3, 1, 1)
+    assert B.conv_output_dims(d) == (13, 13)
+    assert B.conv_dhat_ld(d) == 512                      # 507 rounded up to a multiple of 8
+    d = B.conv_desc(1, 1, 7, 9, 1, 3, 2, (2, 1), (0, 2))
+    assert B.conv_output_dims(d) == (3, 12)
+    assert [B.pool_output_dim(n, 3, 2, True) for n in (32, 16, 8, 55, 27, 13)] == [16, 8, 4, 27, 13, 6]
+    assert [B.pool_output_dim(n, 3, 2, False) for n in (32, 15, 7)] == [15, 7, 3]
+    with pytest.raises(B.OmniError):
+        B.pool_output_dim(2, 3, 2, True)
+
+
+def test_workspace_sizes_grow_linearly_with_the_batch(B):
+    # Sec. III-B / Fig. "parallel"(c): the footprint of the lowered data is proportional to the
+    # number of images lowered at once.
+    sizes = []
+    for n in (8, 16, 32, 64):
+        d = B.conv_desc(n, 96, 27, 27, 256, 5, 5, 1, 2, B.BF16)
+        sizes.append(B.conv_workspace_bytes(d, B.PASS_FORWARD))
+        assert sizes[-1] >= 96 * 25 * n * 27 * 27 * 2
+    khat = 256 * 2400 * 2
+    assert abs((sizes[3] - khat) / (sizes[0] - khat) - 8.0) < 0.01
+    d32 = B.conv_desc(8, 96, 27, 27, 256, 5, 5, 1, 2, B.F32)
+    assert B.conv_workspace_bytes(d32, B.PASS_FORWARD) > 1.9 * sizes[0]
+    for p in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
+        assert B.conv_workspace_bytes(d32, p) % 256 == 0
+    with pytest.raises(B.OmniError):
+        B.conv_workspace_bytes(d32, 7)
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("N", 0, -1), ("C", -1, -1), ("F", 0, -1), ("kh", 0, -1), ("stride_h", 0, -1), ("pad_w", -1, -1),
+    ("kh", 40, -1),                       # window larger than the padded image
+    ("dtype", 2, -2), ("flags", 8, -2), ("F", 70000, -2),
+])
+def test_bad_descriptors(B, field, value, status):
+    d = B.conv_desc(2, 3, 32, 32, 8, 5, 5, 1, 2)
+    setattr(d, field, value)
+    ho, wo = ctypes.c_int32(), ctypes.c_int32()
+    assert B.raw().omni_conv_output_dims(ctypes.byref(d), ctypes.byref(ho), ctypes.byref(wo)) == status
+    # the compute entry points reject the descriptor before looking at any pointer
+    assert B.raw().omni_conv_forward(ctypes.byref(d), 16, 16, None, 16, 16, 1 << 40, None) == status
+    assert B.raw().omni_conv_backward_data(ctypes.byref(d), 16, 16, 16, 16, 1 << 40, None) == status
+    assert B.raw().omni_conv_backward_weights(ctypes.byref(d), 16, 16, 16, None, 16, 1 << 40, None) == status
+
+
+def test_null_misaligned_and_small_workspace_are_reported_without_a_launch(B):
+    lib = B.raw()
+    d = B.conv_desc(2, 3, 32, 32, 8, 5, 5, 1, 2)
+    need = B.conv_workspace_bytes(d, B.PASS_FORWARD)
+    assert lib.omni_conv_forward(None, 16, 16, None, 16, 16, need, None) == -1
+    assert lib.omni_conv_forward(ctypes.byref(d), None, 16, None, 16, 16, need, None) == -1
+    assert lib.omni_conv_forward(ctypes.byref(d), 16, 16, None, 16, None, need, None) == -1
+    assert lib.omni_conv_forward(ctypes.byref(d), 20, 16, None, 16, 16, need, None) == -4
+    assert lib.omni_conv_forward(ctypes.byref(d), 16, 16, 8, 16, 16, need, None) == -4
+    assert lib.omni_conv_forward(ctypes.byref(d), 16, 16, None, 16, 16, need - 1, None) == -3
+    assert lib.omni_conv_backward_data(ctypes.byref(d), 16, 16, 16, 16, 0, None) == -3
+    assert lib.omni_conv_backward_weights(ctypes.byref(d), None, 16, 16, None, 16, 1 << 40, None) == -1
+    assert lib.omni_lower(ctypes.byref(d), 16, 16, 10, None) == -1           # ld below N*Ho*Wo
+    assert lib.omni_col2im(ctypes.byref(d), 16, 10, 16, None) == -1
+    assert lib.omni_sgd_momentum_step(-1, None, None, None, None, None, 0.1, 0.9, 0.0, None) == -1
+    assert lib.omni_sgd_momentum_step(0, None, None, None, None, None, 0.1, 0.9, 0.0, None) == 0
+    assert lib.omni_sgd_momentum_step(1, None, None, None, None, None, 0.1, 0.9, 0.0, None) == -1
+    assert lib.omni_relu_forward(5, 10, 16, 16, None) == -2
+    assert lib.omni_relu_forward(0, -1, 16, 16, None) == -1
+    assert lib.omni_relu_forward(0, 0, None, None, None) == 0
+    assert lib.omni_maxpool_forward(0, 4, 8, 8, 16, 2, 1, 16, 16, None, None) == -1   # window larger than plane
+    assert lib.omni_maxpool_forward(0, 4, 32, 32, 16, 2, 1, 16, 16, None, None) == -2  # k > 15
+    assert lib.omni_maxpool_backward(0, 4, 8, 8, 3, 2, 1, 16, None, 16, None) == -1
+    assert B.status_string(-3) == "workspace too small" and B.status_string(0) == "ok"
+
+
+def test_product_path_has_no_cpu_fallback():
+    # The binding must fail loudly when the library is absent, and must not import the oracle.
+    src = open(os.path.join(ROOT, "paper_1606_04487_amd", "binding.py")).read()
+    assert "raise ImportError" in src
+    for name in ("binding.py", "stack.py", "workloads.py", "__init__.py", "build.py"):
+        text = open(os.path.join(ROOT, "paper_1606_04487_amd", name)).read()
+        assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), name
+    for name in os.listdir(os.path.join(ROOT, "oracle")):
+        if name.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", name)).read()
+            assert "paper_1606_04487_amd" not in text and "omniconv" not in text, name

@@ -1,0 +1,129 @@
+#!/usr/bin/env python3
+"""Throughput of the CaffeNet-shaped convolution stack on one MI355X.
+
+One step = conv1..conv5 (ReLU fused, 3x3/2 max-pools after conv1, conv2, conv5) forward, backward
+(data and model gradients; conv1's data gradient skipped as in the paper's FLOP rule, App. B) and
+one momentum-SGD update, at batch 256 in bf16 storage with fp32 accumulation, on seeded synthetic
+tensors already resident in HBM.  Prints ONE JSON line with images/s, the roofline of the dominant
+kernel (timed with HIP events on the launch stream inside the timed region) and the CPU oracle's
+rate on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(sample_images: int):
+    """The oracle, as it stands, on `sample_images` images of the same five layers (all three passes)."""
+    import oracle
+    from paper_1606_04487_amd import workloads as wl
+    layers = wl.caffenet_stack(sample_images)
+    tensors = [(L, wl.layer_tensors(L, seed=1, bf16=True)) for L in layers]
+    t0 = time.perf_counter()
+    for i, (L, t) in enumerate(tensors):
+        s = oracle.shape(L.N, L.C, L.H, L.W, L.F, L.k, L.k, L.s, L.p)
+        oracle.conv_forward(s, t["X"], t["W"], t["bias"])
+        oracle.conv_backward_weights(s, t["X"], t["dY"])
+        oracle.bias_grad(s, t["dY"])
+        if i > 0:
+            oracle.conv_backward_data(s, t["dY"], t["W"])
+    dt = time.perf_counter() - t0
+    return {"value": sample_images / dt, "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{sample_images} images through conv1-conv5 forward, model gradient and data gradient "
+                      f"(conv1's data gradient skipped), direct loops in fp64, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16")
+    ap.add_argument("--cpu-sample", type=int, default=8, help="images timed through the CPU oracle (0 = skip)")
+    ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+              "(no collectives or sharding are part of it).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1606_04487_amd import binding as B
+    from paper_1606_04487_amd import workloads as wl
+    from paper_1606_04487_amd.stack import ConvStack
+
+    torch.cuda.set_device(0)
+    dtype = B.BF16 if args.dtype == "bf16" else B.F32
+    layers = wl.caffenet_stack(args.batch)
+    stack = ConvStack(layers, dtype=dtype, ceil_mode=False, skip_first_dgrad=True)
+    data = wl.stack_tensors(layers, seed=1, bf16=(dtype == B.BF16), pooled_out=stack.output_shape()[-2:])
+    stack.set_parameters(data["W"], data["bias"])
+    X = torch.from_numpy(data["X"]).cuda().to(B.torch_dtype(dtype))
+    dOut = torch.from_numpy(data["dY"]).cuda().to(B.torch_dtype(dtype))
+    lr, mu = 0.01, 0.9
+
+    for _ in range(args.warmup):
+        stack.step(X, dOut, lr, mu)
+    torch.cuda.synchronize()
+    B.profile_enable(not args.no_events)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        stack.step(X, dOut, lr, mu)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernels = B.profile_summary() if not args.no_events else {}
+    B.profile_enable(False)
+
+    ms_per_step = 1e3 * dt / args.steps
+    images_per_s = args.batch * args.steps / dt
+    flops_step = sum(3 * L.gemm_flops for L in layers) - layers[0].gemm_flops   # App. B rule: 1.6 TFLOP at 256
+    roof = None
+    table = {}
+    for name, k in kernels.items():
+        avg_ms = k["total_ms"] / k["launches"]
+        row = {"launches_per_step": k["launches"] / args.steps, "avg_ms": avg_ms,
+               "ms_per_step": k["total_ms"] / args.steps}
+        if k["flops"] > 0 and name.startswith("gemm"):
+            row["tflops"] = k["flops"] / (k["total_ms"] * 1e-3) / 1e12
+        row["gbs"] = k["bytes"] / (k["total_ms"] * 1e-3) / 1e9
+        table[name] = row
+    if table:
+        dom = max(table, key=lambda n: table[n]["ms_per_step"])
+        k = kernels[dom]
+        if dom.startswith("gemm"):
+            ach = table[dom]["tflops"]
+            roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_TFLOPS[args.dtype],
+                    "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS[args.dtype], "traffic": None,
+                    "avg_launch_ms": table[dom]["avg_ms"], "flops_per_launch": k["flops"] / k["launches"]}
+        else:
+            ach = table[dom]["gbs"]
+            roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_launch_ms": table[dom]["avg_ms"],
+                    "bytes_per_launch": k["bytes"] / k["launches"]}
+
+    cpu = cpu_baseline(args.cpu_sample) if args.cpu_sample > 0 else None
+    out = {
+        "metric": "conv fwd+bwd images/sec, CaffeNet-shaped conv stack, batch 256",
+        "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"caffenet_conv1-5_relu_pool_fwd+bwd+sgd_b{args.batch}_{args.dtype}",
+                   "global_batch": args.batch, "conv1_data_gradient": False},
+        "tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
+        "mfma_frac_of_peak_whole_step": flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype],
+        "roofline": roof, "cpu_baseline": cpu, "kernels": table,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

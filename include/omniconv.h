@@ -160,6 +160,23 @@ int omni_maxpool_backward(int32_t dtype, int64_t planes, int32_t H, int32_t W, i
                           int32_t stride, int32_t ceil_mode, const void *dy, const uint8_t *argmax,
                           void *dx, void *hip_stream);
 
+/*
+ * Per-kernel timing (the paper times with a wall clock, App. C "Experiment Setup"; on a GPU the
+ * equivalent is an event pair on the stream).  omni_profile_enable(1) clears earlier records and
+ * makes every later launch of the library record a start and a stop event on its stream, tagged
+ * with a kernel class and that launch's algorithmic work; omni_profile_enable(0) stops recording
+ * and clears.  omni_profile_summary waits for the recorded events of one kernel class and returns
+ * the number of launches, their summed duration in milliseconds, and their summed algorithmic
+ * flops (GEMMs: 2*M*K*F) and bytes (data-movement kernels: each operand read or written once).
+ * Kernel classes are numbered 0 .. omni_profile_kernel_count()-1 and named by
+ * omni_profile_kernel_name.  Host memory only; not thread-safe against concurrent launches.
+ */
+int omni_profile_enable(int on);
+int omni_profile_kernel_count(void);
+const char *omni_profile_kernel_name(int kernel_id);
+int omni_profile_summary(int kernel_id, int64_t *launches, double *total_ms, double *flops,
+                         double *bytes);
+
 /* Host only.  Static string for a status code. */
 const char *omni_status_string(int status);
 

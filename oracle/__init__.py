@@ -73,6 +73,10 @@ def _ptr(a):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
+def num_threads() -> int:
+    return int(_load().oc_num_threads())
+
+
 def out_dims(s: Shape):
     ho, wo = ctypes.c_int32(), ctypes.c_int32()
     if _load().oc_out_dims(ctypes.byref(s), ctypes.byref(ho), ctypes.byref(wo)) != 0:

@@ -34,12 +34,25 @@
 #include <stddef.h>
 #include <string.h>
 #include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 typedef struct {
     int32_t N, C, H, W;      /* input batch, channels, height, width */
     int32_t F, kh, kw;       /* filters, window */
     int32_t sh, sw, ph, pw;  /* stride, zero padding */
 } oc_shape;
+
+/* Threads the parallel loops below will use. */
+int oc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* Output extent: number of window positions that fit entirely inside the padded input. */
 int oc_out_dims(const oc_shape *s, int32_t *Ho, int32_t *Wo)

@@ -31,6 +31,7 @@ SYMBOLS = [
     "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
     "omni_maxpool_forward", "omni_maxpool_backward", "omni_status_string", "omni_version",
+    "omni_profile_enable", "omni_profile_kernel_count", "omni_profile_kernel_name", "omni_profile_summary",
 ]
 
 
@@ -72,6 +73,13 @@ _lib.omni_relu_backward.argtypes = [_i32, _i64, _vp, _vp, _vp, _vp]
 _lib.omni_pool_output_dim.argtypes = [_i32, _i32, _i32, _i32]
 _lib.omni_maxpool_forward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.omni_maxpool_backward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
+
+
+_lib.omni_profile_enable.argtypes = [ctypes.c_int]
+_lib.omni_profile_kernel_name.restype = ctypes.c_char_p
+_lib.omni_profile_kernel_name.argtypes = [ctypes.c_int]
+_lib.omni_profile_summary.argtypes = [ctypes.c_int, ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
 
 
 def raw():
@@ -263,3 +271,20 @@ def maxpool_backward(dy, argmax, H: int, W: int, k: int = 3, stride: int = 2, ce
     _check(_lib.omni_maxpool_backward(dtype_code(dy.dtype), planes, H, W, k, stride, int(ceil_mode), _p(dy),
                                       _p(argmax), _p(dx), _stream()))
     return dx
+
+
+def profile_enable(on: bool) -> None:
+    """omni_profile_enable: start (and clear) or stop per-kernel event timing."""
+    _check(_lib.omni_profile_enable(int(bool(on))))
+
+
+def profile_summary() -> dict:
+    """omni_profile_summary for every kernel class: name -> launches, total_ms, flops, bytes."""
+    out = {}
+    for kid in range(_lib.omni_profile_kernel_count()):
+        n, ms, fl, by = _i64(), ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+        _check(_lib.omni_profile_summary(kid, ctypes.byref(n), ctypes.byref(ms), ctypes.byref(fl), ctypes.byref(by)))
+        if n.value:
+            out[_lib.omni_profile_kernel_name(kid).decode()] = {
+                "launches": n.value, "total_ms": ms.value, "flops": fl.value, "bytes": by.value}
+    return out

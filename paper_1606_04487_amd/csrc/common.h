@@ -92,6 +92,25 @@ inline size_t elem_size(int dtype) { return dtype == OMNI_BF16 ? 2 : 4; }
         if (hipGetLastError() != hipSuccess) return OMNI_HIP_ERROR; \
     } while (0)
 
+// ---------------------------------------------------------------- optional event timing (profile.hip)
+enum KernelId {
+    KID_LOWER = 0, KID_PACK_KHAT, KID_PACK_DYHAT, KID_BIAS_REDUCE, KID_GEMM_FWD, KID_GEMM_DGRAD, KID_GEMM_WGRAD,
+    KID_REDUCE_PARTIALS, KID_COL2IM, KID_SGD, KID_RELU, KID_POOL_FWD, KID_POOL_BWD, KID_COUNT
+};
+// Brackets the launches made during its lifetime with two events on `s` when profiling is on.
+// flops / bytes are the algorithmic work of the bracketed launch.
+class ProfScope {
+  public:
+    ProfScope(int kernel_id, hipStream_t s, double flops, double bytes);
+    ~ProfScope();
+    ProfScope(const ProfScope &) = delete;
+    ProfScope &operator=(const ProfScope &) = delete;
+
+  private:
+    long slot_;
+    hipStream_t stream_;
+};
+
 // ---------------------------------------------------------------- launchers (one per source file)
 // lowering.hip
 int launch_lower(const ConvGeom &g, int dtype, const void *X, void *Dhat, int64_t ld, hipStream_t s);

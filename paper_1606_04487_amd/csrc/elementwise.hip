@@ -106,6 +106,12 @@ int launch_sgd(int32_t n, float *const *W, float *const *V, const float *const *
             t.count[i] = 0;
             t.first_block[i + 1] = t.first_block[t.n];
         }
+        double params = 0, shadowed = 0;
+        for (int i = 0; i < t.n; ++i) {
+            params += (double)t.count[i];
+            if (t.S[i]) shadowed += (double)t.count[i];
+        }
+        ProfScope prof(KID_SGD, s, 4.0 * params, 20.0 * params + 2.0 * shadowed);
         hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)t.first_block[t.n]), dim3(256), 0, s, t, lr, mu, wd);
         OMNI_LAUNCH_CHECK();
     }
@@ -147,6 +153,7 @@ int launch_relu(int dtype, bool backward, int64_t count, const void *ref, const 
     if (count == 0) return OMNI_OK;
     int vec = dtype == OMNI_BF16 ? 8 : 4;
     dim3 grid((unsigned)((count + 256 * (int64_t)vec - 1) / (256 * (int64_t)vec)));
+    ProfScope prof(KID_RELU, s, 0.0, (backward ? 3.0 : 2.0) * count * elem_size(dtype));
     if (dtype == OMNI_BF16) {
         if (backward)
             hipLaunchKernelGGL((relu_kernel<bf16_t, true>), grid, dim3(256), 0, s, count, (const bf16_t *)ref, (const bf16_t *)dy, (bf16_t *)out);
@@ -260,6 +267,7 @@ int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
     PoolGeom g = make_pool_geom(H, W, k, stride, ceil_mode);
     int64_t per = (int64_t)g.Ho * g.Wo;
     int64_t planes_per_launch = (0x7fffffffll - 4096) / per;
+    ProfScope prof(KID_POOL_FWD, s, 0.0, (double)planes * ((double)H * W + per) * elem_size(dtype) + (argmax ? (double)planes * per : 0.0));
     for (int64_t p0 = 0; p0 < planes; p0 += planes_per_launch) {
         int64_t np = planes - p0 < planes_per_launch ? planes - p0 : planes_per_launch;
         uint32_t count = (uint32_t)(np * per);
@@ -279,6 +287,7 @@ int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
     PoolGeom g = make_pool_geom(H, W, k, stride, ceil_mode);
     int64_t per = (int64_t)H * W;
     int64_t planes_per_launch = (0x7fffffffll - 4096) / per;
+    ProfScope prof(KID_POOL_BWD, s, 0.0, (double)planes * (per + (double)g.Ho * g.Wo) * elem_size(dtype) + (double)planes * g.Ho * g.Wo);
     for (int64_t p0 = 0; p0 < planes; p0 += planes_per_launch) {
         int64_t np = planes - p0 < planes_per_launch ? planes - p0 : planes_per_launch;
         uint32_t count = (uint32_t)(np * per);

@@ -367,6 +367,8 @@ static int run_forward(const ConvGeom &g, const GemmFwdArgs &a, hipStream_t s)
     GemmShape sh = make_shape(g.F, (int)a.ldd, g.K, round_up(g.K, BK));
     FwdEpilogue<T> epi{(T *)a.Y, a.bias, g.F, g.M, g.HoWo, g.div_HoWo, a.relu};
     dim3 grid(sh.per_xcd * 8, 1, 1);
+    ProfScope prof(KID_GEMM_FWD, s, 2.0 * g.M * (double)g.K * g.F,
+                   ((double)g.F * g.K + (double)g.K * g.M + (double)g.F * g.M) * sizeof(T));
     hipLaunchKernelGGL((gemm_kernel<T, true, FwdEpilogue<T>>), grid, dim3(NTHREADS), 0, s, (const T *)a.Khat,
                        a.ldk, (const T *)a.Dhat, a.ldd, sh, epi);
     OMNI_LAUNCH_CHECK();
@@ -385,6 +387,8 @@ static int run_dgrad(const ConvGeom &g, const GemmDgradArgs &a, hipStream_t s)
     GemmShape sh = make_shape(g.K, (int)a.ldd, g.F, round_up(g.F, BK));
     RowMajorEpilogue<T> epi{(T *)a.dDhat, a.ldd, g.K, (int)a.ldd};
     dim3 grid(sh.per_xcd * 8, 1, 1);
+    ProfScope prof(KID_GEMM_DGRAD, s, 2.0 * g.M * (double)g.K * g.F,
+                   ((double)g.F * g.K + (double)g.K * g.M + (double)g.F * g.M) * sizeof(T));
     hipLaunchKernelGGL((gemm_kernel<T, true, RowMajorEpilogue<T>>), grid, dim3(NTHREADS), 0, s,
                        (const T *)a.KhatT, a.ldk, (const T *)a.dYhat, a.ldd, sh, epi);
     OMNI_LAUNCH_CHECK();
@@ -403,11 +407,16 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
     float *target = a.splits == 1 ? a.dW : a.partials;
     PartialEpilogue epi{target, g.F, g.K};
     dim3 grid(sh.per_xcd * 8, a.splits, 1);
-    hipLaunchKernelGGL((gemm_kernel<T, false, PartialEpilogue>), grid, dim3(NTHREADS), 0, s, (const T *)a.dYhat,
-                       a.ldd, (const T *)a.Dhat, a.ldd, sh, epi);
+    {
+        ProfScope prof(KID_GEMM_WGRAD, s, 2.0 * g.M * (double)g.K * g.F,
+                       ((double)g.K * g.M + (double)g.F * g.M) * sizeof(T) + 4.0 * g.F * g.K * a.splits);
+        hipLaunchKernelGGL((gemm_kernel<T, false, PartialEpilogue>), grid, dim3(NTHREADS), 0, s, (const T *)a.dYhat,
+                           a.ldd, (const T *)a.Dhat, a.ldd, sh, epi);
+    }
     OMNI_LAUNCH_CHECK();
     if (a.splits > 1) {
         int64_t count = (int64_t)g.F * g.K;
+        ProfScope prof(KID_REDUCE_PARTIALS, s, 0.0, 4.0 * count * (a.splits + 1));
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s,
                            a.partials, a.splits, count, a.dW);
         OMNI_LAUNCH_CHECK();

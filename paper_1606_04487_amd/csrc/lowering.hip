@@ -61,6 +61,7 @@ static int run_lower(const ConvGeom &g, const U *X, U *D, int64_t ld, hipStream_
 {
     constexpr int VEC = 16 / sizeof(U);
     unsigned gy = (unsigned)(g.K < 65535 ? g.K : 65535);
+    ProfScope prof(KID_LOWER, s, 0.0, ((double)g.N * g.C * g.H * g.W + (double)g.K * g.M) * sizeof(U));
     if (ld % VEC == 0) {
         int64_t vpr = ld / VEC;
         dim3 grid((unsigned)((vpr + 255) / 256), gy, 1);
@@ -119,6 +120,7 @@ int launch_col2im(const ConvGeom &g, int dtype, const void *dDhat, int64_t ld, v
 {
     int64_t planes = (int64_t)g.N * g.C, hw = (int64_t)g.H * g.W;
     int64_t planes_per_launch = (0x7fffffffll - 4096) / hw;
+    ProfScope prof(KID_COL2IM, s, 0.0, ((double)planes * hw + (double)g.K * g.M) * elem_size(dtype));
     for (int64_t p0 = 0; p0 < planes; p0 += planes_per_launch) {
         int64_t np = planes - p0 < planes_per_launch ? planes - p0 : planes_per_launch;
         uint32_t count = (uint32_t)(np * hw);
@@ -151,6 +153,7 @@ static int run_pack_khat(int dtype, const void *W, void *out, int F, int K, int6
                          int transpose, hipStream_t s)
 {
     dim3 grid((unsigned)((rows * cols + 255) / 256));
+    ProfScope prof(KID_PACK_KHAT, s, 0.0, 2.0 * F * K * elem_size(dtype));
     if (dtype == OMNI_BF16)
         hipLaunchKernelGGL(pack_khat_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t *)W, (uint16_t *)out, F, K, rows, cols, transpose);
     else
@@ -247,12 +250,16 @@ int launch_pack_dyhat(const ConvGeom &g, int dtype, const void *dY, void *dYhat,
     int blocks = (int)((ld + PACK_COLS - 1) / PACK_COLS);
     if (bias_partials != nullptr && bias_blocks != blocks) return OMNI_INVALID_ARGUMENT;
     dim3 grid((unsigned)blocks, (unsigned)g.F, 1);
-    if (dtype == OMNI_BF16)
-        hipLaunchKernelGGL((pack_dyhat_kernel<bf16_t, uint16_t>), grid, dim3(256), 0, s, g, (const bf16_t *)dY, (uint16_t *)dYhat, ld, bias_partials);
-    else
-        hipLaunchKernelGGL((pack_dyhat_kernel<float, uint32_t>), grid, dim3(256), 0, s, g, (const float *)dY, (uint32_t *)dYhat, ld, bias_partials);
+    {
+        ProfScope prof(KID_PACK_DYHAT, s, 0.0, 2.0 * g.F * (double)g.M * elem_size(dtype));
+        if (dtype == OMNI_BF16)
+            hipLaunchKernelGGL((pack_dyhat_kernel<bf16_t, uint16_t>), grid, dim3(256), 0, s, g, (const bf16_t *)dY, (uint16_t *)dYhat, ld, bias_partials);
+        else
+            hipLaunchKernelGGL((pack_dyhat_kernel<float, uint32_t>), grid, dim3(256), 0, s, g, (const float *)dY, (uint32_t *)dYhat, ld, bias_partials);
+    }
     OMNI_LAUNCH_CHECK();
     if (bias_partials != nullptr) {
+        ProfScope prof(KID_BIAS_REDUCE, s, 0.0, 4.0 * g.F * (blocks + 1));
         hipLaunchKernelGGL(bias_reduce_kernel, dim3((unsigned)g.F), dim3(64), 0, s, bias_partials, blocks, dbias);
         OMNI_LAUNCH_CHECK();
     }

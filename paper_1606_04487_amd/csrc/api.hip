@@ -35,6 +35,8 @@ int make_geom(const omni_conv_desc *d, ConvGeom *g)
     g->div_khkw = FastDiv((uint32_t)(d->kh * d->kw));
     g->div_W = FastDiv((uint32_t)d->W);
     g->div_HW = FastDiv((uint32_t)(d->H * d->W));
+    g->div_sh = FastDiv((uint32_t)d->stride_h);
+    g->div_sw = FastDiv((uint32_t)d->stride_w);
     return OMNI_OK;
 }
 

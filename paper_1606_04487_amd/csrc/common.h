@@ -66,7 +66,7 @@ struct ConvGeom {
     int32_t K;     // C*kh*kw   rows of D-hat
     int32_t M;     // N*Ho*Wo   columns of D-hat
     int32_t HoWo;  // Ho*Wo
-    FastDiv div_Wo, div_HoWo, div_kw, div_khkw, div_W, div_HW;
+    FastDiv div_Wo, div_HoWo, div_kw, div_khkw, div_W, div_HW, div_sh, div_sw;
 };
 
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }

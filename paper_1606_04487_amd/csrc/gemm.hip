@@ -23,6 +23,8 @@
 // supplies reduction index 4*(2s+h)+e for both operands, which is a permutation of the slab's 8
 // indices -- a sum does not care about the order of its terms.  bf16 uses
 // v_mfma_f32_32x32x16_bf16, one instruction per pair of packs.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace omni {
@@ -30,11 +32,7 @@ namespace omni {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int BM = 128;        // rows of the result tile
-constexpr int BN = 128;        // columns of the result tile
-constexpr int NPACK = 8;       // 16-byte packs along the reduction per LDS tile
-constexpr int LDS_ROWS = 129;  // 128 rows + 1 pack of padding: spreads the 8 packs of a row over the banks
-constexpr int NTHREADS = 256;
+constexpr int NPACK = 8;  // 16-byte packs along the reduction per LDS tile (128 bytes of every row)
 
 template <typename T> struct Pack;
 template <> struct Pack<float> { static constexpr int KP = 4; };
@@ -44,13 +42,16 @@ int gemm_red_tile(int dtype) { return dtype == OMNI_BF16 ? NPACK * 8 : NPACK * 4
 
 // ------------------------------------------------------------------------------------------------
 // Operand loaders: global memory -> registers (issue()), registers -> LDS (commit()).
+// An LDS tile of R rows is uint4[NPACK][R + 1]: pack g of row r at g*(R+1) + r.  The extra pack of
+// padding per group spreads the 8 packs of one row over the banks when they are written together.
 // ------------------------------------------------------------------------------------------------
 
 // Operand stored [rows][ld] with the reduction index contiguous.  Element (r, k) is valid for
 // r < rows and k < red; ld and red are multiples of the pack size and the base is 16-byte aligned.
-template <typename T, int TILE_ROWS> struct RedContigLoader {
+template <typename T, int TILE_ROWS, int NT> struct RedContigLoader {
     static constexpr int KP = Pack<T>::KP;
-    static constexpr int PER_THREAD = TILE_ROWS * NPACK / NTHREADS;
+    static constexpr int PER_THREAD = TILE_ROWS * NPACK / NT;
+    static_assert(TILE_ROWS * NPACK % NT == 0, "tile must divide over the threads");
     uint4 regs[PER_THREAD];
 
     __device__ __forceinline__ void issue(const T *base, int64_t ld, int rows, int64_t red, int row0,
@@ -58,7 +59,7 @@ template <typename T, int TILE_ROWS> struct RedContigLoader {
     {
 #pragma unroll
         for (int q = 0; q < PER_THREAD; ++q) {
-            int t = tid + q * NTHREADS;
+            int t = tid + q * NT;
             int g = t % NPACK, r = t / NPACK;
             int64_t k = k0 + (int64_t)g * KP;
             uint4 v = make_uint4(0, 0, 0, 0);
@@ -71,71 +72,94 @@ template <typename T, int TILE_ROWS> struct RedContigLoader {
     {
 #pragma unroll
         for (int q = 0; q < PER_THREAD; ++q) {
-            int t = tid + q * NTHREADS;
+            int t = tid + q * NT;
             int g = t % NPACK, r = t / NPACK;
-            lds[g * LDS_ROWS + r] = regs[q];
+            lds[g * (TILE_ROWS + 1) + r] = regs[q];
         }
     }
 };
 
 // Operand stored [red][ld] with the result's column index j contiguous.  Element (k, j) is valid
 // for k < red and j < cols; ld and cols are multiples of 8 and the base is 16-byte aligned.
-template <typename T> struct OuterContigLoader;
+// One task = one pack group g (KP reduction rows) x 4 consecutive columns, transposed in registers.
+template <typename T, int TILE_COLS, int NT> struct OuterContigLoader;
 
-template <> struct OuterContigLoader<float> {
-    // one task per thread: pack g (4 reduction rows) x 4 consecutive columns
-    uint4 regs[4];
+template <int TILE_COLS, int NT> struct OuterContigLoader<float, TILE_COLS, NT> {
+    static constexpr int CHUNKS = TILE_COLS / 4;
+    static constexpr int PER_THREAD = NPACK * CHUNKS / NT;
+    static_assert(NPACK * CHUNKS % NT == 0, "tile must divide over the threads");
+    uint4 regs[PER_THREAD][4];
     __device__ __forceinline__ void issue(const float *base, int64_t ld, int64_t red, int cols,
                                           int64_t k0, int col0, int tid)
     {
-        int jc = tid % 32, g = tid / 32;
-        int j = col0 + jc * 4;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            int64_t k = k0 + g * 4 + e;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (k < red && j < cols) v = *reinterpret_cast<const uint4 *>(base + k * ld + j);
-            regs[e] = v;
+        for (int q = 0; q < PER_THREAD; ++q) {
+            int t = tid + q * NT;
+            int jc = t % CHUNKS, g = t / CHUNKS;
+            int j = col0 + jc * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                int64_t k = k0 + g * 4 + e;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (k < red && j < cols) v = *reinterpret_cast<const uint4 *>(base + k * ld + j);
+                regs[q][e] = v;
+            }
         }
     }
     __device__ __forceinline__ void commit(uint4 *lds, int tid) const
     {
-        int jc = tid % 32, g = tid / 32;
-        uint4 *dst = lds + g * LDS_ROWS + jc * 4;
-        dst[0] = make_uint4(regs[0].x, regs[1].x, regs[2].x, regs[3].x);
-        dst[1] = make_uint4(regs[0].y, regs[1].y, regs[2].y, regs[3].y);
-        dst[2] = make_uint4(regs[0].z, regs[1].z, regs[2].z, regs[3].z);
-        dst[3] = make_uint4(regs[0].w, regs[1].w, regs[2].w, regs[3].w);
+#pragma unroll
+        for (int q = 0; q < PER_THREAD; ++q) {
+            int t = tid + q * NT;
+            int jc = t % CHUNKS, g = t / CHUNKS;
+            uint4 *dst = lds + g * (TILE_COLS + 1) + jc * 4;
+            const uint4 *r = regs[q];
+            dst[0] = make_uint4(r[0].x, r[1].x, r[2].x, r[3].x);
+            dst[1] = make_uint4(r[0].y, r[1].y, r[2].y, r[3].y);
+            dst[2] = make_uint4(r[0].z, r[1].z, r[2].z, r[3].z);
+            dst[3] = make_uint4(r[0].w, r[1].w, r[2].w, r[3].w);
+        }
     }
 };
 
-template <> struct OuterContigLoader<bf16_t> {
-    // one task per thread: pack g (8 reduction rows) x 4 consecutive columns (8 bytes per row)
-    uint2 regs[8];
+template <int TILE_COLS, int NT> struct OuterContigLoader<bf16_t, TILE_COLS, NT> {
+    static constexpr int CHUNKS = TILE_COLS / 4;
+    static constexpr int PER_THREAD = NPACK * CHUNKS / NT;
+    static_assert(NPACK * CHUNKS % NT == 0, "tile must divide over the threads");
+    uint2 regs[PER_THREAD][8];
     __device__ __forceinline__ void issue(const bf16_t *base, int64_t ld, int64_t red, int cols,
                                           int64_t k0, int col0, int tid)
     {
-        int jc = tid % 32, g = tid / 32;
-        int j = col0 + jc * 4;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            int64_t k = k0 + g * 8 + e;
-            uint2 v = make_uint2(0, 0);
-            if (k < red && j < cols) v = *reinterpret_cast<const uint2 *>(base + k * ld + j);
-            regs[e] = v;
+        for (int q = 0; q < PER_THREAD; ++q) {
+            int t = tid + q * NT;
+            int jc = t % CHUNKS, g = t / CHUNKS;
+            int j = col0 + jc * 4;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int64_t k = k0 + g * 8 + e;
+                uint2 v = make_uint2(0, 0);
+                if (k < red && j < cols) v = *reinterpret_cast<const uint2 *>(base + k * ld + j);
+                regs[q][e] = v;
+            }
         }
     }
     static __device__ __forceinline__ uint32_t lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
     static __device__ __forceinline__ uint32_t hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
     __device__ __forceinline__ void commit(uint4 *lds, int tid) const
     {
-        int jc = tid % 32, g = tid / 32;
-        uint4 *dst = lds + g * LDS_ROWS + jc * 4;
-        // column j = 2d + h of the 8 x 4 block becomes one pack: 8 reduction indices of column j
-        dst[0] = make_uint4(lo(regs[0].x, regs[1].x), lo(regs[2].x, regs[3].x), lo(regs[4].x, regs[5].x), lo(regs[6].x, regs[7].x));
-        dst[1] = make_uint4(hi(regs[0].x, regs[1].x), hi(regs[2].x, regs[3].x), hi(regs[4].x, regs[5].x), hi(regs[6].x, regs[7].x));
-        dst[2] = make_uint4(lo(regs[0].y, regs[1].y), lo(regs[2].y, regs[3].y), lo(regs[4].y, regs[5].y), lo(regs[6].y, regs[7].y));
-        dst[3] = make_uint4(hi(regs[0].y, regs[1].y), hi(regs[2].y, regs[3].y), hi(regs[4].y, regs[5].y), hi(regs[6].y, regs[7].y));
+#pragma unroll
+        for (int q = 0; q < PER_THREAD; ++q) {
+            int t = tid + q * NT;
+            int jc = t % CHUNKS, g = t / CHUNKS;
+            uint4 *dst = lds + g * (TILE_COLS + 1) + jc * 4;
+            const uint2 *r = regs[q];
+            // column j = 2d + h of the 8 x 4 block becomes one pack: 8 reduction indices of column j
+            dst[0] = make_uint4(lo(r[0].x, r[1].x), lo(r[2].x, r[3].x), lo(r[4].x, r[5].x), lo(r[6].x, r[7].x));
+            dst[1] = make_uint4(hi(r[0].x, r[1].x), hi(r[2].x, r[3].x), hi(r[4].x, r[5].x), hi(r[6].x, r[7].x));
+            dst[2] = make_uint4(lo(r[0].y, r[1].y), lo(r[2].y, r[3].y), lo(r[4].y, r[5].y), lo(r[6].y, r[7].y));
+            dst[3] = make_uint4(hi(r[0].y, r[1].y), hi(r[2].y, r[3].y), hi(r[4].y, r[5].y), hi(r[6].y, r[7].y));
+        }
     }
 };
 
@@ -235,15 +259,26 @@ struct GemmShape {
     int per_xcd;      // ceil(n_blocks / 8)
 };
 
-template <typename T, bool COL_OUTER, typename Epi>
-__global__ __launch_bounds__(NTHREADS) void gemm_kernel(const T *__restrict__ A, int64_t lda,
-                                                        const T *__restrict__ B, int64_t ldb,
-                                                        GemmShape sh, Epi epi)
+// Tile configuration: BM x BN result tile, WM x WN wavefronts, PF reduction steps of global loads in
+// flight (register staging sets).
+template <int BM_, int BN_, int WM_, int WN_, int PF_> struct Tile {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, PF = PF_;
+    static constexpr int NT = 64 * WM * WN;
+    static constexpr int TI = BM / WM / 32, TJ = BN / WN / 32;  // 32 x 32 MFMA tiles per wavefront
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wavefront tiles are multiples of 32");
+};
+
+template <typename T, typename Cfg, bool COL_OUTER, typename Epi>
+__global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, int64_t lda,
+                                                       const T *__restrict__ B, int64_t ldb,
+                                                       GemmShape sh, Epi epi)
 {
     constexpr int KP = Pack<T>::KP;
     constexpr int BK = NPACK * KP;
-    __shared__ uint4 lds_a[2][NPACK * LDS_ROWS];
-    __shared__ uint4 lds_b[2][NPACK * LDS_ROWS];
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, TI = Cfg::TI, TJ = Cfg::TJ, PF = Cfg::PF;
+    constexpr int LA = BM + 1, LB = BN + 1;
+    __shared__ uint4 lds_a[2][NPACK * LA];
+    __shared__ uint4 lds_b[2][NPACK * LB];
 
     // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of tiles
     // (neighbouring tiles share operand panels, and each XCD has its own L2).
@@ -259,75 +294,86 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(const T *__restrict__ A,
 
     int tid = threadIdx.x;
     int lane = tid % 64, wave = tid / 64;
-    int wm = wave / 2, wn = wave % 2;
+    int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
     int li = lane % 32, h = lane / 32;
 
-    f32x16 acc[2][2];
+    f32x16 acc[TI][TJ];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < TI; ++t)
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < TJ; ++u)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
 
-    RedContigLoader<T, BM> la;
-    RedContigLoader<T, BN> lb_red;
-    OuterContigLoader<T> lb_out;
+    RedContigLoader<T, BM, NT> la[PF];
+    RedContigLoader<T, BN, NT> lb_red[PF];
+    OuterContigLoader<T, BN, NT> lb_out[PF];
 
-    auto issue = [&](int64_t k0) {
-        la.issue(A, lda, sh.rows, sh.red, row0, k0, tid);
+    auto issue = [&](int set, int64_t k0) {
+        la[set].issue(A, lda, sh.rows, sh.red, row0, k0, tid);
         if constexpr (COL_OUTER)
-            lb_out.issue(B, ldb, sh.red, sh.cols, k0, col0, tid);
+            lb_out[set].issue(B, ldb, sh.red, sh.cols, k0, col0, tid);
         else
-            lb_red.issue(B, ldb, sh.cols, sh.red, col0, k0, tid);
+            lb_red[set].issue(B, ldb, sh.cols, sh.red, col0, k0, tid);
     };
-    auto commit = [&](int buf) {
-        la.commit(lds_a[buf], tid);
+    auto commit = [&](int set, int buf) {
+        la[set].commit(lds_a[buf], tid);
         if constexpr (COL_OUTER)
-            lb_out.commit(lds_b[buf], tid);
+            lb_out[set].commit(lds_b[buf], tid);
         else
-            lb_red.commit(lds_b[buf], tid);
+            lb_red[set].commit(lds_b[buf], tid);
     };
-
-    if (steps > 0) {
-        issue(k_begin);
-        commit(0);
-    }
-    __syncthreads();
-
-    for (int s = 0; s < steps; ++s) {
-        int buf = s & 1;
-        bool more = s + 1 < steps;
-        if (more) issue(k_begin + (int64_t)(s + 1) * BK);
-
-        const uint4 *pa = lds_a[buf] + wm * 64 + li;
-        const uint4 *pb = lds_b[buf] + wn * 64 + li;
+    auto compute = [&](int buf) {
+        const uint4 *pa = lds_a[buf] + wm * (BM / Cfg::WM) + li;
+        const uint4 *pb = lds_b[buf] + wn * (BN / Cfg::WN) + li;
 #pragma unroll
         for (int slab = 0; slab < NPACK / 2; ++slab) {
             int g = slab * 2 + h;
-            uint4 a0 = pa[g * LDS_ROWS], a1 = pa[g * LDS_ROWS + 32];
-            uint4 b0 = pb[g * LDS_ROWS], b1 = pb[g * LDS_ROWS + 32];
-            Mma<T>::run(a0, b0, acc[0][0]);
-            Mma<T>::run(a0, b1, acc[0][1]);
-            Mma<T>::run(a1, b0, acc[1][0]);
-            Mma<T>::run(a1, b1, acc[1][1]);
+            uint4 a[TI], b[TJ];
+#pragma unroll
+            for (int t = 0; t < TI; ++t) a[t] = pa[g * LA + 32 * t];
+#pragma unroll
+            for (int u = 0; u < TJ; ++u) b[u] = pb[g * LB + 32 * u];
+#pragma unroll
+            for (int t = 0; t < TI; ++t)
+#pragma unroll
+                for (int u = 0; u < TJ; ++u) Mma<T>::run(a[t], b[u], acc[t][u]);
         }
+    };
 
-        if (more) commit(buf ^ 1);
-        __syncthreads();
+    // Step s computes tile s from LDS buffer s&1.  Global loads of tile s+PF are issued at the start
+    // of step s into register set s%PF; the set holding tile s+1 is written to the other LDS buffer at
+    // the end of step s.  The loop is unrolled by PF so that set indices are compile-time constants.
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+        if (p < steps) issue(p, k_begin + (int64_t)p * BK);
+    if (steps > 0) commit(0, 0);
+    __syncthreads();
+
+    for (int s0 = 0; s0 < steps; s0 += PF) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            int s = s0 + p;
+            if (s < steps) {
+                if (s + PF < steps) issue(p, k_begin + (int64_t)(s + PF) * BK);
+                compute(s & 1);
+                if (s + 1 < steps) commit((p + 1) % PF, (s + 1) & 1);
+                __syncthreads();
+            }
+        }
     }
 
     // Result layout of a 32 x 32 MFMA tile: lane holds column lane%32; register v holds row
     // 8*(v/4) + 4*(lane/32) + v%4.
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        int j = col0 + wn * 64 + u * 32 + li;
+    for (int u = 0; u < TJ; ++u) {
+        int j = col0 + wn * (BN / Cfg::WN) + u * 32 + li;
         typename Epi::Col col = epi.column(j);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < TI; ++t) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                int i = row0 + wm * 64 + t * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+                int i = row0 + wm * (BM / Cfg::WM) + t * 32 + 8 * (v / 4) + 4 * h + (v % 4);
                 epi.store(i, col, acc[t][u][v], epi.row_add(i), z);
             }
         }
@@ -345,18 +391,71 @@ __global__ void reduce_partials_kernel(const float *__restrict__ partials, int s
     out[i] = acc;
 }
 
-static GemmShape make_shape(int rows, int cols, int64_t red, int64_t chunk)
+static GemmShape make_shape(int rows, int cols, int64_t red, int64_t chunk, int bm, int bn)
 {
     GemmShape s;
     s.rows = rows;
     s.cols = cols;
     s.red = red;
     s.chunk = chunk;
-    s.tiles_i = (rows + BM - 1) / BM;
-    s.tiles_j = (cols + BN - 1) / BN;
+    s.tiles_i = (rows + bm - 1) / bm;
+    s.tiles_j = (cols + bn - 1) / bn;
     s.n_blocks = s.tiles_i * s.tiles_j;
     s.per_xcd = (s.n_blocks + 7) / 8;
     return s;
+}
+
+// Tile configurations compiled in.  Index = OMNI_GEMM_TILE environment override (for tuning runs) or
+// the choice of pick_tile().
+typedef Tile<128, 128, 2, 2, 1> Tile0;
+typedef Tile<128, 128, 2, 2, 2> Tile1;
+typedef Tile<256, 128, 2, 2, 1> Tile2;
+typedef Tile<256, 128, 2, 2, 2> Tile3;
+typedef Tile<128, 256, 2, 2, 1> Tile4;
+typedef Tile<256, 256, 2, 2, 1> Tile5;
+typedef Tile<256, 256, 4, 2, 1> Tile6;
+typedef Tile<256, 256, 2, 4, 1> Tile7;
+constexpr int N_TILES = 8;
+
+static int tile_override()
+{
+    const char *e = getenv("OMNI_GEMM_TILE");
+    int v = e ? atoi(e) : -1;
+    return (v >= 0 && v < N_TILES) ? v : -1;
+}
+
+static int pick_tile(int rows, int cols)
+{
+    int o = tile_override();
+    if (o >= 0) return o;
+    (void)rows;
+    (void)cols;
+    return 0;
+}
+
+template <typename T, typename Cfg, bool COL_OUTER, typename Epi>
+static void launch_cfg(const T *A, int64_t lda, const T *B, int64_t ldb, int rows, int cols, int64_t red,
+                       int64_t chunk, int splits, const Epi &epi, hipStream_t s)
+{
+    GemmShape sh = make_shape(rows, cols, red, chunk, Cfg::BM, Cfg::BN);
+    dim3 grid(sh.per_xcd * 8, splits, 1);
+    hipLaunchKernelGGL((gemm_kernel<T, Cfg, COL_OUTER, Epi>), grid, dim3(Cfg::NT), 0, s, A, lda, B, ldb, sh, epi);
+}
+
+template <typename T, bool COL_OUTER, typename Epi>
+static void launch_any(int tile, const T *A, int64_t lda, const T *B, int64_t ldb, int rows, int cols, int64_t red,
+                       int64_t chunk, int splits, const Epi &epi, hipStream_t s)
+{
+    switch (tile) {
+    case 1: launch_cfg<T, Tile1, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
+    case 2: launch_cfg<T, Tile2, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
+    case 3: launch_cfg<T, Tile3, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
+    case 4: launch_cfg<T, Tile4, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
+    case 5: launch_cfg<T, Tile5, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
+    case 6: launch_cfg<T, Tile6, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
+    case 7: launch_cfg<T, Tile7, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
+    default: launch_cfg<T, Tile0, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
+    }
 }
 
 template <typename T>
@@ -364,13 +463,11 @@ static int run_forward(const ConvGeom &g, const GemmFwdArgs &a, hipStream_t s)
 {
     constexpr int BK = NPACK * Pack<T>::KP;
     // K-hat is zero-padded along K to a multiple of the pack size; rows of D-hat beyond K read as zero.
-    GemmShape sh = make_shape(g.F, (int)a.ldd, g.K, round_up(g.K, BK));
     FwdEpilogue<T> epi{(T *)a.Y, a.bias, g.F, g.M, g.HoWo, g.div_HoWo, a.relu};
-    dim3 grid(sh.per_xcd * 8, 1, 1);
     ProfScope prof(KID_GEMM_FWD, s, 2.0 * g.M * (double)g.K * g.F,
                    ((double)g.F * g.K + (double)g.K * g.M + (double)g.F * g.M) * sizeof(T));
-    hipLaunchKernelGGL((gemm_kernel<T, true, FwdEpilogue<T>>), grid, dim3(NTHREADS), 0, s, (const T *)a.Khat,
-                       a.ldk, (const T *)a.Dhat, a.ldd, sh, epi);
+    launch_any<T, true, FwdEpilogue<T>>(pick_tile(g.F, (int)a.ldd), (const T *)a.Khat, a.ldk, (const T *)a.Dhat, a.ldd,
+                                        g.F, (int)a.ldd, g.K, round_up(g.K, BK), 1, epi, s);
     OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }
@@ -384,13 +481,11 @@ template <typename T>
 static int run_dgrad(const ConvGeom &g, const GemmDgradArgs &a, hipStream_t s)
 {
     constexpr int BK = NPACK * Pack<T>::KP;
-    GemmShape sh = make_shape(g.K, (int)a.ldd, g.F, round_up(g.F, BK));
     RowMajorEpilogue<T> epi{(T *)a.dDhat, a.ldd, g.K, (int)a.ldd};
-    dim3 grid(sh.per_xcd * 8, 1, 1);
     ProfScope prof(KID_GEMM_DGRAD, s, 2.0 * g.M * (double)g.K * g.F,
                    ((double)g.F * g.K + (double)g.K * g.M + (double)g.F * g.M) * sizeof(T));
-    hipLaunchKernelGGL((gemm_kernel<T, true, RowMajorEpilogue<T>>), grid, dim3(NTHREADS), 0, s,
-                       (const T *)a.KhatT, a.ldk, (const T *)a.dYhat, a.ldd, sh, epi);
+    launch_any<T, true, RowMajorEpilogue<T>>(pick_tile(g.K, (int)a.ldd), (const T *)a.KhatT, a.ldk, (const T *)a.dYhat,
+                                             a.ldd, g.K, (int)a.ldd, g.F, round_up(g.F, BK), 1, epi, s);
     OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }
@@ -403,15 +498,13 @@ int launch_gemm_dgrad(const ConvGeom &g, int dtype, const GemmDgradArgs &a, hipS
 template <typename T>
 static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
 {
-    GemmShape sh = make_shape(g.F, g.K, a.ldd, a.chunk);
     float *target = a.splits == 1 ? a.dW : a.partials;
     PartialEpilogue epi{target, g.F, g.K};
-    dim3 grid(sh.per_xcd * 8, a.splits, 1);
     {
         ProfScope prof(KID_GEMM_WGRAD, s, 2.0 * g.M * (double)g.K * g.F,
                        ((double)g.K * g.M + (double)g.F * g.M) * sizeof(T) + 4.0 * g.F * g.K * a.splits);
-        hipLaunchKernelGGL((gemm_kernel<T, false, PartialEpilogue>), grid, dim3(NTHREADS), 0, s, (const T *)a.dYhat,
-                           a.ldd, (const T *)a.Dhat, a.ldd, sh, epi);
+        launch_any<T, false, PartialEpilogue>(pick_tile(g.F, g.K), (const T *)a.dYhat, a.ldd, (const T *)a.Dhat, a.ldd,
+                                              g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
     }
     OMNI_LAUNCH_CHECK();
     if (a.splits > 1) {

@@ -56,12 +56,202 @@ __global__ __launch_bounds__(256) void lower_kernel(ConvGeom g, const U *__restr
     }
 }
 
+// LDS-staged variant.  A workgroup takes one input channel c of a group of images (small planes) or
+// of a band of output rows of one image (large planes), copies the zero-padded patch it needs into
+// LDS once with coalesced reads, and then writes all kh*kw rows of D-hat that stem from that patch:
+// for each row the columns of the group are one contiguous range, written 16 bytes per lane.  Columns
+// at the ragged ends of the range (ranges need not start on a 16-byte boundary) are stored one by one.
+// X is read from HBM once; every store instruction of a wavefront covers 1 KiB of consecutive bytes.
+struct LowerPlan {
+    int nb;        // images per workgroup (1 in banded mode)
+    int br;        // output rows per band (Ho when nb > 1)
+    int bands;     // bands per image
+    int groups;    // image groups
+    int rows_in;   // input rows held per image: (br-1)*sh + kh
+    int wp;        // padded row pitch: W + 2*pw
+    FastDiv div_wp, div_rows_in;
+};
+
+template <typename U, int VEC, int KW>  // KW > 0: window width known at compile time (inner loop unrolled)
+__global__ __launch_bounds__(256) void lower_lds_kernel(ConvGeom g, LowerPlan p, const U *__restrict__ X,
+                                                        U *__restrict__ D, int64_t ld)
+{
+    extern __shared__ __align__(16) unsigned char lower_smem[];
+    U *tile = reinterpret_cast<U *>(lower_smem);
+    const int tid = threadIdx.x;
+    const int c = blockIdx.y;
+    const int band = blockIdx.x % p.bands, grp = blockIdx.x / p.bands;
+    const int n0 = grp * p.nb;
+    const int nb = g.N - n0 < p.nb ? g.N - n0 : p.nb;
+    const int oy0 = band * p.br;
+    const int br = g.Ho - oy0 < p.br ? g.Ho - oy0 : p.br;
+    const int rows_used = (br - 1) * g.sh + g.kh;
+    const int kw = KW > 0 ? KW : g.kw;
+    constexpr int VECL = 16 / sizeof(U);  // elements per 16-byte global load
+
+    // patch -> LDS.  The padding is zeroed first; then the pixels, which for one image are one
+    // contiguous run of whole input rows, are fetched 16 bytes per lane (the run need not be 16-byte
+    // aligned) and dropped into the padded layout one element at a time.
+    {
+        const int patch16 = (nb * p.rows_in * p.wp * (int)sizeof(U) + 15) / 16;
+        uint4 *t16 = reinterpret_cast<uint4 *>(lower_smem);
+        for (int i = tid; i < patch16; i += 256) t16[i] = make_uint4(0, 0, 0, 0);
+    }
+    __syncthreads();
+    {
+        int iy_lo = oy0 * g.sh - g.ph, iy_hi = iy_lo + rows_used;  // input rows the patch covers
+        const int ry0 = iy_lo < 0 ? -iy_lo : 0;                     // first patch row that lies in the image
+        if (iy_lo < 0) iy_lo = 0;
+        if (iy_hi > g.H) iy_hi = g.H;
+        const int run = (iy_hi - iy_lo) * g.W;                      // elements per image
+        const int chunks = (run + VECL - 1) / VECL;
+        for (int t = tid; t < nb * chunks; t += 256) {
+            int inb = t / chunks, ch = t - inb * chunks;
+            const U *src = X + (((int64_t)(n0 + inb) * g.C + c) * g.H + iy_lo) * g.W + ch * VECL;
+            U vals[VECL];
+            if ((ch + 1) * VECL <= run) {
+                __builtin_memcpy(vals, src, sizeof(vals));
+            } else {
+#pragma unroll
+                for (int e = 0; e < VECL; ++e) vals[e] = ch * VECL + e < run ? src[e] : (U)0;
+            }
+            uint32_t ry, ix;
+            g.div_W.divmod((uint32_t)(ch * VECL), ry, ix);
+            U *drow = tile + (inb * p.rows_in + ry0 + (int)ry) * p.wp + g.pw;
+#pragma unroll
+            for (int e = 0; e < VECL; ++e) {
+                if (ch * VECL + e < run) drow[ix] = vals[e];
+                if (++ix == (uint32_t)g.W) {
+                    ix = 0;
+                    drow += p.wp;
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // the contiguous column range of this workgroup
+    const int seg = p.nb > 1 ? g.HoWo : br * g.Wo;  // columns per image
+    const int64_t m_lo = (int64_t)n0 * g.HoWo + (int64_t)oy0 * g.Wo;
+    const int64_t m_hi = m_lo + (int64_t)(p.nb > 1 ? nb : 1) * seg;
+    const int64_t v_lo = (m_lo + VEC - 1) / VEC, v_hi = m_hi / VEC;  // slots that lie entirely inside the range
+    const int khkw = g.kh * kw;
+    auto locate = [&](int64_t m) -> int {  // LDS index of the window origin of column m
+        uint32_t t = (uint32_t)(m - m_lo), inb = 0, rem = t, oy, ox;
+        if (p.nb > 1) g.div_HoWo.divmod(t, inb, rem);
+        g.div_Wo.divmod(rem, oy, ox);
+        return ((int)inb * p.rows_in + (int)oy * g.sh) * p.wp + (int)ox * g.sw;
+    };
+
+    for (int64_t v = v_lo + tid; v < v_hi; v += 256) {
+        int a[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) a[e] = locate(v * VEC + e);
+        U *dst = D + (int64_t)c * khkw * ld + v * VEC;
+        for (int ky = 0; ky < g.kh; ++ky) {
+            const U *src[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) src[e] = tile + a[e] + ky * p.wp;
+            if constexpr (KW > 0) {
+#pragma unroll
+                for (int kx = 0; kx < KW; ++kx) {
+                    VecOf<U, VEC> out;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) out.v[e] = src[e][kx];
+                    *reinterpret_cast<VecOf<U, VEC> *>(dst) = out;
+                    dst += ld;
+                }
+            } else {
+                for (int kx = 0; kx < kw; ++kx) {
+                    VecOf<U, VEC> out;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) out.v[e] = src[e][kx];
+                    *reinterpret_cast<VecOf<U, VEC> *>(dst) = out;
+                    dst += ld;
+                }
+            }
+        }
+    }
+    // ragged ends: the columns before the first and after the last whole slot, one (row, column) per thread
+    const int head = (int)(v_lo * VEC - m_lo < m_hi - m_lo ? v_lo * VEC - m_lo : m_hi - m_lo);
+    const int tail = v_hi >= v_lo ? (int)(m_hi - v_hi * VEC) : 0;
+    const int edge = head + tail;
+    for (int idx = tid; idx < edge * khkw; idx += 256) {
+        int r = idx / edge, j = idx - r * edge;
+        int64_t m = j < head ? m_lo + j : v_hi * VEC + (j - head);
+        int ky = r / kw, kx = r - ky * kw;
+        D[((int64_t)c * khkw + r) * ld + m] = tile[locate(m) + ky * p.wp + kx];
+    }
+    // columns in [M, ld) of this channel's rows are zero; the workgroup that owns the last column writes them
+    if (m_hi == g.M && ld > g.M) {
+        const int padc = (int)(ld - g.M);
+        for (int idx = tid; idx < khkw * padc; idx += 256) {
+            int r = idx / padc, cc = idx - r * padc;
+            D[((int64_t)c * khkw + r) * ld + g.M + cc] = 0;
+        }
+    }
+}
+
+// Choose the staging plan; returns false when not even one output row's patch fits in LDS.
+static bool make_lower_plan(const ConvGeom &g, size_t elem, LowerPlan *p, size_t *lds_bytes)
+{
+    const size_t small_budget = 32 * 1024, band_budget = 40 * 1024;
+    p->wp = g.W + 2 * g.pw;
+    int rows_full = (g.Ho - 1) * g.sh + g.kh;
+    size_t plane = (size_t)rows_full * p->wp * elem;
+    if (2 * plane <= small_budget) {
+        int nb = (int)(small_budget / plane);
+        if (nb > 32) nb = 32;
+        if (nb > g.N) nb = g.N;
+        p->nb = nb;
+        p->br = g.Ho;
+        p->bands = 1;
+        p->rows_in = rows_full;
+    } else {
+        size_t row_bytes = (size_t)p->wp * elem;
+        if ((size_t)g.kh * row_bytes > 64 * 1024) return false;
+        int64_t rows_fit = (int64_t)(band_budget / row_bytes);
+        int br = rows_fit >= g.kh ? (int)((rows_fit - g.kh) / g.sh + 1) : 1;
+        if (br > g.Ho) br = g.Ho;
+        p->nb = 1;
+        p->br = br;
+        p->bands = (g.Ho + br - 1) / br;
+        p->rows_in = (br - 1) * g.sh + g.kh;
+    }
+    p->groups = (g.N + p->nb - 1) / p->nb;
+    p->div_wp = FastDiv((uint32_t)p->wp);
+    p->div_rows_in = FastDiv((uint32_t)p->rows_in);
+    *lds_bytes = (size_t)p->nb * p->rows_in * p->wp * elem;
+    if ((int64_t)p->bands * p->groups > 0x7fffffffll || g.C > 65535) return false;
+    return true;
+}
+
 template <typename U>
 static int run_lower(const ConvGeom &g, const U *X, U *D, int64_t ld, hipStream_t s)
 {
     constexpr int VEC = 16 / sizeof(U);
-    unsigned gy = (unsigned)(g.K < 65535 ? g.K : 65535);
     ProfScope prof(KID_LOWER, s, 0.0, ((double)g.N * g.C * g.H * g.W + (double)g.K * g.M) * sizeof(U));
+    LowerPlan plan;
+    size_t lds = 0;
+    if (make_lower_plan(g, sizeof(U), &plan, &lds)) {
+        dim3 grid((unsigned)(plan.bands * plan.groups), (unsigned)g.C, 1);
+        const int vec = ld % VEC != 0 ? 1 : VEC;
+#define OMNI_LOWER_CASE(V, KWT) hipLaunchKernelGGL((lower_lds_kernel<U, V, KWT>), grid, dim3(256), lds, s, g, plan, X, D, ld)
+#define OMNI_LOWER_KW(V)                                  \
+    do {                                                  \
+        if (g.kw == 3) OMNI_LOWER_CASE(V, 3);             \
+        else if (g.kw == 5) OMNI_LOWER_CASE(V, 5);        \
+        else if (g.kw == 11) OMNI_LOWER_CASE(V, 11);      \
+        else OMNI_LOWER_CASE(V, 0);                       \
+    } while (0)
+        if (vec == 1) OMNI_LOWER_CASE(1, 0);
+        else OMNI_LOWER_KW(VEC);
+#undef OMNI_LOWER_KW
+#undef OMNI_LOWER_CASE
+        OMNI_LAUNCH_CHECK();
+        return OMNI_OK;
+    }
+    unsigned gy = (unsigned)(g.K < 65535 ? g.K : 65535);
     if (ld % VEC == 0) {
         int64_t vpr = ld / VEC;
         dim3 grid((unsigned)((vpr + 255) / 256), gy, 1);
@@ -84,6 +274,24 @@ int launch_lower(const ConvGeom &g, int dtype, const void *X, void *Dhat, int64_
 // col2im (transpose of the lowering map), gather form: one thread per input pixel sums the entries
 // of dD-hat that were copies of that pixel, in ascending (ky, kx) order, in fp32.  No atomics.
 // ------------------------------------------------------------------------------------------------
+// The window positions that cover input coordinate i along one axis: k = first, first+s, ... <= last,
+// with output coordinate o(first) = (i + pad - first)/s decreasing by one per step.  No per-tap division.
+struct TapRange { int first, last, o_first; };
+__device__ __forceinline__ TapRange tap_range(int i, int pad, int k, int s, int out, const FastDiv &div_s)
+{
+    TapRange t;
+    int top = i + pad;                       // k = top gives o = 0
+    int lo = top - (out - 1) * s;            // smallest k with o <= out-1
+    if (lo < 0) lo = 0;
+    uint32_t q, r;
+    div_s.divmod((uint32_t)(top - lo), q, r);  // top - lo >= 0 whenever the range is non-empty
+    t.first = lo + (int)r;                   // same residue as top modulo s
+    t.o_first = (int)q;
+    t.last = top < k - 1 ? top : k - 1;
+    if (top < lo) t.last = -1;               // empty
+    return t;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void col2im_kernel(ConvGeom g, const T *__restrict__ D, int64_t ld,
                                                      T *__restrict__ dX, uint32_t plane0, uint32_t count)
@@ -98,29 +306,106 @@ __global__ __launch_bounds__(256) void col2im_kernel(ConvGeom g, const T *__rest
     uint32_t n = plane / (uint32_t)g.C, c = plane - n * (uint32_t)g.C;
 
     float acc = 0.f;
-    for (int ky = 0; ky < g.kh; ++ky) {
-        int ty = (int)iy + g.ph - ky;
-        if (ty < 0) break;  // larger ky only moves further up
-        int oy = ty / g.sh;
-        if (oy * g.sh != ty || oy >= g.Ho) continue;
-        for (int kx = 0; kx < g.kw; ++kx) {
-            int tx = (int)ix + g.pw - kx;
-            if (tx < 0) break;
-            int ox = tx / g.sw;
-            if (ox * g.sw != tx || ox >= g.Wo) continue;
+    const TapRange ry = tap_range((int)iy, g.ph, g.kh, g.sh, g.Ho, g.div_sh);
+    const TapRange rx = tap_range((int)ix, g.pw, g.kw, g.sw, g.Wo, g.div_sw);
+    for (int ky = ry.first, oy = ry.o_first; ky <= ry.last; ky += g.sh, --oy)
+        for (int kx = rx.first, ox = rx.o_first; kx <= rx.last; kx += g.sw, --ox) {
             int64_t row = ((int64_t)c * g.kh + ky) * g.kw + kx;
             int64_t col = ((int64_t)n * g.Ho + oy) * g.Wo + ox;
             acc += Elem<T>::to_f32(D[row * ld + col]);
         }
-    }
     dX[(int64_t)plane * g.H * g.W + pix] = Elem<T>::from_f32(acc);
+}
+
+// LDS-staged variant.  A workgroup takes channel c of a group of nb images.  Step 1 copies, for each of
+// the kh*kw rows of that channel, the column range of the group from dD-hat into LDS with 16-byte loads
+// (all loads are in flight together).  Step 2 is the same gather as above, served from LDS: one thread
+// per input pixel, ascending (ky, kx), fp32.  dD-hat is read from HBM exactly once, in full vectors.
+struct Col2imPlan {
+    int nb;      // images per workgroup
+    int groups;  // image groups
+    int pitch;   // LDS elements per row segment (multiple of the vector width)
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void col2im_lds_kernel(ConvGeom g, Col2imPlan p, const T *__restrict__ D,
+                                                         int64_t ld, T *__restrict__ dX)
+{
+    constexpr int VEC = 16 / sizeof(T);
+    extern __shared__ __align__(16) unsigned char col2im_smem[];
+    T *seg = reinterpret_cast<T *>(col2im_smem);
+    const int tid = threadIdx.x;
+    const int c = blockIdx.y;
+    const int n0 = blockIdx.x * p.nb;
+    const int nb = g.N - n0 < p.nb ? g.N - n0 : p.nb;
+    const int khkw = g.kh * g.kw;
+    const int64_t m_lo = (int64_t)n0 * g.HoWo, m_hi = m_lo + (int64_t)nb * g.HoWo;
+    const int64_t v_lo = m_lo / VEC, v_hi = (m_hi + VEC - 1) / VEC;  // 16-byte slots covering the range
+    const int slots = (int)(v_hi - v_lo);
+    const int skew = (int)(m_lo - v_lo * VEC);                        // position of column m_lo inside its slot
+
+    const uint4 *src = reinterpret_cast<const uint4 *>(D + (int64_t)c * khkw * ld) + v_lo;
+    const int64_t row_slots = ld / VEC;
+    uint4 *dst = reinterpret_cast<uint4 *>(col2im_smem);
+    const int pitch_slots = p.pitch / VEC;
+    for (int i = tid; i < khkw * slots; i += 256) {
+        int r = i / slots, v = i - r * slots;
+        dst[r * pitch_slots + v] = src[r * row_slots + v];
+    }
+    __syncthreads();
+
+    const int hw = g.H * g.W;
+    for (int px = tid; px < nb * hw; px += 256) {
+        uint32_t inb, pix, iy, ix;
+        g.div_HW.divmod((uint32_t)px, inb, pix);
+        g.div_W.divmod(pix, iy, ix);
+        const T *base = seg + skew + (int)inb * g.HoWo;
+        float acc = 0.f;
+        const TapRange ry = tap_range((int)iy, g.ph, g.kh, g.sh, g.Ho, g.div_sh);
+        const TapRange rx = tap_range((int)ix, g.pw, g.kw, g.sw, g.Wo, g.div_sw);
+        for (int ky = ry.first, oy = ry.o_first; ky <= ry.last; ky += g.sh, --oy) {
+            const T *row = base + ky * g.kw * p.pitch + oy * g.Wo;
+            for (int kx = rx.first, ox = rx.o_first; kx <= rx.last; kx += g.sw, --ox)
+                acc += Elem<T>::to_f32(row[kx * p.pitch + ox]);
+        }
+        dX[((int64_t)(n0 + inb) * g.C + c) * hw + pix] = Elem<T>::from_f32(acc);
+    }
+}
+
+static bool make_col2im_plan(const ConvGeom &g, size_t elem, int64_t ld, Col2imPlan *p, size_t *lds_bytes)
+{
+    const int vec = (int)(16 / elem);
+    if (ld % vec != 0 || g.C > 65535) return false;
+    const size_t budget = 40 * 1024, hard_limit = 64 * 1024;
+    const int khkw = g.kh * g.kw;
+    size_t per_image = (size_t)khkw * g.HoWo * elem;
+    int nb = (int)(budget / per_image);
+    if (nb < 1) nb = 1;
+    if (nb > 32) nb = 32;
+    if (nb > g.N) nb = g.N;
+    p->nb = nb;
+    p->groups = (g.N + nb - 1) / nb;
+    p->pitch = (int)round_up((int64_t)nb * g.HoWo + vec, vec) + vec;  // room for the skew at both ends
+    *lds_bytes = (size_t)khkw * p->pitch * elem;
+    return *lds_bytes <= hard_limit;
 }
 
 int launch_col2im(const ConvGeom &g, int dtype, const void *dDhat, int64_t ld, void *dX, hipStream_t s)
 {
     int64_t planes = (int64_t)g.N * g.C, hw = (int64_t)g.H * g.W;
-    int64_t planes_per_launch = (0x7fffffffll - 4096) / hw;
     ProfScope prof(KID_COL2IM, s, 0.0, ((double)planes * hw + (double)g.K * g.M) * elem_size(dtype));
+    Col2imPlan plan;
+    size_t lds = 0;
+    if (make_col2im_plan(g, elem_size(dtype), ld, &plan, &lds)) {
+        dim3 grid((unsigned)plan.groups, (unsigned)g.C, 1);
+        if (dtype == OMNI_BF16)
+            hipLaunchKernelGGL(col2im_lds_kernel<bf16_t>, grid, dim3(256), lds, s, g, plan, (const bf16_t *)dDhat, ld, (bf16_t *)dX);
+        else
+            hipLaunchKernelGGL(col2im_lds_kernel<float>, grid, dim3(256), lds, s, g, plan, (const float *)dDhat, ld, (float *)dX);
+        OMNI_LAUNCH_CHECK();
+        return OMNI_OK;
+    }
+    int64_t planes_per_launch = (0x7fffffffll - 4096) / hw;
     for (int64_t p0 = 0; p0 < planes; p0 += planes_per_launch) {
         int64_t np = planes - p0 < planes_per_launch ? planes - p0 : planes_per_launch;
         uint32_t count = (uint32_t)(np * hw);

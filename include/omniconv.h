@@ -77,7 +77,7 @@ typedef struct {
 int omni_conv_output_dims(const omni_conv_desc *desc, int32_t *Ho, int32_t *Wo);
 
 /* Host only.  Leading dimension (in elements) of D-hat inside the workspace: N*Ho*Wo rounded up
- * to a multiple of 8.  omni_lower / omni_col2im take the leading dimension as an argument. */
+ * to a multiple of 64.  omni_lower / omni_col2im take the leading dimension as an argument. */
 int omni_conv_dhat_ld(const omni_conv_desc *desc, int64_t *ld);
 
 /* Host only.  Bytes of scratch the given pass (omni_pass) needs.  The forward and

@@ -47,7 +47,7 @@ void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w)
     size_t e = elem_size(dtype);
     w->ld = dhat_ld(g);
     w->Fp = g.F;
-    w->Kp = round_up(g.K, 8);
+    w->Kp = round_up(g.K, 64);  // zero padded to whole reduction steps
     w->dhat = 0;
     w->khat = align256((size_t)g.K * w->ld * e);
     w->total = w->khat + align256((size_t)w->Fp * w->Kp * e);
@@ -58,7 +58,7 @@ void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w)
     size_t e = elem_size(dtype);
     w->ld = dhat_ld(g);
     w->Kp = g.K;
-    w->Fp = round_up(g.F, 8);
+    w->Fp = round_up(g.F, 64);  // zero padded to whole reduction steps
     w->ddhat = 0;
     w->dyhat = align256((size_t)g.K * w->ld * e);
     w->khat_t = w->dyhat + align256((size_t)g.F * w->ld * e);
@@ -69,12 +69,15 @@ void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w)
 {
     size_t e = elem_size(dtype);
     w->ld = dhat_ld(g);
-    // Split the long reduction (M = N*Ho*Wo) so that about four workgroups per compute unit exist,
-    // each with at least four LDS steps of work.
+    // Split the long reduction (M = N*Ho*Wo) over the chip: about two rounds of workgroups on 256
+    // compute units (just under, so that the last round is full), each with at least four steps.
     int64_t bk = gemm_red_tile(dtype);
-    int64_t tiles = ((g.F + 127) / 128) * (int64_t)((g.K + 127) / 128);
+    int bm, bn;
+    gemm_wgrad_tile(g.F, g.K, &bm, &bn);
+    int64_t tiles = ((g.F + bm - 1) / bm) * (int64_t)((g.K + bn - 1) / bn);
     int64_t steps = (w->ld + bk - 1) / bk;
-    int64_t want = (1024 + tiles - 1) / tiles;
+    int64_t rounds = bm * bn >= 256 * 256 ? 2 : 4;
+    int64_t want = (256 * rounds) / tiles;
     int64_t max_splits = steps / 4 > 0 ? steps / 4 : 1;
     int64_t splits = want < max_splits ? want : max_splits;
     if (splits < 1) splits = 1;

@@ -75,7 +75,8 @@ inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 int make_geom(const omni_conv_desc *desc, ConvGeom *g);
 
 // Leading dimension of D-hat / dY-hat inside a workspace.
-inline int64_t dhat_ld(const ConvGeom &g) { return round_up(g.M, 8); }
+// A multiple of 64 so that a reduction along M can be walked in whole steps without a ragged tail.
+inline int64_t dhat_ld(const ConvGeom &g) { return round_up(g.M, 64); }
 
 // ---------------------------------------------------------------- workspace carving
 struct ForwardWs { size_t dhat, khat, total; int64_t ld, Fp, Kp; };
@@ -131,6 +132,7 @@ int launch_gemm_dgrad(const ConvGeom &g, int dtype, const GemmDgradArgs &a, hipS
 struct GemmWgradArgs { const void *dYhat; const void *Dhat; int64_t ldd; float *partials; int splits; int64_t chunk; float *dW; };
 int launch_gemm_wgrad(const ConvGeom &g, int dtype, const GemmWgradArgs &a, hipStream_t s);
 int gemm_red_tile(int dtype);  // reduction extent of one LDS tile (elements)
+void gemm_wgrad_tile(int F, int K, int *bm, int *bn);
 
 // elementwise.hip
 int launch_sgd(int32_t n, float *const *W, float *const *V, const float *const *G, const int64_t *counts,

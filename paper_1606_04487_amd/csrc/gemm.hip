@@ -24,6 +24,7 @@
 // indices -- a sum does not care about the order of its terms.  bf16 uses
 // v_mfma_f32_32x32x16_bf16, one instruction per pair of packs.
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 
@@ -217,6 +218,25 @@ template <typename T> struct FwdEpilogue {
             Y[c.base + (int64_t)i * HoWo] = Elem<T>::from_f32(v);
         }
     }
+    // 32-bit addressing form: address(i, j) = base + i * row_stride + col_off(j), all in bytes
+    typedef T Out;
+    __device__ __forceinline__ char *base32(int) const { return reinterpret_cast<char *>(Y); }
+    __device__ __forceinline__ uint32_t row_stride32() const { return (uint32_t)HoWo * (uint32_t)sizeof(T); }
+    __device__ __forceinline__ int n_rows() const { return F; }
+    __device__ __forceinline__ uint32_t col_off32(int j, bool &ok) const
+    {
+        ok = j < M;
+        uint32_t n, r;
+        div_HoWo.divmod(ok ? (uint32_t)j : 0u, n, r);
+        return (n * (uint32_t)F * (uint32_t)HoWo + r) * (uint32_t)sizeof(T);
+    }
+    __device__ __forceinline__ T finish(float v, float add) const
+    {
+        v += add;
+        if (relu) v = v > 0.f ? v : 0.f;
+        return Elem<T>::from_f32(v);
+    }
+    bool fits32() const { return (double)M * F * sizeof(T) < 4.0e9; }
 };
 
 // dgrad: i = row k of dD-hat, j = column m; row-major with leading dimension ld.
@@ -231,6 +251,17 @@ template <typename T> struct RowMajorEpilogue {
     {
         if (i < rows && c.ok) out[(int64_t)i * ld + c.base] = Elem<T>::from_f32(v);
     }
+    typedef T Out;
+    __device__ __forceinline__ char *base32(int) const { return reinterpret_cast<char *>(out); }
+    __device__ __forceinline__ uint32_t row_stride32() const { return (uint32_t)ld * (uint32_t)sizeof(T); }
+    __device__ __forceinline__ int n_rows() const { return rows; }
+    __device__ __forceinline__ uint32_t col_off32(int j, bool &ok) const
+    {
+        ok = j < cols;
+        return (uint32_t)j * (uint32_t)sizeof(T);
+    }
+    __device__ __forceinline__ T finish(float v, float) const { return Elem<T>::from_f32(v); }
+    bool fits32() const { return (double)rows * ld * sizeof(T) < 4.0e9; }
 };
 
 // wgrad: i = filter f, j = k; fp32 partial sums, one [rows][cols] slice per split z.
@@ -244,7 +275,113 @@ struct PartialEpilogue {
     {
         if (i < rows && c.ok) out[((int64_t)z * rows + i) * cols + c.base] = v;
     }
+    typedef float Out;
+    __device__ __forceinline__ char *base32(int z) const { return reinterpret_cast<char *>(out + (int64_t)z * rows * cols); }
+    __device__ __forceinline__ uint32_t row_stride32() const { return (uint32_t)cols * 4u; }
+    __device__ __forceinline__ int n_rows() const { return rows; }
+    __device__ __forceinline__ uint32_t col_off32(int j, bool &ok) const
+    {
+        ok = j < cols;
+        return (uint32_t)j * 4u;
+    }
+    __device__ __forceinline__ float finish(float v, float) const { return v; }
+    bool fits32() const { return (double)rows * cols * 4.0 < 4.0e9; }
 };
+
+// Stores a wavefront's TI x TJ grid of 32 x 32 MFMA result tiles.  Result layout of one tile: lane holds
+// column lane%32; register v holds row 8*(v/4) + 4*(lane/32) + v%4.  The address of an element is a
+// wave-uniform 64-bit base (row part, scalar registers) plus a 32-bit per-lane offset (column part and
+// the lane's share of the row), so one element costs a convert, an add and a store.
+template <int TI, int TJ, typename Epi>
+__device__ __forceinline__ void store_tile32(f32x16 (&acc)[TI][TJ], int i_wave, int j_wave, int li, int h, int z,
+                                             const Epi &epi)
+{
+    typedef typename Epi::Out Out;
+    const uint32_t rs = epi.row_stride32();
+    char *base = epi.base32(z);
+    uint32_t voff[TJ];
+    bool ok[TJ];
+#pragma unroll
+    for (int u = 0; u < TJ; ++u) voff[u] = epi.col_off32(j_wave + u * 32 + li, ok[u]) + (uint32_t)(4 * h) * rs;
+    const int rows = epi.n_rows();
+#pragma unroll
+    for (int t = 0; t < TI; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int iu = i_wave + t * 32 + 8 * (v / 4) + (v % 4);  // wave-uniform part of the row
+            const int i = iu + 4 * h;
+            if (iu >= rows) continue;                                 // uniform: nothing of this row exists
+            const float add = epi.row_add(i);
+            char *row = base + (int64_t)iu * rs;                      // uniform 64-bit
+#pragma unroll
+            for (int u = 0; u < TJ; ++u)
+                if (ok[u] && i < rows) *reinterpret_cast<Out *>(row + voff[u]) = epi.finish(acc[t][u][v], add);
+        }
+}
+
+
+// Same job for wavefront tiles that are 128 columns wide, staged through LDS: the wavefront first drops
+// 32 rows x 128 columns of finished results into a private LDS strip, then reads the strip back 16 bytes
+// per lane and stores whole row segments (256 or 512 consecutive bytes per row) instead of one element
+// per lane.  A 16-byte piece whose columns are not consecutive in memory (it straddles two images in the
+// forward pass) or not all valid falls back to element stores.  `strip` is this wavefront's LDS region of
+// 32 * (128 * sizeof(Out) + 16) bytes; only this wavefront touches it, and LDS operations of one
+// wavefront complete in order, so no workgroup barrier is involved.
+template <int TI, typename Epi>
+__device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][4], int i_wave, int j_wave, int lane, int z,
+                                                  const Epi &epi, char *strip)
+{
+    typedef typename Epi::Out Out;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr int VEC = 16 / (int)sizeof(Out);   // elements per 16-byte piece
+    constexpr int GPR = 128 / VEC;               // pieces per row
+    constexpr int RPP = 64 / GPR;                // rows per pass of the wavefront
+    constexpr int PITCH = 128 * (int)sizeof(Out) + 16;
+    const int li = lane % 32, h = lane / 32;
+    const uint32_t rs = epi.row_stride32();
+    char *base = epi.base32(z);
+    const int rows = epi.n_rows();
+    // this lane's piece in the read-back phase
+    const int cg = lane % GPR, rr = lane / GPR;
+    bool ok_first, ok_last;
+    const uint32_t off_first = epi.col_off32(j_wave + cg * VEC, ok_first);
+    const uint32_t off_last = epi.col_off32(j_wave + cg * VEC + VEC - 1, ok_last);
+    const bool whole = ok_first && ok_last && off_last - off_first == (uint32_t)((VEC - 1) * sizeof(Out));
+#pragma unroll
+    for (int t = 0; t < TI; ++t) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v / 4) + 4 * h + (v % 4);
+            const float add = epi.row_add(i_wave + t * 32 + r);
+            Out *row = reinterpret_cast<Out *>(strip + r * PITCH);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) row[u * 32 + li] = epi.finish(acc[t][u][v], add);
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int p = 0; p < 32 / RPP; ++p) {
+            const int r = p * RPP + rr;
+            const int i = i_wave + t * 32 + r;
+            u32x4 piece = *reinterpret_cast<const u32x4 *>(strip + r * PITCH + cg * 16);
+            if (i < rows) {
+                char *dst = base + ((uint32_t)i * rs + off_first);
+                if (whole) {
+                    __builtin_memcpy(dst, &piece, 16);  // element-aligned 16-byte store
+                } else {
+                    Out tmp[VEC];
+                    __builtin_memcpy(tmp, &piece, 16);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        bool ok;
+                        uint32_t off = epi.col_off32(j_wave + cg * VEC + e, ok);
+                        if (ok) *reinterpret_cast<Out *>(base + ((uint32_t)i * rs + off)) = tmp[e];
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
 
 // ------------------------------------------------------------------------------------------------
 // The kernel
@@ -255,8 +392,10 @@ struct GemmShape {
     int64_t red;      // extent of the reduction index (what the loaders may touch)
     int64_t chunk;    // reduction extent handled by one split (multiple of the LDS tile)
     int tiles_i, tiles_j;
-    int n_blocks;     // tiles_i * tiles_j (the launch is padded to a multiple of 8)
-    int per_xcd;      // ceil(n_blocks / 8)
+    int n_blocks;     // tiles_i * tiles_j
+    int n_items;      // n_blocks * splits: work items of the launch
+    int per_xcd;      // ceil(n_items / 8); the launch has 8 * per_xcd workgroups
+    int fast_store;   // the result is below 4 GB: 32-bit store offsets
 };
 
 // Tile configuration: BM x BN result tile, WM x WN wavefronts, PF reduction steps of global loads in
@@ -280,14 +419,15 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
     __shared__ uint4 lds_a[2][NPACK * LA];
     __shared__ uint4 lds_b[2][NPACK * LB];
 
-    // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of tiles
-    // (neighbouring tiles share operand panels, and each XCD has its own L2).
+    // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of the work
+    // items (tile, split), tiles fastest: neighbouring tiles share operand panels and each XCD has its
+    // own L2.  The launch is one-dimensional and padded to a multiple of 8.
     int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-    int tile = xcd * sh.per_xcd + slot;
-    if (tile >= sh.n_blocks) return;
+    int item = xcd * sh.per_xcd + slot;
+    if (item >= sh.n_items) return;
+    int z = item / sh.n_blocks, tile = item - z * sh.n_blocks;
     int ti = tile % sh.tiles_i, tj = tile / sh.tiles_i;  // row tiles fastest: they share the big column panel
     int row0 = ti * BM, col0 = tj * BN;
-    int z = blockIdx.y;
     int64_t k_begin = (int64_t)z * sh.chunk;
     int64_t k_end = k_begin + sh.chunk < sh.red ? k_begin + sh.chunk : sh.red;
     int steps = k_end > k_begin ? (int)((k_end - k_begin + BK - 1) / BK) : 0;
@@ -363,8 +503,11 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
         }
     }
 
-    // Result layout of a 32 x 32 MFMA tile: lane holds column lane%32; register v holds row
-    // 8*(v/4) + 4*(lane/32) + v%4.
+    if (sh.fast_store) {
+        store_tile32<TI, TJ>(acc, row0 + wm * (BM / Cfg::WM), col0 + wn * (BN / Cfg::WN), li, h, z, epi);
+        return;
+    }
+    // 64-bit addressing for results beyond 4 GB
 #pragma unroll
     for (int u = 0; u < TJ; ++u) {
         int j = col0 + wn * (BN / Cfg::WN) + u * 32 + li;
@@ -380,6 +523,295 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Software-pipelined 256 x 256 kernel (4 wavefronts, 128 x 128 each, one workgroup per compute unit).
+//
+// With one wavefront per SIMD nothing hides latency unless the instruction stream itself interleaves
+// MFMAs with LDS and global traffic.  A reduction step is four slabs of 16 MFMAs per wavefront; each
+// slab is cut into four chunks of 4 MFMAs, and between chunks (fenced so the compiler keeps the order)
+// the wavefront issues, in this rotation:
+//   slab 0,1,2 : the 8 fragment reads of the next slab into the other fragment register set
+//   slab 2     : the LDS writes of the next step's tile (its global loads were issued a step earlier)
+//   slab 3     : barrier, the fragment reads of the next step's first slab, and the global loads of
+//                the tile two steps ahead
+// LDS rows are XOR-swizzled (row ^ ((row >> 3) & 7)) so that both the transposing writes of a
+// column-contiguous operand and the fragment reads are free of bank conflicts.
+// ------------------------------------------------------------------------------------------------
+namespace pipe {
+
+constexpr int BM = 256, BN = 256, NT = 256, LROWS = 257;
+
+// Compile-time loop: the body receives std::integral_constant<int, I>, so every register-array index
+// derived from it is a constant for the front end (arrays indexed that way stay in registers).
+template <int I, int N, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+__device__ __forceinline__ int swz(int row) { return row ^ ((row >> 3) & 7); }
+
+// The loaders of this kernel are unpredicated: row, column and reduction indices beyond the operand
+// are clamped to the last valid one (their products only reach results the epilogue discards, or meet
+// the zero padding of the other operand), and the row operand is zero-padded along the reduction to a
+// multiple of the step.  No branch, no zero fill, nothing for the compiler to serialise on.
+// Addresses are a wave-uniform 64-bit base (kept in scalar registers) plus a 32-bit per-lane byte
+// offset that does not change from step to step, which keeps the vector register budget for data.
+template <typename T> struct RedLoader {  // 256 rows x 8 packs: pack g = tid%8 of rows tid/8 + 32q, q = 0..7
+    static constexpr int KP = Pack<T>::KP;
+    // named members instead of arrays: each one is its own SSA value, nothing can end up in scratch
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 r0, r1, r2, r3, r4, r5, r6, r7;
+    uint32_t o0, o1, o2, o3, o4, o5, o6, o7;  // byte offset of (row, pack) from the first row of the tile
+    template <int Q> __device__ __forceinline__ u32x4 &reg()
+    {
+        if constexpr (Q == 0) return r0; else if constexpr (Q == 1) return r1; else if constexpr (Q == 2) return r2;
+        else if constexpr (Q == 3) return r3; else if constexpr (Q == 4) return r4; else if constexpr (Q == 5) return r5;
+        else if constexpr (Q == 6) return r6; else return r7;
+    }
+    template <int Q> __device__ __forceinline__ uint32_t &off()
+    {
+        if constexpr (Q == 0) return o0; else if constexpr (Q == 1) return o1; else if constexpr (Q == 2) return o2;
+        else if constexpr (Q == 3) return o3; else if constexpr (Q == 4) return o4; else if constexpr (Q == 5) return o5;
+        else if constexpr (Q == 6) return o6; else return o7;
+    }
+    __device__ __forceinline__ void init(int64_t ld, int rows, int row0, int tid)
+    {
+        int g = tid % NPACK, rr = tid / NPACK;
+        static_for<0, 8>([&](auto q) {
+            constexpr int Q = decltype(q)::value;
+            int r = row0 + rr + 32 * Q;
+            r = (r < rows ? r : rows - 1) - row0;
+            off<Q>() = (uint32_t)(((int64_t)r * ld + g * KP) * (int64_t)sizeof(T));
+        });
+    }
+    // tile_k: address of element (row0, k0) of the operand, wave-uniform
+    template <int C> __device__ __forceinline__ void issue_part(const char *tile_k)
+    {
+        reg<2 * C>() = *reinterpret_cast<const u32x4 *>(tile_k + off<2 * C>());
+        reg<2 * C + 1>() = *reinterpret_cast<const u32x4 *>(tile_k + off<2 * C + 1>());
+    }
+    template <int C> __device__ __forceinline__ void commit_part(uint4 *lds, int tid)
+    {
+        int g = tid % NPACK, rr = tid / NPACK;
+        u32x4 *l = reinterpret_cast<u32x4 *>(lds);
+        l[g * LROWS + swz(rr + 32 * (2 * C))] = reg<2 * C>();
+        l[g * LROWS + swz(rr + 32 * (2 * C + 1))] = reg<2 * C + 1>();
+    }
+};
+
+template <typename T> struct OuterLoader;
+template <> struct OuterLoader<float> {  // columns 4*(tid%64)..+3, pack groups wave + 4q, q = 0, 1
+    uint4 regs[2][4];
+    uint32_t joff;
+    __device__ __forceinline__ void init(int cols, int col0, int tid)
+    {
+        int j = col0 + (tid % 64) * 4;
+        joff = (uint32_t)(j < cols ? j : cols - 4) * 4u;
+    }
+    template <int C> __device__ __forceinline__ void issue_part(const char *base, int64_t ld, int64_t red, int64_t k0, int wave)
+    {
+        int64_t ka = k0 + wave * 4 + C, kb = ka + 16;
+        ka = ka < red ? ka : red - 1;
+        kb = kb < red ? kb : red - 1;
+        regs[0][C] = *reinterpret_cast<const uint4 *>(base + ka * ld * 4 + joff);
+        regs[1][C] = *reinterpret_cast<const uint4 *>(base + kb * ld * 4 + joff);
+    }
+    template <int C, int Q> __device__ __forceinline__ uint4 column() const
+    {
+        if constexpr (C == 0) return make_uint4(regs[Q][0].x, regs[Q][1].x, regs[Q][2].x, regs[Q][3].x);
+        else if constexpr (C == 1) return make_uint4(regs[Q][0].y, regs[Q][1].y, regs[Q][2].y, regs[Q][3].y);
+        else if constexpr (C == 2) return make_uint4(regs[Q][0].z, regs[Q][1].z, regs[Q][2].z, regs[Q][3].z);
+        else return make_uint4(regs[Q][0].w, regs[Q][1].w, regs[Q][2].w, regs[Q][3].w);
+    }
+    template <int C> __device__ __forceinline__ void commit_part(uint4 *lds, int tid) const
+    {
+        int jc = tid % 64, g = tid / 64;
+        lds[g * LROWS + swz(jc * 4 + C)] = column<C, 0>();
+        lds[(g + 4) * LROWS + swz(jc * 4 + C)] = column<C, 1>();
+    }
+};
+template <> struct OuterLoader<bf16_t> {
+    // one task per thread: 8 reduction rows (pack group tid/32) x 8 consecutive columns (16 bytes per row)
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 r0, r1, r2, r3, r4, r5, r6, r7;
+    uint32_t joff;
+    template <int E> __device__ __forceinline__ u32x4 &reg()
+    {
+        if constexpr (E == 0) return r0; else if constexpr (E == 1) return r1; else if constexpr (E == 2) return r2;
+        else if constexpr (E == 3) return r3; else if constexpr (E == 4) return r4; else if constexpr (E == 5) return r5;
+        else if constexpr (E == 6) return r6; else return r7;
+    }
+    __device__ __forceinline__ void init(int cols, int col0, int tid)
+    {
+        int j = col0 + (tid % 32) * 8;
+        joff = (uint32_t)(j < cols ? j : cols - 8) * 2u;
+    }
+    template <int E> __device__ __forceinline__ void load_one(const char *base, uint32_t row_bytes, int red, int k0, int tid)
+    {
+        int k = k0 + (tid / 32) * 8 + E;
+        k = k < red ? k : red - 1;
+        reg<E>() = *reinterpret_cast<const u32x4 *>(base + ((uint32_t)k * row_bytes + joff));
+    }
+    template <int C> __device__ __forceinline__ void issue_part(const char *base, int64_t ld, int64_t red, int64_t k0, int tid)
+    {
+        load_one<2 * C>(base, (uint32_t)ld * 2u, (int)red, (int)k0, tid);
+        load_one<2 * C + 1>(base, (uint32_t)ld * 2u, (int)red, (int)k0, tid);
+    }
+    static __device__ __forceinline__ uint32_t lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
+    static __device__ __forceinline__ uint32_t hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+    // column J (0..7) of the 8 x 8 block as one pack: the 8 reduction indices of that column
+    template <int J> __device__ __forceinline__ u32x4 column() const
+    {
+        constexpr int D = J / 2;
+        if constexpr (J % 2 == 0) return u32x4{lo(r0[D], r1[D]), lo(r2[D], r3[D]), lo(r4[D], r5[D]), lo(r6[D], r7[D])};
+        else return u32x4{hi(r0[D], r1[D]), hi(r2[D], r3[D]), hi(r4[D], r5[D]), hi(r6[D], r7[D])};
+    }
+    template <int C> __device__ __forceinline__ void commit_part(uint4 *lds, int tid) const
+    {
+        int jc = tid % 32, g = tid / 32;
+        u32x4 *l = reinterpret_cast<u32x4 *>(lds) + g * LROWS;
+        l[swz(jc * 8 + 2 * C)] = column<2 * C>();
+        l[swz(jc * 8 + 2 * C + 1)] = column<2 * C + 1>();
+    }
+};
+
+}  // namespace pipe
+
+template <typename T, bool COL_OUTER, typename Epi>
+__global__ __launch_bounds__(256) void gemm_pipe_kernel(const T *__restrict__ A, int64_t lda,
+                                                        const T *__restrict__ B, int64_t ldb, GemmShape sh, Epi epi)
+{
+    using namespace pipe;
+    constexpr int KP = Pack<T>::KP;
+    constexpr int BK = NPACK * KP;
+    __shared__ uint4 lds_all[4 * NPACK * LROWS];  // A buffers 0, 1 then B buffers 0, 1
+    auto lds_a = [&](int buf) { return lds_all + buf * (NPACK * LROWS); };
+    auto lds_b = [&](int buf) { return lds_all + (2 + buf) * (NPACK * LROWS); };
+
+    int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    int item = xcd * sh.per_xcd + slot;  // contiguous ranges of (tile, split) per XCD, tiles fastest
+    if (item >= sh.n_items) return;
+    int z = item / sh.n_blocks, tile = item - z * sh.n_blocks;
+    int ti = tile % sh.tiles_i, tj = tile / sh.tiles_i;
+    int row0 = ti * BM, col0 = tj * BN;
+    int64_t k_begin = (int64_t)z * sh.chunk;
+    int64_t k_end = k_begin + sh.chunk < sh.red ? k_begin + sh.chunk : sh.red;
+    int steps = k_end > k_begin ? (int)((k_end - k_begin + BK - 1) / BK) : 0;
+
+    int tid = threadIdx.x;
+    int lane = tid % 64, wave = tid / 64;
+    int wm = wave / 2, wn = wave % 2;
+    int li = lane % 32, h = lane / 32;
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
+
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    RedLoader<T> la;
+    RedLoader<T> lb_red;
+    OuterLoader<T> lb_out;
+    la.init(lda, sh.rows, row0, tid);
+    if constexpr (COL_OUTER)
+        lb_out.init(sh.cols, col0, tid);
+    else
+        lb_red.init(ldb, sh.cols, col0, tid);
+    const char *a_tile = reinterpret_cast<const char *>(A + (int64_t)row0 * lda);
+    const char *b_tile = reinterpret_cast<const char *>(COL_OUTER ? B : B + (int64_t)col0 * ldb);
+    auto issue_part = [&](auto c, int64_t k0) {
+        constexpr int C = decltype(c)::value;
+        la.template issue_part<C>(a_tile + k0 * (int64_t)sizeof(T));
+        if constexpr (COL_OUTER)
+            lb_out.template issue_part<C>(b_tile, ldb, sh.red, k0, std::is_same<T, float>::value ? wave_s : tid);
+        else
+            lb_red.template issue_part<C>(b_tile + k0 * (int64_t)sizeof(T));
+    };
+    auto commit_part = [&](auto c, int buf) {
+        constexpr int C = decltype(c)::value;
+        la.template commit_part<C>(lds_a(buf), tid);
+        if constexpr (COL_OUTER)
+            lb_out.template commit_part<C>(lds_b(buf), tid);
+        else
+            lb_red.template commit_part<C>(lds_b(buf), tid);
+    };
+
+    uint4 fa[2][4], fb[2][4];
+    // fragment rows of this lane (swizzled), relative to the tile
+    int ra[4], rb[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        ra[t] = swz(wm * 128 + 32 * t + li);
+        rb[t] = swz(wn * 128 + 32 * t + li);
+    }
+    // reads 2 of the 8 fragments of a slab: part 0 -> b0 b1, 1 -> b2 b3, 2 -> a0 a1, 3 -> a2 a3
+    auto read_part = [&](auto c, auto set, int buf, int slab) {
+        constexpr int C = decltype(c)::value, S = decltype(set)::value;
+        int g = slab * 2 + h;
+        if constexpr (C < 2) {
+            fb[S][2 * C] = lds_b(buf)[g * LROWS + rb[2 * C]];
+            fb[S][2 * C + 1] = lds_b(buf)[g * LROWS + rb[2 * C + 1]];
+        } else {
+            fa[S][2 * (C - 2)] = lds_a(buf)[g * LROWS + ra[2 * (C - 2)]];
+            fa[S][2 * (C - 2) + 1] = lds_a(buf)[g * LROWS + ra[2 * (C - 2) + 1]];
+        }
+    };
+    auto mma_chunk = [&](auto set, auto t) {
+        constexpr int S = decltype(set)::value, Tt = decltype(t)::value;
+        Mma<T>::run(fa[S][Tt], fb[S][0], acc[Tt][0]);
+        Mma<T>::run(fa[S][Tt], fb[S][1], acc[Tt][1]);
+        Mma<T>::run(fa[S][Tt], fb[S][2], acc[Tt][2]);
+        Mma<T>::run(fa[S][Tt], fb[S][3], acc[Tt][3]);
+    };
+    using I0 = std::integral_constant<int, 0>;
+
+    if (steps > 0) {
+        static_for<0, 4>([&](auto c) { issue_part(c, k_begin); });
+        static_for<0, 4>([&](auto c) { commit_part(c, 0); });
+    }
+    __syncthreads();
+    if (steps > 1) static_for<0, 4>([&](auto c) { issue_part(c, k_begin + BK); });
+    if (steps > 0) static_for<0, 4>([&](auto c) { read_part(c, I0{}, 0, 0); });
+
+    for (int s = 0; s < steps; ++s) {
+        const int buf = s & 1;
+        const bool more = s + 1 < steps, more2 = s + 2 < steps;
+        static_for<0, 4>([&](auto q) {
+            constexpr int Q = decltype(q)::value;
+            static_for<0, 4>([&](auto c) {
+                constexpr int C = decltype(c)::value;
+                mma_chunk(std::integral_constant<int, (Q & 1)>{}, c);
+                if constexpr (Q < 3) {
+                    read_part(c, std::integral_constant<int, ((Q + 1) & 1)>{}, buf, Q + 1);
+                    if constexpr (Q == 2) {
+                        if (more) commit_part(c, buf ^ 1);
+                    }
+                } else {
+                    if constexpr (C == 0) __syncthreads();  // every wavefront has read `buf` and written `buf ^ 1`
+                    if (more) read_part(c, I0{}, buf ^ 1, 0);
+                    if (more2) issue_part(c, k_begin + (int64_t)(s + 2) * BK);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+    }
+
+    if constexpr (std::is_same<Epi, PartialEpilogue>::value) {
+        store_tile32<4, 4>(acc, row0 + wm * 128, col0 + wn * 128, li, h, z, epi);
+    } else {
+        __syncthreads();  // every wavefront is done with the operand tiles: LDS becomes staging space
+        constexpr int STRIP = 32 * (128 * (int)sizeof(typename Epi::Out) + 16);
+        static_assert(4 * STRIP <= (int)sizeof(lds_all), "staging strips fit in the operand buffers");
+        store_tile_staged<4>(acc, row0 + wm * 128, col0 + wn * 128, lane, z, epi,
+                             reinterpret_cast<char *>(lds_all) + wave * STRIP);
+    }
+}
+
 // Sum the per-split partial results in split order (deterministic) into the final fp32 tensor.
 __global__ void reduce_partials_kernel(const float *__restrict__ partials, int splits, int64_t count,
                                        float *__restrict__ out)
@@ -391,7 +823,7 @@ __global__ void reduce_partials_kernel(const float *__restrict__ partials, int s
     out[i] = acc;
 }
 
-static GemmShape make_shape(int rows, int cols, int64_t red, int64_t chunk, int bm, int bn)
+static GemmShape make_shape(int rows, int cols, int64_t red, int64_t chunk, int bm, int bn, int splits)
 {
     GemmShape s;
     s.rows = rows;
@@ -401,7 +833,9 @@ static GemmShape make_shape(int rows, int cols, int64_t red, int64_t chunk, int 
     s.tiles_i = (rows + bm - 1) / bm;
     s.tiles_j = (cols + bn - 1) / bn;
     s.n_blocks = s.tiles_i * s.tiles_j;
-    s.per_xcd = (s.n_blocks + 7) / 8;
+    s.n_items = s.n_blocks * splits;
+    s.per_xcd = (s.n_items + 7) / 8;
+    s.fast_store = 0;
     return s;
 }
 
@@ -415,7 +849,8 @@ typedef Tile<128, 256, 2, 2, 1> Tile4;
 typedef Tile<256, 256, 2, 2, 1> Tile5;
 typedef Tile<256, 256, 4, 2, 1> Tile6;
 typedef Tile<256, 256, 2, 4, 1> Tile7;
-constexpr int N_TILES = 8;
+constexpr int TILE_PIPE = 8;  // the software-pipelined 256 x 256 kernel
+constexpr int N_TILES = 9;
 
 static int tile_override()
 {
@@ -424,21 +859,36 @@ static int tile_override()
     return (v >= 0 && v < N_TILES) ? v : -1;
 }
 
+// Tile choice: the 256 x 256 tile halves the operand traffic per flop, so it wins whenever the result
+// fills its tiles about as well as it fills 128 x 128 ones (measured on the CaffeNet-shaped layers: 256
+// and 2400/3456-wide results take it, 96- and 384-wide ones lose a quarter or more of the tile to padding).
 static int pick_tile(int rows, int cols)
 {
     int o = tile_override();
     if (o >= 0) return o;
-    (void)rows;
-    (void)cols;
-    return 0;
+    auto fill = [](int n, int t) { return (double)n / (double)(((n + t - 1) / t) * t); };
+    double u256 = fill(rows, 256) * fill(cols, 256), u128 = fill(rows, 128) * fill(cols, 128);
+    return u256 >= 0.9 * u128 ? 6 : 0;
 }
+
+static void tile_dims(int tile, int *bm, int *bn)
+{
+    static const int dims[N_TILES][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}, {128, 256},
+                                         {256, 256}, {256, 256}, {256, 256}, {256, 256}};
+    *bm = dims[tile][0];
+    *bn = dims[tile][1];
+}
+
+// Result tile of the model-gradient GEMM for a layer (the split planner needs the tile count).
+void gemm_wgrad_tile(int F, int K, int *bm, int *bn) { tile_dims(pick_tile(F, K), bm, bn); }
 
 template <typename T, typename Cfg, bool COL_OUTER, typename Epi>
 static void launch_cfg(const T *A, int64_t lda, const T *B, int64_t ldb, int rows, int cols, int64_t red,
                        int64_t chunk, int splits, const Epi &epi, hipStream_t s)
 {
-    GemmShape sh = make_shape(rows, cols, red, chunk, Cfg::BM, Cfg::BN);
-    dim3 grid(sh.per_xcd * 8, splits, 1);
+    GemmShape sh = make_shape(rows, cols, red, chunk, Cfg::BM, Cfg::BN, splits);
+    sh.fast_store = epi.fits32() ? 1 : 0;
+    dim3 grid(sh.per_xcd * 8, 1, 1);
     hipLaunchKernelGGL((gemm_kernel<T, Cfg, COL_OUTER, Epi>), grid, dim3(Cfg::NT), 0, s, A, lda, B, ldb, sh, epi);
 }
 
@@ -446,6 +896,16 @@ template <typename T, bool COL_OUTER, typename Epi>
 static void launch_any(int tile, const T *A, int64_t lda, const T *B, int64_t ldb, int rows, int cols, int64_t red,
                        int64_t chunk, int splits, const Epi &epi, hipStream_t s)
 {
+    // the pipelined kernel only has 32-bit load and store offsets
+    if (tile == TILE_PIPE && (!epi.fits32() || (double)lda * sizeof(T) * 256 >= 4.0e9 || (double)ldb * sizeof(T) * 256 >= 4.0e9 ||
+                              (COL_OUTER && (double)ldb * sizeof(T) * (double)red >= 4.0e9)))
+        tile = 6;
+    if (tile == TILE_PIPE) {
+        GemmShape sh = make_shape(rows, cols, red, chunk, pipe::BM, pipe::BN, splits);
+        dim3 grid(sh.per_xcd * 8, 1, 1);
+        hipLaunchKernelGGL((gemm_pipe_kernel<T, COL_OUTER, Epi>), grid, dim3(pipe::NT), 0, s, A, lda, B, ldb, sh, epi);
+        return;
+    }
     switch (tile) {
     case 1: launch_cfg<T, Tile1, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
     case 2: launch_cfg<T, Tile2, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;

@@ -38,7 +38,7 @@ def test_output_dims_and_ld(B):
     assert B.conv_dhat_ld(d) == 256 * 55 * 55
     d = B.conv_desc(3, 5, 13, 13, 7, 3, 3, 1, 1)
     assert B.conv_output_dims(d) == (13, 13)
-    assert B.conv_dhat_ld(d) == 512                      # 507 rounded up to a multiple of 8
+    assert B.conv_dhat_ld(d) == 512                      # 507 rounded up to a multiple of 64
     d = B.conv_desc(1, 1, 7, 9, 1, 3, 2, (2, 1), (0, 2))
     assert B.conv_output_dims(d) == (3, 12)
     assert [B.pool_output_dim(n, 3, 2, True) for n in (32, 16, 8, 55, 27, 13)] == [16, 8, 4, 27, 13, 6]
@@ -50,13 +50,17 @@ def test_output_dims_and_ld(B):
 def test_workspace_sizes_grow_linearly_with_the_batch(B):
     # Sec. III-B / Fig. "parallel"(c): the footprint of the lowered data is proportional to the
     # number of images lowered at once.
-    sizes = []
+    sizes, lds = [], []
     for n in (8, 16, 32, 64):
         d = B.conv_desc(n, 96, 27, 27, 256, 5, 5, 1, 2, B.BF16)
         sizes.append(B.conv_workspace_bytes(d, B.PASS_FORWARD))
+        lds.append(B.conv_dhat_ld(d))
         assert sizes[-1] >= 96 * 25 * n * 27 * 27 * 2
-    khat = 256 * 2400 * 2
-    assert abs((sizes[3] - khat) / (sizes[0] - khat) - 8.0) < 0.01
+        assert n * 27 * 27 <= lds[-1] < n * 27 * 27 + 64
+    khat = sizes[0] - 96 * 25 * lds[0] * 2              # what is left is the model matrix, the same for every n
+    assert 256 * 2400 * 2 <= khat <= 256 * 2500 * 2
+    for size, ld in zip(sizes, lds):
+        assert size - khat == 96 * 25 * ld * 2           # exactly proportional to the columns lowered
     d32 = B.conv_desc(8, 96, 27, 27, 256, 5, 5, 1, 2, B.F32)
     assert B.conv_workspace_bytes(d32, B.PASS_FORWARD) > 1.9 * sizes[0]
     for p in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):

@@ -147,6 +147,8 @@ int omni_col2im(const omni_conv_desc *desc, const void *dDhat, int64_t ld, void 
  *       ceil_mode != 0 keeps a last border-clipped window.  The first maximum in (ky, kx) scan
  *       order wins.  argmax (uint8 per output, nullable) receives ky*k+kx of the winner.
  *   maxpool_backward: dx [planes][H][W] (overwritten) receives each dy at its window's winner.
+ *   maxpool_relu_backward: the same followed by the ReLU gradient of the pooled tensor y
+ *       [planes][H][W] (dx = 0 where y <= 0), in one pass; dx must not alias y.
  * omni_pool_output_dim is host only and returns the pooled extent or a negative status.
  */
 int omni_relu_forward(int32_t dtype, int64_t count, const void *x, void *y, void *hip_stream);
@@ -159,6 +161,9 @@ int omni_maxpool_forward(int32_t dtype, int64_t planes, int32_t H, int32_t W, in
 int omni_maxpool_backward(int32_t dtype, int64_t planes, int32_t H, int32_t W, int32_t k,
                           int32_t stride, int32_t ceil_mode, const void *dy, const uint8_t *argmax,
                           void *dx, void *hip_stream);
+int omni_maxpool_relu_backward(int32_t dtype, int64_t planes, int32_t H, int32_t W, int32_t k,
+                               int32_t stride, int32_t ceil_mode, const void *dy, const uint8_t *argmax,
+                               const void *y, void *dx, void *hip_stream);
 
 /*
  * Per-kernel timing (the paper times with a wall clock, App. C "Experiment Setup"; on a GPU the

@@ -30,7 +30,7 @@ SYMBOLS = [
     "omni_conv_output_dims", "omni_conv_dhat_ld", "omni_conv_workspace_bytes", "omni_conv_forward",
     "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
-    "omni_maxpool_forward", "omni_maxpool_backward", "omni_status_string", "omni_version",
+    "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward", "omni_status_string", "omni_version",
     "omni_profile_enable", "omni_profile_kernel_count", "omni_profile_kernel_name", "omni_profile_summary",
 ]
 
@@ -73,6 +73,7 @@ _lib.omni_relu_backward.argtypes = [_i32, _i64, _vp, _vp, _vp, _vp]
 _lib.omni_pool_output_dim.argtypes = [_i32, _i32, _i32, _i32]
 _lib.omni_maxpool_forward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.omni_maxpool_backward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
+_lib.omni_maxpool_relu_backward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
 
 
 _lib.omni_profile_enable.argtypes = [ctypes.c_int]
@@ -270,6 +271,17 @@ def maxpool_backward(dy, argmax, H: int, W: int, k: int = 3, stride: int = 2, ce
         dx = torch.empty(tuple(dy.shape[:-2]) + (H, W), dtype=dy.dtype, device=dy.device)
     _check(_lib.omni_maxpool_backward(dtype_code(dy.dtype), planes, H, W, k, stride, int(ceil_mode), _p(dy),
                                       _p(argmax), _p(dx), _stream()))
+    return dx
+
+
+def maxpool_relu_backward(dy, argmax, y, k: int = 3, stride: int = 2, ceil_mode: bool = True, dx=None):
+    """omni_maxpool_relu_backward: pool backward and the ReLU gradient of the pooled tensor y in one pass."""
+    H, W = y.shape[-2:]
+    planes = dy.numel() // (dy.shape[-1] * dy.shape[-2])
+    if dx is None:
+        dx = torch.empty_like(y)
+    _check(_lib.omni_maxpool_relu_backward(dtype_code(dy.dtype), planes, H, W, k, stride, int(ceil_mode), _p(dy),
+                                           _p(argmax), _p(y), _p(dx), _stream()))
     return dx
 
 

@@ -332,7 +332,19 @@ int omni_maxpool_backward(int32_t dtype, int64_t planes, int32_t H, int32_t W, i
     if (planes == 0) return OMNI_OK;
     if (dy == nullptr || argmax == nullptr || dx == nullptr) return OMNI_INVALID_ARGUMENT;
     if (!aligned16(dy) || !aligned16(dx)) return OMNI_MISALIGNED;
-    return launch_maxpool_bwd(dtype, planes, H, W, k, stride, ceil_mode, dy, argmax, dx, (hipStream_t)hip_stream);
+    return launch_maxpool_bwd(dtype, planes, H, W, k, stride, ceil_mode, dy, argmax, nullptr, dx, (hipStream_t)hip_stream);
+}
+
+int omni_maxpool_relu_backward(int32_t dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride,
+                               int32_t ceil_mode, const void *dy, const uint8_t *argmax, const void *y, void *dx,
+                               void *hip_stream)
+{
+    int st = check_pool(dtype, planes, H, W, k, stride);
+    if (st != OMNI_OK) return st;
+    if (planes == 0) return OMNI_OK;
+    if (dy == nullptr || argmax == nullptr || y == nullptr || dx == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(dy) || !aligned16(y) || !aligned16(dx)) return OMNI_MISALIGNED;
+    return launch_maxpool_bwd(dtype, planes, H, W, k, stride, ceil_mode, dy, argmax, y, dx, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

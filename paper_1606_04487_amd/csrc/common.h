@@ -141,6 +141,6 @@ int launch_relu(int dtype, bool backward, int64_t count, const void *ref, const 
 int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
                        const void *x, void *y, uint8_t *argmax, hipStream_t s);
 int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
-                       const void *dy, const uint8_t *argmax, void *dx, hipStream_t s);
+                       const void *dy, const uint8_t *argmax, const void *y, void *dx, hipStream_t s);
 
 }  // namespace omni

@@ -174,7 +174,7 @@ int launch_relu(int dtype, bool backward, int64_t count, const void *ref, const 
 // ------------------------------------------------------------------------------------------------
 struct PoolGeom {
     int32_t H, W, Ho, Wo, k, s;
-    FastDiv div_Wo, div_HoWo, div_W, div_HW;
+    FastDiv div_Wo, div_HoWo, div_W, div_HW, div_s;
 };
 
 template <typename T>
@@ -215,10 +215,10 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(PoolGeom g, int64_t pl
 
 // Gather form: each input pixel collects the gradient of every window that elected it, in
 // ascending (oy, ox) order, in fp32.
-template <typename T>
+template <typename T, bool RELU>  // RELU: also apply the ReLU gradient of the pooled tensor y (dx = 0 where y <= 0)
 __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolGeom g, int64_t plane0, uint32_t count,
                                                           const T *__restrict__ dy, const uint8_t *__restrict__ argmax,
-                                                          T *__restrict__ dx)
+                                                          const T *__restrict__ y, T *__restrict__ dx)
 {
     uint32_t local = blockIdx.x * 256u + threadIdx.x;
     if (local >= count) return;
@@ -226,13 +226,14 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolGeom g, int64_t pl
     g.div_HW.divmod(local, pl, p);
     g.div_W.divmod(p, iy, ix);
     int64_t plane = plane0 + pl;
+    // windows oy with oy*s <= iy <= oy*s + k - 1, clipped to the pooled extent (multiply-high divisions)
     int oy_lo = (int)iy - g.k + 1;
-    oy_lo = oy_lo <= 0 ? 0 : (oy_lo + g.s - 1) / g.s;
-    int oy_hi = (int)iy / g.s;
+    oy_lo = oy_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(oy_lo + g.s - 1));
+    int oy_hi = (int)g.div_s.div(iy);
     if (oy_hi > g.Ho - 1) oy_hi = g.Ho - 1;
     int ox_lo = (int)ix - g.k + 1;
-    ox_lo = ox_lo <= 0 ? 0 : (ox_lo + g.s - 1) / g.s;
-    int ox_hi = (int)ix / g.s;
+    ox_lo = ox_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(ox_lo + g.s - 1));
+    int ox_hi = (int)g.div_s.div(ix);
     if (ox_hi > g.Wo - 1) ox_hi = g.Wo - 1;
     const int64_t obase = plane * g.Ho * g.Wo;
     float acc = 0.f;
@@ -242,7 +243,122 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolGeom g, int64_t pl
             int64_t o = obase + (int64_t)oy * g.Wo + ox;
             if (argmax[o] == (uint8_t)code) acc += Elem<T>::to_f32(dy[o]);
         }
+    if constexpr (RELU) {
+        if (!(Elem<T>::to_f32(y[plane * g.H * g.W + p]) > 0.f)) acc = 0.f;
+    }
     dx[plane * g.H * g.W + p] = Elem<T>::from_f32(acc);
+}
+
+// LDS-staged variants.  A workgroup takes a few whole planes; their pixels are one contiguous run in
+// memory, fetched 16 bytes per lane into LDS (the run need not be 16-byte aligned), and every window is
+// then evaluated from LDS.  Global traffic is each operand once, in full vectors.
+template <typename T>
+__device__ __forceinline__ void run_to_lds(const T *__restrict__ src, int count, T *dst, int tid)
+{
+    constexpr int VEC = 16 / (int)sizeof(T);
+    const int chunks = (count + VEC - 1) / VEC;
+    for (int c = tid; c < chunks; c += 256) {
+        T v[VEC];
+        if ((c + 1) * VEC <= count) {
+            __builtin_memcpy(v, src + c * VEC, sizeof(v));
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) dst[c * VEC + e] = v[e];
+        } else {
+            for (int e = 0; c * VEC + e < count; ++e) dst[c * VEC + e] = src[c * VEC + e];
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_fwd_lds_kernel(PoolGeom g, int64_t planes, int pb,
+                                                              const T *__restrict__ x, T *__restrict__ y,
+                                                              uint8_t *__restrict__ argmax)
+{
+    extern __shared__ __align__(16) unsigned char pool_smem[];
+    T *tile = reinterpret_cast<T *>(pool_smem);
+    const int64_t p0 = (int64_t)blockIdx.x * pb;
+    const int np = (int)(planes - p0 < pb ? planes - p0 : pb);
+    const int hw = g.H * g.W, howo = g.Ho * g.Wo;
+    run_to_lds(x + p0 * hw, np * hw, tile, threadIdx.x);
+    __syncthreads();
+    for (int o = threadIdx.x; o < np * howo; o += 256) {
+        uint32_t pl, r, oy, ox;
+        g.div_HoWo.divmod((uint32_t)o, pl, r);
+        g.div_Wo.divmod(r, oy, ox);
+        const T *src = tile + pl * hw;
+        int best = -1;
+        float bv = 0.f;
+        T braw = (T)0;
+        for (int ky = 0; ky < g.k; ++ky) {
+            int iy = (int)oy * g.s + ky;
+            if (iy >= g.H) break;
+            for (int kx = 0; kx < g.k; ++kx) {
+                int ix = (int)ox * g.s + kx;
+                if (ix >= g.W) break;
+                T raw = src[iy * g.W + ix];
+                float v = Elem<T>::to_f32(raw);
+                if (best < 0 || v > bv) {  // strict: the first maximum in scan order wins
+                    best = ky * g.k + kx;
+                    bv = v;
+                    braw = raw;
+                }
+            }
+        }
+        y[p0 * howo + o] = braw;
+        if (argmax != nullptr) argmax[p0 * howo + o] = (uint8_t)best;
+    }
+}
+
+template <typename T, bool RELU>
+__global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_t planes, int pb,
+                                                              const T *__restrict__ dy, const uint8_t *__restrict__ argmax,
+                                                              const T *__restrict__ y, T *__restrict__ dx)
+{
+    extern __shared__ __align__(16) unsigned char pool_smem[];
+    const int64_t p0 = (int64_t)blockIdx.x * pb;
+    const int np = (int)(planes - p0 < pb ? planes - p0 : pb);
+    const int hw = g.H * g.W, howo = g.Ho * g.Wo;
+    T *gdy = reinterpret_cast<T *>(pool_smem);
+    uint8_t *gam = pool_smem + (((size_t)pb * howo * sizeof(T) + 15) / 16) * 16;
+    run_to_lds(dy + p0 * howo, np * howo, gdy, threadIdx.x);
+    run_to_lds(argmax + p0 * howo, np * howo, gam, threadIdx.x);
+    __syncthreads();
+    for (int px = threadIdx.x; px < np * hw; px += 256) {
+        uint32_t pl, p, iy, ix;
+        g.div_HW.divmod((uint32_t)px, pl, p);
+        g.div_W.divmod(p, iy, ix);
+        int oy_lo = (int)iy - g.k + 1;
+        oy_lo = oy_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(oy_lo + g.s - 1));
+        int oy_hi = (int)g.div_s.div(iy);
+        if (oy_hi > g.Ho - 1) oy_hi = g.Ho - 1;
+        int ox_lo = (int)ix - g.k + 1;
+        ox_lo = ox_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(ox_lo + g.s - 1));
+        int ox_hi = (int)g.div_s.div(ix);
+        if (ox_hi > g.Wo - 1) ox_hi = g.Wo - 1;
+        const int obase = (int)pl * howo;
+        float acc = 0.f;
+        for (int oy = oy_lo; oy <= oy_hi; ++oy)
+            for (int ox = ox_lo; ox <= ox_hi; ++ox) {
+                int code = ((int)iy - oy * g.s) * g.k + ((int)ix - ox * g.s);
+                int o = obase + oy * g.Wo + ox;
+                if (gam[o] == (uint8_t)code) acc += Elem<T>::to_f32(gdy[o]);
+            }
+        if constexpr (RELU) {
+            if (!(Elem<T>::to_f32(y[p0 * hw + px]) > 0.f)) acc = 0.f;
+        }
+        dx[p0 * hw + px] = Elem<T>::from_f32(acc);
+    }
+}
+
+// planes per workgroup for the LDS variants (0: a single plane does not fit, use the direct kernels)
+static int pool_planes_per_block(int64_t plane_bytes, int64_t plane_elems)
+{
+    const int64_t budget = 32 * 1024;
+    if (plane_bytes > 2 * budget) return 0;
+    int64_t pb = 4096 / plane_elems;
+    if (pb < 1) pb = 1;
+    while (pb > 1 && pb * plane_bytes > budget) --pb;
+    return (int)pb;
 }
 
 static PoolGeom make_pool_geom(int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode)
@@ -258,6 +374,7 @@ static PoolGeom make_pool_geom(int32_t H, int32_t W, int32_t k, int32_t stride, 
     g.div_HoWo = FastDiv((uint32_t)(g.Ho * g.Wo));
     g.div_W = FastDiv((uint32_t)W);
     g.div_HW = FastDiv((uint32_t)(H * W));
+    g.div_s = FastDiv((uint32_t)stride);
     return g;
 }
 
@@ -268,6 +385,18 @@ int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
     int64_t per = (int64_t)g.Ho * g.Wo;
     int64_t planes_per_launch = (0x7fffffffll - 4096) / per;
     ProfScope prof(KID_POOL_FWD, s, 0.0, (double)planes * ((double)H * W + per) * elem_size(dtype) + (argmax ? (double)planes * per : 0.0));
+    const int64_t hw = (int64_t)H * W;
+    int pb = pool_planes_per_block(hw * (int64_t)elem_size(dtype), hw);
+    if (pb > 0 && (planes + pb - 1) / pb <= 0x7fffffffll) {
+        dim3 grid((unsigned)((planes + pb - 1) / pb));
+        size_t lds = (size_t)pb * hw * elem_size(dtype) + 16;
+        if (dtype == OMNI_BF16)
+            hipLaunchKernelGGL(maxpool_fwd_lds_kernel<bf16_t>, grid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)x, (bf16_t *)y, argmax);
+        else
+            hipLaunchKernelGGL(maxpool_fwd_lds_kernel<float>, grid, dim3(256), lds, s, g, planes, pb, (const float *)x, (float *)y, argmax);
+        OMNI_LAUNCH_CHECK();
+        return OMNI_OK;
+    }
     for (int64_t p0 = 0; p0 < planes; p0 += planes_per_launch) {
         int64_t np = planes - p0 < planes_per_launch ? planes - p0 : planes_per_launch;
         uint32_t count = (uint32_t)(np * per);
@@ -282,20 +411,45 @@ int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
 }
 
 int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
-                       const void *dy, const uint8_t *argmax, void *dx, hipStream_t s)
+                       const void *dy, const uint8_t *argmax, const void *y, void *dx, hipStream_t s)
 {
     PoolGeom g = make_pool_geom(H, W, k, stride, ceil_mode);
     int64_t per = (int64_t)H * W;
     int64_t planes_per_launch = (0x7fffffffll - 4096) / per;
-    ProfScope prof(KID_POOL_BWD, s, 0.0, (double)planes * (per + (double)g.Ho * g.Wo) * elem_size(dtype) + (double)planes * g.Ho * g.Wo);
+    ProfScope prof(KID_POOL_BWD, s, 0.0,
+                   (double)planes * (per * (y ? 2.0 : 1.0) + (double)g.Ho * g.Wo) * elem_size(dtype) + (double)planes * g.Ho * g.Wo);
+    {
+        const int64_t howo = (int64_t)g.Ho * g.Wo;
+        int pb = pool_planes_per_block(howo * (int64_t)(elem_size(dtype) + 1), per);
+        if (pb > 0 && (planes + pb - 1) / pb <= 0x7fffffffll) {
+            dim3 grid((unsigned)((planes + pb - 1) / pb));
+            size_t lds = (((size_t)pb * howo * elem_size(dtype) + 15) / 16) * 16 + (size_t)pb * howo + 16;
+#define OMNI_POOL_BWD(T, R) hipLaunchKernelGGL((maxpool_bwd_lds_kernel<T, R>), grid, dim3(256), lds, s, g, planes, pb, (const T *)dy, argmax, (const T *)y, (T *)dx)
+            if (dtype == OMNI_BF16) {
+                if (y) OMNI_POOL_BWD(bf16_t, true); else OMNI_POOL_BWD(bf16_t, false);
+            } else {
+                if (y) OMNI_POOL_BWD(float, true); else OMNI_POOL_BWD(float, false);
+            }
+#undef OMNI_POOL_BWD
+            OMNI_LAUNCH_CHECK();
+            return OMNI_OK;
+        }
+    }
     for (int64_t p0 = 0; p0 < planes; p0 += planes_per_launch) {
         int64_t np = planes - p0 < planes_per_launch ? planes - p0 : planes_per_launch;
         uint32_t count = (uint32_t)(np * per);
         dim3 grid((count + 255u) / 256u);
-        if (dtype == OMNI_BF16)
-            hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, grid, dim3(256), 0, s, g, p0, count, (const bf16_t *)dy, argmax, (bf16_t *)dx);
-        else
-            hipLaunchKernelGGL(maxpool_bwd_kernel<float>, grid, dim3(256), 0, s, g, p0, count, (const float *)dy, argmax, (float *)dx);
+        if (dtype == OMNI_BF16) {
+            if (y)
+                hipLaunchKernelGGL((maxpool_bwd_kernel<bf16_t, true>), grid, dim3(256), 0, s, g, p0, count, (const bf16_t *)dy, argmax, (const bf16_t *)y, (bf16_t *)dx);
+            else
+                hipLaunchKernelGGL((maxpool_bwd_kernel<bf16_t, false>), grid, dim3(256), 0, s, g, p0, count, (const bf16_t *)dy, argmax, (const bf16_t *)nullptr, (bf16_t *)dx);
+        } else {
+            if (y)
+                hipLaunchKernelGGL((maxpool_bwd_kernel<float, true>), grid, dim3(256), 0, s, g, p0, count, (const float *)dy, argmax, (const float *)y, (float *)dx);
+            else
+                hipLaunchKernelGGL((maxpool_bwd_kernel<float, false>), grid, dim3(256), 0, s, g, p0, count, (const float *)dy, argmax, (const float *)nullptr, (float *)dx);
+        }
         OMNI_LAUNCH_CHECK();
     }
     return OMNI_OK;

@@ -56,8 +56,8 @@ __global__ __launch_bounds__(256) void sgd_kernel(SgdTable t, float lr, float mu
             *reinterpret_cast<float4 *>(V + i) = v;
             if (S != nullptr) {
                 uint2 p;
-                p.x = (uint32_t)f32_to_bf16(w.x) | ((uint32_t)f32_to_bf16(w.y) << 16);
-                p.y = (uint32_t)f32_to_bf16(w.z) | ((uint32_t)f32_to_bf16(w.w) << 16);
+                p.x = f32x2_to_bf16x2(w.x, w.y);
+                p.y = f32x2_to_bf16x2(w.z, w.w);
                 *reinterpret_cast<uint2 *>(S + i) = p;
             }
         } else {

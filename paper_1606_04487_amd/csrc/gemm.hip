@@ -230,12 +230,14 @@ template <typename T> struct FwdEpilogue {
         div_HoWo.divmod(ok ? (uint32_t)j : 0u, n, r);
         return (n * (uint32_t)F * (uint32_t)HoWo + r) * (uint32_t)sizeof(T);
     }
-    __device__ __forceinline__ T finish(float v, float add) const
+    static constexpr bool HAS_ROW_ADD = true;
+    __device__ __forceinline__ float apply(float v, float add) const
     {
         v += add;
         if (relu) v = v > 0.f ? v : 0.f;
-        return Elem<T>::from_f32(v);
+        return v;
     }
+    __device__ __forceinline__ T finish(float v, float add) const { return Elem<T>::from_f32(apply(v, add)); }
     bool fits32() const { return (double)M * F * sizeof(T) < 4.0e9; }
 };
 
@@ -260,6 +262,8 @@ template <typename T> struct RowMajorEpilogue {
         ok = j < cols;
         return (uint32_t)j * (uint32_t)sizeof(T);
     }
+    static constexpr bool HAS_ROW_ADD = false;
+    __device__ __forceinline__ float apply(float v, float) const { return v; }
     __device__ __forceinline__ T finish(float v, float) const { return Elem<T>::from_f32(v); }
     bool fits32() const { return (double)rows * ld * sizeof(T) < 4.0e9; }
 };
@@ -284,6 +288,8 @@ struct PartialEpilogue {
         ok = j < cols;
         return (uint32_t)j * 4u;
     }
+    static constexpr bool HAS_ROW_ADD = false;
+    __device__ __forceinline__ float apply(float v, float) const { return v; }
     __device__ __forceinline__ float finish(float v, float) const { return v; }
     bool fits32() const { return (double)rows * cols * 4.0 < 4.0e9; }
 };
@@ -320,23 +326,32 @@ __device__ __forceinline__ void store_tile32(f32x16 (&acc)[TI][TJ], int i_wave, 
 }
 
 
-// Same job for wavefront tiles that are 128 columns wide, staged through LDS: the wavefront first drops
-// 32 rows x 128 columns of finished results into a private LDS strip, then reads the strip back 16 bytes
-// per lane and stores whole row segments (256 or 512 consecutive bytes per row) instead of one element
-// per lane.  A 16-byte piece whose columns are not consecutive in memory (it straddles two images in the
-// forward pass) or not all valid falls back to element stores.  `strip` is this wavefront's LDS region of
-// 32 * (128 * sizeof(Out) + 16) bytes; only this wavefront touches it, and LDS operations of one
-// wavefront complete in order, so no workgroup barrier is involved.
-template <int TI, typename Epi>
-__device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][4], int i_wave, int j_wave, int lane, int z,
-                                                  const Epi &epi, char *strip)
+// Same job staged through LDS.  The wavefront drops SR rows x (32*TJ) columns of raw fp32 results into
+// a private LDS strip, then reads the strip back one 16-byte output piece per lane (4 fp32 or 8 bf16
+// results of one row), applies the epilogue (row term, ReLU, rounding: two results per conversion
+// instruction) and stores whole row segments instead of one element per lane.  A piece whose columns
+// are not consecutive in memory (it straddles two images in the forward pass) or not all valid falls
+// back to element stores.  `strip` is this wavefront's LDS region of SR * staged_pitch(TJ) bytes; only
+// this wavefront touches it, and LDS operations of one wavefront complete in order, so no workgroup
+// barrier is involved.  `row_add` is an LDS table of the tile's row terms indexed by (row - i_tile),
+// read only if the epilogue has one.
+// The pitch makes the two half-waves (rows r and r + 4) land 32 banks apart.
+constexpr int staged_pitch(int TJ) { return 32 * TJ * 4 + 32; }
+
+template <int TI, int TJ, int SR, typename Epi>
+__device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][TJ], int i_wave, int j_wave, int lane, int z,
+                                                  const Epi &epi, char *strip, const float *row_add, int i_tile)
 {
     typedef typename Epi::Out Out;
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    constexpr int VEC = 16 / (int)sizeof(Out);   // elements per 16-byte piece
-    constexpr int GPR = 128 / VEC;               // pieces per row
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    static_assert(SR == 16 || SR == 32, "a strip holds half or all of a 32-row MFMA tile");
+    constexpr int COLS = 32 * TJ;
+    constexpr int VEC = 16 / (int)sizeof(Out);   // results per 16-byte output piece
+    constexpr int GPR = COLS / VEC;              // pieces per row
     constexpr int RPP = 64 / GPR;                // rows per pass of the wavefront
-    constexpr int PITCH = 128 * (int)sizeof(Out) + 16;
+    constexpr int PITCH = staged_pitch(TJ);
+    static_assert(GPR <= 64 && SR % RPP == 0, "pass shape");
     const int li = lane % 32, h = lane / 32;
     const uint32_t rs = epi.row_stride32();
     char *base = epi.base32(z);
@@ -350,36 +365,51 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][4], int i_wa
 #pragma unroll
     for (int t = 0; t < TI; ++t) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = 8 * (v / 4) + 4 * h + (v % 4);
-            const float add = epi.row_add(i_wave + t * 32 + r);
-            Out *row = reinterpret_cast<Out *>(strip + r * PITCH);
+        for (int half = 0; half < 32 / SR; ++half) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) row[u * 32 + li] = epi.finish(acc[t][u][v], add);
-        }
-        __builtin_amdgcn_wave_barrier();
+            for (int vv = 0; vv < SR / 2; ++vv) {
+                const int v = half * (SR / 2) + vv;
+                const int r = 8 * (vv / 4) + 4 * h + (vv % 4);
+                float *row = reinterpret_cast<float *>(strip + r * PITCH);
 #pragma unroll
-        for (int p = 0; p < 32 / RPP; ++p) {
-            const int r = p * RPP + rr;
-            const int i = i_wave + t * 32 + r;
-            u32x4 piece = *reinterpret_cast<const u32x4 *>(strip + r * PITCH + cg * 16);
-            if (i < rows) {
-                char *dst = base + ((uint32_t)i * rs + off_first);
-                if (whole) {
-                    __builtin_memcpy(dst, &piece, 16);  // element-aligned 16-byte store
-                } else {
-                    Out tmp[VEC];
-                    __builtin_memcpy(tmp, &piece, 16);
+                for (int u = 0; u < TJ; ++u) row[u * 32 + li] = acc[t][u][v];
+            }
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) {
-                        bool ok;
-                        uint32_t off = epi.col_off32(j_wave + cg * VEC + e, ok);
-                        if (ok) *reinterpret_cast<Out *>(base + ((uint32_t)i * rs + off)) = tmp[e];
+            for (int p = 0; p < SR / RPP; ++p) {
+                const int r = p * RPP + rr;
+                const int i = i_wave + t * 32 + half * SR + r;
+                float x[VEC];
+#pragma unroll
+                for (int q = 0; q < VEC / 4; ++q) {
+                    f32x4 f = *reinterpret_cast<const f32x4 *>(strip + r * PITCH + cg * (VEC * 4) + q * 16);
+                    x[4 * q] = f[0], x[4 * q + 1] = f[1], x[4 * q + 2] = f[2], x[4 * q + 3] = f[3];
+                }
+                float add = 0.f;
+                if constexpr (Epi::HAS_ROW_ADD) add = row_add[i - i_tile];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[e] = epi.apply(x[e], add);
+                if (i < rows) {
+                    if (whole) {
+                        u32x4 piece;
+                        if constexpr (sizeof(Out) == 4)
+                            piece = u32x4{__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
+                        else
+                            piece = u32x4{f32x2_to_bf16x2(x[0], x[1]), f32x2_to_bf16x2(x[2], x[3]),
+                                          f32x2_to_bf16x2(x[4], x[5]), f32x2_to_bf16x2(x[6], x[7])};
+                        __builtin_memcpy(base + ((uint32_t)i * rs + off_first), &piece, 16);  // element-aligned 16-byte store
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) {
+                            bool ok;
+                            uint32_t off = epi.col_off32(j_wave + cg * VEC + e, ok);
+                            if (ok) *reinterpret_cast<Out *>(base + ((uint32_t)i * rs + off)) = Elem<Out>::from_f32(x[e]);
+                        }
                     }
                 }
             }
+            __builtin_amdgcn_wave_barrier();
         }
-        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -416,8 +446,10 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
     constexpr int BK = NPACK * KP;
     constexpr int BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, TI = Cfg::TI, TJ = Cfg::TJ, PF = Cfg::PF;
     constexpr int LA = BM + 1, LB = BN + 1;
-    __shared__ uint4 lds_a[2][NPACK * LA];
-    __shared__ uint4 lds_b[2][NPACK * LB];
+    __shared__ uint4 lds_all[2 * NPACK * (LA + LB)];  // A buffers 0, 1 then B buffers 0, 1
+    __shared__ float lds_add[Epi::HAS_ROW_ADD ? BM : 1];
+    auto lds_a = [&](int buf) { return lds_all + buf * (NPACK * LA); };
+    auto lds_b = [&](int buf) { return lds_all + 2 * NPACK * LA + buf * (NPACK * LB); };
 
     // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of the work
     // items (tile, split), tiles fastest: neighbouring tiles share operand panels and each XCD has its
@@ -436,6 +468,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
     int lane = tid % 64, wave = tid / 64;
     int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
     int li = lane % 32, h = lane / 32;
+    if constexpr (Epi::HAS_ROW_ADD)  // read back after the main loop's barriers
+        for (int i = tid; i < BM; i += NT) lds_add[i] = epi.row_add(row0 + i);
 
     f32x16 acc[TI][TJ];
 #pragma unroll
@@ -457,15 +491,15 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
             lb_red[set].issue(B, ldb, sh.cols, sh.red, col0, k0, tid);
     };
     auto commit = [&](int set, int buf) {
-        la[set].commit(lds_a[buf], tid);
+        la[set].commit(lds_a(buf), tid);
         if constexpr (COL_OUTER)
-            lb_out[set].commit(lds_b[buf], tid);
+            lb_out[set].commit(lds_b(buf), tid);
         else
-            lb_red[set].commit(lds_b[buf], tid);
+            lb_red[set].commit(lds_b(buf), tid);
     };
     auto compute = [&](int buf) {
-        const uint4 *pa = lds_a[buf] + wm * (BM / Cfg::WM) + li;
-        const uint4 *pb = lds_b[buf] + wn * (BN / Cfg::WN) + li;
+        const uint4 *pa = lds_a(buf) + wm * (BM / Cfg::WM) + li;
+        const uint4 *pb = lds_b(buf) + wn * (BN / Cfg::WN) + li;
 #pragma unroll
         for (int slab = 0; slab < NPACK / 2; ++slab) {
             int g = slab * 2 + h;
@@ -504,7 +538,15 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
     }
 
     if (sh.fast_store) {
-        store_tile32<TI, TJ>(acc, row0 + wm * (BM / Cfg::WM), col0 + wn * (BN / Cfg::WN), li, h, z, epi);
+        if constexpr (std::is_same<Epi, PartialEpilogue>::value) {
+            store_tile32<TI, TJ>(acc, row0 + wm * (BM / Cfg::WM), col0 + wn * (BN / Cfg::WN), li, h, z, epi);
+        } else {
+            __syncthreads();  // every wavefront is done with the operand tiles (and with none, if steps == 0)
+            constexpr int STRIP = 16 * staged_pitch(TJ);
+            static_assert((NT / 64) * STRIP <= (int)sizeof(lds_all), "staging strips fit in the operand buffers");
+            store_tile_staged<TI, TJ, 16>(acc, row0 + wm * (BM / Cfg::WM), col0 + wn * (BN / Cfg::WN), lane, z, epi,
+                                          reinterpret_cast<char *>(lds_all) + wave * STRIP, lds_add, row0);
+        }
         return;
     }
     // 64-bit addressing for results beyond 4 GB
@@ -687,6 +729,7 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const T *__restrict__ A,
     constexpr int KP = Pack<T>::KP;
     constexpr int BK = NPACK * KP;
     __shared__ uint4 lds_all[4 * NPACK * LROWS];  // A buffers 0, 1 then B buffers 0, 1
+    __shared__ float lds_add[Epi::HAS_ROW_ADD ? BM : 1];
     auto lds_a = [&](int buf) { return lds_all + buf * (NPACK * LROWS); };
     auto lds_b = [&](int buf) { return lds_all + (2 + buf) * (NPACK * LROWS); };
 
@@ -712,6 +755,8 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const T *__restrict__ A,
         for (int u = 0; u < 4; ++u)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
+
+    if constexpr (Epi::HAS_ROW_ADD) lds_add[tid] = epi.row_add(row0 + tid);  // read back after the main loop's barriers
 
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     RedLoader<T> la;
@@ -805,10 +850,10 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const T *__restrict__ A,
         store_tile32<4, 4>(acc, row0 + wm * 128, col0 + wn * 128, li, h, z, epi);
     } else {
         __syncthreads();  // every wavefront is done with the operand tiles: LDS becomes staging space
-        constexpr int STRIP = 32 * (128 * (int)sizeof(typename Epi::Out) + 16);
+        constexpr int STRIP = 32 * staged_pitch(4);
         static_assert(4 * STRIP <= (int)sizeof(lds_all), "staging strips fit in the operand buffers");
-        store_tile_staged<4>(acc, row0 + wm * 128, col0 + wn * 128, lane, z, epi,
-                             reinterpret_cast<char *>(lds_all) + wave * STRIP);
+        store_tile_staged<4, 4, 32>(acc, row0 + wm * 128, col0 + wn * 128, lane, z, epi,
+                                    reinterpret_cast<char *>(lds_all) + wave * STRIP, lds_add, row0);
     }
 }
 

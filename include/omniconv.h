@@ -56,6 +56,12 @@ typedef enum {
                                     omni_conv_forward for the same descriptor and the same X, so
                                     the lowering pass is skipped (the paper's b_p = b: with 288 GB
                                     of HBM every layer's D-hat can stay resident)                */
+#define OMNI_FLAG_FUSED 4u       /* forward, backward_data: where omni_conv_fused_supported() says so,
+                                    compute the same result without D-hat / dD-hat in memory (lowering,
+                                    resp. col2im, fused into the matrix product; App. C names this as
+                                    the way past the replication cost of the lowering phase).  The
+                                    workspace then holds no D-hat afterwards.  Elsewhere the flag is
+                                    ignored and the explicit path runs.                           */
 
 /*
  * A convolution layer (Sec. III-A, Eq. (conv_full); App. C adds stride and zero padding):
@@ -84,6 +90,12 @@ int omni_conv_dhat_ld(const omni_conv_desc *desc, int64_t *ld);
  * backward-weights workspaces both begin with D-hat ([C*kh*kw][ld], desc->dtype), which is what
  * makes OMNI_FLAG_DHAT_CACHED possible when the same buffer is passed to both. */
 int omni_conv_workspace_bytes(const omni_conv_desc *desc, int pass, size_t *bytes);
+
+/* Host only.  1 if the pass (omni_pass) of this layer runs fused under OMNI_FLAG_FUSED, 0 if it
+ * falls back to the explicit path (fused: bf16, stride 1, input channels a multiple of 32, and the
+ * pixels needed by 256 consecutive output positions fit the kernel's LDS patch), negative status
+ * for a bad descriptor.  The workspace size of a pass does not depend on the flag. */
+int omni_conv_fused_supported(const omni_conv_desc *desc, int pass);
 
 /*
  * Forward pass (Sec. III-B: lower all N images, then a single GEMM; App. C: lifting is pure

@@ -24,10 +24,11 @@ _lib = ctypes.CDLL(str(_LIB_PATH))
 
 F32, BF16 = 0, 1
 PASS_FORWARD, PASS_BACKWARD_DATA, PASS_BACKWARD_WEIGHTS = 0, 1, 2
-FLAG_RELU, FLAG_DHAT_CACHED = 1, 2
+FLAG_RELU, FLAG_DHAT_CACHED, FLAG_FUSED = 1, 2, 4
 
 SYMBOLS = [
-    "omni_conv_output_dims", "omni_conv_dhat_ld", "omni_conv_workspace_bytes", "omni_conv_forward",
+    "omni_conv_output_dims", "omni_conv_dhat_ld", "omni_conv_workspace_bytes", "omni_conv_fused_supported",
+    "omni_conv_forward",
     "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
     "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward", "omni_status_string", "omni_version",
@@ -60,6 +61,7 @@ _lib.omni_status_string.argtypes = [ctypes.c_int]
 _lib.omni_version.restype = ctypes.c_char_p
 _lib.omni_conv_output_dims.argtypes = [_dp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
 _lib.omni_conv_dhat_ld.argtypes = [_dp, ctypes.POINTER(_i64)]
+_lib.omni_conv_fused_supported.argtypes = [_dp, ctypes.c_int]
 _lib.omni_conv_workspace_bytes.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(_sz)]
 _lib.omni_conv_forward.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.omni_conv_backward_data.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -142,6 +144,13 @@ def conv_dhat_ld(desc: ConvDesc) -> int:
     ld = _i64()
     _check(_lib.omni_conv_dhat_ld(ctypes.byref(desc), ctypes.byref(ld)))
     return ld.value
+
+
+def conv_fused_supported(desc: ConvDesc, which_pass: int) -> bool:
+    r = _lib.omni_conv_fused_supported(ctypes.byref(desc), which_pass)
+    if r < 0:
+        raise OmniError(r)
+    return bool(r)
 
 
 def conv_workspace_bytes(desc: ConvDesc, which_pass: int) -> int:

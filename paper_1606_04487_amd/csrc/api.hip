@@ -17,7 +17,7 @@ int make_geom(const omni_conv_desc *d, ConvGeom *g)
     int64_t ew = (int64_t)d->W + 2 * (int64_t)d->pad_w - d->kw;
     if (eh < 0 || ew < 0) return OMNI_INVALID_ARGUMENT;  // the window does not fit: empty output
     if (d->dtype != OMNI_F32 && d->dtype != OMNI_BF16) return OMNI_UNSUPPORTED;
-    if (d->flags & ~(OMNI_FLAG_RELU | OMNI_FLAG_DHAT_CACHED)) return OMNI_UNSUPPORTED;
+    if (d->flags & ~(OMNI_FLAG_RELU | OMNI_FLAG_DHAT_CACHED | OMNI_FLAG_FUSED)) return OMNI_UNSUPPORTED;
     int64_t Ho = eh / d->stride_h + 1, Wo = ew / d->stride_w + 1;
     int64_t M = (int64_t)d->N * Ho * Wo;
     int64_t K = (int64_t)d->C * d->kh * d->kw;
@@ -51,6 +51,8 @@ void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w)
     w->dhat = 0;
     w->khat = align256((size_t)g.K * w->ld * e);
     w->total = w->khat + align256((size_t)w->Fp * w->Kp * e);
+    // the fused path keeps only its repacked weights here
+    if (fused_supported(g, dtype, false) && fused_weight_bytes(g, false) > w->total) w->total = align256(fused_weight_bytes(g, false));
 }
 
 void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w)
@@ -63,6 +65,7 @@ void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w)
     w->dyhat = align256((size_t)g.K * w->ld * e);
     w->khat_t = w->dyhat + align256((size_t)g.F * w->ld * e);
     w->total = w->khat_t + align256((size_t)w->Kp * w->Fp * e);
+    if (fused_supported(g, dtype, true) && fused_weight_bytes(g, true) > w->total) w->total = align256(fused_weight_bytes(g, true));
 }
 
 void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w)
@@ -159,6 +162,25 @@ int omni_conv_workspace_bytes(const omni_conv_desc *desc, int pass, size_t *byte
     return OMNI_OK;
 }
 
+int omni_conv_fused_supported(const omni_conv_desc *desc, int pass)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (pass == OMNI_PASS_FORWARD) {
+        ForwardWs w;
+        plan_forward(g, desc->dtype, &w);
+        return fused_supported(g, desc->dtype, false) && fused_weight_bytes(g, false) <= w.total ? 1 : 0;
+    }
+    if (pass == OMNI_PASS_BACKWARD_DATA) {
+        BwdDataWs w;
+        plan_backward_data(g, desc->dtype, &w);
+        return fused_supported(g, desc->dtype, true) && fused_weight_bytes(g, true) <= w.total ? 1 : 0;
+    }
+    if (pass == OMNI_PASS_BACKWARD_WEIGHTS) return 0;
+    return OMNI_INVALID_ARGUMENT;
+}
+
 int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, const float *bias, void *Y,
                       void *workspace, size_t workspace_bytes, void *hip_stream)
 {
@@ -174,6 +196,10 @@ int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, 
     hipStream_t s = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
     void *Dhat = ws + w.dhat, *Khat = ws + w.khat;
+
+    if ((desc->flags & OMNI_FLAG_FUSED) && fused_supported(g, desc->dtype, false) &&
+        fused_weight_bytes(g, false) <= w.total)
+        return launch_fused_conv(g, false, X, W, bias, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0, Y, ws, s);
 
     st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
     if (st != OMNI_OK) return st;
@@ -197,6 +223,10 @@ int omni_conv_backward_data(const omni_conv_desc *desc, const void *dY, const vo
     hipStream_t s = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
     void *dDhat = ws + w.ddhat, *dYhat = ws + w.dyhat, *KhatT = ws + w.khat_t;
+
+    if ((desc->flags & OMNI_FLAG_FUSED) && fused_supported(g, desc->dtype, true) &&
+        fused_weight_bytes(g, true) <= w.total)
+        return launch_fused_conv(g, true, dY, W, nullptr, 0, dX, ws, s);
 
     st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, nullptr, 0, nullptr, s);
     if (st != OMNI_OK) return st;

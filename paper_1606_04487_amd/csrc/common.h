@@ -100,7 +100,8 @@ inline size_t elem_size(int dtype) { return dtype == OMNI_BF16 ? 2 : 4; }
 // ---------------------------------------------------------------- optional event timing (profile.hip)
 enum KernelId {
     KID_LOWER = 0, KID_PACK_KHAT, KID_PACK_DYHAT, KID_BIAS_REDUCE, KID_GEMM_FWD, KID_GEMM_DGRAD, KID_GEMM_WGRAD,
-    KID_REDUCE_PARTIALS, KID_COL2IM, KID_SGD, KID_RELU, KID_POOL_FWD, KID_POOL_BWD, KID_COUNT
+    KID_REDUCE_PARTIALS, KID_COL2IM, KID_SGD, KID_RELU, KID_POOL_FWD, KID_POOL_BWD, KID_FUSED_FWD, KID_FUSED_DGRAD,
+    KID_COUNT
 };
 // Brackets the launches made during its lifetime with two events on `s` when profiling is on.
 // flops / bytes are the algorithmic work of the bracketed launch.
@@ -137,6 +138,14 @@ struct GemmWgradArgs { const void *dYhat; const void *Dhat; int64_t ldd; float *
 int launch_gemm_wgrad(const ConvGeom &g, int dtype, const GemmWgradArgs &a, hipStream_t s);
 int gemm_red_tile(int dtype);  // reduction extent of one LDS tile (elements)
 void gemm_wgrad_tile(int F, int K, int *bm, int *bn);
+
+// implicit.hip: the convolution with lowering (forward) or col2im (data gradient) fused into the matrix
+// product; bf16, stride 1, shapes whose column tiles fit the kernel's LDS patch.  wt_scratch receives the
+// repacked weights (fused_weight_bytes).
+bool fused_supported(const ConvGeom &g, int dtype, bool data_gradient);
+size_t fused_weight_bytes(const ConvGeom &g, bool data_gradient);
+int launch_fused_conv(const ConvGeom &g, bool data_gradient, const void *X, const void *W, const float *bias,
+                      int relu, void *Y, void *wt_scratch, hipStream_t s);
 
 // elementwise.hip
 int launch_sgd(int32_t n, float *const *W, float *const *V, const float *const *G, const int64_t *counts,

@@ -1,0 +1,382 @@
+// Convolution with the lowering fused into the matrix product (gfx950, bf16, stride 1).
+//
+// The lowered matrix D-hat repeats every input element kh*kw times (App. C: the replication factor of
+// the lowering phase), and the explicit path moves it through HBM several times per training step.
+// This kernel computes the same product  Y-hat[F x M] = K-hat[F x K] * D-hat[K x M]  without D-hat ever
+// existing in memory: a workgroup that owns 256 consecutive columns m = (n, oy, ox) keeps the zero-padded
+// input pixels those columns touch in LDS, one 32-channel chunk at a time, and reads its MFMA operand
+// straight out of that patch -- entry ((c, ky, kx), m) of D-hat is the patch pixel (oy + ky, ox + kx) of
+// channel c, so a window tap is a constant LDS offset.  The reduction runs over (chunk, tap, channel in
+// chunk); a sum does not care about the order of its terms, and the weights are repacked to match.
+//
+// The data gradient of a stride-1 layer is the same computation with the roles of the two channel
+// counts exchanged, the window flipped and padding k - 1 - p (the col2im sum, written as a gather), so
+// it runs on the same kernel and needs neither dD-hat nor a scatter step.
+//
+// LDS layout: patch[buffer][g][pixel] and atile[buffer][g][row] of 16-byte packs, pack g holding channels
+// 8g .. 8g+7 of the chunk, so a fragment is one 16-byte read per lane and consecutive lanes (consecutive
+// pixels or rows) read consecutive packs.  Pixels are transposed from the input's [channel][pixel]
+// order in registers on their way into LDS (8 channels x 8 pixels per thread).  Padding pixels are
+// zeroed once: the patch layout is the same for every chunk, and loads only ever write real pixels.
+#include <cstdlib>
+
+#include "common.h"
+#include "mma_epilogue.h"
+
+namespace omni {
+namespace fused {
+
+constexpr int CH = 32;           // channels per reduction chunk
+constexpr int NG = CH / 8;       // 16-byte packs per pixel and chunk
+constexpr int NT = 512;          // 8 wavefronts
+constexpr int BN = 256;          // columns (output pixels) per workgroup
+constexpr int PATCH_PIX = 640;   // capacity of a patch buffer in pixels
+constexpr int MAX_SLOTS = 8;     // images a column tile may touch
+constexpr uint32_t NO_PIX = 0xffffu;
+
+struct Geom {
+    int32_t N, C, H, W;      // input  [N][C][H][W]
+    int32_t F, Ho, Wo;       // output [N][F][Ho][Wo],  Ho = H + 2*ph - kh + 1
+    int32_t kh, kw, ph, pw;  // window, zero padding
+    int32_t Wp;              // W + 2*pw: width of a padded row
+    int32_t HW, HoWo, M, KK;
+    int32_t n_chunks;        // C / CH
+    int32_t Fp;              // F rounded up to the row tile
+    int32_t tiles_f, tiles_m, n_items, per_xcd;
+    FastDiv div_HoWo, div_Wo, div_W;
+};
+
+// What a column tile [col0, m_last] needs of image n: padded rows [ra, ra + nrows) of which the real
+// input rows are [ya, ya + len / W).
+struct SlotSpan { int ra, nrows, ya, len; };
+__host__ __device__ inline SlotSpan slot_span(const Geom &g, int col0, int m_last, int n)
+{
+    int base = n * g.HoWo;
+    int qa = col0 > base ? col0 - base : 0;
+    int qb = m_last - base < g.HoWo - 1 ? m_last - base : g.HoWo - 1;
+    int oya = (int)g.div_Wo.div((uint32_t)qa), oyb = (int)g.div_Wo.div((uint32_t)qb);
+    SlotSpan s;
+    s.ra = oya;
+    s.nrows = oyb - oya + g.kh;
+    int ya = s.ra - g.ph, yb = s.ra + s.nrows - g.ph;
+    if (ya < 0) ya = 0;
+    if (yb > g.H) yb = g.H;
+    s.ya = ya;
+    s.len = yb > ya ? (yb - ya) * g.W : 0;
+    return s;
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t lo16(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
+__device__ __forceinline__ uint32_t hi16(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+
+template <int BM, int WM, int WN>
+__global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Wt,
+                                                        Geom g, FwdEpilogue<bf16_t> epi)
+{
+    static_assert(WM * WN * 64 == NT, "eight wavefronts");
+    constexpr int TI = BM / WM / 32, TJ = BN / WN / 32;
+    constexpr int LA = BM + 1;
+    constexpr int A_PIECES = BM * NG / NT;
+    static_assert(BM * NG % NT == 0, "weight tile divides over the threads");
+    __shared__ uint4 patch[2 * NG * PATCH_PIX];
+    __shared__ uint4 atile[2 * NG * LA];
+    __shared__ float lds_add[BM];
+    __shared__ int slot_so[MAX_SLOTS], slot_ra[MAX_SLOTS], slot_p0[MAX_SLOTS], slot_ya[MAX_SLOTS], slot_len[MAX_SLOTS];
+    __shared__ int total_pieces;
+
+    const int xcd = blockIdx.x % 8, slot_id = blockIdx.x / 8;
+    const int item = xcd * g.per_xcd + slot_id;  // contiguous ranges of tiles per XCD, row tiles fastest
+    if (item >= g.n_items) return;
+    const int tm = item / g.tiles_f, tf = item - tm * g.tiles_f;
+    const int row0 = tf * BM, col0 = tm * BN;
+    const int m_last = (col0 + BN < g.M ? col0 + BN : g.M) - 1;
+    const int n0 = (int)g.div_HoWo.div((uint32_t)col0);
+    const int nslots = (int)g.div_HoWo.div((uint32_t)m_last) - n0 + 1;
+
+    const int tid = threadIdx.x;
+    const int lane = tid % 64, wave = tid / 64;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane % 32, h = lane / 32;
+
+    if (tid == 0) {
+        int so = 0, p0 = 0;
+        for (int i = 0; i < nslots; ++i) {
+            SlotSpan s = slot_span(g, col0, m_last, n0 + i);
+            slot_so[i] = so, slot_ra[i] = s.ra, slot_p0[i] = p0, slot_ya[i] = s.ya, slot_len[i] = s.len;
+            so += s.nrows;
+            p0 += (s.len + 7) / 8;
+        }
+        total_pieces = p0;
+    }
+    for (int i = tid; i < 2 * NG * PATCH_PIX; i += NT) patch[i] = make_uint4(0, 0, 0, 0);
+    for (int i = tid; i < BM; i += NT) lds_add[i] = epi.row_add(row0 + i);
+    __syncthreads();
+
+    // patch pixel of each of this lane's columns at tap (0, 0)
+    int pp0[TJ];
+#pragma unroll
+    for (int u = 0; u < TJ; ++u) {
+        int m = col0 + wn * (BN / WN) + 32 * u + li;
+        m = m < g.M ? m : g.M - 1;
+        uint32_t n, q, oy, ox;
+        g.div_HoWo.divmod((uint32_t)m, n, q);
+        g.div_Wo.divmod(q, oy, ox);
+        int i = (int)n - n0;
+        pp0[u] = (slot_so[i] + (int)oy - slot_ra[i]) * g.Wp + (int)ox;
+    }
+
+    // This thread's share of a chunk: 8 channels (pack tg) x 8 consecutive elements of one image's rows.
+    const int PT = total_pieces;
+    const bool has_task = tid < NG * PT;
+    uint32_t goff = 0;                        // byte offset of the task's first element in chunk 0
+    uint32_t l01 = NO_PIX | (NO_PIX << 16), l23 = l01, l45 = l01, l67 = l01;  // patch index of each element
+    if (has_task) {
+        int tg = tid / PT, jj = tid - tg * PT;
+        int i = nslots - 1;
+        while (i > 0 && jj < slot_p0[i]) --i;
+        int ea = slot_ya[i] * g.W, eb = ea + slot_len[i];
+        int e0 = ea + 8 * (jj - slot_p0[i]);
+        e0 = e0 < g.HW - 8 ? e0 : g.HW - 8;  // stay inside the plane: the overlap rewrites equal values
+        goff = ((uint32_t)((n0 + i) * g.C + 8 * tg) * (uint32_t)g.HW + (uint32_t)e0) * 2u;
+        uint32_t l[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int flat = e0 + e;
+            uint32_t y, x;
+            g.div_W.divmod((uint32_t)flat, y, x);
+            int pp = (slot_so[i] + (int)y + g.ph - slot_ra[i]) * g.Wp + (int)x + g.pw;
+            l[e] = (flat >= ea && flat < eb) ? (uint32_t)(tg * PATCH_PIX + pp) : NO_PIX;
+        }
+        l01 = l[0] | (l[1] << 16), l23 = l[2] | (l[3] << 16), l45 = l[4] | (l[5] << 16), l67 = l[6] | (l[7] << 16);
+    }
+
+    u32x4 r0, r1, r2, r3, r4, r5, r6, r7;  // 8 channels x 8 elements
+    const char *xb = reinterpret_cast<const char *>(X);
+    const uint32_t plane_b = (uint32_t)g.HW * 2u, chunk_b = plane_b * CH;
+    auto issue_patch = [&](int chunk) {
+        const char *p = xb + (goff + (uint32_t)chunk * chunk_b);  // threads without a task read a valid address too
+        __builtin_memcpy(&r0, p, 16);
+        __builtin_memcpy(&r1, p + plane_b, 16);
+        __builtin_memcpy(&r2, p + 2 * plane_b, 16);
+        __builtin_memcpy(&r3, p + 3 * plane_b, 16);
+        __builtin_memcpy(&r4, p + 4 * plane_b, 16);
+        __builtin_memcpy(&r5, p + 5 * plane_b, 16);
+        __builtin_memcpy(&r6, p + 6 * plane_b, 16);
+        __builtin_memcpy(&r7, p + 7 * plane_b, 16);
+    };
+    auto commit_patch = [&](int buf) {
+        u32x4 *dst = reinterpret_cast<u32x4 *>(patch) + buf * (NG * PATCH_PIX);
+        uint32_t l;
+        // element e of the 8 x 8 block as one pack: the 8 channels of that pixel
+        l = l01 & 0xffffu; if (l != NO_PIX) dst[l] = u32x4{lo16(r0[0], r1[0]), lo16(r2[0], r3[0]), lo16(r4[0], r5[0]), lo16(r6[0], r7[0])};
+        l = l01 >> 16;     if (l != NO_PIX) dst[l] = u32x4{hi16(r0[0], r1[0]), hi16(r2[0], r3[0]), hi16(r4[0], r5[0]), hi16(r6[0], r7[0])};
+        l = l23 & 0xffffu; if (l != NO_PIX) dst[l] = u32x4{lo16(r0[1], r1[1]), lo16(r2[1], r3[1]), lo16(r4[1], r5[1]), lo16(r6[1], r7[1])};
+        l = l23 >> 16;     if (l != NO_PIX) dst[l] = u32x4{hi16(r0[1], r1[1]), hi16(r2[1], r3[1]), hi16(r4[1], r5[1]), hi16(r6[1], r7[1])};
+        l = l45 & 0xffffu; if (l != NO_PIX) dst[l] = u32x4{lo16(r0[2], r1[2]), lo16(r2[2], r3[2]), lo16(r4[2], r5[2]), lo16(r6[2], r7[2])};
+        l = l45 >> 16;     if (l != NO_PIX) dst[l] = u32x4{hi16(r0[2], r1[2]), hi16(r2[2], r3[2]), hi16(r4[2], r5[2]), hi16(r6[2], r7[2])};
+        l = l67 & 0xffffu; if (l != NO_PIX) dst[l] = u32x4{lo16(r0[3], r1[3]), lo16(r2[3], r3[3]), lo16(r4[3], r5[3]), lo16(r6[3], r7[3])};
+        l = l67 >> 16;     if (l != NO_PIX) dst[l] = u32x4{hi16(r0[3], r1[3]), hi16(r2[3], r3[3]), hi16(r4[3], r5[3]), hi16(r6[3], r7[3])};
+    };
+
+    // weight tile of reduction step st = chunk * KK + tap: [g][Fp] packs, contiguous per g
+    uint4 areg[A_PIECES];
+    const uint4 *wt = reinterpret_cast<const uint4 *>(Wt) + row0;
+    auto issue_a = [&](int st) {
+#pragma unroll
+        for (int q = 0; q < A_PIECES; ++q) {
+            int p = tid + q * NT;
+            int ag = p / BM, af = p % BM;
+            areg[q] = wt[(st * NG + ag) * g.Fp + af];
+        }
+    };
+    auto commit_a = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < A_PIECES; ++q) {
+            int p = tid + q * NT;
+            int ag = p / BM, af = p % BM;
+            atile[buf * (NG * LA) + ag * LA + af] = areg[q];
+        }
+    };
+
+    f32x16 acc[TI][TJ];
+#pragma unroll
+    for (int t = 0; t < TI; ++t)
+#pragma unroll
+        for (int u = 0; u < TJ; ++u)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
+
+    auto compute = [&](int abuf, int pbuf, int tapoff) {
+        const uint4 *pa = atile + abuf * (NG * LA) + wm * (BM / WM) + li;
+        const uint4 *pb = patch + pbuf * (NG * PATCH_PIX) + tapoff;
+#pragma unroll
+        for (int s = 0; s < NG / 2; ++s) {
+            const int g2 = 2 * s + h;
+            uint4 a[TI], b[TJ];
+#pragma unroll
+            for (int t = 0; t < TI; ++t) a[t] = pa[g2 * LA + 32 * t];
+#pragma unroll
+            for (int u = 0; u < TJ; ++u) b[u] = pb[g2 * PATCH_PIX + pp0[u]];
+#pragma unroll
+            for (int t = 0; t < TI; ++t)
+#pragma unroll
+                for (int u = 0; u < TJ; ++u) Mma<bf16_t>::run(a[t], b[u], acc[t][u]);
+        }
+    };
+
+    // Step st = (chunk, tap) computes from weight buffer st & 1 and patch buffer chunk & 1.  The next
+    // step's weight tile is loaded during the step; the next chunk's pixels are loaded during the chunk's
+    // first tap and written to the other patch buffer during its last.
+    const int KK = g.KK, n_steps = g.n_chunks * KK;
+    issue_patch(0);
+    issue_a(0);
+    commit_patch(0);
+    commit_a(0);
+    __syncthreads();
+    int chunk = 0, tap = 0, ky = 0, kx = 0;
+    for (int st = 0; st < n_steps; ++st) {
+        const bool more = st + 1 < n_steps, more_chunks = chunk + 1 < g.n_chunks;
+        if (more) issue_a(st + 1);
+        if (tap == 0 && more_chunks) issue_patch(chunk + 1);
+        compute(st & 1, chunk & 1, ky * g.Wp + kx);
+        if (more) commit_a((st + 1) & 1);
+        if (tap == KK - 1 && more_chunks) commit_patch((chunk + 1) & 1);
+        __syncthreads();
+        if (++kx == g.kw) kx = 0, ++ky;
+        if (++tap == KK) tap = 0, ky = 0, ++chunk;
+    }
+
+    // every wavefront is past the loop's last barrier: the patch buffers become staging space
+    constexpr int STRIP = 16 * staged_pitch(TJ);
+    static_assert((NT / 64) * STRIP <= (int)sizeof(patch), "staging strips fit in the patch buffers");
+    store_tile_staged<TI, TJ, 16>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, 0, epi,
+                                  reinterpret_cast<char *>(patch) + wave * STRIP, lds_add, row0);
+}
+
+// Weights [out][in][kh][kw] (forward) or [in][out][kh][kw] read flipped (data gradient) -> the kernel's
+// order [chunk][tap][g][Fp][8]: pack (chunk, tap, g, row) = input channels chunk*32 + 8g .. +7 of output
+// channel `row` at window tap `tap`; rows beyond F are zero.  One thread per pack.
+__global__ void pack_weights_kernel(const bf16_t *__restrict__ W, uint4 *__restrict__ Wt, int F, int Fp, int KK,
+                                    int n_chunks, int64_t stride_out, int64_t stride_in, int flip)
+{
+    int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (int64_t)n_chunks * KK * NG * Fp;
+    if (p >= total) return;
+    int row = (int)(p % Fp);
+    int64_t t = p / Fp;
+    int gq = (int)(t % NG);
+    t /= NG;
+    int tap = (int)(t % KK), chunk = (int)(t / KK);
+    uint32_t v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        int c = chunk * CH + gq * 8 + j;
+        int src_tap = flip ? KK - 1 - tap : tap;
+        v[j] = row < F ? (uint32_t)W[row * stride_out + c * stride_in + src_tap] : 0u;
+    }
+    Wt[p] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+}
+
+static int row_tile(int F)
+{
+    const char *e = getenv("OMNI_FUSED_TILE");  // tuning override: 128 or 256
+    if (e != nullptr && (atoi(e) == 128 || atoi(e) == 256)) return atoi(e);
+    return round_up(F, 128) < round_up(F, 256) ? 128 : 256;
+}
+
+// The convolution as this kernel sees it; for the data gradient the layer's output gradient is the
+// input and the window is flipped.
+static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
+{
+    if (c.sh != 1 || c.sw != 1) return false;
+    if (!data_gradient) {
+        g->N = c.N, g->C = c.C, g->H = c.H, g->W = c.W, g->F = c.F, g->Ho = c.Ho, g->Wo = c.Wo;
+        g->ph = c.ph, g->pw = c.pw;
+    } else {
+        g->N = c.N, g->C = c.F, g->H = c.Ho, g->W = c.Wo, g->F = c.C, g->Ho = c.H, g->Wo = c.W;
+        g->ph = c.kh - 1 - c.ph, g->pw = c.kw - 1 - c.pw;
+        if (g->ph < 0 || g->pw < 0) return false;
+    }
+    g->kh = c.kh, g->kw = c.kw;
+    g->Wp = g->W + 2 * g->pw;
+    g->HW = g->H * g->W, g->HoWo = g->Ho * g->Wo, g->KK = c.kh * c.kw;
+    int64_t M = (int64_t)g->N * g->HoWo;
+    if (g->C % CH != 0 || g->HW < 8 || M > 0x7fffffffll - 4096) return false;
+    if ((double)g->N * g->C * g->HW * 2.0 >= 4.0e9 || (double)M * g->F * 2.0 >= 4.0e9) return false;
+    g->M = (int32_t)M;
+    g->n_chunks = g->C / CH;
+    int bm = row_tile(g->F);
+    g->Fp = (int32_t)round_up(g->F, bm);
+    g->tiles_f = g->Fp / bm;
+    g->tiles_m = (g->M + BN - 1) / BN;
+    g->n_items = g->tiles_f * g->tiles_m;
+    g->per_xcd = (g->n_items + 7) / 8;
+    g->div_HoWo = FastDiv((uint32_t)g->HoWo);
+    g->div_Wo = FastDiv((uint32_t)g->Wo);
+    g->div_W = FastDiv((uint32_t)g->W);
+    // every column tile must fit the kernel's fixed LDS patch and its one-task-per-thread loader
+    // (the tiles' positions inside an image repeat with period HoWo / gcd(BN, HoWo))
+    int a = BN, b = g->HoWo;
+    while (b != 0) { int t = a % b; a = b, b = t; }
+    int period = g->HoWo / a + 1;
+    for (int tm = 0; tm < g->tiles_m && tm < period; ++tm) {
+        int col0 = tm * BN, m_last = (col0 + BN < g->M ? col0 + BN : g->M) - 1;
+        int n0 = col0 / g->HoWo, n1 = m_last / g->HoWo;
+        if (n1 - n0 + 1 > MAX_SLOTS) return false;
+        int rows = 0, pieces = 0;
+        for (int n = n0; n <= n1; ++n) {
+            SlotSpan s = slot_span(*g, col0, m_last, n);
+            rows += s.nrows;
+            pieces += (s.len + 7) / 8;
+        }
+        if (rows * g->Wp > PATCH_PIX || NG * pieces > NT) return false;
+    }
+    return true;
+}
+
+}  // namespace fused
+
+bool fused_supported(const ConvGeom &c, int dtype, bool data_gradient)
+{
+    fused::Geom g;
+    return dtype == OMNI_BF16 && fused::make_fused_geom(c, data_gradient, &g);
+}
+
+size_t fused_weight_bytes(const ConvGeom &c, bool data_gradient)
+{
+    fused::Geom g;
+    if (!fused::make_fused_geom(c, data_gradient, &g)) return 0;
+    return (size_t)g.n_chunks * g.KK * fused::NG * g.Fp * 16;
+}
+
+int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, const void *W, const float *bias,
+                      int relu, void *Y, void *wt_scratch, hipStream_t s)
+{
+    using namespace fused;
+    Geom g;
+    if (!make_fused_geom(c, data_gradient, &g)) return OMNI_UNSUPPORTED;
+    {
+        ProfScope prof(KID_PACK_KHAT, s, 0.0, 2.0 * (double)c.F * c.K * 2.0);
+        int64_t total = (int64_t)g.n_chunks * g.KK * NG * g.Fp;
+        int64_t so = data_gradient ? g.KK : (int64_t)g.C * g.KK, si = data_gradient ? (int64_t)g.F * g.KK : g.KK;
+        hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const bf16_t *)W, (uint4 *)wt_scratch, g.F, g.Fp, g.KK, g.n_chunks, so, si,
+                           data_gradient ? 1 : 0);
+        OMNI_LAUNCH_CHECK();
+    }
+    FwdEpilogue<bf16_t> epi{(bf16_t *)Y, bias, g.F, g.M, g.HoWo, g.div_HoWo, relu};
+    ProfScope prof(data_gradient ? KID_FUSED_DGRAD : KID_FUSED_FWD, s, 2.0 * (double)c.M * c.K * c.F, 0.0);
+    dim3 grid((unsigned)(g.per_xcd * 8)), block(NT);
+    if (g.Fp / g.tiles_f == 128)
+        hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4>), grid, block, 0, s, (const bf16_t *)X,
+                           (const bf16_t *)wt_scratch, g, epi);
+    else
+        hipLaunchKernelGGL((fused_conv_kernel<256, 4, 2>), grid, block, 0, s, (const bf16_t *)X,
+                           (const bf16_t *)wt_scratch, g, epi);
+    OMNI_LAUNCH_CHECK();
+    return OMNI_OK;
+}
+
+}  // namespace omni

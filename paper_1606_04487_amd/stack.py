@@ -22,16 +22,20 @@ from .workloads import ConvLayer
 
 class ConvStack:
     def __init__(self, layers: Sequence[ConvLayer], dtype: int = B.F32, ceil_mode: bool = True,
-                 skip_first_dgrad: bool = True, device: str = "cuda"):
+                 skip_first_dgrad: bool = True, device: str = "cuda", fused: bool = True):
         self.layers = list(layers)
         self.dtype = dtype
         self.tdtype = B.torch_dtype(dtype)
         self.ceil_mode = ceil_mode
         self.skip_first_dgrad = skip_first_dgrad   # App. B: the first layer needs no data gradient
         self.device = device
-        self.desc = [B.conv_desc(L.N, L.C, L.H, L.W, L.F, L.k, L.k, L.s, L.p, dtype, B.FLAG_RELU)
+        # fused = let the library skip D-hat / dD-hat where it can (App. C: fusing lowering and GEMM);
+        # the model gradient then lowers X itself instead of finding D-hat cached by the forward pass
+        extra = B.FLAG_FUSED if fused else 0
+        self.desc = [B.conv_desc(L.N, L.C, L.H, L.W, L.F, L.k, L.k, L.s, L.p, dtype, B.FLAG_RELU | extra)
                      for L in self.layers]
-        self.desc_cached = [d.with_flags(B.FLAG_DHAT_CACHED) for d in self.desc]
+        self.fwd_fused = [fused and B.conv_fused_supported(d, B.PASS_FORWARD) for d in self.desc]
+        self.desc_wgrad = [d.with_flags(0 if ff else B.FLAG_DHAT_CACHED) for d, ff in zip(self.desc, self.fwd_fused)]
         # parameters: fp32 masters, velocity, gradients; bf16 copies of W for the bf16 passes
         self.W = [torch.zeros((L.F, L.C, L.k, L.k), dtype=torch.float32, device=device) for L in self.layers]
         self.b = [torch.zeros((L.F,), dtype=torch.float32, device=device) for L in self.layers]
@@ -101,7 +105,7 @@ class ConvStack:
                 B.maxpool_relu_backward(g, self.A[i], Y, 3, 2, self.ceil_mode, self.dYc[i])
             else:
                 B.relu_backward(Y, g, self.dYc[i])
-            B.conv_backward_weights(self.desc_cached[i], self.X[i], self.dYc[i], self.dW[i], self.db[i],
+            B.conv_backward_weights(self.desc_wgrad[i], self.X[i], self.dYc[i], self.dW[i], self.db[i],
                                     self.ws_layer[i])
             if self.dXl[i] is None:
                 return None

@@ -1,0 +1,151 @@
+"""GPU parity of the fused path (OMNI_FLAG_FUSED): forward and data gradient without D-hat in memory.
+
+Same bar as the explicit path: bf16 storage, tensor-normalised error <= 2e-2 against the fp64 oracle on
+identical bf16-representable inputs; and, because both paths add the same products in fp32 (in a
+different order), the two GPU paths must agree with each other far more tightly than with the oracle's
+tolerance.  Shapes cover several column tiles with a ragged last one, tiles that straddle images, a
+second (nearly empty) row tile, non-square images and windows, padding 0 .. k-1, a 1 x 1 window, and
+shapes the fused kernel must decline (stride 2, channels not a multiple of 32, fp32).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1606_04487_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+BF16 = 1
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1606_04487_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def gpu(a, bf16=True):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if bf16 else t
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def rel_err(got, ref):
+    scale = np.max(np.abs(ref))
+    return np.max(np.abs(got - ref)) / (scale if scale > 0 else 1.0)
+
+
+# (N, C, H, W, F, kh, kw, ph, pw), stride 1
+FUSED_SHAPES = [
+    (6, 32, 13, 13, 40, 3, 3, 1, 1),      # tiles straddle images; F = 40
+    (3, 64, 27, 27, 130, 5, 5, 2, 2),     # conv2-like; F = 130: second row tile nearly empty
+    (20, 32, 8, 8, 64, 5, 5, 2, 2),       # CIFAR conv3-like: four images per tile
+    (3, 32, 9, 11, 32, 3, 2, 0, 1),       # non-square image and window, no vertical padding
+    (2, 64, 7, 5, 32, 3, 3, 2, 2),        # padding k - 1 (the data gradient then has none)
+    (5, 32, 6, 6, 8, 1, 1, 0, 0),         # 1 x 1 window
+    (1, 32, 3, 3, 8, 3, 3, 1, 1),         # a single 9-pixel image
+    (2, 96, 27, 27, 256, 5, 5, 2, 2),     # conv2 at its real channel counts
+    (4, 256, 13, 13, 384, 3, 3, 1, 1),    # conv3 at its real channel counts (F = 384: three 128-row tiles)
+]
+
+
+def make(cfg, seed):
+    N, C, H, W, F, kh, kw, ph, pw = cfg
+    s = oracle.shape(N, C, H, W, F, kh, kw, (1, 1), (ph, pw))
+    ho, wo = oracle.out_dims(s)
+    rng = np.random.default_rng(seed)
+    X = wl.to_bf16_values(rng.standard_normal((N, C, H, W)))
+    Wt = wl.to_bf16_values(0.05 * rng.standard_normal((F, C, kh, kw)))
+    b = (0.05 * rng.standard_normal(F)).astype(np.float32)
+    dY = wl.to_bf16_values(rng.standard_normal((N, F, ho, wo)))
+    return s, X, Wt, b, dY
+
+
+def desc_of(B, cfg, flags):
+    N, C, H, W, F, kh, kw, ph, pw = cfg
+    return B.conv_desc(N, C, H, W, F, kh, kw, (1, 1), (ph, pw), BF16, flags)
+
+
+@pytest.mark.parametrize("cfg", FUSED_SHAPES)
+def test_fused_forward(B, cfg):
+    s, X, Wt, b, _ = make(cfg, 11)
+    d = desc_of(B, cfg, B.FLAG_FUSED)
+    assert B.conv_fused_supported(d, B.PASS_FORWARD)
+    Xg, Wg, bg = gpu(X), gpu(Wt), gpu(b, False)
+    ref = oracle.conv_forward(s, X, Wt, b)
+    got = host(B.conv_forward(d, Xg, Wg, bg))
+    assert rel_err(got, ref) <= TOL
+    explicit = host(B.conv_forward(desc_of(B, cfg, 0), Xg, Wg, bg))
+    assert rel_err(got, explicit) <= 1e-2          # one bf16 rounding step apart at most
+    assert np.mean(got == explicit) > 0.9          # and nearly always the same rounding
+    got_nb = host(B.conv_forward(d, Xg, Wg, None))
+    assert rel_err(got_nb, oracle.conv_forward(s, X, Wt, None)) <= TOL
+    got_relu = host(B.conv_forward(desc_of(B, cfg, B.FLAG_FUSED | B.FLAG_RELU), Xg, Wg, bg))
+    assert rel_err(got_relu, np.maximum(ref, 0)) <= TOL and got_relu.min() >= 0
+    again = host(B.conv_forward(d, Xg, Wg, bg))
+    assert np.array_equal(got, again)              # deterministic
+
+
+@pytest.mark.parametrize("cfg", FUSED_SHAPES)
+def test_fused_backward_data(B, cfg):
+    N, C, H, W, F, kh, kw, ph, pw = cfg
+    if F % 32 != 0:
+        # the data gradient reduces over F: declined, and the flag must fall back to the explicit path
+        d = desc_of(B, cfg, B.FLAG_FUSED)
+        assert not B.conv_fused_supported(d, B.PASS_BACKWARD_DATA)
+    s, X, Wt, b, dY = make(cfg, 12)
+    d = desc_of(B, cfg, B.FLAG_FUSED)
+    dYg, Wg = gpu(dY), gpu(Wt)
+    ref = oracle.conv_backward_data(s, dY, Wt)
+    got = host(B.conv_backward_data(d, dYg, Wg))
+    assert rel_err(got, ref) <= TOL
+    explicit = host(B.conv_backward_data(desc_of(B, cfg, 0), dYg, Wg))
+    assert rel_err(got, explicit) <= 1e-2
+    again = host(B.conv_backward_data(d, dYg, Wg))
+    assert np.array_equal(got, again)
+
+
+def test_fused_declines_and_falls_back(B):
+    # stride 2, channels not a multiple of 32, fp32: the flag is accepted and the explicit path runs
+    for cfg, dtype in [((2, 32, 9, 9, 8, 3, 3, 2, 2, 1, 1), 1), ((2, 20, 9, 9, 8, 3, 3, 1, 1, 1, 1), 1),
+                       ((2, 32, 9, 9, 8, 3, 3, 1, 1, 1, 1), 0)]:
+        N, C, H, W, F, kh, kw, sh, sw, ph, pw = cfg
+        d = B.conv_desc(N, C, H, W, F, kh, kw, (sh, sw), (ph, pw), dtype, B.FLAG_FUSED)
+        assert not B.conv_fused_supported(d, B.PASS_FORWARD)
+        assert not B.conv_fused_supported(d, B.PASS_BACKWARD_WEIGHTS)
+        s = oracle.shape(N, C, H, W, F, kh, kw, (sh, sw), (ph, pw))
+        rng = np.random.default_rng(3)
+        X = rng.standard_normal((N, C, H, W))
+        Wt = 0.05 * rng.standard_normal((F, C, kh, kw))
+        if dtype == 1:
+            X, Wt = wl.to_bf16_values(X), wl.to_bf16_values(Wt)
+        else:
+            X, Wt = X.astype(np.float32), Wt.astype(np.float32)
+        got = host(B.conv_forward(d, gpu(X, dtype == 1), gpu(Wt, dtype == 1), None))
+        assert rel_err(got, oracle.conv_forward(s, X, Wt, None)) <= (TOL if dtype == 1 else 1e-4)
+
+
+def test_fused_stack_matches_explicit_stack(B):
+    """The chained CIFAR-shaped stack in bf16: fused and explicit runs agree on outputs and gradients."""
+    from paper_1606_04487_amd.stack import ConvStack
+    layers = wl.cifar_stack(16)
+    t = wl.stack_tensors(layers, seed=5, bf16=True, pooled_out=(4, 4))
+    Ws, bs, X, dOut = t["W"], t["bias"], t["X"], t["dY"]
+    res = []
+    for fused in (False, True):
+        st = ConvStack(layers, dtype=B.BF16, ceil_mode=True, skip_first_dgrad=False, fused=fused)
+        st.set_parameters(Ws, bs)
+        out = st.forward(gpu(X))
+        dx = st.backward(gpu(dOut))
+        res.append((host(out), host(dx), [host(w) for w in st.dW], st.fwd_fused))
+    assert res[1][3][1] and res[1][3][2] and not res[1][3][0]   # conv2, conv3 fused; conv1 (C = 3) not
+    assert rel_err(res[1][0], res[0][0]) <= 2e-2
+    assert rel_err(res[1][1], res[0][1]) <= 3e-2
+    for a, b in zip(res[1][2], res[0][2]):
+        assert rel_err(a, b) <= 3e-2

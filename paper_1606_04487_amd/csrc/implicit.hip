@@ -13,12 +13,19 @@
 // counts exchanged, the window flipped and padding k - 1 - p (the col2im sum, written as a gather), so
 // it runs on the same kernel and needs neither dD-hat nor a scatter step.
 //
-// LDS layout: patch[buffer][g][pixel] and atile[buffer][g][row] of 16-byte packs, pack g holding channels
+// LDS layout: patch[g][pixel] and atile[tap][g][row] of 16-byte packs, pack g holding channels
 // 8g .. 8g+7 of the chunk, so a fragment is one 16-byte read per lane and consecutive lanes (consecutive
 // pixels or rows) read consecutive packs.  Pixels are transposed from the input's [channel][pixel]
 // order in registers on their way into LDS (8 channels x 8 pixels per thread).  Padding pixels are
 // zeroed once: the patch layout is the same for every chunk, and loads only ever write real pixels.
+//
+// Schedule: the weights of up to TG window taps are staged in LDS together, so a workgroup runs TG taps
+// (TG x 8 MFMAs per wavefront) between synchronisation points.  While it does, the next group's weights
+// and -- during a chunk's first group -- the next chunk's pixels are in flight into registers; at the
+// group's end one barrier retires the readers, the registers go to LDS, a second barrier publishes them.
+// Every request is therefore waited for at one place only, a whole group after it was issued.
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 #include "mma_epilogue.h"
@@ -30,7 +37,8 @@ constexpr int CH = 32;           // channels per reduction chunk
 constexpr int NG = CH / 8;       // 16-byte packs per pixel and chunk
 constexpr int NT = 512;          // 8 wavefronts
 constexpr int BN = 256;          // columns (output pixels) per workgroup
-constexpr int PATCH_PIX = 640;   // capacity of a patch buffer in pixels
+constexpr int PATCH_PIX = 640;   // capacity of the patch in pixels
+constexpr int TG = 9;            // window taps whose weights are staged in LDS together
 constexpr int MAX_SLOTS = 8;     // images a column tile may touch
 constexpr uint32_t NO_PIX = 0xffffu;
 
@@ -68,20 +76,34 @@ __host__ __device__ inline SlotSpan slot_span(const Geom &g, int col0, int m_las
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Patch pixels are stored at swz(pixel): a loader thread writes 8 consecutive pixels and its neighbour the
+// next 8, so without the permutation every lane of a store would fall on the same two bank groups.  The
+// permutation stays inside aligned blocks of 8, so a run of consecutive pixels read by consecutive lanes
+// still covers all banks.
+__device__ __forceinline__ int swz(int pix) { return pix ^ ((pix >> 4) & 7); }
+
 __device__ __forceinline__ uint32_t lo16(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t hi16(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+
+// Compile-time loop: the body receives std::integral_constant<int, I>.
+template <int I, int N, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
 
 template <int BM, int WM, int WN>
 __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Wt,
                                                         Geom g, FwdEpilogue<bf16_t> epi)
 {
     static_assert(WM * WN * 64 == NT, "eight wavefronts");
+    static_assert(BM * NG == NT, "one 16-byte piece of a tap's weight tile per thread");
     constexpr int TI = BM / WM / 32, TJ = BN / WN / 32;
     constexpr int LA = BM + 1;
-    constexpr int A_PIECES = BM * NG / NT;
-    static_assert(BM * NG % NT == 0, "weight tile divides over the threads");
-    __shared__ uint4 patch[2 * NG * PATCH_PIX];
-    __shared__ uint4 atile[2 * NG * LA];
+    __shared__ uint4 patch[NG * PATCH_PIX];
+    __shared__ uint4 atile[TG * NG * LA];
     __shared__ float lds_add[BM];
     __shared__ int slot_so[MAX_SLOTS], slot_ra[MAX_SLOTS], slot_p0[MAX_SLOTS], slot_ya[MAX_SLOTS], slot_len[MAX_SLOTS];
     __shared__ int total_pieces;
@@ -110,7 +132,7 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         }
         total_pieces = p0;
     }
-    for (int i = tid; i < 2 * NG * PATCH_PIX; i += NT) patch[i] = make_uint4(0, 0, 0, 0);
+    for (int i = tid; i < NG * PATCH_PIX; i += NT) patch[i] = make_uint4(0, 0, 0, 0);
     for (int i = tid; i < BM; i += NT) lds_add[i] = epi.row_add(row0 + i);
     __syncthreads();
 
@@ -147,7 +169,7 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
             uint32_t y, x;
             g.div_W.divmod((uint32_t)flat, y, x);
             int pp = (slot_so[i] + (int)y + g.ph - slot_ra[i]) * g.Wp + (int)x + g.pw;
-            l[e] = (flat >= ea && flat < eb) ? (uint32_t)(tg * PATCH_PIX + pp) : NO_PIX;
+            l[e] = (flat >= ea && flat < eb) ? (uint32_t)(tg * PATCH_PIX + swz(pp)) : NO_PIX;
         }
         l01 = l[0] | (l[1] << 16), l23 = l[2] | (l[3] << 16), l45 = l[4] | (l[5] << 16), l67 = l[6] | (l[7] << 16);
     }
@@ -166,8 +188,8 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         __builtin_memcpy(&r6, p + 6 * plane_b, 16);
         __builtin_memcpy(&r7, p + 7 * plane_b, 16);
     };
-    auto commit_patch = [&](int buf) {
-        u32x4 *dst = reinterpret_cast<u32x4 *>(patch) + buf * (NG * PATCH_PIX);
+    auto commit_patch = [&]() {
+        u32x4 *dst = reinterpret_cast<u32x4 *>(patch);
         uint32_t l;
         // element e of the 8 x 8 block as one pack: the 8 channels of that pixel
         l = l01 & 0xffffu; if (l != NO_PIX) dst[l] = u32x4{lo16(r0[0], r1[0]), lo16(r2[0], r3[0]), lo16(r4[0], r5[0]), lo16(r6[0], r7[0])};
@@ -180,24 +202,30 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         l = l67 >> 16;     if (l != NO_PIX) dst[l] = u32x4{hi16(r0[3], r1[3]), hi16(r2[3], r3[3]), hi16(r4[3], r5[3]), hi16(r6[3], r7[3])};
     };
 
-    // weight tile of reduction step st = chunk * KK + tap: [g][Fp] packs, contiguous per g
-    uint4 areg[A_PIECES];
-    const uint4 *wt = reinterpret_cast<const uint4 *>(Wt) + row0;
-    auto issue_a = [&](int st) {
-#pragma unroll
-        for (int q = 0; q < A_PIECES; ++q) {
-            int p = tid + q * NT;
-            int ag = p / BM, af = p % BM;
-            areg[q] = wt[(st * NG + ag) * g.Fp + af];
-        }
+    // The weight tile of reduction step st = chunk * KK + tap is [g][Fp] packs, contiguous per g; this
+    // thread moves pack (tid / BM, row0 + tid % BM) of each of a group's TG tiles.  Requests are
+    // unconditional: steps past the group's (or the reduction's) end repeat a valid tile that nobody reads.
+    static_assert(TG == 9, "named staging registers below");
+    u32x4 a0, a1, a2, a3, a4, a5, a6, a7, a8;  // named so that each stays a register
+    auto areg = [&](auto q) -> u32x4 & {
+        constexpr int Q = decltype(q)::value;
+        if constexpr (Q == 0) return a0; else if constexpr (Q == 1) return a1; else if constexpr (Q == 2) return a2;
+        else if constexpr (Q == 3) return a3; else if constexpr (Q == 4) return a4; else if constexpr (Q == 5) return a5;
+        else if constexpr (Q == 6) return a6; else if constexpr (Q == 7) return a7; else return a8;
     };
-    auto commit_a = [&](int buf) {
-#pragma unroll
-        for (int q = 0; q < A_PIECES; ++q) {
-            int p = tid + q * NT;
-            int ag = p / BM, af = p % BM;
-            atile[buf * (NG * LA) + ag * LA + af] = areg[q];
-        }
+    const int KK = g.KK, n_steps = g.n_chunks * KK;
+    const u32x4 *wt = reinterpret_cast<const u32x4 *>(Wt) + (row0 + (tid / BM) * g.Fp + tid % BM);
+    const int step_stride = NG * g.Fp;  // packs from one step's tile to the next
+    u32x4 *const at = reinterpret_cast<u32x4 *>(atile) + (tid / BM) * LA + tid % BM;
+    auto issue_a = [&](int st0) {
+        static_for<0, TG>([&](auto q) {
+            int st = st0 + decltype(q)::value;
+            st = st < n_steps ? st : n_steps - 1;
+            areg(q) = wt[st * step_stride];
+        });
+    };
+    auto commit_a = [&]() {
+        static_for<0, TG>([&](auto q) { at[decltype(q)::value * (NG * LA)] = areg(q); });
     };
 
     f32x16 acc[TI][TJ];
@@ -208,9 +236,11 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
 
-    auto compute = [&](int abuf, int pbuf, int tapoff) {
-        const uint4 *pa = atile + abuf * (NG * LA) + wm * (BM / WM) + li;
-        const uint4 *pb = patch + pbuf * (NG * PATCH_PIX) + tapoff;
+    auto compute = [&](int slot, int tapoff) {
+        const uint4 *pa = atile + slot * (NG * LA) + wm * (BM / WM) + li;
+        int pix[TJ];
+#pragma unroll
+        for (int u = 0; u < TJ; ++u) pix[u] = swz(pp0[u] + tapoff);
 #pragma unroll
         for (int s = 0; s < NG / 2; ++s) {
             const int g2 = 2 * s + h;
@@ -218,7 +248,7 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
 #pragma unroll
             for (int t = 0; t < TI; ++t) a[t] = pa[g2 * LA + 32 * t];
 #pragma unroll
-            for (int u = 0; u < TJ; ++u) b[u] = pb[g2 * PATCH_PIX + pp0[u]];
+            for (int u = 0; u < TJ; ++u) b[u] = patch[g2 * PATCH_PIX + pix[u]];
 #pragma unroll
             for (int t = 0; t < TI; ++t)
 #pragma unroll
@@ -226,33 +256,36 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         }
     };
 
-    // Step st = (chunk, tap) computes from weight buffer st & 1 and patch buffer chunk & 1.  The next
-    // step's weight tile is loaded during the step; the next chunk's pixels are loaded during the chunk's
-    // first tap and written to the other patch buffer during its last.
-    const int KK = g.KK, n_steps = g.n_chunks * KK;
     issue_patch(0);
     issue_a(0);
-    commit_patch(0);
-    commit_a(0);
+    commit_patch();
+    commit_a();
     __syncthreads();
-    int chunk = 0, tap = 0, ky = 0, kx = 0;
-    for (int st = 0; st < n_steps; ++st) {
-        const bool more = st + 1 < n_steps, more_chunks = chunk + 1 < g.n_chunks;
-        if (more) issue_a(st + 1);
-        if (tap == 0 && more_chunks) issue_patch(chunk + 1);
-        compute(st & 1, chunk & 1, ky * g.Wp + kx);
-        if (more) commit_a((st + 1) & 1);
-        if (tap == KK - 1 && more_chunks) commit_patch((chunk + 1) & 1);
-        __syncthreads();
-        if (++kx == g.kw) kx = 0, ++ky;
-        if (++tap == KK) tap = 0, ky = 0, ++chunk;
+    int ky = 0, kx = 0;
+    for (int chunk = 0; chunk < g.n_chunks; ++chunk) {
+        const bool more_chunks = chunk + 1 < g.n_chunks;
+        for (int t0 = 0; t0 < KK; t0 += TG) {
+            const int nt = KK - t0 < TG ? KK - t0 : TG;
+            const bool last_group = t0 + TG >= KK;
+            issue_a(chunk * KK + t0 + nt);                     // the next group (of this chunk or the next)
+            if (t0 == 0 && more_chunks) issue_patch(chunk + 1);
+            for (int t = 0; t < nt; ++t) {
+                compute(t, ky * g.Wp + kx);
+                if (++kx == g.kw) kx = 0, ++ky;
+            }
+            if (last_group) ky = 0;
+            __syncthreads();  // every wavefront has read this group's weights (and, after a chunk's last group, its pixels)
+            commit_a();
+            if (last_group && more_chunks) commit_patch();
+            __syncthreads();
+        }
     }
 
-    // every wavefront is past the loop's last barrier: the patch buffers become staging space
+    // every wavefront is past the loop's last barrier: the weight tiles become staging space
     constexpr int STRIP = 16 * staged_pitch(TJ);
-    static_assert((NT / 64) * STRIP <= (int)sizeof(patch), "staging strips fit in the patch buffers");
+    static_assert((NT / 64) * STRIP <= (int)sizeof(atile), "staging strips fit in the weight tiles");
     store_tile_staged<TI, TJ, 16>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, 0, epi,
-                                  reinterpret_cast<char *>(patch) + wave * STRIP, lds_add, row0);
+                                  reinterpret_cast<char *>(atile) + wave * STRIP, lds_add, row0);
 }
 
 // Weights [out][in][kh][kw] (forward) or [in][out][kh][kw] read flipped (data gradient) -> the kernel's
@@ -279,12 +312,7 @@ __global__ void pack_weights_kernel(const bf16_t *__restrict__ W, uint4 *__restr
     Wt[p] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
 }
 
-static int row_tile(int F)
-{
-    const char *e = getenv("OMNI_FUSED_TILE");  // tuning override: 128 or 256
-    if (e != nullptr && (atoi(e) == 128 || atoi(e) == 256)) return atoi(e);
-    return round_up(F, 128) < round_up(F, 256) ? 128 : 256;
-}
+static int row_tile(int) { return 128; }
 
 // The convolution as this kernel sees it; for the data gradient the layer's output gradient is the
 // input and the window is flipped.
@@ -369,12 +397,8 @@ int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, cons
     FwdEpilogue<bf16_t> epi{(bf16_t *)Y, bias, g.F, g.M, g.HoWo, g.div_HoWo, relu};
     ProfScope prof(data_gradient ? KID_FUSED_DGRAD : KID_FUSED_FWD, s, 2.0 * (double)c.M * c.K * c.F, 0.0);
     dim3 grid((unsigned)(g.per_xcd * 8)), block(NT);
-    if (g.Fp / g.tiles_f == 128)
-        hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4>), grid, block, 0, s, (const bf16_t *)X,
-                           (const bf16_t *)wt_scratch, g, epi);
-    else
-        hipLaunchKernelGGL((fused_conv_kernel<256, 4, 2>), grid, block, 0, s, (const bf16_t *)X,
-                           (const bf16_t *)wt_scratch, g, epi);
+    hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4>), grid, block, 0, s, (const bf16_t *)X, (const bf16_t *)wt_scratch, g,
+                       epi);
     OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }

@@ -19,6 +19,15 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
+MFMA_KERNELS = ("gemm", "conv_fused")          # kernel classes bound by the matrix cores
+# HBM bytes per launch (fetched + written, averaged over the class's launches of one step) at the default
+# workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by the readings for
+# the 256 MiB calibration copy below; the summary and its commands are profiles/*_hbm_traffic.md.
+MEASURED_HBM_BYTES_PER_LAUNCH = {
+    ("bf16", 256): {"gemm_wgrad": 628.3e6, "gemm_forward": 714.2e6, "conv_fused_forward": 113.2e6,
+                    "conv_fused_dgrad": 113.2e6, "lower": 502.4e6, "maxpool_backward": 214.4e6,
+                    "pack_dyhat": 144.6e6, "reduce_partials": 88.4e6, "maxpool_forward": 122.6e6},
+}
 
 
 def cpu_baseline(sample_images: int):
@@ -71,6 +80,13 @@ def main():
     dOut = torch.from_numpy(data["dY"]).cuda().to(B.torch_dtype(dtype))
     lr, mu = 0.01, 0.9
 
+    # One plain device copy of known size (256 MiB read, 256 MiB written) before anything is timed: under
+    # rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the counters' units.
+    cal_src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    del cal_src, cal_dst
+
     for _ in range(args.warmup):
         stack.step(X, dOut, lr, mu)
     torch.cuda.synchronize()
@@ -92,22 +108,23 @@ def main():
         avg_ms = k["total_ms"] / k["launches"]
         row = {"launches_per_step": k["launches"] / args.steps, "avg_ms": avg_ms,
                "ms_per_step": k["total_ms"] / args.steps}
-        if k["flops"] > 0 and name.startswith("gemm"):
+        if k["flops"] > 0 and name.startswith(MFMA_KERNELS):
             row["tflops"] = k["flops"] / (k["total_ms"] * 1e-3) / 1e12
         row["gbs"] = k["bytes"] / (k["total_ms"] * 1e-3) / 1e9
         table[name] = row
     if table:
         dom = max(table, key=lambda n: table[n]["ms_per_step"])
         k = kernels[dom]
-        if dom.startswith("gemm"):
+        traffic = MEASURED_HBM_BYTES_PER_LAUNCH.get((args.dtype, args.batch), {}).get(dom)
+        if dom.startswith(MFMA_KERNELS):
             ach = table[dom]["tflops"]
             roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_TFLOPS[args.dtype],
-                    "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS[args.dtype], "traffic": None,
+                    "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS[args.dtype], "traffic": traffic,
                     "avg_launch_ms": table[dom]["avg_ms"], "flops_per_launch": k["flops"] / k["launches"]}
         else:
             ach = table[dom]["gbs"]
             roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_launch_ms": table[dom]["avg_ms"],
+                    "frac": ach / PEAK_HBM_GBS, "traffic": traffic, "avg_launch_ms": table[dom]["avg_ms"],
                     "bytes_per_launch": k["bytes"] / k["launches"]}
 
     cpu = cpu_baseline(args.cpu_sample) if args.cpu_sample > 0 else None

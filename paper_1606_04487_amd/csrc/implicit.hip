@@ -269,9 +269,21 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
             const bool last_group = t0 + TG >= KK;
             issue_a(chunk * KK + t0 + nt);                     // the next group (of this chunk or the next)
             if (t0 == 0 && more_chunks) issue_patch(chunk + 1);
-            for (int t = 0; t < nt; ++t) {
-                compute(t, ky * g.Wp + kx);
-                if (++kx == g.kw) kx = 0, ++ky;
+            if (nt == TG) {
+                // a full group as straight-line code: the compiler may start a tap's LDS reads under the
+                // previous tap's MFMAs
+                int off[TG];
+#pragma unroll
+                for (int t = 0; t < TG; ++t) {
+                    off[t] = ky * g.Wp + kx;
+                    if (++kx == g.kw) kx = 0, ++ky;
+                }
+                static_for<0, TG>([&](auto q) { compute(decltype(q)::value, off[decltype(q)::value]); });
+            } else {
+                for (int t = 0; t < nt; ++t) {
+                    compute(t, ky * g.Wp + kx);
+                    if (++kx == g.kw) kx = 0, ++ky;
+                }
             }
             if (last_group) ky = 0;
             __syncthreads();  // every wavefront has read this group's weights (and, after a chunk's last group, its pixels)

@@ -36,8 +36,11 @@ namespace fused {
 constexpr int CH = 32;           // channels per reduction chunk
 constexpr int NG = CH / 8;       // 16-byte packs per pixel and chunk
 constexpr int NT = 512;          // 8 wavefronts
-constexpr int BN = 256;          // columns (output pixels) per workgroup
-constexpr int PATCH_PIX = 640;   // capacity of the patch in pixels
+// Columns (output positions) per workgroup and the patch capacity in pixels that goes with them.  The wide
+// tile gives each wavefront 64 x 128 results: 6 instead of 8 LDS fragment reads per 8 MFMAs, and LDS
+// bandwidth is what caps this kernel.
+constexpr int BN_NARROW = 256, PATCH_NARROW = 640;
+constexpr int BN_WIDE = 512, PATCH_WIDE = 960;
 constexpr int TG = 9;            // window taps whose weights are staged in LDS together
 constexpr int MAX_SLOTS = 8;     // images a column tile may touch
 constexpr uint32_t NO_PIX = 0xffffu;
@@ -51,6 +54,7 @@ struct Geom {
     int32_t n_chunks;        // C / CH
     int32_t Fp;              // F rounded up to the row tile
     int32_t tiles_f, tiles_m, n_items, per_xcd;
+    int32_t bn;              // columns per workgroup: BN_NARROW or BN_WIDE
     FastDiv div_HoWo, div_Wo, div_W;
 };
 
@@ -94,7 +98,7 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
     }
 }
 
-template <int BM, int WM, int WN>
+template <int BM, int WM, int WN, int BN, int PATCH_PIX>
 __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Wt,
                                                         Geom g, FwdEpilogue<bf16_t> epi)
 {
@@ -269,7 +273,7 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
             const bool last_group = t0 + TG >= KK;
             issue_a(chunk * KK + t0 + nt);                     // the next group (of this chunk or the next)
             if (t0 == 0 && more_chunks) issue_patch(chunk + 1);
-            if (nt == TG) {
+            if (TJ <= 2 && nt == TG) {
                 // a full group as straight-line code: the compiler may start a tap's LDS reads under the
                 // previous tap's MFMAs
                 int off[TG];
@@ -350,29 +354,44 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
     int bm = row_tile(g->F);
     g->Fp = (int32_t)round_up(g->F, bm);
     g->tiles_f = g->Fp / bm;
-    g->tiles_m = (g->M + BN - 1) / BN;
-    g->n_items = g->tiles_f * g->tiles_m;
-    g->per_xcd = (g->n_items + 7) / 8;
     g->div_HoWo = FastDiv((uint32_t)g->HoWo);
     g->div_Wo = FastDiv((uint32_t)g->Wo);
     g->div_W = FastDiv((uint32_t)g->W);
-    // every column tile must fit the kernel's fixed LDS patch and its one-task-per-thread loader
-    // (the tiles' positions inside an image repeat with period HoWo / gcd(BN, HoWo))
-    int a = BN, b = g->HoWo;
-    while (b != 0) { int t = a % b; a = b, b = t; }
-    int period = g->HoWo / a + 1;
-    for (int tm = 0; tm < g->tiles_m && tm < period; ++tm) {
-        int col0 = tm * BN, m_last = (col0 + BN < g->M ? col0 + BN : g->M) - 1;
-        int n0 = col0 / g->HoWo, n1 = m_last / g->HoWo;
-        if (n1 - n0 + 1 > MAX_SLOTS) return false;
-        int rows = 0, pieces = 0;
-        for (int n = n0; n <= n1; ++n) {
-            SlotSpan s = slot_span(*g, col0, m_last, n);
-            rows += s.nrows;
-            pieces += (s.len + 7) / 8;
+    // Every column tile must fit the kernel's fixed LDS patch and its one-task-per-thread loader.
+    // (The tiles' positions inside an image repeat with period HoWo / gcd(bn, HoWo).)
+    auto fits = [&](int bn, int patch_pix) {
+        int tiles_m = (g->M + bn - 1) / bn;
+        int a = bn, b = g->HoWo;
+        while (b != 0) { int t = a % b; a = b, b = t; }
+        int period = g->HoWo / a + 1;
+        for (int tm = 0; tm < tiles_m && tm < period; ++tm) {
+            int col0 = tm * bn, m_last = (col0 + bn < g->M ? col0 + bn : g->M) - 1;
+            int n0 = col0 / g->HoWo, n1 = m_last / g->HoWo;
+            if (n1 - n0 + 1 > MAX_SLOTS) return false;
+            int rows = 0, pieces = 0;
+            for (int n = n0; n <= n1; ++n) {
+                SlotSpan s = slot_span(*g, col0, m_last, n);
+                rows += s.nrows;
+                pieces += (s.len + 7) / 8;
+            }
+            if (rows * g->Wp > patch_pix || NG * pieces > NT) return false;
         }
-        if (rows * g->Wp > PATCH_PIX || NG * pieces > NT) return false;
-    }
+        return true;
+    };
+    // The wide tile when it fits and fills the 256 compute units' rounds about as well as the narrow one.
+    const char *e = getenv("OMNI_FUSED_BN");  // tuning override: 256 or 512
+    int want = e != nullptr ? atoi(e) : 0;
+    auto fill = [&](int bn) {
+        int64_t items = (int64_t)g->tiles_f * ((g->M + bn - 1) / bn);
+        return (double)items / (double)((items + 255) / 256 * 256);
+    };
+    bool wide = fits(BN_WIDE, PATCH_WIDE) &&
+                (want == BN_WIDE || (want != BN_NARROW && fill(BN_WIDE) >= fill(BN_NARROW) - 0.05));
+    if (!wide && !fits(BN_NARROW, PATCH_NARROW)) return false;
+    g->bn = wide ? BN_WIDE : BN_NARROW;
+    g->tiles_m = (g->M + g->bn - 1) / g->bn;
+    g->n_items = g->tiles_f * g->tiles_m;
+    g->per_xcd = (g->n_items + 7) / 8;
     return true;
 }
 
@@ -409,8 +428,12 @@ int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, cons
     FwdEpilogue<bf16_t> epi{(bf16_t *)Y, bias, g.F, g.M, g.HoWo, g.div_HoWo, relu};
     ProfScope prof(data_gradient ? KID_FUSED_DGRAD : KID_FUSED_FWD, s, 2.0 * (double)c.M * c.K * c.F, 0.0);
     dim3 grid((unsigned)(g.per_xcd * 8)), block(NT);
-    hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4>), grid, block, 0, s, (const bf16_t *)X, (const bf16_t *)wt_scratch, g,
-                       epi);
+    if (g.bn == BN_WIDE)
+        hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4, BN_WIDE, PATCH_WIDE>), grid, block, 0, s, (const bf16_t *)X,
+                           (const bf16_t *)wt_scratch, g, epi);
+    else
+        hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4, BN_NARROW, PATCH_NARROW>), grid, block, 0, s, (const bf16_t *)X,
+                           (const bf16_t *)wt_scratch, g, epi);
     OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }

@@ -56,12 +56,14 @@ typedef enum {
                                     omni_conv_forward for the same descriptor and the same X, so
                                     the lowering pass is skipped (the paper's b_p = b: with 288 GB
                                     of HBM every layer's D-hat can stay resident)                */
-#define OMNI_FLAG_FUSED 4u       /* forward, backward_data: where omni_conv_fused_supported() says so,
-                                    compute the same result without D-hat / dD-hat in memory (lowering,
-                                    resp. col2im, fused into the matrix product; App. C names this as
-                                    the way past the replication cost of the lowering phase).  The
-                                    workspace then holds no D-hat afterwards.  Elsewhere the flag is
-                                    ignored and the explicit path runs.                           */
+#define OMNI_FLAG_FUSED 4u       /* every pass: where omni_conv_fused_supported() says so, compute the
+                                    same result without D-hat / dD-hat in memory (App. C names fusing
+                                    lowering and GEMM as the way past the replication cost of the
+                                    lowering phase).  forward / backward_data: lowering, resp. col2im, is
+                                    folded into the matrix product.  backward_weights (unless
+                                    OMNI_FLAG_DHAT_CACHED is also set): the product reads the entries of
+                                    D-hat straight from X.  The workspace then holds no D-hat afterwards.
+                                    Elsewhere the flag is ignored and the explicit path runs.            */
 
 /*
  * A convolution layer (Sec. III-A, Eq. (conv_full); App. C adds stride and zero padding):
@@ -92,9 +94,10 @@ int omni_conv_dhat_ld(const omni_conv_desc *desc, int64_t *ld);
 int omni_conv_workspace_bytes(const omni_conv_desc *desc, int pass, size_t *bytes);
 
 /* Host only.  1 if the pass (omni_pass) of this layer runs fused under OMNI_FLAG_FUSED, 0 if it
- * falls back to the explicit path (fused: bf16, stride 1, input channels a multiple of 32, and the
- * pixels needed by 256 consecutive output positions fit the kernel's LDS patch), negative status
- * for a bad descriptor.  The workspace size of a pass does not depend on the flag. */
+ * falls back to the explicit path, negative status for a bad descriptor.  Fused forward and
+ * backward_data: bf16, stride 1, reduced channels a multiple of 32, and the pixels needed by 256
+ * consecutive output positions fit the kernel's LDS patch.  Fused backward_weights: bf16, stride 1,
+ * output rows of at least 8 positions.  The workspace size of a pass does not depend on the flag. */
 int omni_conv_fused_supported(const omni_conv_desc *desc, int pass);
 
 /*

@@ -177,7 +177,7 @@ int omni_conv_fused_supported(const omni_conv_desc *desc, int pass)
         plan_backward_data(g, desc->dtype, &w);
         return fused_supported(g, desc->dtype, true) && fused_weight_bytes(g, true) <= w.total ? 1 : 0;
     }
-    if (pass == OMNI_PASS_BACKWARD_WEIGHTS) return 0;
+    if (pass == OMNI_PASS_BACKWARD_WEIGHTS) return wgrad_direct_supported(g, desc->dtype) ? 1 : 0;
     return OMNI_INVALID_ARGUMENT;
 }
 
@@ -258,13 +258,14 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
     void *Dhat = ws + w.dhat, *dYhat = ws + w.dyhat;
     float *partials = (float *)(ws + w.partials), *bias_partials = (float *)(ws + w.bias_partials);
 
-    if (!cached) {
+    const bool direct = (desc->flags & OMNI_FLAG_FUSED) && !cached && wgrad_direct_supported(g, desc->dtype);
+    if (!cached && !direct) {
         st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
         if (st != OMNI_OK) return st;
     }
     st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, dbias ? bias_partials : nullptr, w.bias_blocks, dbias, s);
     if (st != OMNI_OK) return st;
-    GemmWgradArgs a{dYhat, Dhat, w.ld, partials, w.splits, w.chunk, dW};
+    GemmWgradArgs a{dYhat, Dhat, w.ld, partials, w.splits, w.chunk, dW, direct ? X : nullptr};
     return launch_gemm_wgrad(g, desc->dtype, a, s);
 }
 

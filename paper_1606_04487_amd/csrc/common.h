@@ -134,8 +134,10 @@ struct GemmFwdArgs { const void *Khat; int64_t ldk; const void *Dhat; int64_t ld
 int launch_gemm_forward(const ConvGeom &g, int dtype, const GemmFwdArgs &a, hipStream_t s);
 struct GemmDgradArgs { const void *KhatT; int64_t ldk; const void *dYhat; int64_t ldd; void *dDhat; };
 int launch_gemm_dgrad(const ConvGeom &g, int dtype, const GemmDgradArgs &a, hipStream_t s);
-struct GemmWgradArgs { const void *dYhat; const void *Dhat; int64_t ldd; float *partials; int splits; int64_t chunk; float *dW; };
+// X_direct != null: D-hat is not in memory, its entries are read from X (wgrad_direct_supported layers)
+struct GemmWgradArgs { const void *dYhat; const void *Dhat; int64_t ldd; float *partials; int splits; int64_t chunk; float *dW; const void *X_direct; };
 int launch_gemm_wgrad(const ConvGeom &g, int dtype, const GemmWgradArgs &a, hipStream_t s);
+bool wgrad_direct_supported(const ConvGeom &g, int dtype);
 int gemm_red_tile(int dtype);  // reduction extent of one LDS tile (elements)
 void gemm_wgrad_tile(int F, int K, int *bm, int *bn);
 

@@ -163,6 +163,112 @@ template <int TILE_COLS, int NT> struct OuterContigLoader<bf16_t, TILE_COLS, NT>
 };
 
 // ------------------------------------------------------------------------------------------------
+// The lowered matrix read straight from the input tensor (stride-1 layers, bf16): row k = (c, ky, kx) of
+// D-hat, 8 consecutive columns m = (n, oy, ox) .. -- one pack of the model-gradient product's column
+// operand -- are 8 consecutive input pixels of one image row, or the tail of one output row followed by
+// the head of the next.  Each pack is assembled from two 16-byte loads at element granularity: the
+// second is positioned so that element j of the pack sits at index j of whichever load supplies it, and
+// two 8-bit masks say which.  Pixels in the zero padding, beyond the last image, or rows outside the
+// image stay zero.  The same input bytes serve the kh*kw window taps of a channel, so nearly all of these
+// loads hit in L1/L2 and D-hat is never written or read.
+// ------------------------------------------------------------------------------------------------
+struct DirectSrc {
+    const bf16_t *X;
+    int32_t C, H, W, Ho, Wo, HoWo, HW, M, K, kw, khkw, ph, pw;
+    int32_t total;  // elements of X (< 2^31)
+    FastDiv div_HoWo, div_Wo, div_khkw, div_kw;
+};
+
+template <int TILE_ROWS, int NT> struct DirectLoader {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    static constexpr int PER_THREAD = TILE_ROWS * NPACK / NT;
+    static_assert(TILE_ROWS * NPACK % NT == 0 && NT % NPACK == 0, "tile must divide over the threads");
+    u32x4 v1[PER_THREAD], v2[PER_THREAD];
+    uint32_t masks[PER_THREAD];                 // bits 0..7: element from load 1, bits 8..15: from load 2
+    int cbase[PER_THREAD], dky[PER_THREAD], dkx[PER_THREAD];
+
+    __device__ __forceinline__ void init(const DirectSrc &d, int col0, int tid)
+    {
+#pragma unroll
+        for (int q = 0; q < PER_THREAD; ++q) {
+            int k = col0 + (tid + q * NT) / NPACK;
+            uint32_t c, rem, ky, kx;
+            d.div_khkw.divmod((uint32_t)(k < d.K ? k : 0), c, rem);
+            d.div_kw.divmod(rem, ky, kx);
+            cbase[q] = k < d.K ? (int)c * d.HW : -1;
+            dky[q] = (int)ky - d.ph;
+            dkx[q] = (int)kx - d.pw;
+        }
+    }
+    static __device__ __forceinline__ uint32_t bits(int lo, int hi)  // bits [lo, hi) of a byte, empty if hi <= lo
+    {
+        return hi > lo ? ((1u << hi) - 1u) & ~((1u << lo) - 1u) : 0u;
+    }
+    static __device__ __forceinline__ u32x4 load16(const bf16_t *p)
+    {
+        u32x4 v;
+        __builtin_memcpy(&v, p, 16);
+        return v;
+    }
+    // Slow path for a load that would leave the tensor (first or last row of X only): element loads.
+    static __device__ __noinline__ u32x4 load_edge(const bf16_t *X, int e, uint32_t mask)
+    {
+        uint32_t w[4] = {0, 0, 0, 0};
+        for (int j = 0; j < 8; ++j)
+            if ((mask >> j) & 1u) w[j / 2] |= (uint32_t)X[e + j] << (16 * (j & 1));
+        return u32x4{w[0], w[1], w[2], w[3]};
+    }
+    // m0: first column of this thread's packs (the same for all of them: NT is a multiple of NPACK)
+    __device__ __forceinline__ void issue(const DirectSrc &d, int m0)
+    {
+        const bool live = m0 < d.M;
+        const uint32_t mm = live ? (uint32_t)m0 : 0u;
+        uint32_t n, q, oy, ox0;
+        d.div_HoWo.divmod(mm, n, q);
+        d.div_Wo.divmod(q, oy, ox0);
+        const int jmax = live ? (d.M - m0 < 8 ? d.M - m0 : 8) : 0;  // columns of the pack that exist
+        const int na = d.Wo - (int)ox0 < 8 ? d.Wo - (int)ox0 : 8;    // of which in the first output row
+        const bool wrap = (int)oy + 1 == d.Ho;                       // the second row belongs to the next image
+        const int oy2 = wrap ? 0 : (int)oy + 1;
+        const int img1 = (int)n * d.C * d.HW, img2 = img1 + (wrap ? d.C * d.HW : 0);
+#pragma unroll
+        for (int p = 0; p < PER_THREAD; ++p) {
+            const bool rowk = cbase[p] >= 0;
+            const int iy1 = (int)oy + dky[p], ix1 = (int)ox0 + dkx[p];
+            const int iy2 = oy2 + dky[p], ix2 = dkx[p] - na;
+            const int h1 = na < jmax ? na : jmax;
+            uint32_t m1 = (rowk && iy1 >= 0 && iy1 < d.H) ? bits(ix1 < 0 ? -ix1 : 0, d.W - ix1 < h1 ? d.W - ix1 : h1) : 0u;
+            uint32_t m2 = (rowk && iy2 >= 0 && iy2 < d.H) ? bits(-ix2 > na ? -ix2 : na, d.W - ix2 < jmax ? d.W - ix2 : jmax) : 0u;
+            const int e1 = img1 + cbase[p] + iy1 * d.W + ix1, e2 = img2 + cbase[p] + iy2 * d.W + ix2;
+            const bool in1 = e1 >= 0 && e1 <= d.total - 8, in2 = e2 >= 0 && e2 <= d.total - 8;
+            v1[p] = load16(d.X + ((m1 != 0u && in1) ? e1 : 0));
+            v2[p] = load16(d.X + ((m2 != 0u && in2) ? e2 : 0));
+            if (m1 != 0u && !in1) v1[p] = load_edge(d.X, e1, m1);
+            if (m2 != 0u && !in2) v2[p] = load_edge(d.X, e2, m2);
+            masks[p] = m1 | (m2 << 8);
+        }
+    }
+    static __device__ __forceinline__ uint32_t spread(uint32_t m, int bit)  // two mask bits -> two 16-bit fields
+    {
+        uint32_t lo = (uint32_t)((int32_t)(m << (31 - bit)) >> 31), hi = (uint32_t)((int32_t)(m << (30 - bit)) >> 31);
+        return (lo & 0xffffu) | (hi & 0xffff0000u);
+    }
+    __device__ __forceinline__ void commit(uint4 *lds, int tid) const
+    {
+#pragma unroll
+        for (int p = 0; p < PER_THREAD; ++p) {
+            int t = tid + p * NT;
+            int g = t % NPACK, r = t / NPACK;
+            u32x4 o;
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                o[w] = (v1[p][w] & spread(masks[p], 2 * w)) | (v2[p][w] & spread(masks[p], 8 + 2 * w));
+            reinterpret_cast<u32x4 *>(lds)[g * (TILE_ROWS + 1) + r] = o;
+        }
+    }
+};
+
+// ------------------------------------------------------------------------------------------------
 // The kernel
 // ------------------------------------------------------------------------------------------------
 struct GemmShape {
@@ -186,11 +292,12 @@ template <int BM_, int BN_, int WM_, int WN_, int PF_> struct Tile {
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wavefront tiles are multiples of 32");
 };
 
-template <typename T, typename Cfg, bool COL_OUTER, typename Epi>
+template <typename T, typename Cfg, bool COL_OUTER, typename Epi, bool DIRECT = false>
 __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, int64_t lda,
                                                        const T *__restrict__ B, int64_t ldb,
-                                                       GemmShape sh, Epi epi)
+                                                       GemmShape sh, Epi epi, DirectSrc direct)
 {
+    static_assert(!DIRECT || (!COL_OUTER && std::is_same<T, bf16_t>::value), "direct operand: bf16 model gradient only");
     constexpr int KP = Pack<T>::KP;
     constexpr int BK = NPACK * KP;
     constexpr int BM = Cfg::BM, BN = Cfg::BN, NT = Cfg::NT, TI = Cfg::TI, TJ = Cfg::TJ, PF = Cfg::PF;
@@ -231,17 +338,25 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
     RedContigLoader<T, BM, NT> la[PF];
     RedContigLoader<T, BN, NT> lb_red[PF];
     OuterContigLoader<T, BN, NT> lb_out[PF];
+    DirectLoader<BN, NT> lb_dir[DIRECT ? PF : 1];
+    if constexpr (DIRECT)
+#pragma unroll
+        for (int p = 0; p < PF; ++p) lb_dir[p].init(direct, col0, tid);
 
     auto issue = [&](int set, int64_t k0) {
         la[set].issue(A, lda, sh.rows, sh.red, row0, k0, tid);
-        if constexpr (COL_OUTER)
+        if constexpr (DIRECT)
+            lb_dir[set].issue(direct, (int)k0 + (tid % NPACK) * 8);
+        else if constexpr (COL_OUTER)
             lb_out[set].issue(B, ldb, sh.red, sh.cols, k0, col0, tid);
         else
             lb_red[set].issue(B, ldb, sh.cols, sh.red, col0, k0, tid);
     };
     auto commit = [&](int set, int buf) {
         la[set].commit(lds_a(buf), tid);
-        if constexpr (COL_OUTER)
+        if constexpr (DIRECT)
+            lb_dir[set].commit(lds_b(buf), tid);
+        else if constexpr (COL_OUTER)
             lb_out[set].commit(lds_b(buf), tid);
         else
             lb_red[set].commit(lds_b(buf), tid);
@@ -673,6 +788,14 @@ static void tile_dims(int tile, int *bm, int *bn)
     *bn = dims[tile][1];
 }
 
+// Whether the model gradient of this layer can take its column operand straight from X.
+bool wgrad_direct_supported(const ConvGeom &g, int dtype)
+{
+    int t = pick_tile(g.F, g.K);
+    return dtype == OMNI_BF16 && g.sh == 1 && g.sw == 1 && g.Wo >= 8 && g.pw < 24 && (t == 0 || t == 6) &&
+           (int64_t)g.N * g.C * g.H * g.W < 0x7fffffffll - 16 && (int64_t)g.N * g.C * g.H * g.W >= 8;
+}
+
 // Result tile of the model-gradient GEMM for a layer (the split planner needs the tile count).
 void gemm_wgrad_tile(int F, int K, int *bm, int *bn) { tile_dims(pick_tile(F, K), bm, bn); }
 
@@ -683,7 +806,20 @@ static void launch_cfg(const T *A, int64_t lda, const T *B, int64_t ldb, int row
     GemmShape sh = make_shape(rows, cols, red, chunk, Cfg::BM, Cfg::BN, splits);
     sh.fast_store = epi.fits32() ? 1 : 0;
     dim3 grid(sh.per_xcd * 8, 1, 1);
-    hipLaunchKernelGGL((gemm_kernel<T, Cfg, COL_OUTER, Epi>), grid, dim3(Cfg::NT), 0, s, A, lda, B, ldb, sh, epi);
+    hipLaunchKernelGGL((gemm_kernel<T, Cfg, COL_OUTER, Epi>), grid, dim3(Cfg::NT), 0, s, A, lda, B, ldb, sh, epi,
+                       DirectSrc{});
+}
+
+// Model gradient with the column operand read from X (see DirectLoader); tiles 0 and 6 only.
+template <typename Cfg>
+static void launch_direct(const bf16_t *A, int64_t lda, const DirectSrc &d, int rows, int cols, int64_t red,
+                          int64_t chunk, int splits, const PartialEpilogue &epi, hipStream_t s)
+{
+    GemmShape sh = make_shape(rows, cols, red, chunk, Cfg::BM, Cfg::BN, splits);
+    sh.fast_store = epi.fits32() ? 1 : 0;
+    dim3 grid(sh.per_xcd * 8, 1, 1);
+    hipLaunchKernelGGL((gemm_kernel<bf16_t, Cfg, false, PartialEpilogue, true>), grid, dim3(Cfg::NT), 0, s, A, lda,
+                       (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
 }
 
 template <typename T, bool COL_OUTER, typename Epi>
@@ -757,8 +893,20 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
     {
         ProfScope prof(KID_GEMM_WGRAD, s, 2.0 * g.M * (double)g.K * g.F,
                        ((double)g.K * g.M + (double)g.F * g.M) * sizeof(T) + 4.0 * g.F * g.K * a.splits);
-        launch_any<T, false, PartialEpilogue>(pick_tile(g.F, g.K), (const T *)a.dYhat, a.ldd, (const T *)a.Dhat, a.ldd,
-                                              g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
+        if (a.X_direct != nullptr) {
+            if constexpr (std::is_same<T, bf16_t>::value) {
+                DirectSrc d{(const bf16_t *)a.X_direct, g.C, g.H, g.W, g.Ho, g.Wo, g.HoWo, g.H * g.W, g.M, g.K, g.kw,
+                            g.kh * g.kw, g.ph, g.pw, (int32_t)((int64_t)g.N * g.C * g.H * g.W), g.div_HoWo, g.div_Wo,
+                            g.div_khkw, g.div_kw};
+                if (pick_tile(g.F, g.K) == 6)
+                    launch_direct<Tile6>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
+                else
+                    launch_direct<Tile0>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
+            }
+        } else {
+            launch_any<T, false, PartialEpilogue>(pick_tile(g.F, g.K), (const T *)a.dYhat, a.ldd, (const T *)a.Dhat,
+                                                  a.ldd, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
+        }
     }
     OMNI_LAUNCH_CHECK();
     if (a.splits > 1) {

@@ -30,12 +30,13 @@ class ConvStack:
         self.skip_first_dgrad = skip_first_dgrad   # App. B: the first layer needs no data gradient
         self.device = device
         # fused = let the library skip D-hat / dD-hat where it can (App. C: fusing lowering and GEMM);
-        # the model gradient then lowers X itself instead of finding D-hat cached by the forward pass
+        # the model gradient then reads its lowered operand straight from X (or lowers X itself where it
+        # cannot) instead of finding D-hat cached by the forward pass
         extra = B.FLAG_FUSED if fused else 0
         self.desc = [B.conv_desc(L.N, L.C, L.H, L.W, L.F, L.k, L.k, L.s, L.p, dtype, B.FLAG_RELU | extra)
                      for L in self.layers]
         self.fwd_fused = [fused and B.conv_fused_supported(d, B.PASS_FORWARD) for d in self.desc]
-        self.desc_wgrad = [d.with_flags(0 if ff else B.FLAG_DHAT_CACHED) for d, ff in zip(self.desc, self.fwd_fused)]
+        self.desc_wgrad = [d.with_flags(B.FLAG_FUSED if ff else B.FLAG_DHAT_CACHED) for d, ff in zip(self.desc, self.fwd_fused)]
         # parameters: fp32 masters, velocity, gradients; bf16 copies of W for the bf16 passes
         self.W = [torch.zeros((L.F, L.C, L.k, L.k), dtype=torch.float32, device=device) for L in self.layers]
         self.b = [torch.zeros((L.F,), dtype=torch.float32, device=device) for L in self.layers]

@@ -111,6 +111,24 @@ def test_fused_backward_data(B, cfg):
     assert np.array_equal(got, again)
 
 
+@pytest.mark.parametrize("cfg", FUSED_SHAPES + [(3, 5, 13, 13, 7, 3, 3, 1, 1), (2, 20, 27, 27, 130, 5, 5, 2, 2),
+                                                (2, 3, 9, 30, 4, 3, 5, 2, 4)])
+def test_fused_backward_weights(B, cfg):
+    """Model gradient with the lowered operand read straight from X: same products, same order as the
+    explicit path (bit-identical), and within the fp32-output bar of the oracle."""
+    N, C, H, W, F, kh, kw, ph, pw = cfg
+    s, X, Wt, b, dY = make(cfg, 13)
+    d = desc_of(B, cfg, B.FLAG_FUSED)
+    wo = W + 2 * pw - kw + 1
+    assert B.conv_fused_supported(d, B.PASS_BACKWARD_WEIGHTS) == (wo >= 8)
+    Xg, dYg = gpu(X), gpu(dY)
+    dW, db = B.conv_backward_weights(d, Xg, dYg)
+    assert rel_err(host(dW), oracle.conv_backward_weights(s, X, dY)) <= 1e-4
+    assert rel_err(host(db), oracle.bias_grad(s, dY)) <= 1e-4
+    dW2, _ = B.conv_backward_weights(desc_of(B, cfg, 0), Xg, dYg)
+    assert torch.equal(dW, dW2)
+
+
 def test_fused_declines_and_falls_back(B):
     # stride 2, channels not a multiple of 32, fp32: the flag is accepted and the explicit path runs
     for cfg, dtype in [((2, 32, 9, 9, 8, 3, 3, 2, 2, 1, 1), 1), ((2, 20, 9, 9, 8, 3, 3, 1, 1, 1, 1), 1),
@@ -118,7 +136,7 @@ def test_fused_declines_and_falls_back(B):
         N, C, H, W, F, kh, kw, sh, sw, ph, pw = cfg
         d = B.conv_desc(N, C, H, W, F, kh, kw, (sh, sw), (ph, pw), dtype, B.FLAG_FUSED)
         assert not B.conv_fused_supported(d, B.PASS_FORWARD)
-        assert not B.conv_fused_supported(d, B.PASS_BACKWARD_WEIGHTS)
+        assert B.conv_fused_supported(d, B.PASS_BACKWARD_WEIGHTS) == (dtype == 1 and sh == 1)
         s = oracle.shape(N, C, H, W, F, kh, kw, (sh, sw), (ph, pw))
         rng = np.random.default_rng(3)
         X = rng.standard_normal((N, C, H, W))

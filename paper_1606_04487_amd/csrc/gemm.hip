@@ -184,8 +184,10 @@ template <int TILE_ROWS, int NT> struct DirectLoader {
     static constexpr int PER_THREAD = TILE_ROWS * NPACK / NT;
     static_assert(TILE_ROWS * NPACK % NT == 0 && NT % NPACK == 0, "tile must divide over the threads");
     u32x4 v1[PER_THREAD], v2[PER_THREAD];
-    uint32_t masks[PER_THREAD];                 // bits 0..7: element from load 1, bits 8..15: from load 2
-    int cbase[PER_THREAD], dky[PER_THREAD], dkx[PER_THREAD];
+    // bits 0..7: element comes from load 1; 8..15: from load 2; 16..19 / 20..23: signed element shift of
+    // load 1 / 2 (non-zero only where the 16 bytes had to be moved to stay inside the tensor)
+    uint32_t masks[PER_THREAD];
+    int kbase[PER_THREAD], dky[PER_THREAD], dkx[PER_THREAD];
 
     __device__ __forceinline__ void init(const DirectSrc &d, int col0, int tid)
     {
@@ -195,14 +197,10 @@ template <int TILE_ROWS, int NT> struct DirectLoader {
             uint32_t c, rem, ky, kx;
             d.div_khkw.divmod((uint32_t)(k < d.K ? k : 0), c, rem);
             d.div_kw.divmod(rem, ky, kx);
-            cbase[q] = k < d.K ? (int)c * d.HW : -1;
-            dky[q] = (int)ky - d.ph;
+            dky[q] = k < d.K ? (int)ky - d.ph : -(1 << 24);  // rows beyond K: no input row is ever valid
             dkx[q] = (int)kx - d.pw;
+            kbase[q] = (int)c * d.HW + ((int)ky - d.ph) * d.W + dkx[q];
         }
-    }
-    static __device__ __forceinline__ uint32_t bits(int lo, int hi)  // bits [lo, hi) of a byte, empty if hi <= lo
-    {
-        return hi > lo ? ((1u << hi) - 1u) & ~((1u << lo) - 1u) : 0u;
     }
     static __device__ __forceinline__ u32x4 load16(const bf16_t *p)
     {
@@ -210,42 +208,38 @@ template <int TILE_ROWS, int NT> struct DirectLoader {
         __builtin_memcpy(&v, p, 16);
         return v;
     }
-    // Slow path for a load that would leave the tensor (first or last row of X only): element loads.
-    static __device__ __noinline__ u32x4 load_edge(const bf16_t *X, int e, uint32_t mask)
-    {
-        uint32_t w[4] = {0, 0, 0, 0};
-        for (int j = 0; j < 8; ++j)
-            if ((mask >> j) & 1u) w[j / 2] |= (uint32_t)X[e + j] << (16 * (j & 1));
-        return u32x4{w[0], w[1], w[2], w[3]};
-    }
     // m0: first column of this thread's packs (the same for all of them: NT is a multiple of NPACK)
     __device__ __forceinline__ void issue(const DirectSrc &d, int m0)
     {
         const bool live = m0 < d.M;
-        const uint32_t mm = live ? (uint32_t)m0 : 0u;
         uint32_t n, q, oy, ox0;
-        d.div_HoWo.divmod(mm, n, q);
+        d.div_HoWo.divmod(live ? (uint32_t)m0 : 0u, n, q);
         d.div_Wo.divmod(q, oy, ox0);
         const int jmax = live ? (d.M - m0 < 8 ? d.M - m0 : 8) : 0;  // columns of the pack that exist
         const int na = d.Wo - (int)ox0 < 8 ? d.Wo - (int)ox0 : 8;    // of which in the first output row
+        const int h1 = na < jmax ? na : jmax;
         const bool wrap = (int)oy + 1 == d.Ho;                       // the second row belongs to the next image
         const int oy2 = wrap ? 0 : (int)oy + 1;
-        const int img1 = (int)n * d.C * d.HW, img2 = img1 + (wrap ? d.C * d.HW : 0);
+        const int img = (int)n * d.C * d.HW;
+        const int base1 = img + (int)oy * d.W + (int)ox0;
+        const int base2 = img + (wrap ? d.C * d.HW : 0) + oy2 * d.W - na;
+        const int top = d.total - 8;
 #pragma unroll
         for (int p = 0; p < PER_THREAD; ++p) {
-            const bool rowk = cbase[p] >= 0;
-            const int iy1 = (int)oy + dky[p], ix1 = (int)ox0 + dkx[p];
-            const int iy2 = oy2 + dky[p], ix2 = dkx[p] - na;
-            const int h1 = na < jmax ? na : jmax;
-            uint32_t m1 = (rowk && iy1 >= 0 && iy1 < d.H) ? bits(ix1 < 0 ? -ix1 : 0, d.W - ix1 < h1 ? d.W - ix1 : h1) : 0u;
-            uint32_t m2 = (rowk && iy2 >= 0 && iy2 < d.H) ? bits(-ix2 > na ? -ix2 : na, d.W - ix2 < jmax ? d.W - ix2 : jmax) : 0u;
-            const int e1 = img1 + cbase[p] + iy1 * d.W + ix1, e2 = img2 + cbase[p] + iy2 * d.W + ix2;
-            const bool in1 = e1 >= 0 && e1 <= d.total - 8, in2 = e2 >= 0 && e2 <= d.total - 8;
-            v1[p] = load16(d.X + ((m1 != 0u && in1) ? e1 : 0));
-            v2[p] = load16(d.X + ((m2 != 0u && in2) ? e2 : 0));
-            if (m1 != 0u && !in1) v1[p] = load_edge(d.X, e1, m1);
-            if (m2 != 0u && !in2) v2[p] = load_edge(d.X, e2, m2);
-            masks[p] = m1 | (m2 << 8);
+            const int ix1 = (int)ox0 + dkx[p], ix2 = dkx[p] - na;
+            const int lo1 = ix1 < 0 ? -ix1 : 0, hi1 = d.W - ix1 < h1 ? d.W - ix1 : h1;
+            const int lo2 = -ix2 > na ? -ix2 : na, hi2 = d.W - ix2 < jmax ? d.W - ix2 : jmax;
+            const bool ok1 = (unsigned)((int)oy + dky[p]) < (unsigned)d.H && hi1 > lo1;
+            const bool ok2 = (unsigned)(oy2 + dky[p]) < (unsigned)d.H && hi2 > lo2;
+            const uint32_t m1 = ok1 ? (1u << hi1) - (1u << lo1) : 0u, m2 = ok2 ? (1u << hi2) - (1u << lo2) : 0u;
+            // element offsets of the two loads, moved inside [0, total - 8] where they stick out
+            const int e1 = base1 + kbase[p], e2 = base2 + kbase[p];
+            const int c1 = ok1 ? (e1 < 0 ? 0 : (e1 > top ? top : e1)) : 0;
+            const int c2 = ok2 ? (e2 < 0 ? 0 : (e2 > top ? top : e2)) : 0;
+            const uint32_t s1 = ok1 ? (uint32_t)(e1 - c1) & 15u : 0u, s2 = ok2 ? (uint32_t)(e2 - c2) & 15u : 0u;
+            v1[p] = load16(d.X + c1);
+            v2[p] = load16(d.X + c2);
+            masks[p] = m1 | (m2 << 8) | (s1 << 16) | (s2 << 20);
         }
     }
     static __device__ __forceinline__ uint32_t spread(uint32_t m, int bit)  // two mask bits -> two 16-bit fields
@@ -253,16 +247,29 @@ template <int TILE_ROWS, int NT> struct DirectLoader {
         uint32_t lo = (uint32_t)((int32_t)(m << (31 - bit)) >> 31), hi = (uint32_t)((int32_t)(m << (30 - bit)) >> 31);
         return (lo & 0xffffu) | (hi & 0xffff0000u);
     }
+    // element j of the result = element j + s of v (s = 4-bit two's complement, |s| <= 7)
+    static __device__ __forceinline__ u32x4 shifted(u32x4 v, uint32_t s4)
+    {
+        unsigned __int128 x = ((unsigned __int128)(((uint64_t)v[3] << 32) | v[2]) << 64) | (((uint64_t)v[1] << 32) | v[0]);
+        x = (s4 & 8u) ? x << (16 * (16 - (int)s4)) : x >> (16 * (int)s4);
+        uint64_t lo = (uint64_t)x, hi = (uint64_t)(x >> 64);
+        return u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+    }
     __device__ __forceinline__ void commit(uint4 *lds, int tid) const
     {
 #pragma unroll
         for (int p = 0; p < PER_THREAD; ++p) {
             int t = tid + p * NT;
             int g = t % NPACK, r = t / NPACK;
+            u32x4 a = v1[p], b = v2[p];
+            if (masks[p] >> 16) {  // first or last few elements of the whole tensor only
+                a = shifted(a, (masks[p] >> 16) & 15u);
+                b = shifted(b, (masks[p] >> 20) & 15u);
+            }
             u32x4 o;
 #pragma unroll
             for (int w = 0; w < 4; ++w)
-                o[w] = (v1[p][w] & spread(masks[p], 2 * w)) | (v2[p][w] & spread(masks[p], 8 + 2 * w));
+                o[w] = (a[w] & spread(masks[p], 2 * w)) | (b[w] & spread(masks[p], 8 + 2 * w));
             reinterpret_cast<u32x4 *>(lds)[g * (TILE_ROWS + 1) + r] = o;
         }
     }
@@ -788,11 +795,12 @@ static void tile_dims(int tile, int *bm, int *bn)
     *bn = dims[tile][1];
 }
 
-// Whether the model gradient of this layer can take its column operand straight from X.
+// Whether the model gradient of this layer takes its column operand straight from X.  Assembling a pack
+// costs vector ALU work that is shared by the rows of the result tile, so this pays only with the
+// 256 x 256 tile (measured: with 128-row tiles lowering first and streaming D-hat is faster).
 bool wgrad_direct_supported(const ConvGeom &g, int dtype)
 {
-    int t = pick_tile(g.F, g.K);
-    return dtype == OMNI_BF16 && g.sh == 1 && g.sw == 1 && g.Wo >= 8 && g.pw < 24 && (t == 0 || t == 6) &&
+    return dtype == OMNI_BF16 && g.sh == 1 && g.sw == 1 && g.Wo >= 8 && g.pw < 24 && pick_tile(g.F, g.K) == 6 &&
            (int64_t)g.N * g.C * g.H * g.W < 0x7fffffffll - 16 && (int64_t)g.N * g.C * g.H * g.W >= 8;
 }
 
@@ -810,7 +818,7 @@ static void launch_cfg(const T *A, int64_t lda, const T *B, int64_t ldb, int row
                        DirectSrc{});
 }
 
-// Model gradient with the column operand read from X (see DirectLoader); tiles 0 and 6 only.
+// Model gradient with the column operand read from X (see DirectLoader); the 256 x 256 tile only.
 template <typename Cfg>
 static void launch_direct(const bf16_t *A, int64_t lda, const DirectSrc &d, int rows, int cols, int64_t red,
                           int64_t chunk, int splits, const PartialEpilogue &epi, hipStream_t s)
@@ -898,10 +906,7 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
                 DirectSrc d{(const bf16_t *)a.X_direct, g.C, g.H, g.W, g.Ho, g.Wo, g.HoWo, g.H * g.W, g.M, g.K, g.kw,
                             g.kh * g.kw, g.ph, g.pw, (int32_t)((int64_t)g.N * g.C * g.H * g.W), g.div_HoWo, g.div_Wo,
                             g.div_khkw, g.div_kw};
-                if (pick_tile(g.F, g.K) == 6)
-                    launch_direct<Tile6>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
-                else
-                    launch_direct<Tile0>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
+                launch_direct<Tile6>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
             }
         } else {
             launch_any<T, false, PartialEpilogue>(pick_tile(g.F, g.K), (const T *)a.dYhat, a.ldd, (const T *)a.Dhat,

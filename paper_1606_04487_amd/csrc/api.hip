@@ -68,32 +68,47 @@ void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w)
     if (fused_supported(g, dtype, true) && fused_weight_bytes(g, true) > w->total) w->total = align256(fused_weight_bytes(g, true));
 }
 
-void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w)
+// Split the long reduction (extent ld) over the chip: about two rounds of workgroups on 256 compute
+// units (just under, so that the last round is full), each with at least four steps.
+static void plan_splits(const ConvGeom &g, int dtype, int64_t ld, int *splits_out, int64_t *chunk_out)
 {
-    size_t e = elem_size(dtype);
-    w->ld = dhat_ld(g);
-    // Split the long reduction (M = N*Ho*Wo) over the chip: about two rounds of workgroups on 256
-    // compute units (just under, so that the last round is full), each with at least four steps.
     int64_t bk = gemm_red_tile(dtype);
     int bm, bn;
     gemm_wgrad_tile(g.F, g.K, &bm, &bn);
     int64_t tiles = ((g.F + bm - 1) / bm) * (int64_t)((g.K + bn - 1) / bn);
-    int64_t steps = (w->ld + bk - 1) / bk;
+    int64_t steps = (ld + bk - 1) / bk;
     int64_t rounds = bm * bn >= 256 * 256 ? 2 : 4;
     int64_t want = (256 * rounds) / tiles;
     int64_t max_splits = steps / 4 > 0 ? steps / 4 : 1;
     int64_t splits = want < max_splits ? want : max_splits;
     if (splits < 1) splits = 1;
-    int64_t chunk = round_up((w->ld + splits - 1) / splits, bk);
-    splits = (w->ld + chunk - 1) / chunk;
-    w->splits = (int)splits;
-    w->chunk = chunk;
+    int64_t chunk = round_up((ld + splits - 1) / splits, bk);
+    *splits_out = (int)((ld + chunk - 1) / chunk);
+    *chunk_out = chunk;
+}
+
+void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w)
+{
+    size_t e = elem_size(dtype);
+    w->ld = dhat_ld(g);
+    plan_splits(g, dtype, w->ld, &w->splits, &w->chunk);
     w->bias_blocks = pack_dyhat_blocks(g);
+    // the direct model gradient uses a row-padded dY-hat; the regions are sized for whichever is larger
+    const bool direct = wgrad_direct_supported(g, dtype);
+    w->ld_rows = direct ? dyhat_rows_ld(g) : w->ld;
+    w->splits_rows = w->splits, w->chunk_rows = w->chunk, w->bias_blocks_rows = w->bias_blocks;
+    if (direct) {
+        plan_splits(g, dtype, w->ld_rows, &w->splits_rows, &w->chunk_rows);
+        w->bias_blocks_rows = pack_dyhat_rows_blocks(g);
+    }
+    int64_t ld_max = w->ld > w->ld_rows ? w->ld : w->ld_rows;
+    int splits_max = w->splits > w->splits_rows ? w->splits : w->splits_rows;
+    int bb_max = w->bias_blocks > w->bias_blocks_rows ? w->bias_blocks : w->bias_blocks_rows;
     w->dhat = 0;
     w->dyhat = align256((size_t)g.K * w->ld * e);
-    w->partials = w->dyhat + align256((size_t)g.F * w->ld * e);
-    w->bias_partials = w->partials + align256(splits > 1 ? (size_t)splits * g.F * g.K * sizeof(float) : 0);
-    w->total = w->bias_partials + align256((size_t)g.F * w->bias_blocks * sizeof(float));
+    w->partials = w->dyhat + align256((size_t)g.F * ld_max * e);
+    w->bias_partials = w->partials + align256(splits_max > 1 ? (size_t)splits_max * g.F * g.K * sizeof(float) : 0);
+    w->total = w->bias_partials + align256((size_t)g.F * bb_max * sizeof(float));
 }
 
 }  // namespace omni
@@ -263,9 +278,15 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
         st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
         if (st != OMNI_OK) return st;
     }
+    if (direct) {
+        st = launch_pack_dyhat_rows(g, dY, dYhat, w.ld_rows, dbias ? bias_partials : nullptr, w.bias_blocks_rows, dbias, s);
+        if (st != OMNI_OK) return st;
+        GemmWgradArgs a{dYhat, nullptr, w.ld_rows, partials, w.splits_rows, w.chunk_rows, dW, X};
+        return launch_gemm_wgrad(g, desc->dtype, a, s);
+    }
     st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, dbias ? bias_partials : nullptr, w.bias_blocks, dbias, s);
     if (st != OMNI_OK) return st;
-    GemmWgradArgs a{dYhat, Dhat, w.ld, partials, w.splits, w.chunk, dW, direct ? X : nullptr};
+    GemmWgradArgs a{dYhat, Dhat, w.ld, partials, w.splits, w.chunk, dW, nullptr};
     return launch_gemm_wgrad(g, desc->dtype, a, s);
 }
 

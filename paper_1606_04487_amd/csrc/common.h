@@ -85,7 +85,12 @@ inline int64_t dhat_ld(const ConvGeom &g) { return round_up(g.M, 64); }
 // ---------------------------------------------------------------- workspace carving
 struct ForwardWs { size_t dhat, khat, total; int64_t ld, Fp, Kp; };
 struct BwdDataWs { size_t ddhat, dyhat, khat_t, total; int64_t ld, Kp, Fp; };
-struct BwdWeightsWs { size_t dhat, dyhat, partials, bias_partials, total; int64_t ld; int splits; int64_t chunk; int bias_blocks; };
+// *_rows: the same plan for the row-padded dY-hat of the direct model gradient (reduction extent ld_rows)
+struct BwdWeightsWs {
+    size_t dhat, dyhat, partials, bias_partials, total;
+    int64_t ld; int splits; int64_t chunk; int bias_blocks;
+    int64_t ld_rows; int splits_rows; int64_t chunk_rows; int bias_blocks_rows;
+};
 void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w);
 void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w);
 void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w);
@@ -128,6 +133,11 @@ int launch_pack_khat_t(const ConvGeom &g, int dtype, const void *W, void *KhatT,
 int launch_pack_dyhat(const ConvGeom &g, int dtype, const void *dY, void *dYhat, int64_t ld,
                       float *bias_partials, int bias_blocks, float *dbias, hipStream_t s);
 int pack_dyhat_blocks(const ConvGeom &g);
+// row-padded variant (bf16): every output row padded to a multiple of 8 columns
+int64_t dyhat_rows_ld(const ConvGeom &g);
+int pack_dyhat_rows_blocks(const ConvGeom &g);
+int launch_pack_dyhat_rows(const ConvGeom &g, const void *dY, void *dYhat, int64_t ld, float *bias_partials,
+                           int bias_blocks, float *dbias, hipStream_t s);
 
 // gemm.hip
 struct GemmFwdArgs { const void *Khat; int64_t ldk; const void *Dhat; int64_t ldd; const float *bias; void *Y; int relu; };

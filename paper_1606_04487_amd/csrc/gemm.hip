@@ -163,29 +163,29 @@ template <int TILE_COLS, int NT> struct OuterContigLoader<bf16_t, TILE_COLS, NT>
 };
 
 // ------------------------------------------------------------------------------------------------
-// The lowered matrix read straight from the input tensor (stride-1 layers, bf16): row k = (c, ky, kx) of
-// D-hat, 8 consecutive columns m = (n, oy, ox) .. -- one pack of the model-gradient product's column
-// operand -- are 8 consecutive input pixels of one image row, or the tail of one output row followed by
-// the head of the next.  Each pack is assembled from two 16-byte loads at element granularity: the
-// second is positioned so that element j of the pack sits at index j of whichever load supplies it, and
-// two 8-bit masks say which.  Pixels in the zero padding, beyond the last image, or rows outside the
-// image stay zero.  The same input bytes serve the kh*kw window taps of a channel, so nearly all of these
-// loads hit in L1/L2 and D-hat is never written or read.
+// The lowered matrix read straight from the input tensor (stride-1 layers, bf16), for the model gradient.
+// The reduction runs over row-padded columns: column ((n*Ho + oy) * P8 + i) * 8 + e stands for output
+// position (n, oy, 8i + e), P8 = ceil(Wo / 8), and dY-hat is packed the same way with zeros in the padding
+// (a sum does not care about the order or about zero terms).  A pack of 8 columns of row k = (c, ky, kx)
+// of D-hat is then 8 consecutive pixels of ONE input row: one 16-byte load at element granularity plus an
+// 8-bit mask for pixels in the zero padding or outside the image.  The same input bytes serve the kh*kw
+// window taps of a channel, so nearly all of these loads hit in L1/L2; D-hat is never written or read.
 // ------------------------------------------------------------------------------------------------
 struct DirectSrc {
     const bf16_t *X;
-    int32_t C, H, W, Ho, Wo, HoWo, HW, M, K, kw, khkw, ph, pw;
+    int32_t C, H, W, HW, K, ph, pw;
+    int32_t rows;   // N * Ho: output rows in the batch
     int32_t total;  // elements of X (< 2^31)
-    FastDiv div_HoWo, div_Wo, div_khkw, div_kw;
+    FastDiv div_p8, div_Ho, div_khkw, div_kw;
 };
 
 template <int TILE_ROWS, int NT> struct DirectLoader {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     static constexpr int PER_THREAD = TILE_ROWS * NPACK / NT;
     static_assert(TILE_ROWS * NPACK % NT == 0 && NT % NPACK == 0, "tile must divide over the threads");
-    u32x4 v1[PER_THREAD], v2[PER_THREAD];
-    // bits 0..7: element comes from load 1; 8..15: from load 2; 16..19 / 20..23: signed element shift of
-    // load 1 / 2 (non-zero only where the 16 bytes had to be moved to stay inside the tensor)
+    u32x4 v[PER_THREAD];
+    // bits 0..7: which elements are real pixels; 8..11: signed element shift (non-zero only where the 16
+    // bytes had to be moved to stay inside the tensor: first and last row of X)
     uint32_t masks[PER_THREAD];
     int kbase[PER_THREAD], dky[PER_THREAD], dkx[PER_THREAD];
 
@@ -202,44 +202,29 @@ template <int TILE_ROWS, int NT> struct DirectLoader {
             kbase[q] = (int)c * d.HW + ((int)ky - d.ph) * d.W + dkx[q];
         }
     }
-    static __device__ __forceinline__ u32x4 load16(const bf16_t *p)
-    {
-        u32x4 v;
-        __builtin_memcpy(&v, p, 16);
-        return v;
-    }
-    // m0: first column of this thread's packs (the same for all of them: NT is a multiple of NPACK)
+    // m0: first (row-padded) column of this thread's packs -- the same for all of them, NT being a
+    // multiple of NPACK
     __device__ __forceinline__ void issue(const DirectSrc &d, int m0)
     {
-        const bool live = m0 < d.M;
-        uint32_t n, q, oy, ox0;
-        d.div_HoWo.divmod(live ? (uint32_t)m0 : 0u, n, q);
-        d.div_Wo.divmod(q, oy, ox0);
-        const int jmax = live ? (d.M - m0 < 8 ? d.M - m0 : 8) : 0;  // columns of the pack that exist
-        const int na = d.Wo - (int)ox0 < 8 ? d.Wo - (int)ox0 : 8;    // of which in the first output row
-        const int h1 = na < jmax ? na : jmax;
-        const bool wrap = (int)oy + 1 == d.Ho;                       // the second row belongs to the next image
-        const int oy2 = wrap ? 0 : (int)oy + 1;
-        const int img = (int)n * d.C * d.HW;
-        const int base1 = img + (int)oy * d.W + (int)ox0;
-        const int base2 = img + (wrap ? d.C * d.HW : 0) + oy2 * d.W - na;
+        uint32_t row, i, n, oy;
+        d.div_p8.divmod((uint32_t)m0 >> 3, row, i);
+        const bool live = (int)row < d.rows;
+        d.div_Ho.divmod(live ? row : 0u, n, oy);
+        const int ox0 = 8 * (int)i;
+        const int base = (int)n * d.C * d.HW + (int)oy * d.W + ox0;
         const int top = d.total - 8;
 #pragma unroll
         for (int p = 0; p < PER_THREAD; ++p) {
-            const int ix1 = (int)ox0 + dkx[p], ix2 = dkx[p] - na;
-            const int lo1 = ix1 < 0 ? -ix1 : 0, hi1 = d.W - ix1 < h1 ? d.W - ix1 : h1;
-            const int lo2 = -ix2 > na ? -ix2 : na, hi2 = d.W - ix2 < jmax ? d.W - ix2 : jmax;
-            const bool ok1 = (unsigned)((int)oy + dky[p]) < (unsigned)d.H && hi1 > lo1;
-            const bool ok2 = (unsigned)(oy2 + dky[p]) < (unsigned)d.H && hi2 > lo2;
-            const uint32_t m1 = ok1 ? (1u << hi1) - (1u << lo1) : 0u, m2 = ok2 ? (1u << hi2) - (1u << lo2) : 0u;
-            // element offsets of the two loads, moved inside [0, total - 8] where they stick out
-            const int e1 = base1 + kbase[p], e2 = base2 + kbase[p];
-            const int c1 = ok1 ? (e1 < 0 ? 0 : (e1 > top ? top : e1)) : 0;
-            const int c2 = ok2 ? (e2 < 0 ? 0 : (e2 > top ? top : e2)) : 0;
-            const uint32_t s1 = ok1 ? (uint32_t)(e1 - c1) & 15u : 0u, s2 = ok2 ? (uint32_t)(e2 - c2) & 15u : 0u;
-            v1[p] = load16(d.X + c1);
-            v2[p] = load16(d.X + c2);
-            masks[p] = m1 | (m2 << 8) | (s1 << 16) | (s2 << 20);
+            const int ix = ox0 + dkx[p];
+            const int lo = ix < 0 ? -ix : 0, hi = d.W - ix < 8 ? d.W - ix : 8;
+            const bool ok = live && (unsigned)((int)oy + dky[p]) < (unsigned)d.H && hi > lo;
+            const uint32_t m = ok ? (1u << hi) - (1u << lo) : 0u;
+            // element offset of the load, moved inside [0, total - 8] where it sticks out
+            const int e = base + kbase[p];
+            const int c = ok ? (e < 0 ? 0 : (e > top ? top : e)) : 0;
+            const uint32_t sft = ok ? (uint32_t)(e - c) & 15u : 0u;
+            __builtin_memcpy(&v[p], d.X + c, 16);
+            masks[p] = m | (sft << 8);
         }
     }
     static __device__ __forceinline__ uint32_t spread(uint32_t m, int bit)  // two mask bits -> two 16-bit fields
@@ -247,10 +232,10 @@ template <int TILE_ROWS, int NT> struct DirectLoader {
         uint32_t lo = (uint32_t)((int32_t)(m << (31 - bit)) >> 31), hi = (uint32_t)((int32_t)(m << (30 - bit)) >> 31);
         return (lo & 0xffffu) | (hi & 0xffff0000u);
     }
-    // element j of the result = element j + s of v (s = 4-bit two's complement, |s| <= 7)
-    static __device__ __forceinline__ u32x4 shifted(u32x4 v, uint32_t s4)
+    // element j of the result = element j + s of x (s = 4-bit two's complement, |s| <= 7)
+    static __device__ __forceinline__ u32x4 shifted(u32x4 x4, uint32_t s4)
     {
-        unsigned __int128 x = ((unsigned __int128)(((uint64_t)v[3] << 32) | v[2]) << 64) | (((uint64_t)v[1] << 32) | v[0]);
+        unsigned __int128 x = ((unsigned __int128)(((uint64_t)x4[3] << 32) | x4[2]) << 64) | (((uint64_t)x4[1] << 32) | x4[0]);
         x = (s4 & 8u) ? x << (16 * (16 - (int)s4)) : x >> (16 * (int)s4);
         uint64_t lo = (uint64_t)x, hi = (uint64_t)(x >> 64);
         return u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
@@ -261,15 +246,11 @@ template <int TILE_ROWS, int NT> struct DirectLoader {
         for (int p = 0; p < PER_THREAD; ++p) {
             int t = tid + p * NT;
             int g = t % NPACK, r = t / NPACK;
-            u32x4 a = v1[p], b = v2[p];
-            if (masks[p] >> 16) {  // first or last few elements of the whole tensor only
-                a = shifted(a, (masks[p] >> 16) & 15u);
-                b = shifted(b, (masks[p] >> 20) & 15u);
-            }
+            u32x4 a = v[p];
+            if (masks[p] >> 8) a = shifted(a, (masks[p] >> 8) & 15u);  // first or last few elements of the tensor only
             u32x4 o;
 #pragma unroll
-            for (int w = 0; w < 4; ++w)
-                o[w] = (a[w] & spread(masks[p], 2 * w)) | (b[w] & spread(masks[p], 8 + 2 * w));
+            for (int w = 0; w < 4; ++w) o[w] = a[w] & spread(masks[p], 2 * w);
             reinterpret_cast<u32x4 *>(lds)[g * (TILE_ROWS + 1) + r] = o;
         }
     }
@@ -800,7 +781,7 @@ static void tile_dims(int tile, int *bm, int *bn)
 // 256 x 256 tile (measured: with 128-row tiles lowering first and streaming D-hat is faster).
 bool wgrad_direct_supported(const ConvGeom &g, int dtype)
 {
-    return dtype == OMNI_BF16 && g.sh == 1 && g.sw == 1 && g.Wo >= 8 && g.pw < 24 && pick_tile(g.F, g.K) == 6 &&
+    return dtype == OMNI_BF16 && g.sh == 1 && g.sw == 1 && g.pw < 24 && pick_tile(g.F, g.K) == 6 &&
            (int64_t)g.N * g.C * g.H * g.W < 0x7fffffffll - 16 && (int64_t)g.N * g.C * g.H * g.W >= 8;
 }
 
@@ -903,9 +884,9 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
                        ((double)g.K * g.M + (double)g.F * g.M) * sizeof(T) + 4.0 * g.F * g.K * a.splits);
         if (a.X_direct != nullptr) {
             if constexpr (std::is_same<T, bf16_t>::value) {
-                DirectSrc d{(const bf16_t *)a.X_direct, g.C, g.H, g.W, g.Ho, g.Wo, g.HoWo, g.H * g.W, g.M, g.K, g.kw,
-                            g.kh * g.kw, g.ph, g.pw, (int32_t)((int64_t)g.N * g.C * g.H * g.W), g.div_HoWo, g.div_Wo,
-                            g.div_khkw, g.div_kw};
+                DirectSrc d{(const bf16_t *)a.X_direct, g.C, g.H, g.W, g.H * g.W, g.K, g.ph, g.pw, g.N * g.Ho,
+                            (int32_t)((int64_t)g.N * g.C * g.H * g.W), FastDiv((uint32_t)((g.Wo + 7) / 8)),
+                            FastDiv((uint32_t)g.Ho), g.div_khkw, g.div_kw};
                 launch_direct<Tile6>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
             }
         } else {

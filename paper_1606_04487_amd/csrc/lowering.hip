@@ -527,6 +527,69 @@ __global__ __launch_bounds__(64) void bias_reduce_kernel(const float *__restrict
     if (threadIdx.x == 0) dbias[f] = acc;
 }
 
+// The same matrix with every output row padded with zeros to a multiple of 8 columns:
+// column ((n*Ho + oy) * P8 + i) * 8 + e holds dY[n][f][oy][8i + e], P8 = ceil(Wo / 8).  A pack of 8 columns
+// then never leaves its output row, which is what lets the model-gradient product read the matching
+// entries of D-hat straight from X with one load per pack.  One thread per pack; bias partial sums as above.
+__global__ __launch_bounds__(256) void pack_dyhat_rows_kernel(ConvGeom g, FastDiv div_p8, FastDiv div_Ho,
+                                                              const bf16_t *__restrict__ dY, uint16_t *__restrict__ out,
+                                                              int64_t ld, float *__restrict__ bias_partials)
+{
+    int f = blockIdx.y;
+    int64_t pack = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float sum = 0.f;
+    if (pack * 8 < ld) {
+        uint32_t row, i, n, oy;
+        div_p8.divmod((uint32_t)pack, row, i);
+        div_Ho.divmod(row, n, oy);
+        VecOf<uint16_t, 8> o;
+        const bool live = (int)n < g.N;
+        const bf16_t *src = dY + (((int64_t)(live ? n : 0) * g.F + f) * g.Ho + oy) * g.Wo + 8 * i;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            uint16_t bits = 0;
+            if (live && 8 * (int)i + e < g.Wo) {
+                bits = src[e];
+                sum += bf16_to_f32(bits);
+            }
+            o.v[e] = bits;
+        }
+        *reinterpret_cast<VecOf<uint16_t, 8> *>(out + (int64_t)f * ld + pack * 8) = o;
+    }
+    if (bias_partials != nullptr) {
+        __shared__ float wave_sum[4];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
+        if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = sum;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            bias_partials[(int64_t)f * gridDim.x + blockIdx.x] = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
+    }
+}
+
+int64_t dyhat_rows_ld(const ConvGeom &g) { return round_up((int64_t)g.N * g.Ho * ((g.Wo + 7) / 8) * 8, 64); }
+int pack_dyhat_rows_blocks(const ConvGeom &g) { return (int)((dyhat_rows_ld(g) + PACK_COLS - 1) / PACK_COLS); }
+
+int launch_pack_dyhat_rows(const ConvGeom &g, const void *dY, void *dYhat, int64_t ld, float *bias_partials,
+                           int bias_blocks, float *dbias, hipStream_t s)
+{
+    int blocks = (int)((ld + PACK_COLS - 1) / PACK_COLS);
+    if (bias_partials != nullptr && bias_blocks != blocks) return OMNI_INVALID_ARGUMENT;
+    dim3 grid((unsigned)blocks, (unsigned)g.F, 1);
+    {
+        ProfScope prof(KID_PACK_DYHAT, s, 0.0, 2.0 * g.F * (double)g.M * 2.0);
+        hipLaunchKernelGGL(pack_dyhat_rows_kernel, grid, dim3(256), 0, s, g, FastDiv((uint32_t)((g.Wo + 7) / 8)),
+                           FastDiv((uint32_t)g.Ho), (const bf16_t *)dY, (uint16_t *)dYhat, ld, bias_partials);
+    }
+    OMNI_LAUNCH_CHECK();
+    if (bias_partials != nullptr) {
+        ProfScope prof(KID_BIAS_REDUCE, s, 0.0, 4.0 * g.F * (blocks + 1));
+        hipLaunchKernelGGL(bias_reduce_kernel, dim3((unsigned)g.F), dim3(64), 0, s, bias_partials, blocks, dbias);
+        OMNI_LAUNCH_CHECK();
+    }
+    return OMNI_OK;
+}
+
 int pack_dyhat_blocks(const ConvGeom &g) { return (int)((dhat_ld(g) + PACK_COLS - 1) / PACK_COLS); }
 
 int launch_pack_dyhat(const ConvGeom &g, int dtype, const void *dY, void *dYhat, int64_t ld, float *bias_partials,

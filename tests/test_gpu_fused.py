@@ -115,20 +115,20 @@ def test_fused_backward_data(B, cfg):
                                                 (2, 3, 9, 30, 4, 3, 5, 2, 4), (2, 30, 13, 13, 250, 3, 3, 1, 1),
                                                 (3, 29, 9, 11, 256, 3, 2, 0, 1), (1, 57, 27, 27, 200, 5, 5, 2, 2)])
 def test_fused_backward_weights(B, cfg):
-    """Model gradient with the lowered operand read straight from X: same products, same order as the
-    explicit path (bit-identical), and within the fp32-output bar of the oracle."""
+    """Model gradient with the lowered operand read straight from X: the same products as the explicit
+    path, summed in fp32 in another order (row-padded columns), within the fp32-output bar of the oracle."""
     N, C, H, W, F, kh, kw, ph, pw = cfg
     s, X, Wt, b, dY = make(cfg, 13)
     d = desc_of(B, cfg, B.FLAG_FUSED)
     wo = W + 2 * pw - kw + 1
-    if wo < 8:
-        assert not B.conv_fused_supported(d, B.PASS_BACKWARD_WEIGHTS)
     Xg, dYg = gpu(X), gpu(dY)
     dW, db = B.conv_backward_weights(d, Xg, dYg)
     assert rel_err(host(dW), oracle.conv_backward_weights(s, X, dY)) <= 1e-4
     assert rel_err(host(db), oracle.bias_grad(s, dY)) <= 1e-4
     dW2, _ = B.conv_backward_weights(desc_of(B, cfg, 0), Xg, dYg)
-    assert torch.equal(dW, dW2)
+    assert rel_err(host(dW), host(dW2)) <= 2e-5
+    again, _ = B.conv_backward_weights(d, Xg, dYg)
+    assert torch.equal(dW, again)                  # deterministic
 
 
 def test_fused_declines_and_falls_back(B):

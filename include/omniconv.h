@@ -162,8 +162,10 @@ int omni_col2im(const omni_conv_desc *desc, const void *dDhat, int64_t ld, void 
  *       ceil_mode != 0 keeps a last border-clipped window.  The first maximum in (ky, kx) scan
  *       order wins.  argmax (uint8 per output, nullable) receives ky*k+kx of the winner.
  *   maxpool_backward: dx [planes][H][W] (overwritten) receives each dy at its window's winner.
- *   maxpool_relu_backward: the same followed by the ReLU gradient of the pooled tensor y
- *       [planes][H][W] (dx = 0 where y <= 0), in one pass; dx must not alias y.
+ *   maxpool_relu_backward: the same, times the gradient of a ReLU applied just before the pool, in one
+ *       pass.  y_pooled [planes][Ho][Wo] is the forward pool's output: it equals the winner's value, so a
+ *       window routes its gradient iff y_pooled > 0 (the result equals pool backward followed by
+ *       dx = 0 where the pool's input <= 0, without reading that input).
  * omni_pool_output_dim is host only and returns the pooled extent or a negative status.
  */
 int omni_relu_forward(int32_t dtype, int64_t count, const void *x, void *y, void *hip_stream);
@@ -178,7 +180,7 @@ int omni_maxpool_backward(int32_t dtype, int64_t planes, int32_t H, int32_t W, i
                           void *dx, void *hip_stream);
 int omni_maxpool_relu_backward(int32_t dtype, int64_t planes, int32_t H, int32_t W, int32_t k,
                                int32_t stride, int32_t ceil_mode, const void *dy, const uint8_t *argmax,
-                               const void *y, void *dx, void *hip_stream);
+                               const void *y_pooled, void *dx, void *hip_stream);
 
 /*
  * Per-kernel timing (the paper times with a wall clock, App. C "Experiment Setup"; on a GPU the

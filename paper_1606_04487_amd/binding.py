@@ -283,14 +283,15 @@ def maxpool_backward(dy, argmax, H: int, W: int, k: int = 3, stride: int = 2, ce
     return dx
 
 
-def maxpool_relu_backward(dy, argmax, y, k: int = 3, stride: int = 2, ceil_mode: bool = True, dx=None):
-    """omni_maxpool_relu_backward: pool backward and the ReLU gradient of the pooled tensor y in one pass."""
-    H, W = y.shape[-2:]
+def maxpool_relu_backward(dy, argmax, y_pooled, H: int, W: int, k: int = 3, stride: int = 2, ceil_mode: bool = True,
+                          dx=None):
+    """omni_maxpool_relu_backward: pool backward times the gradient of the ReLU in front of the pool, in one
+    pass; y_pooled is the forward pool's output (same shape as dy)."""
     planes = dy.numel() // (dy.shape[-1] * dy.shape[-2])
     if dx is None:
-        dx = torch.empty_like(y)
+        dx = torch.empty(tuple(dy.shape[:-2]) + (H, W), dtype=dy.dtype, device=dy.device)
     _check(_lib.omni_maxpool_relu_backward(dtype_code(dy.dtype), planes, H, W, k, stride, int(ceil_mode), _p(dy),
-                                           _p(argmax), _p(y), _p(dx), _stream()))
+                                           _p(argmax), _p(y_pooled), _p(dx), _stream()))
     return dx
 
 

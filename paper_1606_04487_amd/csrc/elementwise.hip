@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(PoolGeom g, int64_t pl
 
 // Gather form: each input pixel collects the gradient of every window that elected it, in
 // ascending (oy, ox) order, in fp32.
-template <typename T, bool RELU>  // RELU: also apply the ReLU gradient of the pooled tensor y (dx = 0 where y <= 0)
+template <typename T, bool RELU>  // RELU: a window routes its gradient only if its pooled value y is > 0
 __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolGeom g, int64_t plane0, uint32_t count,
                                                           const T *__restrict__ dy, const uint8_t *__restrict__ argmax,
                                                           const T *__restrict__ y, T *__restrict__ dx)
@@ -241,11 +241,10 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolGeom g, int64_t pl
         for (int ox = ox_lo; ox <= ox_hi; ++ox) {
             int code = ((int)iy - oy * g.s) * g.k + ((int)ix - ox * g.s);
             int64_t o = obase + (int64_t)oy * g.Wo + ox;
-            if (argmax[o] == (uint8_t)code) acc += Elem<T>::to_f32(dy[o]);
+            bool hit = argmax[o] == (uint8_t)code;
+            if constexpr (RELU) hit = hit && Elem<T>::to_f32(y[o]) > 0.f;
+            if (hit) acc += Elem<T>::to_f32(dy[o]);
         }
-    if constexpr (RELU) {
-        if (!(Elem<T>::to_f32(y[plane * g.H * g.W + p]) > 0.f)) acc = 0.f;
-    }
     dx[plane * g.H * g.W + p] = Elem<T>::from_f32(acc);
 }
 
@@ -315,6 +314,7 @@ __global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_
                                                               const T *__restrict__ y, T *__restrict__ dx)
 {
     extern __shared__ __align__(16) unsigned char pool_smem[];
+    constexpr int VEC = 16 / (int)sizeof(T);
     const int64_t p0 = (int64_t)blockIdx.x * pb;
     const int np = (int)(planes - p0 < pb ? planes - p0 : pb);
     const int hw = g.H * g.W, howo = g.Ho * g.Wo;
@@ -322,31 +322,65 @@ __global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_
     uint8_t *gam = pool_smem + (((size_t)pb * howo * sizeof(T) + 15) / 16) * 16;
     run_to_lds(dy + p0 * howo, np * howo, gdy, threadIdx.x);
     run_to_lds(argmax + p0 * howo, np * howo, gam, threadIdx.x);
-    __syncthreads();
-    for (int px = threadIdx.x; px < np * hw; px += 256) {
-        uint32_t pl, p, iy, ix;
-        g.div_HW.divmod((uint32_t)px, pl, p);
-        g.div_W.divmod(p, iy, ix);
-        int oy_lo = (int)iy - g.k + 1;
-        oy_lo = oy_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(oy_lo + g.s - 1));
-        int oy_hi = (int)g.div_s.div(iy);
-        if (oy_hi > g.Ho - 1) oy_hi = g.Ho - 1;
-        int ox_lo = (int)ix - g.k + 1;
-        ox_lo = ox_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(ox_lo + g.s - 1));
-        int ox_hi = (int)g.div_s.div(ix);
-        if (ox_hi > g.Wo - 1) ox_hi = g.Wo - 1;
-        const int obase = (int)pl * howo;
-        float acc = 0.f;
-        for (int oy = oy_lo; oy <= oy_hi; ++oy)
-            for (int ox = ox_lo; ox <= ox_hi; ++ox) {
-                int code = ((int)iy - oy * g.s) * g.k + ((int)ix - ox * g.s);
-                int o = obase + oy * g.Wo + ox;
-                if (gam[o] == (uint8_t)code) acc += Elem<T>::to_f32(gdy[o]);
+    if constexpr (RELU) {
+        // the pooled value is the winner's value: where it is not positive the ReLU under the pool
+        // passes nothing, so that window's gradient is dropped while it is staged
+        __syncthreads();
+        const T *yp = y + p0 * howo;
+        const int chunks = (np * howo + VEC - 1) / VEC;
+        for (int c = threadIdx.x; c < chunks; c += 256) {
+            if ((c + 1) * VEC <= np * howo) {
+                T v[VEC];
+                __builtin_memcpy(v, yp + c * VEC, sizeof(v));
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    if (!(Elem<T>::to_f32(v[e]) > 0.f)) gdy[c * VEC + e] = (T)0;
+            } else {
+                for (int e = 0; c * VEC + e < np * howo; ++e)
+                    if (!(Elem<T>::to_f32(yp[c * VEC + e]) > 0.f)) gdy[c * VEC + e] = (T)0;
             }
-        if constexpr (RELU) {
-            if (!(Elem<T>::to_f32(y[p0 * hw + px]) > 0.f)) acc = 0.f;
         }
-        dx[p0 * hw + px] = Elem<T>::from_f32(acc);
+    }
+    __syncthreads();
+    // each thread produces VEC consecutive pixels of the workgroup's run of planes and stores them at once
+    T *out = dx + p0 * hw;
+    const int total = np * hw;
+    for (int v0 = threadIdx.x * VEC; v0 < total; v0 += 256 * VEC) {
+        uint32_t pl, p, iy, ix;
+        g.div_HW.divmod((uint32_t)v0, pl, p);
+        g.div_W.divmod(p, iy, ix);
+        T res[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            float acc = 0.f;
+            if (v0 + e < total) {
+                int oy_lo = (int)iy - g.k + 1;
+                oy_lo = oy_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(oy_lo + g.s - 1));
+                int oy_hi = (int)g.div_s.div(iy);
+                if (oy_hi > g.Ho - 1) oy_hi = g.Ho - 1;
+                int ox_lo = (int)ix - g.k + 1;
+                ox_lo = ox_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(ox_lo + g.s - 1));
+                int ox_hi = (int)g.div_s.div(ix);
+                if (ox_hi > g.Wo - 1) ox_hi = g.Wo - 1;
+                const int obase = (int)pl * howo;
+                for (int oy = oy_lo; oy <= oy_hi; ++oy)
+                    for (int ox = ox_lo; ox <= ox_hi; ++ox) {
+                        int code = ((int)iy - oy * g.s) * g.k + ((int)ix - ox * g.s);
+                        int o = obase + oy * g.Wo + ox;
+                        if (gam[o] == (uint8_t)code) acc += Elem<T>::to_f32(gdy[o]);
+                    }
+            }
+            res[e] = Elem<T>::from_f32(acc);
+            if (++ix == (uint32_t)g.W) {
+                ix = 0;
+                if (++iy == (uint32_t)g.H) iy = 0, ++pl;
+            }
+        }
+        if (v0 + VEC <= total) {
+            __builtin_memcpy(out + v0, res, sizeof(res));  // element-aligned 16-byte store
+        } else {
+            for (int e = 0; v0 + e < total; ++e) out[v0 + e] = res[e];
+        }
     }
 }
 

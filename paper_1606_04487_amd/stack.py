@@ -103,7 +103,8 @@ class ConvStack:
         for i in reversed(range(len(self.layers))):
             L, Y = self.layers[i], self.Y[i]
             if L.pool_after:
-                B.maxpool_relu_backward(g, self.A[i], Y, 3, 2, self.ceil_mode, self.dYc[i])
+                B.maxpool_relu_backward(g, self.A[i], self.P[i], Y.shape[-2], Y.shape[-1], 3, 2, self.ceil_mode,
+                                        self.dYc[i])
             else:
                 B.relu_backward(Y, g, self.dYc[i])
             B.conv_backward_weights(self.desc_wgrad[i], self.X[i], self.dYc[i], self.dW[i], self.db[i],

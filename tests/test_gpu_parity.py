@@ -242,8 +242,9 @@ def test_maxpool(B, dtype, H, W, ceil_mode):
         assert rel_err(host(dx), ref) <= 1e-6
     else:
         assert rel_err(host(dx), ref) <= TOL[1]
-    # fused with the ReLU gradient of the pooled tensor: exactly the unfused result where x > 0, else 0
-    fused = B.maxpool_relu_backward(gpu(dy, dtype), am, gpu(x, dtype), 3, 2, ceil_mode)
+    # fused with the gradient of a ReLU in front of the pool (mask taken from the pooled values): exactly
+    # the unfused result where x > 0, else 0
+    fused = B.maxpool_relu_backward(gpu(dy, dtype), am, gpu(y_ref, dtype), H, W, 3, 2, ceil_mode)
     expect = torch.where(gpu(x, dtype) > 0, dx, torch.zeros_like(dx))
     assert torch.equal(fused, expect)
     assert np.array_equal(host(fused) != 0, (oracle.relu_backward(x, np.ones_like(x)) * ref) != 0) or dtype == 1

@@ -68,8 +68,10 @@ void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w)
     if (fused_supported(g, dtype, true) && fused_weight_bytes(g, true) > w->total) w->total = align256(fused_weight_bytes(g, true));
 }
 
-// Split the long reduction (extent ld) over the chip: about two rounds of workgroups on 256 compute
-// units (just under, so that the last round is full), each with at least four steps.
+// Split the long reduction (extent ld) over the chip: one round of 256 x 256 workgroups on the 256 compute
+// units or two rounds of 128 x 128 ones (just under, so that the last round is full), each with at least
+// four steps.  More splits would balance better but every split writes, and the reduction re-reads, a
+// whole fp32 copy of the gradient (measured: twice as many splits cost 4 % of the training step).
 static void plan_splits(const ConvGeom &g, int dtype, int64_t ld, int *splits_out, int64_t *chunk_out)
 {
     int64_t bk = gemm_red_tile(dtype);
@@ -77,7 +79,7 @@ static void plan_splits(const ConvGeom &g, int dtype, int64_t ld, int *splits_ou
     gemm_wgrad_tile(g.F, g.K, &bm, &bn);
     int64_t tiles = ((g.F + bm - 1) / bm) * (int64_t)((g.K + bn - 1) / bn);
     int64_t steps = (ld + bk - 1) / bk;
-    int64_t rounds = bm * bn >= 256 * 256 ? 2 : 4;
+    int64_t rounds = bm * bn >= 256 * 256 ? 1 : 2;
     int64_t want = (256 * rounds) / tiles;
     int64_t max_splits = steps / 4 > 0 ? steps / 4 : 1;
     int64_t splits = want < max_splits ? want : max_splits;

@@ -110,6 +110,20 @@ int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, 
                       void *Y, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Forward pass with partial batching (Sec. III-B, "Batching and Data Parallelism": b_p of the b images are
+ * lowered and multiplied at a time; App. C, Fig. (b), (c): the lowered data grows linearly with b_p and one
+ * large product beats many small ones).  Runs omni_conv_forward's explicit path on consecutive groups of
+ * b_p images (the last group may be smaller) through ONE workspace sized for b_p images:
+ * workspace_bytes >= omni_conv_workspace_bytes of the same descriptor with N = b_p.  Every output element
+ * is the same sum in the same order for every b_p, so Y is bit-identical to omni_conv_forward's.
+ * 1 <= b_p <= N; for b_p < N one image of X and of Y must be a multiple of 16 bytes (OMNI_MISALIGNED
+ * otherwise).  OMNI_FLAG_FUSED is ignored: the knob is about D-hat's footprint.
+ */
+int omni_conv_forward_partial(const omni_conv_desc *desc, int32_t b_p, const void *X, const void *W,
+                              const float *bias, void *Y, void *workspace, size_t workspace_bytes,
+                              void *hip_stream);
+
+/*
  * Data gradient (Sec. II-B: BW maps the gradient w.r.t. the layer's output to the gradient
  * w.r.t. its input).  Steps: dY is packed into the matrix dY-hat [F][ld]; one MFMA GEMM
  * dD-hat[K x M] = K-hat^T[K x F] * dY-hat[F x M]; col2im sums the entries of dD-hat that were copies

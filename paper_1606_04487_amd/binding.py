@@ -28,7 +28,7 @@ FLAG_RELU, FLAG_DHAT_CACHED, FLAG_FUSED = 1, 2, 4
 
 SYMBOLS = [
     "omni_conv_output_dims", "omni_conv_dhat_ld", "omni_conv_workspace_bytes", "omni_conv_fused_supported",
-    "omni_conv_forward",
+    "omni_conv_forward", "omni_conv_forward_partial",
     "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
     "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward", "omni_status_string", "omni_version",
@@ -62,6 +62,7 @@ _lib.omni_version.restype = ctypes.c_char_p
 _lib.omni_conv_output_dims.argtypes = [_dp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
 _lib.omni_conv_dhat_ld.argtypes = [_dp, ctypes.POINTER(_i64)]
 _lib.omni_conv_fused_supported.argtypes = [_dp, ctypes.c_int]
+_lib.omni_conv_forward_partial.argtypes = [_dp, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.omni_conv_workspace_bytes.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(_sz)]
 _lib.omni_conv_forward.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.omni_conv_backward_data.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -172,6 +173,20 @@ def conv_forward(desc: ConvDesc, X, W, bias=None, Y=None, workspace=None):
         workspace = alloc_workspace(desc, PASS_FORWARD, X.device)
     _check(_lib.omni_conv_forward(ctypes.byref(desc), _p(X), _p(W), _p(bias), _p(Y), _p(workspace),
                                   workspace.numel(), _stream()))
+    return Y
+
+
+def conv_forward_partial(desc: ConvDesc, b_p: int, X, W, bias=None, Y=None, workspace=None):
+    """omni_conv_forward_partial: the forward pass b_p images at a time through a workspace sized for b_p."""
+    ho, wo = conv_output_dims(desc)
+    if Y is None:
+        Y = torch.empty((desc.N, desc.F, ho, wo), dtype=torch_dtype(desc.dtype), device=X.device)
+    if workspace is None:
+        sub = ConvDesc.from_buffer_copy(desc)
+        sub.N = b_p
+        workspace = alloc_workspace(sub, PASS_FORWARD, X.device)
+    _check(_lib.omni_conv_forward_partial(ctypes.byref(desc), b_p, _p(X), _p(W), _p(bias), _p(Y), _p(workspace),
+                                          workspace.numel(), _stream()))
     return Y
 
 

@@ -226,6 +226,38 @@ int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, 
     return launch_gemm_forward(g, desc->dtype, a, s);
 }
 
+int omni_conv_forward_partial(const omni_conv_desc *desc, int32_t b_p, const void *X, const void *W,
+                              const float *bias, void *Y, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (b_p < 1 || b_p > desc->N || X == nullptr || Y == nullptr) return OMNI_INVALID_ARGUMENT;
+    const size_t e = elem_size(desc->dtype);
+    const size_t x_image = (size_t)g.C * g.H * g.W * e, y_image = (size_t)g.F * g.HoWo * e;
+    if (b_p < desc->N && (x_image % 16 != 0 || y_image % 16 != 0)) return OMNI_MISALIGNED;
+    omni_conv_desc part = *desc;
+    part.flags &= ~(uint32_t)OMNI_FLAG_FUSED;
+    // check every group's arguments before the first launch: a failed call launches nothing
+    part.N = b_p;
+    ForwardWs w;
+    ConvGeom gp;
+    st = make_geom(&part, &gp);
+    if (st != OMNI_OK) return st;
+    plan_forward(gp, part.dtype, &w);
+    if (W == nullptr || workspace == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(workspace) || (bias && !aligned16(bias)))
+        return OMNI_MISALIGNED;
+    if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
+    for (int32_t n0 = 0; n0 < desc->N; n0 += b_p) {
+        part.N = desc->N - n0 < b_p ? desc->N - n0 : b_p;
+        st = omni_conv_forward(&part, (const char *)X + (size_t)n0 * x_image, W, bias, (char *)Y + (size_t)n0 * y_image,
+                               workspace, workspace_bytes, hip_stream);
+        if (st != OMNI_OK) return st;
+    }
+    return OMNI_OK;
+}
+
 int omni_conv_backward_data(const omni_conv_desc *desc, const void *dY, const void *W, void *dX, void *workspace,
                             size_t workspace_bytes, void *hip_stream)
 {

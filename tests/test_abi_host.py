@@ -122,3 +122,26 @@ def test_product_path_has_no_cpu_fallback():
         if name.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", name)).read()
             assert "paper_1606_04487_amd" not in text and "omniconv" not in text, name
+
+
+def test_partial_batching_workspace_is_linear_in_bp_and_checks_arguments():
+    """Sec. III-B / App. C Fig. (c): the lowered data, hence the workspace, grows linearly with b_p."""
+    from paper_1606_04487_amd import binding as B
+    sizes = {}
+    for bp in (1, 2, 4, 8, 64, 256):
+        d = B.conv_desc(bp, 96, 27, 27, 256, 5, 5, 1, 2, B.BF16)
+        sizes[bp] = B.conv_workspace_bytes(d, B.PASS_FORWARD)
+    khat = 256 * 2432 * 2                                   # the model matrix does not grow with b_p
+    for bp in (64, 256):
+        dhat = 2400 * bp * 27 * 27 * 2                      # K x (b_p * m^2) elements of 2 bytes (+ padding to 64 columns)
+        assert dhat <= sizes[bp] - khat <= dhat * 1.01 + 4096
+    assert abs((sizes[256] - khat) / (sizes[64] - khat) - 4.0) < 0.01
+    # argument checks happen on the host, before any launch
+    d = B.conv_desc(8, 96, 27, 27, 256, 5, 5, 1, 2, B.BF16)
+    import ctypes
+    lib = B._lib
+    assert lib.omni_conv_forward_partial(ctypes.byref(d), 0, 16, 16, None, 16, 16, 1 << 40, None) == -1
+    assert lib.omni_conv_forward_partial(ctypes.byref(d), 9, 16, 16, None, 16, 16, 1 << 40, None) == -1
+    assert lib.omni_conv_forward_partial(ctypes.byref(d), 2, 16, 16, None, 16, 16, 64, None) == -3
+    odd = B.conv_desc(4, 3, 5, 5, 2, 3, 3, 1, 1, B.BF16)    # one image = 150 bytes: groups would be misaligned
+    assert lib.omni_conv_forward_partial(ctypes.byref(odd), 2, 16, 16, None, 16, 16, 1 << 40, None) == -4

@@ -311,3 +311,19 @@ def test_workspace_too_small_and_misaligned(B):
     with pytest.raises(B.OmniError) as e:
         B.conv_forward(d, Xg, Wg, None, workspace=ws[4:])
     assert e.value.status == -4
+
+
+# ------------------------------------------------------------------------------------ partial batching
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_partial_batching_gives_identical_results(B, dtype):
+    """Sec. III-B: lowering and multiplying b_p images at a time changes memory and speed, not the result."""
+    cfg = (12, 8, 13, 13, 24, 3, 3, 1, 1, 1, 1)
+    s, X, Wt, b, _ = make(cfg, dtype, 21)
+    d = desc_of(B, cfg, dtype, B.FLAG_RELU)
+    Xg, Wg, bg = gpu(X, dtype), gpu(Wt, dtype), gpu(b)
+    whole = B.conv_forward(d, Xg, Wg, bg)
+    assert rel_err(host(whole), np.maximum(oracle.conv_forward(s, X, Wt, b), 0)) <= TOL[dtype]
+    for bp in (1, 2, 5, 6, 12):                      # 5 does not divide 12: a smaller last group
+        part = B.conv_forward_partial(d, bp, Xg, Wg, bg)
+        assert torch.equal(part, whole), bp

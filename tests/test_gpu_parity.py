@@ -327,3 +327,26 @@ def test_partial_batching_gives_identical_results(B, dtype):
     for bp in (1, 2, 5, 6, 12):                      # 5 does not divide 12: a smaller last group
         part = B.conv_forward_partial(d, bp, Xg, Wg, bg)
         assert torch.equal(part, whole), bp
+
+
+# ------------------------------------------------------------------------------------ fully connected layers
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("cfg", [(16, 64, 6, 6, 136, 6, 6, 1, 1, 0, 0),     # FC6-like: the window covers the whole image
+                                 (40, 200, 1, 1, 72, 1, 1, 1, 1, 0, 0)])   # FC7/8-like: 1 x 1 images
+def test_fully_connected_as_convolution(B, cfg, dtype):
+    """Sec. II-C: a fully connected layer is a dense matrix product; it is the convolution whose window is
+    the whole image (App. C's m = n - k + 1 = 1), so the same three entry points serve the FC phase."""
+    s, X, Wt, b, dY = make(cfg, dtype, 31)
+    d = desc_of(B, cfg, dtype)
+    Xg, Wg, bg, dYg = gpu(X, dtype), gpu(Wt, dtype), gpu(b), gpu(dY, dtype)
+    N, C, H, W, F = cfg[:5]
+    Y = B.conv_forward(d, Xg, Wg, bg)
+    ref = X.reshape(N, -1).astype(np.float64) @ Wt.reshape(F, -1).astype(np.float64).T + b      # the plain definition
+    assert rel_err(host(Y).reshape(N, F), ref) <= TOL[dtype]
+    assert rel_err(host(Y), oracle.conv_forward(s, X, Wt, b)) <= TOL[dtype]
+    dX = B.conv_backward_data(d, dYg, Wg)
+    assert rel_err(host(dX).reshape(N, -1), dY.reshape(N, F).astype(np.float64) @ Wt.reshape(F, -1)) <= TOL[dtype]
+    dW, db = B.conv_backward_weights(d, Xg, dYg)
+    assert rel_err(host(dW).reshape(F, -1), dY.reshape(N, F).astype(np.float64).T @ X.reshape(N, -1)) <= 1e-4
+    assert rel_err(host(db), dY.reshape(N, F).sum(0)) <= 1e-4

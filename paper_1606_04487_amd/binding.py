@@ -32,7 +32,7 @@ SYMBOLS = [
     "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
     "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward", "omni_status_string", "omni_version",
-    "omni_profile_enable", "omni_profile_kernel_count", "omni_profile_kernel_name", "omni_profile_summary",
+    "omni_profile_enable", "omni_profile_select", "omni_profile_kernel_count", "omni_profile_kernel_name", "omni_profile_summary",
 ]
 
 
@@ -313,6 +313,15 @@ def maxpool_relu_backward(dy, argmax, y_pooled, H: int, W: int, k: int = 3, stri
 def profile_enable(on: bool) -> None:
     """omni_profile_enable: start (and clear) or stop per-kernel event timing."""
     _check(_lib.omni_profile_enable(int(bool(on))))
+
+
+def profile_select(kernel_name: Optional[str]) -> None:
+    """omni_profile_select: record events for one kernel class only (None: all classes)."""
+    if kernel_name is None:
+        _check(_lib.omni_profile_select(-1))
+        return
+    names = [_lib.omni_profile_kernel_name(i).decode() for i in range(_lib.omni_profile_kernel_count())]
+    _check(_lib.omni_profile_select(names.index(kernel_name)))
 
 
 def profile_summary() -> dict:

@@ -22,6 +22,7 @@ struct Record { int kid; hipEvent_t start, stop; double flops, bytes; };
 
 static std::mutex g_mu;
 static bool g_on = false;
+static int g_only = -1;  // record this kernel class only (-1: all)
 static std::vector<Record> g_records;
 static std::vector<hipEvent_t> g_free;
 static const size_t kMaxRecords = 1u << 20;
@@ -42,7 +43,7 @@ static hipEvent_t get_event()
 
 ProfScope::ProfScope(int kid, hipStream_t s, double flops, double bytes) : slot_(-1), stream_(s)
 {
-    if (!g_on) return;
+    if (!g_on || (g_only >= 0 && kid != g_only)) return;
     std::lock_guard<std::mutex> lock(g_mu);
     if (g_records.size() >= kMaxRecords) return;
     Record r{kid, get_event(), get_event(), flops, bytes};
@@ -74,6 +75,15 @@ int omni_profile_enable(int on)
     }
     g_records.clear();
     g_on = on != 0;
+    g_only = -1;
+    return OMNI_OK;
+}
+
+int omni_profile_select(int kernel_id)
+{
+    if (kernel_id < -1 || kernel_id >= KID_COUNT) return OMNI_INVALID_ARGUMENT;
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_only = kernel_id;
     return OMNI_OK;
 }
 

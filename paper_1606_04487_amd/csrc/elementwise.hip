@@ -268,7 +268,8 @@ __device__ __forceinline__ void run_to_lds(const T *__restrict__ src, int count,
     }
 }
 
-template <typename T>
+// K3S2: the 3 x 3 / stride 2 pool of the paper's networks with its loops unrolled and its divisions as shifts
+template <typename T, bool K3S2>
 __global__ __launch_bounds__(256) void maxpool_fwd_lds_kernel(PoolGeom g, int64_t planes, int pb,
                                                               const T *__restrict__ x, T *__restrict__ y,
                                                               uint8_t *__restrict__ argmax)
@@ -288,18 +289,35 @@ __global__ __launch_bounds__(256) void maxpool_fwd_lds_kernel(PoolGeom g, int64_
         int best = -1;
         float bv = 0.f;
         T braw = (T)0;
-        for (int ky = 0; ky < g.k; ++ky) {
-            int iy = (int)oy * g.s + ky;
-            if (iy >= g.H) break;
-            for (int kx = 0; kx < g.k; ++kx) {
-                int ix = (int)ox * g.s + kx;
-                if (ix >= g.W) break;
-                T raw = src[iy * g.W + ix];
-                float v = Elem<T>::to_f32(raw);
-                if (best < 0 || v > bv) {  // strict: the first maximum in scan order wins
-                    best = ky * g.k + kx;
-                    bv = v;
-                    braw = raw;
+        if constexpr (K3S2) {
+            const T *w0 = src + (int)oy * 2 * g.W + (int)ox * 2;  // the window's first pixel is always inside
+#pragma unroll
+            for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+                for (int kx = 0; kx < 3; ++kx) {
+                    const bool in = (int)oy * 2 + ky < g.H && (int)ox * 2 + kx < g.W;
+                    T raw = in ? w0[ky * g.W + kx] : (T)0;
+                    float v = Elem<T>::to_f32(raw);
+                    if (in && (best < 0 || v > bv)) {
+                        best = ky * 3 + kx;
+                        bv = v;
+                        braw = raw;
+                    }
+                }
+        } else {
+            for (int ky = 0; ky < g.k; ++ky) {
+                int iy = (int)oy * g.s + ky;
+                if (iy >= g.H) break;
+                for (int kx = 0; kx < g.k; ++kx) {
+                    int ix = (int)ox * g.s + kx;
+                    if (ix >= g.W) break;
+                    T raw = src[iy * g.W + ix];
+                    float v = Elem<T>::to_f32(raw);
+                    if (best < 0 || v > bv) {  // strict: the first maximum in scan order wins
+                        best = ky * g.k + kx;
+                        bv = v;
+                        braw = raw;
+                    }
                 }
             }
         }
@@ -308,7 +326,7 @@ __global__ __launch_bounds__(256) void maxpool_fwd_lds_kernel(PoolGeom g, int64_
     }
 }
 
-template <typename T, bool RELU>
+template <typename T, bool RELU, bool K3S2>
 __global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_t planes, int pb,
                                                               const T *__restrict__ dy, const uint8_t *__restrict__ argmax,
                                                               const T *__restrict__ y, T *__restrict__ dx)
@@ -354,21 +372,37 @@ __global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_
         for (int e = 0; e < VEC; ++e) {
             float acc = 0.f;
             if (v0 + e < total) {
-                int oy_lo = (int)iy - g.k + 1;
-                oy_lo = oy_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(oy_lo + g.s - 1));
-                int oy_hi = (int)g.div_s.div(iy);
-                if (oy_hi > g.Ho - 1) oy_hi = g.Ho - 1;
-                int ox_lo = (int)ix - g.k + 1;
-                ox_lo = ox_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(ox_lo + g.s - 1));
-                int ox_hi = (int)g.div_s.div(ix);
-                if (ox_hi > g.Wo - 1) ox_hi = g.Wo - 1;
                 const int obase = (int)pl * howo;
-                for (int oy = oy_lo; oy <= oy_hi; ++oy)
-                    for (int ox = ox_lo; ox <= ox_hi; ++ox) {
-                        int code = ((int)iy - oy * g.s) * g.k + ((int)ix - ox * g.s);
-                        int o = obase + oy * g.Wo + ox;
-                        if (gam[o] == (uint8_t)code) acc += Elem<T>::to_f32(gdy[o]);
-                    }
+                if constexpr (K3S2) {
+                    // windows oy with 2*oy <= iy <= 2*oy + 2: (iy-1)/2 rounded up .. iy/2, at most two of them
+                    const int oy_hi = (int)(iy >> 1), ox_hi = (int)(ix >> 1);
+#pragma unroll
+                    for (int dy_ = 1; dy_ >= 0; --dy_)
+#pragma unroll
+                        for (int dx_ = 1; dx_ >= 0; --dx_) {
+                            const int oy = oy_hi - dy_, ox = ox_hi - dx_;
+                            const int wy = (int)iy - 2 * oy, wx = (int)ix - 2 * ox;  // position inside that window
+                            if (oy >= 0 && ox >= 0 && oy < g.Ho && ox < g.Wo && wy < 3 && wx < 3) {
+                                int o = obase + oy * g.Wo + ox;
+                                if (gam[o] == (uint8_t)(wy * 3 + wx)) acc += Elem<T>::to_f32(gdy[o]);
+                            }
+                        }
+                } else {
+                    int oy_lo = (int)iy - g.k + 1;
+                    oy_lo = oy_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(oy_lo + g.s - 1));
+                    int oy_hi = (int)g.div_s.div(iy);
+                    if (oy_hi > g.Ho - 1) oy_hi = g.Ho - 1;
+                    int ox_lo = (int)ix - g.k + 1;
+                    ox_lo = ox_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(ox_lo + g.s - 1));
+                    int ox_hi = (int)g.div_s.div(ix);
+                    if (ox_hi > g.Wo - 1) ox_hi = g.Wo - 1;
+                    for (int oy = oy_lo; oy <= oy_hi; ++oy)
+                        for (int ox = ox_lo; ox <= ox_hi; ++ox) {
+                            int code = ((int)iy - oy * g.s) * g.k + ((int)ix - ox * g.s);
+                            int o = obase + oy * g.Wo + ox;
+                            if (gam[o] == (uint8_t)code) acc += Elem<T>::to_f32(gdy[o]);
+                        }
+                }
             }
             res[e] = Elem<T>::from_f32(acc);
             if (++ix == (uint32_t)g.W) {
@@ -425,9 +459,15 @@ int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
         dim3 grid((unsigned)((planes + pb - 1) / pb));
         size_t lds = (size_t)pb * hw * elem_size(dtype) + 16;
         if (dtype == OMNI_BF16)
-            hipLaunchKernelGGL(maxpool_fwd_lds_kernel<bf16_t>, grid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)x, (bf16_t *)y, argmax);
+            if (k == 3 && stride == 2)
+                hipLaunchKernelGGL((maxpool_fwd_lds_kernel<bf16_t, true>), grid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)x, (bf16_t *)y, argmax);
+            else
+                hipLaunchKernelGGL((maxpool_fwd_lds_kernel<bf16_t, false>), grid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)x, (bf16_t *)y, argmax);
         else
-            hipLaunchKernelGGL(maxpool_fwd_lds_kernel<float>, grid, dim3(256), lds, s, g, planes, pb, (const float *)x, (float *)y, argmax);
+            if (k == 3 && stride == 2)
+                hipLaunchKernelGGL((maxpool_fwd_lds_kernel<float, true>), grid, dim3(256), lds, s, g, planes, pb, (const float *)x, (float *)y, argmax);
+            else
+                hipLaunchKernelGGL((maxpool_fwd_lds_kernel<float, false>), grid, dim3(256), lds, s, g, planes, pb, (const float *)x, (float *)y, argmax);
         OMNI_LAUNCH_CHECK();
         return OMNI_OK;
     }
@@ -458,7 +498,13 @@ int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
         if (pb > 0 && (planes + pb - 1) / pb <= 0x7fffffffll) {
             dim3 grid((unsigned)((planes + pb - 1) / pb));
             size_t lds = (((size_t)pb * howo * elem_size(dtype) + 15) / 16) * 16 + (size_t)pb * howo + 16;
-#define OMNI_POOL_BWD(T, R) hipLaunchKernelGGL((maxpool_bwd_lds_kernel<T, R>), grid, dim3(256), lds, s, g, planes, pb, (const T *)dy, argmax, (const T *)y, (T *)dx)
+#define OMNI_POOL_BWD(T, R)                                                                                              \
+    do {                                                                                                             \
+        if (k == 3 && stride == 2)                                                                                   \
+            hipLaunchKernelGGL((maxpool_bwd_lds_kernel<T, R, true>), grid, dim3(256), lds, s, g, planes, pb, (const T *)dy, argmax, (const T *)y, (T *)dx); \
+        else                                                                                                         \
+            hipLaunchKernelGGL((maxpool_bwd_lds_kernel<T, R, false>), grid, dim3(256), lds, s, g, planes, pb, (const T *)dy, argmax, (const T *)y, (T *)dx); \
+    } while (0)
             if (dtype == OMNI_BF16) {
                 if (y) OMNI_POOL_BWD(bf16_t, true); else OMNI_POOL_BWD(bf16_t, false);
             } else {

@@ -476,18 +476,29 @@ __global__ __launch_bounds__(256) void pack_dyhat_kernel(ConvGeom g, const T *__
         uint32_t n, r;
         g.div_HoWo.divmod(m0 < g.M ? (uint32_t)m0 : 0u, n, r);
         VecOf<U, PACK_VEC> o;
+        if (m0 + PACK_VEC <= g.M && r + PACK_VEC <= (uint32_t)g.HoWo) {
+            // the 8 columns lie in one image: one load (element-aligned), two for fp32
+            __builtin_memcpy(&o, dY + ((int64_t)n * g.F + f) * g.HoWo + r, sizeof(o));
 #pragma unroll
-        for (int e = 0; e < PACK_VEC; ++e) {
-            U bits = 0;
-            if (m0 + e < g.M) {
-                const T *src = dY + ((int64_t)n * g.F + f) * g.HoWo + r;
-                bits = *reinterpret_cast<const U *>(src);
-                sum += Elem<T>::to_f32(*src);
+            for (int e = 0; e < PACK_VEC; ++e) {
+                T v;
+                __builtin_memcpy(&v, &o.v[e], sizeof(T));
+                sum += Elem<T>::to_f32(v);
             }
-            o.v[e] = bits;
-            if (++r == (uint32_t)g.HoWo) {
-                r = 0;
-                ++n;
+        } else {
+#pragma unroll
+            for (int e = 0; e < PACK_VEC; ++e) {
+                U bits = 0;
+                if (m0 + e < g.M) {
+                    const T *src = dY + ((int64_t)n * g.F + f) * g.HoWo + r;
+                    bits = *reinterpret_cast<const U *>(src);
+                    sum += Elem<T>::to_f32(*src);
+                }
+                o.v[e] = bits;
+                if (++r == (uint32_t)g.HoWo) {
+                    r = 0;
+                    ++n;
+                }
             }
         }
         // 8 x 4 bytes does not fit one 16-byte store: write two halves for fp32
@@ -545,14 +556,20 @@ __global__ __launch_bounds__(256) void pack_dyhat_rows_kernel(ConvGeom g, FastDi
         VecOf<uint16_t, 8> o;
         const bool live = (int)n < g.N;
         const bf16_t *src = dY + (((int64_t)(live ? n : 0) * g.F + f) * g.Ho + oy) * g.Wo + 8 * i;
+        if (live && 8 * (int)i + 8 <= g.Wo) {
+            __builtin_memcpy(&o, src, 16);  // element-aligned 16-byte load
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            uint16_t bits = 0;
-            if (live && 8 * (int)i + e < g.Wo) {
-                bits = src[e];
-                sum += bf16_to_f32(bits);
+            for (int e = 0; e < 8; ++e) sum += bf16_to_f32(o.v[e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                uint16_t bits = 0;
+                if (live && 8 * (int)i + e < g.Wo) {
+                    bits = src[e];
+                    sum += bf16_to_f32(bits);
+                }
+                o.v[e] = bits;
             }
-            o.v[e] = bits;
         }
         *reinterpret_cast<VecOf<uint16_t, 8> *>(out + (int64_t)f * ld + pack * 8) = o;
     }

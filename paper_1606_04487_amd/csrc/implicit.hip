@@ -40,6 +40,7 @@ constexpr int NT = 512;          // 8 wavefronts
 // tile gives each wavefront 64 x 128 results: 6 instead of 8 LDS fragment reads per 8 MFMAs, and LDS
 // bandwidth is what caps this kernel.
 constexpr int BN_NARROW = 256, PATCH_NARROW = 640;
+constexpr int BN_MID = 384, PATCH_MID = 800;
 constexpr int BN_WIDE = 512, PATCH_WIDE = 960;
 constexpr int TG = 9;            // window taps whose weights are staged in LDS together
 constexpr int MAX_SLOTS = 8;     // images a column tile may touch
@@ -54,7 +55,7 @@ struct Geom {
     int32_t n_chunks;        // C / CH
     int32_t Fp;              // F rounded up to the row tile
     int32_t tiles_f, tiles_m, n_items, per_xcd;
-    int32_t bn;              // columns per workgroup: BN_NARROW or BN_WIDE
+    int32_t bn;              // columns per workgroup: BN_NARROW, BN_MID or BN_WIDE
     FastDiv div_HoWo, div_Wo, div_W;
 };
 
@@ -378,17 +379,22 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
         }
         return true;
     };
-    // The wide tile when it fits and fills the 256 compute units' rounds about as well as the narrow one.
-    const char *e = getenv("OMNI_FUSED_BN");  // tuning override: 256 or 512
+    // Among the tiles that fit, the one with the least estimated time: rounds of the 256 compute units
+    // times the tile's width, the narrower tiles a few per cent dearer per column (their weights are
+    // staged for fewer columns, and they read more LDS fragments per MFMA).
+    const char *e = getenv("OMNI_FUSED_BN");  // tuning override: 256, 384 or 512
     int want = e != nullptr ? atoi(e) : 0;
-    auto fill = [&](int bn) {
-        int64_t items = (int64_t)g->tiles_f * ((g->M + bn - 1) / bn);
-        return (double)items / (double)((items + 255) / 256 * 256);
-    };
-    bool wide = fits(BN_WIDE, PATCH_WIDE) &&
-                (want == BN_WIDE || (want != BN_NARROW && fill(BN_WIDE) >= fill(BN_NARROW) - 0.05));
-    if (!wide && !fits(BN_NARROW, PATCH_NARROW)) return false;
-    g->bn = wide ? BN_WIDE : BN_NARROW;
+    const struct { int bn, patch; double per_column; } tiles[3] = {
+        {BN_WIDE, PATCH_WIDE, 1.0}, {BN_MID, PATCH_MID, 1.03}, {BN_NARROW, PATCH_NARROW, 1.06}};
+    double best = 0.0;
+    g->bn = 0;
+    for (const auto &t : tiles) {
+        if ((want != 0 && want != t.bn) || !fits(t.bn, t.patch)) continue;
+        int64_t items = (int64_t)g->tiles_f * ((g->M + t.bn - 1) / t.bn);
+        double cost = (double)((items + 255) / 256) * t.bn * t.per_column;
+        if (g->bn == 0 || cost < best) g->bn = t.bn, best = cost;
+    }
+    if (g->bn == 0) return false;
     g->tiles_m = (g->M + g->bn - 1) / g->bn;
     g->n_items = g->tiles_f * g->tiles_m;
     g->per_xcd = (g->n_items + 7) / 8;
@@ -430,6 +436,9 @@ int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, cons
     dim3 grid((unsigned)(g.per_xcd * 8)), block(NT);
     if (g.bn == BN_WIDE)
         hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4, BN_WIDE, PATCH_WIDE>), grid, block, 0, s, (const bf16_t *)X,
+                           (const bf16_t *)wt_scratch, g, epi);
+    else if (g.bn == BN_MID)
+        hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4, BN_MID, PATCH_MID>), grid, block, 0, s, (const bf16_t *)X,
                            (const bf16_t *)wt_scratch, g, epi);
     else
         hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4, BN_NARROW, PATCH_NARROW>), grid, block, 0, s, (const bf16_t *)X,

@@ -197,8 +197,10 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][TJ], int i_w
     constexpr int VEC = 16 / (int)sizeof(Out);   // results per 16-byte output piece
     constexpr int GPR = COLS / VEC;              // pieces per row
     constexpr int RPP = 64 / GPR;                // rows per pass of the wavefront
+    constexpr int PASSES = (SR + RPP - 1) / RPP;
+    constexpr bool EXACT = RPP * GPR == 64 && SR % RPP == 0;  // else some lanes or pass rows are idle
     constexpr int PITCH = staged_pitch(TJ);
-    static_assert(GPR <= 64 && SR % RPP == 0, "pass shape");
+    static_assert(GPR <= 64, "pass shape");
     const int li = lane % 32, h = lane / 32;
     const uint32_t rs = epi.row_stride32();
     char *base = epi.base32(z);
@@ -223,8 +225,9 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][TJ], int i_w
             }
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int p = 0; p < SR / RPP; ++p) {
+            for (int p = 0; p < PASSES; ++p) {
                 const int r = p * RPP + rr;
+                if (!EXACT && (rr >= RPP || r >= SR)) continue;
                 const int i = i_wave + t * 32 + half * SR + r;
                 float x[VEC];
 #pragma unroll

@@ -111,6 +111,26 @@ def test_fused_backward_data(B, cfg):
     assert np.array_equal(got, again)
 
 
+@pytest.mark.parametrize("bn", ["256", "384", "512"])
+@pytest.mark.parametrize("cfg", [FUSED_SHAPES[1], FUSED_SHAPES[2], FUSED_SHAPES[8], (7, 64, 13, 13, 96, 3, 3, 1, 1)])
+def test_fused_every_column_tile(B, cfg, bn, monkeypatch):
+    """Each of the kernel's column-tile widths, forced through the tuning override, on both fused passes
+    (a width whose patch does not fit a shape is skipped by the library, which then declines)."""
+    monkeypatch.setenv("OMNI_FUSED_BN", bn)
+    s, X, Wt, b, dY = make(cfg, 21)
+    d = desc_of(B, cfg, B.FLAG_FUSED | B.FLAG_RELU)
+    ran = 0
+    if B.conv_fused_supported(d, B.PASS_FORWARD):
+        got = host(B.conv_forward(d, gpu(X), gpu(Wt), gpu(b, False)))
+        assert rel_err(got, np.maximum(oracle.conv_forward(s, X, Wt, b), 0)) <= TOL
+        ran += 1
+    if B.conv_fused_supported(d, B.PASS_BACKWARD_DATA):
+        got = host(B.conv_backward_data(d, gpu(dY), gpu(Wt)))
+        assert rel_err(got, oracle.conv_backward_data(s, dY, Wt)) <= TOL
+        ran += 1
+    assert ran > 0 or bn != "256"
+
+
 @pytest.mark.parametrize("cfg", FUSED_SHAPES + [(3, 5, 13, 13, 7, 3, 3, 1, 1), (2, 20, 27, 27, 130, 5, 5, 2, 2),
                                                 (2, 3, 9, 30, 4, 3, 5, 2, 4), (2, 30, 13, 13, 250, 3, 3, 1, 1),
                                                 (3, 29, 9, 11, 256, 3, 2, 0, 1), (1, 57, 27, 27, 200, 5, 5, 2, 2)])

@@ -79,7 +79,7 @@ static void plan_splits(const ConvGeom &g, int dtype, int64_t ld, int *splits_ou
     gemm_wgrad_tile(g.F, g.K, &bm, &bn);
     int64_t tiles = ((g.F + bm - 1) / bm) * (int64_t)((g.K + bn - 1) / bn);
     int64_t steps = (ld + bk - 1) / bk;
-    int64_t rounds = bm * bn >= 256 * 256 ? 1 : 2;
+    int64_t rounds = bm * bn >= 192 * 256 ? 1 : 2;
     int64_t want = (256 * rounds) / tiles;
     int64_t max_splits = steps / 4 > 0 ? steps / 4 : 1;
     int64_t splits = want < max_splits ? want : max_splits;

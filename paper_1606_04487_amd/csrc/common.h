@@ -148,6 +148,7 @@ int launch_gemm_dgrad(const ConvGeom &g, int dtype, const GemmDgradArgs &a, hipS
 struct GemmWgradArgs { const void *dYhat; const void *Dhat; int64_t ldd; float *partials; int splits; int64_t chunk; float *dW; const void *X_direct; };
 int launch_gemm_wgrad(const ConvGeom &g, int dtype, const GemmWgradArgs &a, hipStream_t s);
 bool wgrad_direct_supported(const ConvGeom &g, int dtype);
+bool wgrad_direct_planes(const ConvGeom &g);  // its padded unit is the image plane, not the output row
 int gemm_red_tile(int dtype);  // reduction extent of one LDS tile (elements)
 void gemm_wgrad_tile(int F, int K, int *bm, int *bn);
 

@@ -174,69 +174,151 @@ template <int TILE_COLS, int NT> struct OuterContigLoader<bf16_t, TILE_COLS, NT>
 struct DirectSrc {
     const bf16_t *X;
     int32_t C, H, W, HW, K, ph, pw;
-    int32_t rows;   // N * Ho: output rows in the batch
+    int32_t rows;   // padded units in the batch: N * Ho output rows, or N image planes
     int32_t total;  // elements of X (< 2^31)
     FastDiv div_p8, div_Ho, div_khkw, div_kw;
+    int32_t HoWo, KK;  // plane mode: output positions per image, window taps
+    FastDiv div_W;
 };
 
-template <int TILE_ROWS, int NT> struct DirectLoader {
+// Plane mode.  When the output is as wide as the input (stride 1, 2*pw = kw - 1), output position q of an
+// image and window tap (ky, kx) meet input element q + (ky - ph) * W + (kx - pw) of the channel's plane,
+// also where q wraps from one output row to the next.  So only each image's whole plane is padded to a
+// multiple of 8 positions (not every row), a pack is still one 16-byte load, and which of its 8 elements
+// are real pixels depends on (pack within the plane, tap) alone: a table in LDS, one byte per element,
+// built when the workgroup starts.  Row (pack j, tap KK) of the table is zero: result columns beyond K.
+constexpr int DIRECT_TAB = 2560;  // table entries (8 bytes each) a workgroup can hold beside its tiles
+enum { DIRECT_ROWS = 1, DIRECT_ROWS_FIXED = 2, DIRECT_PLANES = 3 };
+
+__device__ __forceinline__ void build_plane_table(const DirectSrc &d, uint2 *tab, int tid, int nt)
+{
+    const int p8 = (int)d.div_p8.d, kw = (int)d.div_kw.d;
+    for (int idx = tid; idx < p8 * (d.KK + 1); idx += nt) {
+        const int j = idx / (d.KK + 1), tap = idx - j * (d.KK + 1);
+        uint32_t ky, kx;
+        d.div_kw.divmod((uint32_t)(tap < d.KK ? tap : 0), ky, kx);
+        uint32_t w[2] = {0u, 0u};
+        for (int e = 0; e < 8; ++e) {
+            const int q = 8 * j + e;
+            uint32_t oy, ox;
+            d.div_W.divmod((uint32_t)q, oy, ox);
+            const bool ok = tap < d.KK && q < d.HoWo && (unsigned)((int)oy + (int)ky - d.ph) < (unsigned)d.H &&
+                            (unsigned)((int)ox + (int)kx - d.pw) < (unsigned)d.W;
+            if (ok) w[e / 4] |= 0xffu << (8 * (e % 4));
+        }
+        tab[idx] = make_uint2(w[0], w[1]);
+    }
+    (void)kw;
+}
+
+// MODE DIRECT_ROWS_FIXED: the row-padded rows are 1, 2, 4 or 8 packs long, so a reduction step (8 packs)
+// moves every thread by whole output rows and the pack's place in its row -- hence which of its 8 elements
+// fall beside the image for a given window column -- is the same in every step: those masks are built once.
+template <int TILE_ROWS, int NT, int MODE> struct DirectLoader {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    static constexpr bool FIXED = MODE == DIRECT_ROWS_FIXED, PLANES = MODE == DIRECT_PLANES;
     static constexpr int PER_THREAD = TILE_ROWS * NPACK / NT;
     static_assert(TILE_ROWS * NPACK % NT == 0 && NT % NPACK == 0, "tile must divide over the threads");
     u32x4 v[PER_THREAD];
-    // bits 0..7: which elements are real pixels; 8..11: signed element shift (non-zero only where the 16
-    // bytes had to be moved to stay inside the tensor: first and last row of X)
+    // rows: bits 0..7: which elements are real pixels (FIXED: bit 0: the input row exists).
+    // bits 8..11: signed element shift (non-zero only where the 16 bytes had to be moved to stay inside
+    // the tensor: first and last row of X)
     uint32_t masks[PER_THREAD];
-    int kbase[PER_THREAD], dky[PER_THREAD], dkx[PER_THREAD];
+    int kbase[PER_THREAD];
+    int dky[PLANES ? 1 : PER_THREAD], dkx[FIXED || PLANES ? 1 : PER_THREAD];
+    u32x4 colmask[FIXED ? PER_THREAD : 1];
+    int tap[PLANES ? PER_THREAD : 1];       // planes: column of the mask table
+    uint2 emask[PLANES ? PER_THREAD : 1];   // planes: this step's table entries
 
+    static __device__ __forceinline__ uint32_t spread(uint32_t m, int bit)  // two mask bits -> two 16-bit fields
+    {
+        uint32_t lo = (uint32_t)((int32_t)(m << (31 - bit)) >> 31), hi = (uint32_t)((int32_t)(m << (30 - bit)) >> 31);
+        return (lo & 0xffffu) | (hi & 0xffff0000u);
+    }
     __device__ __forceinline__ void init(const DirectSrc &d, int col0, int tid)
     {
+        uint32_t row_unused, i;
+        d.div_p8.divmod((uint32_t)(tid % NPACK), row_unused, i);  // FIXED: this thread's pack within its row
+        const int ox0 = 8 * (int)i;
 #pragma unroll
         for (int q = 0; q < PER_THREAD; ++q) {
             int k = col0 + (tid + q * NT) / NPACK;
             uint32_t c, rem, ky, kx;
             d.div_khkw.divmod((uint32_t)(k < d.K ? k : 0), c, rem);
             d.div_kw.divmod(rem, ky, kx);
-            dky[q] = k < d.K ? (int)ky - d.ph : -(1 << 24);  // rows beyond K: no input row is ever valid
-            dkx[q] = (int)kx - d.pw;
-            kbase[q] = (int)c * d.HW + ((int)ky - d.ph) * d.W + dkx[q];
-        }
-    }
-    // m0: first (row-padded) column of this thread's packs -- the same for all of them, NT being a
-    // multiple of NPACK
-    __device__ __forceinline__ void issue(const DirectSrc &d, int m0)
-    {
-        uint32_t row, i, n, oy;
-        d.div_p8.divmod((uint32_t)m0 >> 3, row, i);
-        const bool live = (int)row < d.rows;
-        d.div_Ho.divmod(live ? row : 0u, n, oy);
-        const int ox0 = 8 * (int)i;
-        const int base = (int)n * d.C * d.HW + (int)oy * d.W + ox0;
-        const int top = d.total - 8;
+            const int dx = (int)kx - d.pw;
+            kbase[q] = (int)c * d.HW + ((int)ky - d.ph) * d.W + dx;
+            if constexpr (PLANES) {
+                tap[q] = k < d.K ? (int)rem : d.KK;
+            } else {
+                dky[q] = k < d.K ? (int)ky - d.ph : -(1 << 24);  // rows beyond K: no input row is ever valid
+                if constexpr (FIXED) {
+                    const int ix = ox0 + dx;
+                    const int lo = ix < 0 ? -ix : 0, hi = d.W - ix < 8 ? d.W - ix : 8;
+                    const uint32_t m = hi > lo ? (1u << hi) - (1u << lo) : 0u;
+                    if (m == 0u) dky[q] = -(1 << 24);
 #pragma unroll
-        for (int p = 0; p < PER_THREAD; ++p) {
-            const int ix = ox0 + dkx[p];
-            const int lo = ix < 0 ? -ix : 0, hi = d.W - ix < 8 ? d.W - ix : 8;
-            const bool ok = live && (unsigned)((int)oy + dky[p]) < (unsigned)d.H && hi > lo;
-            const uint32_t m = ok ? (1u << hi) - (1u << lo) : 0u;
-            // element offset of the load, moved inside [0, total - 8] where it sticks out
-            const int e = base + kbase[p];
-            const int c = ok ? (e < 0 ? 0 : (e > top ? top : e)) : 0;
-            const uint32_t sft = ok ? (uint32_t)(e - c) & 15u : 0u;
-            __builtin_memcpy(&v[p], d.X + c, 16);
-            masks[p] = m | (sft << 8);
+                    for (int w = 0; w < 4; ++w) colmask[q][w] = spread(m, 2 * w);
+                } else {
+                    dkx[q] = dx;
+                }
+            }
         }
     }
-    static __device__ __forceinline__ uint32_t spread(uint32_t m, int bit)  // two mask bits -> two 16-bit fields
+    // m0: first padded column of this thread's packs -- the same for all of them, NT being a multiple of
+    // NPACK.  tab: the plane mode's mask table.
+    __device__ __forceinline__ void issue(const DirectSrc &d, int m0, const uint2 *tab)
     {
-        uint32_t lo = (uint32_t)((int32_t)(m << (31 - bit)) >> 31), hi = (uint32_t)((int32_t)(m << (30 - bit)) >> 31);
-        return (lo & 0xffffu) | (hi & 0xffff0000u);
+        const int top = d.total - 8;
+        const char *xb = reinterpret_cast<const char *>(d.X);
+        if constexpr (PLANES) {
+            uint32_t n, j;
+            d.div_p8.divmod((uint32_t)m0 >> 3, n, j);
+            const bool live = (int)n < d.rows;
+            const int base = (live ? (int)n : 0) * d.C * d.HW + 8 * (int)j;
+            const int trow = (int)j * (d.KK + 1);
+#pragma unroll
+            for (int p = 0; p < PER_THREAD; ++p) {
+                // element offset of the load, moved inside [0, total - 8] where it sticks out (by at most 7
+                // elements if any element of the pack is a real pixel; else the mask is zero anyway)
+                const int e = base + kbase[p];
+                const int c = e < 0 ? 0 : (e > top ? top : e);
+                __builtin_memcpy(&v[p], xb + 2u * (uint32_t)c, 16);
+                masks[p] = (uint32_t)(e - c) & 15u;
+                emask[p] = tab[live ? trow + tap[p] : d.KK];
+            }
+        } else {
+            uint32_t row, i, n, oy;
+            d.div_p8.divmod((uint32_t)m0 >> 3, row, i);
+            const bool live = (int)row < d.rows;
+            d.div_Ho.divmod(live ? row : 0u, n, oy);
+            const int ox0 = 8 * (int)i;
+            const int base = (int)n * d.C * d.HW + (int)oy * d.W + ox0;
+#pragma unroll
+            for (int p = 0; p < PER_THREAD; ++p) {
+                bool ok = live && (unsigned)((int)oy + dky[p]) < (unsigned)d.H;
+                uint32_t m = 1u;
+                if constexpr (!FIXED) {
+                    const int ix = ox0 + dkx[p];
+                    const int lo = ix < 0 ? -ix : 0, hi = d.W - ix < 8 ? d.W - ix : 8;
+                    ok = ok && hi > lo;
+                    m = (1u << hi) - (1u << lo);
+                }
+                // element offset of the load, moved inside [0, total - 8] where it sticks out
+                const int e = base + kbase[p];
+                const int c = ok ? (e < 0 ? 0 : (e > top ? top : e)) : 0;
+                const uint32_t sft = ok ? (uint32_t)(e - c) & 15u : 0u;
+                __builtin_memcpy(&v[p], xb + 2u * (uint32_t)c, 16);
+                masks[p] = (ok ? m : 0u) | (sft << 8);
+            }
+        }
     }
-    // element j of the result = element j + s of x (s = 4-bit two's complement, |s| <= 7)
+    // element j of the result = element j + s of x (s = 4-bit two's complement, |s| <= 7 where it matters)
     static __device__ __forceinline__ u32x4 shifted(u32x4 x4, uint32_t s4)
     {
         unsigned __int128 x = ((unsigned __int128)(((uint64_t)x4[3] << 32) | x4[2]) << 64) | (((uint64_t)x4[1] << 32) | x4[0]);
-        x = (s4 & 8u) ? x << (16 * (16 - (int)s4)) : x >> (16 * (int)s4);
+        const int up = 16 - (int)s4 > 7 ? 7 : 16 - (int)s4;
+        x = (s4 & 8u) ? x << (16 * up) : x >> (16 * (int)s4);
         uint64_t lo = (uint64_t)x, hi = (uint64_t)(x >> 64);
         return u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
     }
@@ -247,10 +329,26 @@ template <int TILE_ROWS, int NT> struct DirectLoader {
             int t = tid + p * NT;
             int g = t % NPACK, r = t / NPACK;
             u32x4 a = v[p];
-            if (masks[p] >> 8) a = shifted(a, (masks[p] >> 8) & 15u);  // first or last few elements of the tensor only
             u32x4 o;
+            if constexpr (PLANES) {
+                if (masks[p]) a = shifted(a, masks[p]);  // first or last few elements of the tensor only
+                // one mask byte per element -> 16 bits per element (both operands the same word: either
+                // half of the selector range picks from it)
+                o[0] = a[0] & __builtin_amdgcn_perm(emask[p].x, emask[p].x, 0x01010000u);
+                o[1] = a[1] & __builtin_amdgcn_perm(emask[p].x, emask[p].x, 0x03030202u);
+                o[2] = a[2] & __builtin_amdgcn_perm(emask[p].y, emask[p].y, 0x01010000u);
+                o[3] = a[3] & __builtin_amdgcn_perm(emask[p].y, emask[p].y, 0x03030202u);
+            } else {
+                if (masks[p] >> 8) a = shifted(a, (masks[p] >> 8) & 15u);
+                if constexpr (FIXED) {
+                    const uint32_t row_ok = 0u - (masks[p] & 1u);
 #pragma unroll
-            for (int w = 0; w < 4; ++w) o[w] = a[w] & spread(masks[p], 2 * w);
+                    for (int w = 0; w < 4; ++w) o[w] = a[w] & colmask[p][w] & row_ok;
+                } else {
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) o[w] = a[w] & spread(masks[p], 2 * w);
+                }
+            }
             reinterpret_cast<u32x4 *>(lds)[g * (TILE_ROWS + 1) + r] = o;
         }
     }
@@ -280,7 +378,7 @@ template <int BM_, int BN_, int WM_, int WN_, int PF_> struct Tile {
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wavefront tiles are multiples of 32");
 };
 
-template <typename T, typename Cfg, bool COL_OUTER, typename Epi, bool DIRECT = false>
+template <typename T, typename Cfg, bool COL_OUTER, typename Epi, int DIRECT = 0>  // DIRECT_ROWS ... DIRECT_PLANES
 __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, int64_t lda,
                                                        const T *__restrict__ B, int64_t ldb,
                                                        GemmShape sh, Epi epi, DirectSrc direct)
@@ -324,17 +422,24 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
             for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
 
     RedContigLoader<T, BM, NT> la[PF];
-    RedContigLoader<T, BN, NT> lb_red[PF];
-    OuterContigLoader<T, BN, NT> lb_out[PF];
-    DirectLoader<BN, NT> lb_dir[DIRECT ? PF : 1];
-    if constexpr (DIRECT)
+    struct Unused {};  // only the column loader in use is instantiated: not every tile suits every loader
+    typename std::conditional<!COL_OUTER && !DIRECT, RedContigLoader<T, BN, NT>, Unused>::type lb_red[PF];
+    typename std::conditional<COL_OUTER, OuterContigLoader<T, BN, NT>, Unused>::type lb_out[PF];
+    DirectLoader<BN, NT, DIRECT> lb_dir[DIRECT ? PF : 1];
+    __shared__ uint2 plane_tab[DIRECT == DIRECT_PLANES ? DIRECT_TAB : 1];
+    if constexpr (DIRECT != 0) {
 #pragma unroll
         for (int p = 0; p < PF; ++p) lb_dir[p].init(direct, col0, tid);
+        if constexpr (DIRECT == DIRECT_PLANES) {
+            build_plane_table(direct, plane_tab, tid, NT);
+            __syncthreads();
+        }
+    }
 
     auto issue = [&](int set, int64_t k0) {
         la[set].issue(A, lda, sh.rows, sh.red, row0, k0, tid);
         if constexpr (DIRECT)
-            lb_dir[set].issue(direct, (int)k0 + (tid % NPACK) * 8);
+            lb_dir[set].issue(direct, (int)k0 + (tid % NPACK) * 8, plane_tab);
         else if constexpr (COL_OUTER)
             lb_out[set].issue(B, ldb, sh.red, sh.cols, k0, col0, tid);
         else
@@ -747,7 +852,9 @@ typedef Tile<256, 256, 2, 2, 1> Tile5;
 typedef Tile<256, 256, 4, 2, 1> Tile6;
 typedef Tile<256, 256, 2, 4, 1> Tile7;
 constexpr int TILE_PIPE = 8;  // the software-pipelined 256 x 256 kernel
-constexpr int N_TILES = 9;
+typedef Tile<192, 256, 2, 4, 1> Tile9;
+typedef Tile<384, 128, 4, 2, 1> Tile10;
+constexpr int N_TILES = 11;
 
 static int tile_override()
 {
@@ -768,10 +875,24 @@ static int pick_tile(int rows, int cols)
     return u256 >= 0.9 * u128 ? 6 : 0;
 }
 
+// The model gradient has a third candidate: 384 x 128, which takes a 384-row result (F = 384) in one row tile.
+static int pick_wgrad_tile(int rows, int cols)
+{
+    int o = tile_override();
+    if (o >= 0) return o;
+    auto fill = [](int n, int t) { return (double)n / (double)(((n + t - 1) / t) * t); };
+    double u256 = fill(rows, 256) * fill(cols, 256), u128 = fill(rows, 128) * fill(cols, 128);
+    double u384 = fill(rows, 384) * fill(cols, 128);
+    if (u384 > u256 && u384 >= 0.9 * u128) return 10;
+    return u256 >= 0.9 * u128 ? 6 : 0;
+}
+
+static bool direct_tile(int tile) { return tile == 6 || tile == 9 || tile == 10; }
+
 static void tile_dims(int tile, int *bm, int *bn)
 {
     static const int dims[N_TILES][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}, {128, 256},
-                                         {256, 256}, {256, 256}, {256, 256}, {256, 256}};
+                                         {256, 256}, {256, 256}, {256, 256}, {256, 256}, {192, 256}, {384, 128}};
     *bm = dims[tile][0];
     *bn = dims[tile][1];
 }
@@ -781,12 +902,19 @@ static void tile_dims(int tile, int *bm, int *bn)
 // 256 x 256 tile (measured: with 128-row tiles lowering first and streaming D-hat is faster).
 bool wgrad_direct_supported(const ConvGeom &g, int dtype)
 {
-    return dtype == OMNI_BF16 && g.sh == 1 && g.sw == 1 && g.pw < 24 && pick_tile(g.F, g.K) == 6 &&
+    return dtype == OMNI_BF16 && g.sh == 1 && g.sw == 1 && g.pw < 24 && direct_tile(pick_wgrad_tile(g.F, g.K)) &&
            (int64_t)g.N * g.C * g.H * g.W < 0x7fffffffll - 16 && (int64_t)g.N * g.C * g.H * g.W >= 8;
 }
 
+// Whether the direct model gradient pads whole image planes (see DIRECT_PLANES) rather than output rows.
+bool wgrad_direct_planes(const ConvGeom &g)
+{
+    return g.sh == 1 && g.sw == 1 && g.Wo == g.W &&
+           (int64_t)((g.Ho * g.Wo + 7) / 8) * (g.kh * g.kw + 1) <= DIRECT_TAB;
+}
+
 // Result tile of the model-gradient GEMM for a layer (the split planner needs the tile count).
-void gemm_wgrad_tile(int F, int K, int *bm, int *bn) { tile_dims(pick_tile(F, K), bm, bn); }
+void gemm_wgrad_tile(int F, int K, int *bm, int *bn) { tile_dims(pick_wgrad_tile(F, K), bm, bn); }
 
 template <typename T, typename Cfg, bool COL_OUTER, typename Epi>
 static void launch_cfg(const T *A, int64_t lda, const T *B, int64_t ldb, int rows, int cols, int64_t red,
@@ -807,8 +935,16 @@ static void launch_direct(const bf16_t *A, int64_t lda, const DirectSrc &d, int 
     GemmShape sh = make_shape(rows, cols, red, chunk, Cfg::BM, Cfg::BN, splits);
     sh.fast_store = epi.fits32() ? 1 : 0;
     dim3 grid(sh.per_xcd * 8, 1, 1);
-    hipLaunchKernelGGL((gemm_kernel<bf16_t, Cfg, false, PartialEpilogue, true>), grid, dim3(Cfg::NT), 0, s, A, lda,
-                       (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
+    const int p8 = (int)d.div_p8.d;
+    if (d.KK > 0)
+        hipLaunchKernelGGL((gemm_kernel<bf16_t, Cfg, false, PartialEpilogue, DIRECT_PLANES>), grid, dim3(Cfg::NT), 0, s, A,
+                           lda, (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
+    else if (p8 == 1 || p8 == 2 || p8 == 4 || p8 == 8)
+        hipLaunchKernelGGL((gemm_kernel<bf16_t, Cfg, false, PartialEpilogue, DIRECT_ROWS_FIXED>), grid, dim3(Cfg::NT), 0, s,
+                           A, lda, (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
+    else
+        hipLaunchKernelGGL((gemm_kernel<bf16_t, Cfg, false, PartialEpilogue, DIRECT_ROWS>), grid, dim3(Cfg::NT), 0, s, A, lda,
+                           (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
 }
 
 template <typename T, bool COL_OUTER, typename Epi>
@@ -833,6 +969,13 @@ static void launch_any(int tile, const T *A, int64_t lda, const T *B, int64_t ld
     case 5: launch_cfg<T, Tile5, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
     case 6: launch_cfg<T, Tile6, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
     case 7: launch_cfg<T, Tile7, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
+    case 9: launch_cfg<T, Tile9, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
+    case 10:
+        if constexpr (!COL_OUTER) {  // too few columns for the column-contiguous loader's tasks
+            launch_cfg<T, Tile10, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s);
+            break;
+        }
+        [[fallthrough]];
     default: launch_cfg<T, Tile0, COL_OUTER, Epi>(A, lda, B, ldb, rows, cols, red, chunk, splits, epi, s); break;
     }
 }
@@ -884,13 +1027,20 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
                        ((double)g.K * g.M + (double)g.F * g.M) * sizeof(T) + 4.0 * g.F * g.K * a.splits);
         if (a.X_direct != nullptr) {
             if constexpr (std::is_same<T, bf16_t>::value) {
-                DirectSrc d{(const bf16_t *)a.X_direct, g.C, g.H, g.W, g.H * g.W, g.K, g.ph, g.pw, g.N * g.Ho,
-                            (int32_t)((int64_t)g.N * g.C * g.H * g.W), FastDiv((uint32_t)((g.Wo + 7) / 8)),
-                            FastDiv((uint32_t)g.Ho), g.div_khkw, g.div_kw};
-                launch_direct<Tile6>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
+                const bool planes = wgrad_direct_planes(g);
+                const int unit = planes ? g.Ho * g.Wo : g.Wo;  // what is padded to a multiple of 8 positions
+                DirectSrc d{(const bf16_t *)a.X_direct, g.C, g.H, g.W, g.H * g.W, g.K, g.ph, g.pw,
+                            planes ? g.N : g.N * g.Ho, (int32_t)((int64_t)g.N * g.C * g.H * g.W),
+                            FastDiv((uint32_t)((unit + 7) / 8)), FastDiv((uint32_t)g.Ho), g.div_khkw, g.div_kw,
+                            g.Ho * g.Wo, planes ? g.kh * g.kw : 0, FastDiv((uint32_t)g.W)};
+                switch (pick_wgrad_tile(g.F, g.K)) {
+                case 9: launch_direct<Tile9>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s); break;
+                case 10: launch_direct<Tile10>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s); break;
+                default: launch_direct<Tile6>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s); break;
+                }
             }
         } else {
-            launch_any<T, false, PartialEpilogue>(pick_tile(g.F, g.K), (const T *)a.dYhat, a.ldd, (const T *)a.Dhat,
+            launch_any<T, false, PartialEpilogue>(pick_wgrad_tile(g.F, g.K), (const T *)a.dYhat, a.ldd, (const T *)a.Dhat,
                                                   a.ldd, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s);
         }
     }

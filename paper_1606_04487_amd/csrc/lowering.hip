@@ -584,12 +584,26 @@ __global__ __launch_bounds__(256) void pack_dyhat_rows_kernel(ConvGeom g, FastDi
     }
 }
 
-int64_t dyhat_rows_ld(const ConvGeom &g) { return round_up((int64_t)g.N * g.Ho * ((g.Wo + 7) / 8) * 8, 64); }
+// The padded unit is the output row, or the whole plane of an image where the direct model gradient
+// works on planes: a plane is then handled as one long row.
+static ConvGeom padded_unit_view(const ConvGeom &g)
+{
+    ConvGeom v = g;
+    if (wgrad_direct_planes(g)) v.Wo = g.Ho * g.Wo, v.Ho = 1;
+    return v;
+}
+
+int64_t dyhat_rows_ld(const ConvGeom &g)
+{
+    ConvGeom v = padded_unit_view(g);
+    return round_up((int64_t)v.N * v.Ho * ((v.Wo + 7) / 8) * 8, 64);
+}
 int pack_dyhat_rows_blocks(const ConvGeom &g) { return (int)((dyhat_rows_ld(g) + PACK_COLS - 1) / PACK_COLS); }
 
-int launch_pack_dyhat_rows(const ConvGeom &g, const void *dY, void *dYhat, int64_t ld, float *bias_partials,
+int launch_pack_dyhat_rows(const ConvGeom &geom, const void *dY, void *dYhat, int64_t ld, float *bias_partials,
                            int bias_blocks, float *dbias, hipStream_t s)
 {
+    const ConvGeom g = padded_unit_view(geom);
     int blocks = (int)((ld + PACK_COLS - 1) / PACK_COLS);
     if (bias_partials != nullptr && bias_blocks != blocks) return OMNI_INVALID_ARGUMENT;
     dim3 grid((unsigned)blocks, (unsigned)g.F, 1);

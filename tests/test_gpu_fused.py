@@ -133,7 +133,12 @@ def test_fused_every_column_tile(B, cfg, bn, monkeypatch):
 
 @pytest.mark.parametrize("cfg", FUSED_SHAPES + [(3, 5, 13, 13, 7, 3, 3, 1, 1), (2, 20, 27, 27, 130, 5, 5, 2, 2),
                                                 (2, 3, 9, 30, 4, 3, 5, 2, 4), (2, 30, 13, 13, 250, 3, 3, 1, 1),
-                                                (3, 29, 9, 11, 256, 3, 2, 0, 1), (1, 57, 27, 27, 200, 5, 5, 2, 2)])
+                                                (3, 29, 9, 11, 256, 3, 2, 0, 1), (1, 57, 27, 27, 200, 5, 5, 2, 2),
+                                                (2, 16, 20, 22, 256, 3, 4, 1, 1),    # rows of 3 packs
+                                                (2, 8, 30, 28, 256, 3, 5, 1, 1),     # rows of 4 packs, Wo != W
+                                                (3, 16, 9, 9, 384, 3, 3, 1, 1),      # 384-row tile, planes
+                                                (2, 8, 60, 60, 256, 3, 3, 1, 1),     # plane too long for the mask table
+                                                (1, 8, 3, 3, 256, 3, 3, 1, 1)])      # X barely larger than a pack
 def test_fused_backward_weights(B, cfg):
     """Model gradient with the lowered operand read straight from X: the same products as the explicit
     path, summed in fp32 in another order (row-padded columns), within the fp32-output bar of the oracle."""

@@ -116,7 +116,7 @@ int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, 
  * b_p images (the last group may be smaller) through ONE workspace sized for b_p images:
  * workspace_bytes >= omni_conv_workspace_bytes of the same descriptor with N = b_p.  Every output element
  * is the same sum in the same order for every b_p, so Y is bit-identical to omni_conv_forward's.
- * 1 <= b_p <= N; for b_p < N one image of X and of Y must be a multiple of 16 bytes (OMNI_MISALIGNED
+ * 1 <= b_p <= N; for b_p < N a group of b_p images of X and of Y must be a multiple of 16 bytes (OMNI_MISALIGNED
  * otherwise).  OMNI_FLAG_FUSED is ignored: the knob is about D-hat's footprint.
  */
 int omni_conv_forward_partial(const omni_conv_desc *desc, int32_t b_p, const void *X, const void *W,

@@ -235,7 +235,7 @@ int omni_conv_forward_partial(const omni_conv_desc *desc, int32_t b_p, const voi
     if (b_p < 1 || b_p > desc->N || X == nullptr || Y == nullptr) return OMNI_INVALID_ARGUMENT;
     const size_t e = elem_size(desc->dtype);
     const size_t x_image = (size_t)g.C * g.H * g.W * e, y_image = (size_t)g.F * g.HoWo * e;
-    if (b_p < desc->N && (x_image % 16 != 0 || y_image % 16 != 0)) return OMNI_MISALIGNED;
+    if (b_p < desc->N && ((x_image * (size_t)b_p) % 16 != 0 || (y_image * (size_t)b_p) % 16 != 0)) return OMNI_MISALIGNED;
     omni_conv_desc part = *desc;
     part.flags &= ~(uint32_t)OMNI_FLAG_FUSED;
     // check every group's arguments before the first launch: a failed call launches nothing

@@ -175,6 +175,7 @@ int launch_relu(int dtype, bool backward, int64_t count, const void *ref, const 
 struct PoolGeom {
     int32_t H, W, Ho, Wo, k, s;
     FastDiv div_Wo, div_HoWo, div_W, div_HW, div_s;
+    FastDiv div_rp, div_xb;  // row pairs per plane, 8-pixel blocks per row (backward, 3 x 3 / stride 2)
 };
 
 template <typename T>
@@ -338,28 +339,94 @@ __global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_
     const int hw = g.H * g.W, howo = g.Ho * g.Wo;
     T *gdy = reinterpret_cast<T *>(pool_smem);
     uint8_t *gam = pool_smem + (((size_t)pb * howo * sizeof(T) + 15) / 16) * 16;
-    run_to_lds(dy + p0 * howo, np * howo, gdy, threadIdx.x);
     run_to_lds(argmax + p0 * howo, np * howo, gam, threadIdx.x);
     if constexpr (RELU) {
         // the pooled value is the winner's value: where it is not positive the ReLU under the pool
         // passes nothing, so that window's gradient is dropped while it is staged
-        __syncthreads();
-        const T *yp = y + p0 * howo;
+        const T *yp = y + p0 * howo, *dp = dy + p0 * howo;
         const int chunks = (np * howo + VEC - 1) / VEC;
         for (int c = threadIdx.x; c < chunks; c += 256) {
             if ((c + 1) * VEC <= np * howo) {
-                T v[VEC];
+                T v[VEC], d[VEC];
                 __builtin_memcpy(v, yp + c * VEC, sizeof(v));
+                __builtin_memcpy(d, dp + c * VEC, sizeof(d));
 #pragma unroll
-                for (int e = 0; e < VEC; ++e)
-                    if (!(Elem<T>::to_f32(v[e]) > 0.f)) gdy[c * VEC + e] = (T)0;
+                for (int e = 0; e < VEC; ++e) gdy[c * VEC + e] = Elem<T>::to_f32(v[e]) > 0.f ? d[e] : (T)0;
             } else {
                 for (int e = 0; c * VEC + e < np * howo; ++e)
-                    if (!(Elem<T>::to_f32(yp[c * VEC + e]) > 0.f)) gdy[c * VEC + e] = (T)0;
+                    gdy[c * VEC + e] = Elem<T>::to_f32(yp[c * VEC + e]) > 0.f ? dp[c * VEC + e] : (T)0;
             }
         }
+    } else {
+        run_to_lds(dy + p0 * howo, np * howo, gdy, threadIdx.x);
     }
     __syncthreads();
+    if constexpr (K3S2) {
+        // One task = input rows 2t, 2t+1 x pixels 8b .. 8b+7 of a plane.  The windows that can hold them
+        // are output rows t-1, t x columns 4b-1 .. 4b+3: ten (winner, gradient) pairs read once, and for
+        // every pixel the candidate windows and the winner code each would have follow from the pixel's
+        // parities, known at compile time.  Contributions are added in ascending (oy, ox).
+        T *out = dx + p0 * hw;
+        const int rp = (g.H + 1) >> 1, xb = (g.W + 7) >> 3;
+        const int tasks = np * rp * xb;
+        for (int task = threadIdx.x; task < tasks; task += 256) {
+            uint32_t rest, b, pl, t;
+            g.div_xb.divmod((uint32_t)task, rest, b);
+            g.div_rp.divmod(rest, pl, t);
+            const int obase = (int)pl * howo, ox0 = 4 * (int)b - 1;
+            float d[2][5];
+            int code[2][5];
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int q = 0; q < 5; ++q) {
+                    const int oy = (int)t - 1 + r, ox = ox0 + q;
+                    const bool ok = oy >= 0 && oy < g.Ho && ox >= 0 && ox < g.Wo;
+                    const int o = ok ? obase + oy * g.Wo + ox : obase;
+                    code[r][q] = ok ? (int)gam[o] : 255;
+                    d[r][q] = Elem<T>::to_f32(gdy[o]);
+                }
+            T res[2][8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int q = (e >> 1) + 1;  // the window column that starts at or just left of this pixel
+                float top = 0.f, bot = 0.f;  // input rows 2t and 2t+1
+                if ((e & 1) == 0) {
+                    top += code[0][q - 1] == 8 ? d[0][q - 1] : 0.f;
+                    top += code[0][q] == 6 ? d[0][q] : 0.f;
+                    top += code[1][q - 1] == 2 ? d[1][q - 1] : 0.f;
+                    top += code[1][q] == 0 ? d[1][q] : 0.f;
+                    bot += code[1][q - 1] == 5 ? d[1][q - 1] : 0.f;
+                    bot += code[1][q] == 3 ? d[1][q] : 0.f;
+                } else {
+                    top += code[0][q] == 7 ? d[0][q] : 0.f;
+                    top += code[1][q] == 1 ? d[1][q] : 0.f;
+                    bot += code[1][q] == 4 ? d[1][q] : 0.f;
+                }
+                res[0][e] = Elem<T>::from_f32(top);
+                res[1][e] = Elem<T>::from_f32(bot);
+            }
+            const int x0 = 8 * (int)b, nv = g.W - x0 < 8 ? g.W - x0 : 8;
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int iy = 2 * (int)t + r;
+                if (iy >= g.H) break;
+                T *row = out + (int)pl * hw + iy * g.W + x0;
+                if (nv == 8) {
+                    __builtin_memcpy(row, res[r], 8 * sizeof(T));  // element-aligned stores
+                } else {
+                    // 4, 2 and 1 pixels as nv's bits say; positions spelled out so that res stays in registers
+                    if (nv & 4) __builtin_memcpy(row, res[r], 4 * sizeof(T));
+                    if ((nv & 6) == 6) __builtin_memcpy(row + 4, res[r] + 4, 2 * sizeof(T));
+                    if ((nv & 6) == 2) __builtin_memcpy(row, res[r], 2 * sizeof(T));
+#pragma unroll
+                    for (int at = 0; at < 8; at += 2)
+                        if ((nv & 1) && (nv & 6) == at) row[at] = res[r][at];
+                }
+            }
+        }
+        return;
+    }
     // each thread produces VEC consecutive pixels of the workgroup's run of planes and stores them at once
     T *out = dx + p0 * hw;
     const int total = np * hw;
@@ -373,21 +440,7 @@ __global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_
             float acc = 0.f;
             if (v0 + e < total) {
                 const int obase = (int)pl * howo;
-                if constexpr (K3S2) {
-                    // windows oy with 2*oy <= iy <= 2*oy + 2: (iy-1)/2 rounded up .. iy/2, at most two of them
-                    const int oy_hi = (int)(iy >> 1), ox_hi = (int)(ix >> 1);
-#pragma unroll
-                    for (int dy_ = 1; dy_ >= 0; --dy_)
-#pragma unroll
-                        for (int dx_ = 1; dx_ >= 0; --dx_) {
-                            const int oy = oy_hi - dy_, ox = ox_hi - dx_;
-                            const int wy = (int)iy - 2 * oy, wx = (int)ix - 2 * ox;  // position inside that window
-                            if (oy >= 0 && ox >= 0 && oy < g.Ho && ox < g.Wo && wy < 3 && wx < 3) {
-                                int o = obase + oy * g.Wo + ox;
-                                if (gam[o] == (uint8_t)(wy * 3 + wx)) acc += Elem<T>::to_f32(gdy[o]);
-                            }
-                        }
-                } else {
+                {
                     int oy_lo = (int)iy - g.k + 1;
                     oy_lo = oy_lo <= 0 ? 0 : (int)g.div_s.div((uint32_t)(oy_lo + g.s - 1));
                     int oy_hi = (int)g.div_s.div(iy);
@@ -443,6 +496,8 @@ static PoolGeom make_pool_geom(int32_t H, int32_t W, int32_t k, int32_t stride, 
     g.div_W = FastDiv((uint32_t)W);
     g.div_HW = FastDiv((uint32_t)(H * W));
     g.div_s = FastDiv((uint32_t)stride);
+    g.div_rp = FastDiv((uint32_t)((H + 1) / 2));
+    g.div_xb = FastDiv((uint32_t)((W + 7) / 8));
     return g;
 }
 

@@ -221,7 +221,9 @@ def test_relu(B, dtype):
 
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("H,W,ceil_mode", [(32, 32, True), (32, 32, False), (16, 16, True), (8, 8, True),
-                                            (55, 55, True), (13, 13, False), (7, 9, True), (3, 3, True)])
+                                            (55, 55, True), (13, 13, False), (7, 9, True), (3, 3, True),
+                                            (27, 27, True), (6, 20, True), (5, 14, False), (9, 11, True),
+                                            (4, 10, True), (5, 17, False), (12, 29, True)])
 def test_maxpool(B, dtype, H, W, ceil_mode):
     rng = np.random.default_rng(H * 100 + W)
     x = prep(rng.standard_normal((3, 5, H, W)), dtype)

@@ -250,23 +250,28 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolGeom g, int64_t pl
 }
 
 // LDS-staged variants.  A workgroup takes a few whole planes; their pixels are one contiguous run in
-// memory, fetched 16 bytes per lane into LDS (the run need not be 16-byte aligned), and every window is
+// memory, fetched 16 bytes per lane into LDS (the run need not be 16-byte aligned; dst must be), and every window is
 // then evaluated from LDS.  Global traffic is each operand once, in full vectors.
 template <typename T>
 __device__ __forceinline__ void run_to_lds(const T *__restrict__ src, int count, T *dst, int tid)
 {
     constexpr int VEC = 16 / (int)sizeof(T);
-    const int chunks = (count + VEC - 1) / VEC;
-    for (int c = tid; c < chunks; c += 256) {
-        T v[VEC];
-        if ((c + 1) * VEC <= count) {
-            __builtin_memcpy(v, src + c * VEC, sizeof(v));
+    constexpr int U = 4;  // loads in flight per thread
+    const int full = count / VEC;
+    for (int c0 = tid; c0 < full; c0 += 256 * U) {
+        T v[U][VEC];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) dst[c * VEC + e] = v[e];
-        } else {
-            for (int e = 0; c * VEC + e < count; ++e) dst[c * VEC + e] = src[c * VEC + e];
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + 256 * u < full ? c0 + 256 * u : c0;  // clamped: the loads never depend on a branch
+            __builtin_memcpy(v[u], src + c * VEC, sizeof(v[u]));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + 256 * u;
+            if (c < full) __builtin_memcpy(__builtin_assume_aligned(dst + c * VEC, 16), v[u], sizeof(v[u]));
         }
     }
+    for (int i = full * VEC + tid; i < count; i += 256) dst[i] = src[i];
 }
 
 // K3S2: the 3 x 3 / stride 2 pool of the paper's networks with its loops unrolled and its divisions as shifts
@@ -351,7 +356,8 @@ __global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_
                 __builtin_memcpy(v, yp + c * VEC, sizeof(v));
                 __builtin_memcpy(d, dp + c * VEC, sizeof(d));
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) gdy[c * VEC + e] = Elem<T>::to_f32(v[e]) > 0.f ? d[e] : (T)0;
+                for (int e = 0; e < VEC; ++e) d[e] = Elem<T>::to_f32(v[e]) > 0.f ? d[e] : (T)0;
+                __builtin_memcpy(__builtin_assume_aligned(gdy + c * VEC, 16), d, sizeof(d));
             } else {
                 for (int e = 0; c * VEC + e < np * howo; ++e)
                     gdy[c * VEC + e] = Elem<T>::to_f32(yp[c * VEC + e]) > 0.f ? dp[c * VEC + e] : (T)0;
@@ -482,6 +488,21 @@ static int pool_planes_per_block(int64_t plane_bytes, int64_t plane_elems)
     return (int)pb;
 }
 
+// 3 x 3 / stride 2 backward: the planes per workgroup that keep its 256 threads busiest (a plane is
+// ceil(H/2) * ceil(W/8) tasks), within the LDS budget and four passes of the threads.
+static int pool_bwd_planes_k3s2(int H, int W, int64_t plane_bytes)
+{
+    const int tasks = ((H + 1) / 2) * ((W + 7) / 8);
+    int best = 0;
+    double best_fill = 0.0;
+    for (int pb = 1; pb <= 64; ++pb) {
+        if (pb * plane_bytes > 32 * 1024 || (pb > 1 && pb * tasks > 1024)) break;
+        double fill = (double)(pb * tasks) / (double)((pb * tasks + 255) / 256 * 256);
+        if (fill >= best_fill) best = pb, best_fill = fill;
+    }
+    return best;
+}
+
 static PoolGeom make_pool_geom(int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode)
 {
     PoolGeom g;
@@ -550,6 +571,7 @@ int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
     {
         const int64_t howo = (int64_t)g.Ho * g.Wo;
         int pb = pool_planes_per_block(howo * (int64_t)(elem_size(dtype) + 1), per);
+        if (pb > 0 && k == 3 && stride == 2) pb = pool_bwd_planes_k3s2(H, W, howo * (int64_t)(elem_size(dtype) + 1));
         if (pb > 0 && (planes + pb - 1) / pb <= 0x7fffffffll) {
             dim3 grid((unsigned)((planes + pb - 1) / pb));
             size_t lds = (((size_t)pb * howo * elem_size(dtype) + 15) / 16) * 16 + (size_t)pb * howo + 16;

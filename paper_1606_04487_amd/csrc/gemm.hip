@@ -814,15 +814,29 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const T *__restrict__ A,
     }
 }
 
-// Sum the per-split partial results in split order (deterministic) into the final fp32 tensor.
-__global__ void reduce_partials_kernel(const float *__restrict__ partials, int splits, int64_t count,
-                                       float *__restrict__ out)
+// Sum the per-split partial results into the final fp32 tensor, in a fixed order (deterministic): a
+// workgroup takes 64 consecutive elements; wavefront l adds splits l, l+4, l+8, ... in that order, four
+// loads in flight, and the four sums are then added as (s0 + s1) + (s2 + s3).
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partials, int splits,
+                                                              int64_t count, float *__restrict__ out)
 {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count) return;
+    __shared__ float part[4][64];
+    const int c = threadIdx.x % 64, l = threadIdx.x / 64;
+    const int64_t i = (int64_t)blockIdx.x * 64 + c;
     float acc = 0.f;
-    for (int z = 0; z < splits; ++z) acc += partials[(int64_t)z * count + i];
-    out[i] = acc;
+    if (i < count) {
+        const float *p = partials + i;
+        int z = l;
+        for (; z + 12 < splits; z += 16) {
+            float a0 = p[(int64_t)z * count], a1 = p[(int64_t)(z + 4) * count];
+            float a2 = p[(int64_t)(z + 8) * count], a3 = p[(int64_t)(z + 12) * count];
+            acc += a0, acc += a1, acc += a2, acc += a3;
+        }
+        for (; z < splits; z += 4) acc += p[(int64_t)z * count];
+    }
+    part[l][c] = acc;
+    __syncthreads();
+    if (l == 0 && i < count) out[i] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
 }
 
 static GemmShape make_shape(int rows, int cols, int64_t red, int64_t chunk, int bm, int bn, int splits)
@@ -1048,7 +1062,7 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
     if (a.splits > 1) {
         int64_t count = (int64_t)g.F * g.K;
         ProfScope prof(KID_REDUCE_PARTIALS, s, 0.0, 4.0 * count * (a.splits + 1));
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s,
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, s,
                            a.partials, a.splits, count, a.dW);
         OMNI_LAUNCH_CHECK();
     }

@@ -164,11 +164,12 @@ template <int TILE_COLS, int NT> struct OuterContigLoader<bf16_t, TILE_COLS, NT>
 
 // ------------------------------------------------------------------------------------------------
 // The lowered matrix read straight from the input tensor (stride-1 layers, bf16), for the model gradient.
-// The reduction runs over row-padded columns: column ((n*Ho + oy) * P8 + i) * 8 + e stands for output
-// position (n, oy, 8i + e), P8 = ceil(Wo / 8), and dY-hat is packed the same way with zeros in the padding
-// (a sum does not care about the order or about zero terms).  A pack of 8 columns of row k = (c, ky, kx)
-// of D-hat is then 8 consecutive pixels of ONE input row: one 16-byte load at element granularity plus an
-// 8-bit mask for pixels in the zero padding or outside the image.  The same input bytes serve the kh*kw
+// The reduction runs over padded columns.  Row mode: column ((n*Ho + oy) * P8 + i) * 8 + e stands for output
+// position (n, oy, 8i + e), P8 = ceil(Wo / 8); plane mode (further down): only whole image planes are
+// padded.  dY-hat is packed the same way with zeros in the padding (a sum does not care about the order or
+// about zero terms).  A pack of 8 columns of row k = (c, ky, kx) of D-hat is then 8 consecutive input
+// pixels: one 16-byte load at element granularity plus a mask for pixels in the zero padding or outside
+// the image.  The same input bytes serve the kh*kw
 // window taps of a channel, so nearly all of these loads hit in L1/L2; D-hat is never written or read.
 // ------------------------------------------------------------------------------------------------
 struct DirectSrc {
@@ -941,7 +942,7 @@ static void launch_cfg(const T *A, int64_t lda, const T *B, int64_t ldb, int row
                        DirectSrc{});
 }
 
-// Model gradient with the column operand read from X (see DirectLoader); the 256 x 256 tile only.
+// Model gradient with the column operand read from X (see DirectLoader), in the mode the geometry allows.
 template <typename Cfg>
 static void launch_direct(const bf16_t *A, int64_t lda, const DirectSrc &d, int rows, int cols, int64_t red,
                           int64_t chunk, int splits, const PartialEpilogue &epi, hipStream_t s)

@@ -65,6 +65,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=64, help="images timed through the CPU oracle (0 = skip)")
     ap.add_argument("--no-events", action="store_true", help="record no events at all (no kernel table, no roofline)")
     ap.add_argument("--table-steps", type=int, default=5, help="instrumented steps before the timed region")
+    ap.add_argument("--overlap", action="store_true", help="model gradients on a second stream beside the data gradients")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -79,7 +80,7 @@ def main():
     torch.cuda.set_device(0)
     dtype = B.BF16 if args.dtype == "bf16" else B.F32
     layers = wl.caffenet_stack(args.batch)
-    stack = ConvStack(layers, dtype=dtype, ceil_mode=False, skip_first_dgrad=True)
+    stack = ConvStack(layers, dtype=dtype, ceil_mode=False, skip_first_dgrad=True, overlap_wgrad=args.overlap)
     data = wl.stack_tensors(layers, seed=1, bf16=(dtype == B.BF16), pooled_out=stack.output_shape()[-2:])
     stack.set_parameters(data["W"], data["bias"])
     X = torch.from_numpy(data["X"]).cuda().to(B.torch_dtype(dtype))

@@ -22,13 +22,18 @@ from .workloads import ConvLayer
 
 class ConvStack:
     def __init__(self, layers: Sequence[ConvLayer], dtype: int = B.F32, ceil_mode: bool = True,
-                 skip_first_dgrad: bool = True, device: str = "cuda", fused: bool = True):
+                 skip_first_dgrad: bool = True, device: str = "cuda", fused: bool = True,
+                 overlap_wgrad: bool = False):
         self.layers = list(layers)
         self.dtype = dtype
         self.tdtype = B.torch_dtype(dtype)
         self.ceil_mode = ceil_mode
         self.skip_first_dgrad = skip_first_dgrad   # App. B: the first layer needs no data gradient
         self.device = device
+        # overlap_wgrad = run every layer's model gradient on a second stream beside the data gradient of the
+        # same layer (both only read dY of that layer; they write different tensors and use different
+        # workspaces); the streams join before backward() returns
+        self.side = torch.cuda.Stream(device=device) if overlap_wgrad else None
         # fused = let the library skip D-hat / dD-hat where it can (App. C: fusing lowering and GEMM);
         # the model gradient then reads its lowered operand straight from X (or lowers X itself where it
         # cannot) instead of finding D-hat cached by the forward pass
@@ -107,12 +112,21 @@ class ConvStack:
                                         self.dYc[i])
             else:
                 B.relu_backward(Y, g, self.dYc[i])
-            B.conv_backward_weights(self.desc_wgrad[i], self.X[i], self.dYc[i], self.dW[i], self.db[i],
-                                    self.ws_layer[i])
+            if self.side is not None:
+                self.side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(self.side):
+                    B.conv_backward_weights(self.desc_wgrad[i], self.X[i], self.dYc[i], self.dW[i], self.db[i],
+                                            self.ws_layer[i])
+            else:
+                B.conv_backward_weights(self.desc_wgrad[i], self.X[i], self.dYc[i], self.dW[i], self.db[i],
+                                        self.ws_layer[i])
             if self.dXl[i] is None:
-                return None
+                g = None
+                break
             B.conv_backward_data(self.desc[i], self.dYc[i], self.Wc[i], self.dXl[i], self.ws_bwd)
             g = self.dXl[i]
+        if self.side is not None:
+            torch.cuda.current_stream().wait_stream(self.side)
         return g
 
     def sgd_step(self, lr: float, momentum: float, weight_decay: float = 0.0) -> None:

@@ -195,3 +195,27 @@ def test_fused_stack_matches_explicit_stack(B):
     assert rel_err(res[1][1], res[0][1]) <= 3e-2
     for a, b in zip(res[1][2], res[0][2]):
         assert rel_err(a, b) <= 3e-2
+
+
+def test_second_stream_model_gradient_is_identical(B):
+    """ConvStack(overlap_wgrad=True) runs each layer's model gradient on a second stream beside the data
+    gradient; the same kernels on the same inputs: every result bit-identical, step after step."""
+    from paper_1606_04487_amd.stack import ConvStack
+    layers = wl.cifar_stack(16)
+    t = wl.stack_tensors(layers, seed=7, bf16=True, pooled_out=(4, 4))
+    res = []
+    for overlap in (False, True):
+        st = ConvStack(layers, dtype=B.BF16, ceil_mode=True, skip_first_dgrad=False, overlap_wgrad=overlap)
+        st.set_parameters(t["W"], t["bias"])
+        outs = []
+        for _ in range(3):
+            out = st.step(gpu(t["X"]), gpu(t["dY"]), 0.01, 0.9)
+            outs.append(out.clone())
+        torch.cuda.synchronize()
+        res.append((outs, [w.clone() for w in st.W], [d.clone() for d in st.dW], st.dXl[0].clone()))
+    for a, b in zip(res[0][0], res[1][0]):
+        assert torch.equal(a, b)
+    for k in (1, 2):
+        for a, b in zip(res[0][k], res[1][k]):
+            assert torch.equal(a, b)
+    assert torch.equal(res[0][3], res[1][3])

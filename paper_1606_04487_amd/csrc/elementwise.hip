@@ -1,6 +1,8 @@
 // Element-wise and window kernels (gfx950): the fused momentum-SGD update over a list of tensors,
 // ReLU, and 2-D max-pooling.  All are bound by HBM traffic; each thread moves 16 bytes where the
 // layout allows it and nothing uses floating point atomics.
+#include <type_traits>
+
 #include "common.h"
 
 namespace omni {
@@ -255,23 +257,50 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(PoolGeom g, int64_t pl
 template <typename T>
 __device__ __forceinline__ void run_to_lds(const T *__restrict__ src, int count, T *dst, int tid)
 {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     constexpr int VEC = 16 / (int)sizeof(T);
     constexpr int U = 4;  // loads in flight per thread
     const int full = count / VEC;
-    for (int c0 = tid; c0 < full; c0 += 256 * U) {
-        T v[U][VEC];
+    if (full == 0) {
+        if (tid < count) dst[tid] = src[tid];
+        return;
+    }
+    // The ragged end: the last VEC elements once more, as a piece moved back to end at the run's end.
+    // Issued first, stored last (the same values land on the bytes it shares with the last whole piece).
+    u32x4 tail = {0, 0, 0, 0};
+    const bool ragged = full * VEC < count && tid == 255;
+    if (ragged) __builtin_memcpy(&tail, src + (count - VEC), 16);
+    // Whole pieces, ceil(full / 256) per thread, in batches of up to U: all loads of a batch are issued
+    // before the first is waited for.  A piece index past the end is clamped to the last piece (the
+    // duplicate rewrites the same bytes), so neither the loads nor the LDS stores sit behind a per-thread
+    // branch; the batch size is the same for the whole workgroup.
+    auto batch = [&](auto n_tag, int first) {
+        constexpr int N = decltype(n_tag)::value;
+        u32x4 v[N];
+        int c[N];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int c = c0 + 256 * u < full ? c0 + 256 * u : c0;  // clamped: the loads never depend on a branch
-            __builtin_memcpy(v[u], src + c * VEC, sizeof(v[u]));
+        for (int u = 0; u < N; ++u) {
+            c[u] = tid + 256 * (first + u) < full ? tid + 256 * (first + u) : full - 1;
+            __builtin_memcpy(&v[u], src + c[u] * VEC, 16);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int c = c0 + 256 * u;
-            if (c < full) __builtin_memcpy(__builtin_assume_aligned(dst + c * VEC, 16), v[u], sizeof(v[u]));
+        for (int u = 0; u < N; ++u) *reinterpret_cast<u32x4 *>(dst + c[u] * VEC) = v[u];
+    };
+    const int per = (full + 255) / 256;
+    for (int b = 0; b < per; b += U) {
+        switch (per - b < U ? per - b : U) {
+        case 1: batch(std::integral_constant<int, 1>(), b); break;
+        case 2: batch(std::integral_constant<int, 2>(), b); break;
+        case 3: batch(std::integral_constant<int, 3>(), b); break;
+        default: batch(std::integral_constant<int, 4>(), b); break;
         }
     }
-    for (int i = full * VEC + tid; i < count; i += 256) dst[i] = src[i];
+    if (ragged) {
+        T t[VEC];
+        __builtin_memcpy(t, &tail, 16);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) dst[count - VEC + e] = t[e];
+    }
 }
 
 // K3S2: the 3 x 3 / stride 2 pool of the paper's networks with its loops unrolled and its divisions as shifts
@@ -296,20 +325,29 @@ __global__ __launch_bounds__(256) void maxpool_fwd_lds_kernel(PoolGeom g, int64_
         float bv = 0.f;
         T braw = (T)0;
         if constexpr (K3S2) {
-            const T *w0 = src + (int)oy * 2 * g.W + (int)ox * 2;  // the window's first pixel is always inside
+            // nine reads at coordinates clamped into the plane (no read sits behind a branch), then the scan
+            // in window order over the pixels that are really inside; the first pixel always is
+            const int y0 = (int)oy * 2, x0 = (int)ox * 2;
+            T raw[9];
 #pragma unroll
             for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
                 for (int kx = 0; kx < 3; ++kx) {
-                    const bool in = (int)oy * 2 + ky < g.H && (int)ox * 2 + kx < g.W;
-                    T raw = in ? w0[ky * g.W + kx] : (T)0;
-                    float v = Elem<T>::to_f32(raw);
-                    if (in && (best < 0 || v > bv)) {
-                        best = ky * 3 + kx;
-                        bv = v;
-                        braw = raw;
-                    }
+                    const int iy = y0 + ky < g.H ? y0 + ky : g.H - 1, ix = x0 + kx < g.W ? x0 + kx : g.W - 1;
+                    raw[ky * 3 + kx] = src[iy * g.W + ix];
                 }
+            best = 0;
+            braw = raw[0];
+            bv = Elem<T>::to_f32(raw[0]);
+#pragma unroll
+            for (int k = 1; k < 9; ++k) {
+                const bool in = y0 + k / 3 < g.H && x0 + k % 3 < g.W;
+                const float v = Elem<T>::to_f32(raw[k]);
+                const bool take = in && v > bv;  // strict: the first maximum in scan order wins
+                best = take ? k : best;
+                bv = take ? v : bv;
+                braw = take ? raw[k] : braw;
+            }
         } else {
             for (int ky = 0; ky < g.k; ++ky) {
                 int iy = (int)oy * g.s + ky;
@@ -332,6 +370,177 @@ __global__ __launch_bounds__(256) void maxpool_fwd_lds_kernel(PoolGeom g, int64_
     }
 }
 
+// N consecutive results to element-aligned memory in as few store instructions as possible.  16-bit
+// results are first packed two to a register: left to itself the compiler stores some of them one by one
+// (to save the packing), which multiplies the write requests the memory system has to merge again.
+template <int N, typename T>
+__device__ __forceinline__ void store_packed(T *dst, const T *src)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    if constexpr (sizeof(T) == 2 && N == 8) {
+        u32x4 w;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)src[2 * i] | ((uint32_t)src[2 * i + 1] << 16);
+        __builtin_memcpy(dst, &w, 16);
+    } else if constexpr (sizeof(T) == 2 && N == 4) {
+        u32x2 w;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) w[i] = (uint32_t)src[2 * i] | ((uint32_t)src[2 * i + 1] << 16);
+        __builtin_memcpy(dst, &w, 8);
+    } else if constexpr (sizeof(T) == 2 && N == 2) {
+        uint32_t w = (uint32_t)src[0] | ((uint32_t)src[1] << 16);
+        __builtin_memcpy(dst, &w, 4);
+    } else {
+        __builtin_memcpy(dst, src, N * sizeof(T));
+    }
+}
+
+// 3 x 3 / stride 2 backward from the staged gradients and winners of np planes.
+// One task = input rows 2t, 2t+1 x pixels 8b .. 8b+7 of a plane.  The windows that can hold them
+// are output rows t-1, t x columns 4b-1 .. 4b+3: ten (winner, gradient) pairs read once, and for
+// every pixel the candidate windows and the winner code each would have follow from the pixel's
+// parities, known at compile time.  Contributions are added in ascending (oy, ox).
+template <typename T>
+__device__ __forceinline__ void pool_bwd_k3s2_tasks(const PoolGeom &g, int np, const T *gdy, const uint8_t *gam,
+                                                    T *__restrict__ out, int hw, int howo)
+{
+    const int rp = (g.H + 1) >> 1, xb = (g.W + 7) >> 3;
+    const int tasks = np * rp * xb;
+    for (int task = threadIdx.x; task < tasks; task += 256) {
+        uint32_t rest, b, pl, t;
+        g.div_xb.divmod((uint32_t)task, rest, b);
+        g.div_rp.divmod(rest, pl, t);
+        const int obase = (int)pl * howo, ox0 = 4 * (int)b - 1;
+        float d[2][5];
+        int code[2][5];
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int q = 0; q < 5; ++q) {
+                const int oy = (int)t - 1 + r, ox = ox0 + q;
+                const bool ok = oy >= 0 && oy < g.Ho && ox >= 0 && ox < g.Wo;
+                const int o = ok ? obase + oy * g.Wo + ox : obase;
+                code[r][q] = ok ? (int)gam[o] : 255;
+                d[r][q] = Elem<T>::to_f32(gdy[o]);
+            }
+        T res[2][8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int q = (e >> 1) + 1;  // the window column that starts at or just left of this pixel
+            float top = 0.f, bot = 0.f;  // input rows 2t and 2t+1
+            if ((e & 1) == 0) {
+                top += code[0][q - 1] == 8 ? d[0][q - 1] : 0.f;
+                top += code[0][q] == 6 ? d[0][q] : 0.f;
+                top += code[1][q - 1] == 2 ? d[1][q - 1] : 0.f;
+                top += code[1][q] == 0 ? d[1][q] : 0.f;
+                bot += code[1][q - 1] == 5 ? d[1][q - 1] : 0.f;
+                bot += code[1][q] == 3 ? d[1][q] : 0.f;
+            } else {
+                top += code[0][q] == 7 ? d[0][q] : 0.f;
+                top += code[1][q] == 1 ? d[1][q] : 0.f;
+                bot += code[1][q] == 4 ? d[1][q] : 0.f;
+            }
+            res[0][e] = Elem<T>::from_f32(top);
+            res[1][e] = Elem<T>::from_f32(bot);
+        }
+        const int x0 = 8 * (int)b, nv = g.W - x0 < 8 ? g.W - x0 : 8;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int iy = 2 * (int)t + r;
+            if (iy >= g.H) break;
+            T *row = out + (int)pl * hw + iy * g.W + x0;
+            if (nv == 8) {
+                store_packed<8>(row, res[r]);  // element-aligned stores
+            } else {
+                // 4, 2 and 1 pixels as nv's bits say; positions spelled out so that res stays in registers
+                if (nv & 4) store_packed<4>(row, res[r]);
+                if ((nv & 6) == 6) store_packed<2>(row + 4, res[r] + 4);
+                if ((nv & 6) == 2) store_packed<2>(row, res[r]);
+#pragma unroll
+                for (int at = 0; at < 8; at += 2)
+                    if ((nv & 1) && (nv & 6) == at) row[at] = res[r][at];
+            }
+        }
+    }
+}
+
+// Persistent form of the 3 x 3 / stride 2 backward pass.  A workgroup walks groups of pb planes with the
+// grid's stride; the loads of its next group (gradient, pooled values, winners: 16-byte pieces held in
+// registers) are issued before the current group is computed and stored, so every resident workgroup has
+// reads in flight all the time instead of only during its load phase.  Requires 16 <= pb * Ho*Wo <= 4096
+// for every group (the host checks, also for the last, smaller group).
+template <typename T, bool RELU>
+__global__ __launch_bounds__(256) void maxpool_bwd_k3s2_kernel(PoolGeom g, int64_t planes, int pb,
+                                                               const T *__restrict__ dy, const uint8_t *__restrict__ argmax,
+                                                               const T *__restrict__ y, T *__restrict__ dx)
+{
+    extern __shared__ __align__(16) unsigned char pool_smem[];
+    constexpr int VEC = 16 / (int)sizeof(T);
+    constexpr int MAXC = 4096 / VEC / 256;
+    const int hw = g.H * g.W, howo = g.Ho * g.Wo;
+    const int64_t groups = (planes + pb - 1) / pb;
+    T *gdy = reinterpret_cast<T *>(pool_smem);
+    uint8_t *gam = pool_smem + (((size_t)pb * howo * sizeof(T) + 15) / 16) * 16;
+    T d[MAXC][VEC], v[MAXC][VEC];
+    uint8_t a[16];
+    int at[MAXC], aat = 0, n = 0;
+    // A piece that would stick out of the group's run is moved back to end at the run's end: it then
+    // overlaps its neighbour, and both write the same values to the same LDS bytes.
+    auto load = [&](int64_t grp) {
+        const int64_t p0 = grp * pb;
+        n = (int)(planes - p0 < pb ? planes - p0 : pb) * howo;
+        const T *dp = dy + p0 * howo, *yp = y + p0 * howo;
+#pragma unroll
+        for (int u = 0; u < MAXC; ++u) {
+            const int c = (int)threadIdx.x + 256 * u;
+            at[u] = c * VEC + VEC <= n ? c * VEC : n - VEC;
+            __builtin_memcpy(d[u], dp + at[u], sizeof(d[u]));
+            if constexpr (RELU) __builtin_memcpy(v[u], yp + at[u], sizeof(v[u]));
+        }
+        aat = (int)threadIdx.x * 16 + 16 <= n ? (int)threadIdx.x * 16 : n - 16;
+        __builtin_memcpy(a, argmax + p0 * howo + aat, 16);
+    };
+    int64_t grp = blockIdx.x;
+    if (grp >= groups) return;
+    load(grp);
+    for (;;) {
+        const int np = n / howo;
+#pragma unroll
+        for (int u = 0; u < MAXC; ++u) {
+            const int c = (int)threadIdx.x + 256 * u;
+            if (c * VEC >= n) continue;
+            // the pooled value is the winner's value: where it is not positive the ReLU under the pool
+            // passes nothing, so that window's gradient is dropped while it is staged
+            if constexpr (RELU) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) d[u][e] = Elem<T>::to_f32(v[u][e]) > 0.f ? d[u][e] : (T)0;
+            }
+            if (at[u] == c * VEC) {
+                __builtin_memcpy(__builtin_assume_aligned(gdy + c * VEC, 16), d[u], sizeof(d[u]));
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) gdy[at[u] + e] = d[u][e];
+            }
+        }
+        if ((int)threadIdx.x * 16 < n) {
+            if (aat == (int)threadIdx.x * 16) {
+                __builtin_memcpy(__builtin_assume_aligned(gam + aat, 16), a, 16);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) gam[aat + e] = a[e];
+            }
+        }
+        __syncthreads();
+        const int64_t next = grp + gridDim.x;
+        if (next < groups) load(next);
+        pool_bwd_k3s2_tasks<T>(g, np, gdy, gam, dx + grp * pb * hw, hw, howo);
+        if (next >= groups) break;
+        __syncthreads();  // the staged group has been read by everyone
+        grp = next;
+    }
+}
+
 template <typename T, bool RELU, bool K3S2>
 __global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_t planes, int pb,
                                                               const T *__restrict__ dy, const uint8_t *__restrict__ argmax,
@@ -344,93 +553,76 @@ __global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_
     const int hw = g.H * g.W, howo = g.Ho * g.Wo;
     T *gdy = reinterpret_cast<T *>(pool_smem);
     uint8_t *gam = pool_smem + (((size_t)pb * howo * sizeof(T) + 15) / 16) * 16;
-    run_to_lds(argmax + p0 * howo, np * howo, gam, threadIdx.x);
-    if constexpr (RELU) {
-        // the pooled value is the winner's value: where it is not positive the ReLU under the pool
-        // passes nothing, so that window's gradient is dropped while it is staged
-        const T *yp = y + p0 * howo, *dp = dy + p0 * howo;
-        const int chunks = (np * howo + VEC - 1) / VEC;
-        for (int c = threadIdx.x; c < chunks; c += 256) {
-            if ((c + 1) * VEC <= np * howo) {
-                T v[VEC], d[VEC];
-                __builtin_memcpy(v, yp + c * VEC, sizeof(v));
-                __builtin_memcpy(d, dp + c * VEC, sizeof(d));
+    const int n = np * howo;
+    constexpr int MAXC = 4096 / VEC / 256;  // 16-byte pieces of dy (and y) per thread when n <= 4096
+    if (n <= 4096 && n >= 16) {
+        // All of the run's loads go out before the first is waited for (one memory latency, not one per
+        // operand and loop trip).  A piece that would stick out of the run is moved back to end at the
+        // run's end: it then overlaps its neighbour, and both write the same values to the same LDS bytes.
+        const T *dp = dy + p0 * howo, *yp = y + p0 * howo;
+        const uint8_t *ap = argmax + p0 * howo;
+        T d[MAXC][VEC], v[MAXC][VEC];
+        uint8_t a[16];
+        int at[MAXC];
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) d[e] = Elem<T>::to_f32(v[e]) > 0.f ? d[e] : (T)0;
-                __builtin_memcpy(__builtin_assume_aligned(gdy + c * VEC, 16), d, sizeof(d));
+        for (int u = 0; u < MAXC; ++u) {
+            const int c = (int)threadIdx.x + 256 * u;
+            at[u] = c * VEC + VEC <= n ? c * VEC : n - VEC;
+            __builtin_memcpy(d[u], dp + at[u], sizeof(d[u]));
+            if constexpr (RELU) __builtin_memcpy(v[u], yp + at[u], sizeof(v[u]));
+        }
+        const int aat = (int)threadIdx.x * 16 + 16 <= n ? (int)threadIdx.x * 16 : n - 16;
+        __builtin_memcpy(a, ap + aat, 16);
+#pragma unroll
+        for (int u = 0; u < MAXC; ++u) {
+            const int c = (int)threadIdx.x + 256 * u;
+            if (c * VEC >= n) continue;
+            // the pooled value is the winner's value: where it is not positive the ReLU under the pool
+            // passes nothing, so that window's gradient is dropped while it is staged
+            if constexpr (RELU) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) d[u][e] = Elem<T>::to_f32(v[u][e]) > 0.f ? d[u][e] : (T)0;
+            }
+            if (at[u] == c * VEC) {
+                __builtin_memcpy(__builtin_assume_aligned(gdy + c * VEC, 16), d[u], sizeof(d[u]));
             } else {
-                for (int e = 0; c * VEC + e < np * howo; ++e)
-                    gdy[c * VEC + e] = Elem<T>::to_f32(yp[c * VEC + e]) > 0.f ? dp[c * VEC + e] : (T)0;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) gdy[at[u] + e] = d[u][e];
+            }
+        }
+        if ((int)threadIdx.x * 16 < n) {
+            if (aat == (int)threadIdx.x * 16) {
+                __builtin_memcpy(__builtin_assume_aligned(gam + aat, 16), a, 16);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) gam[aat + e] = a[e];
             }
         }
     } else {
-        run_to_lds(dy + p0 * howo, np * howo, gdy, threadIdx.x);
+        run_to_lds(argmax + p0 * howo, n, gam, threadIdx.x);
+        if constexpr (RELU) {
+            const T *yp = y + p0 * howo, *dp = dy + p0 * howo;
+            const int chunks = (n + VEC - 1) / VEC;
+            for (int c = threadIdx.x; c < chunks; c += 256) {
+                if ((c + 1) * VEC <= n) {
+                    T v[VEC], d[VEC];
+                    __builtin_memcpy(v, yp + c * VEC, sizeof(v));
+                    __builtin_memcpy(d, dp + c * VEC, sizeof(d));
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) d[e] = Elem<T>::to_f32(v[e]) > 0.f ? d[e] : (T)0;
+                    __builtin_memcpy(__builtin_assume_aligned(gdy + c * VEC, 16), d, sizeof(d));
+                } else {
+                    for (int e = 0; c * VEC + e < n; ++e)
+                        gdy[c * VEC + e] = Elem<T>::to_f32(yp[c * VEC + e]) > 0.f ? dp[c * VEC + e] : (T)0;
+                }
+            }
+        } else {
+            run_to_lds(dy + p0 * howo, n, gdy, threadIdx.x);
+        }
     }
     __syncthreads();
     if constexpr (K3S2) {
-        // One task = input rows 2t, 2t+1 x pixels 8b .. 8b+7 of a plane.  The windows that can hold them
-        // are output rows t-1, t x columns 4b-1 .. 4b+3: ten (winner, gradient) pairs read once, and for
-        // every pixel the candidate windows and the winner code each would have follow from the pixel's
-        // parities, known at compile time.  Contributions are added in ascending (oy, ox).
-        T *out = dx + p0 * hw;
-        const int rp = (g.H + 1) >> 1, xb = (g.W + 7) >> 3;
-        const int tasks = np * rp * xb;
-        for (int task = threadIdx.x; task < tasks; task += 256) {
-            uint32_t rest, b, pl, t;
-            g.div_xb.divmod((uint32_t)task, rest, b);
-            g.div_rp.divmod(rest, pl, t);
-            const int obase = (int)pl * howo, ox0 = 4 * (int)b - 1;
-            float d[2][5];
-            int code[2][5];
-#pragma unroll
-            for (int r = 0; r < 2; ++r)
-#pragma unroll
-                for (int q = 0; q < 5; ++q) {
-                    const int oy = (int)t - 1 + r, ox = ox0 + q;
-                    const bool ok = oy >= 0 && oy < g.Ho && ox >= 0 && ox < g.Wo;
-                    const int o = ok ? obase + oy * g.Wo + ox : obase;
-                    code[r][q] = ok ? (int)gam[o] : 255;
-                    d[r][q] = Elem<T>::to_f32(gdy[o]);
-                }
-            T res[2][8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int q = (e >> 1) + 1;  // the window column that starts at or just left of this pixel
-                float top = 0.f, bot = 0.f;  // input rows 2t and 2t+1
-                if ((e & 1) == 0) {
-                    top += code[0][q - 1] == 8 ? d[0][q - 1] : 0.f;
-                    top += code[0][q] == 6 ? d[0][q] : 0.f;
-                    top += code[1][q - 1] == 2 ? d[1][q - 1] : 0.f;
-                    top += code[1][q] == 0 ? d[1][q] : 0.f;
-                    bot += code[1][q - 1] == 5 ? d[1][q - 1] : 0.f;
-                    bot += code[1][q] == 3 ? d[1][q] : 0.f;
-                } else {
-                    top += code[0][q] == 7 ? d[0][q] : 0.f;
-                    top += code[1][q] == 1 ? d[1][q] : 0.f;
-                    bot += code[1][q] == 4 ? d[1][q] : 0.f;
-                }
-                res[0][e] = Elem<T>::from_f32(top);
-                res[1][e] = Elem<T>::from_f32(bot);
-            }
-            const int x0 = 8 * (int)b, nv = g.W - x0 < 8 ? g.W - x0 : 8;
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                const int iy = 2 * (int)t + r;
-                if (iy >= g.H) break;
-                T *row = out + (int)pl * hw + iy * g.W + x0;
-                if (nv == 8) {
-                    __builtin_memcpy(row, res[r], 8 * sizeof(T));  // element-aligned stores
-                } else {
-                    // 4, 2 and 1 pixels as nv's bits say; positions spelled out so that res stays in registers
-                    if (nv & 4) __builtin_memcpy(row, res[r], 4 * sizeof(T));
-                    if ((nv & 6) == 6) __builtin_memcpy(row + 4, res[r] + 4, 2 * sizeof(T));
-                    if ((nv & 6) == 2) __builtin_memcpy(row, res[r], 2 * sizeof(T));
-#pragma unroll
-                    for (int at = 0; at < 8; at += 2)
-                        if ((nv & 1) && (nv & 6) == at) row[at] = res[r][at];
-                }
-            }
-        }
+        pool_bwd_k3s2_tasks<T>(g, np, gdy, gam, dx + p0 * hw, hw, howo);
         return;
     }
     // each thread produces VEC consecutive pixels of the workgroup's run of planes and stores them at once
@@ -470,7 +662,7 @@ __global__ __launch_bounds__(256) void maxpool_bwd_lds_kernel(PoolGeom g, int64_
             }
         }
         if (v0 + VEC <= total) {
-            __builtin_memcpy(out + v0, res, sizeof(res));  // element-aligned 16-byte store
+            store_packed<VEC>(out + v0, res);  // element-aligned 16-byte store
         } else {
             for (int e = 0; v0 + e < total; ++e) out[v0 + e] = res[e];
         }
@@ -490,13 +682,13 @@ static int pool_planes_per_block(int64_t plane_bytes, int64_t plane_elems)
 
 // 3 x 3 / stride 2 backward: the planes per workgroup that keep its 256 threads busiest (a plane is
 // ceil(H/2) * ceil(W/8) tasks), within the LDS budget and four passes of the threads.
-static int pool_bwd_planes_k3s2(int H, int W, int64_t plane_bytes)
+static int pool_bwd_planes_k3s2(int H, int W, int64_t plane_bytes, int64_t howo)
 {
     const int tasks = ((H + 1) / 2) * ((W + 7) / 8);
     int best = 0;
     double best_fill = 0.0;
     for (int pb = 1; pb <= 64; ++pb) {
-        if (pb * plane_bytes > 32 * 1024 || (pb > 1 && pb * tasks > 1024)) break;
+        if (pb * plane_bytes > 32 * 1024 || (pb > 1 && (pb * tasks > 1024 || pb * howo > 4096))) break;
         double fill = (double)(pb * tasks) / (double)((pb * tasks + 255) / 256 * 256);
         if (fill >= best_fill) best = pb, best_fill = fill;
     }
@@ -571,10 +763,25 @@ int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
     {
         const int64_t howo = (int64_t)g.Ho * g.Wo;
         int pb = pool_planes_per_block(howo * (int64_t)(elem_size(dtype) + 1), per);
-        if (pb > 0 && k == 3 && stride == 2) pb = pool_bwd_planes_k3s2(H, W, howo * (int64_t)(elem_size(dtype) + 1));
+        if (pb > 0 && k == 3 && stride == 2) pb = pool_bwd_planes_k3s2(H, W, howo * (int64_t)(elem_size(dtype) + 1), howo);
         if (pb > 0 && (planes + pb - 1) / pb <= 0x7fffffffll) {
             dim3 grid((unsigned)((planes + pb - 1) / pb));
             size_t lds = (((size_t)pb * howo * elem_size(dtype) + 15) / 16) * 16 + (size_t)pb * howo + 16;
+            const int64_t last = planes % pb == 0 ? pb : planes % pb;
+            if (k == 3 && stride == 2 && (int64_t)pb * howo <= 4096 && last * howo >= 16) {
+                // persistent: a few workgroups per compute unit, each walking the groups with the grid's stride
+                const unsigned resident = 256u * 6u;
+                dim3 pgrid(grid.x < resident ? grid.x : resident);
+                if (dtype == OMNI_BF16) {
+                    if (y) hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<bf16_t, true>), pgrid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)dy, argmax, (const bf16_t *)y, (bf16_t *)dx);
+                    else hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<bf16_t, false>), pgrid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)dy, argmax, (const bf16_t *)nullptr, (bf16_t *)dx);
+                } else {
+                    if (y) hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<float, true>), pgrid, dim3(256), lds, s, g, planes, pb, (const float *)dy, argmax, (const float *)y, (float *)dx);
+                    else hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<float, false>), pgrid, dim3(256), lds, s, g, planes, pb, (const float *)dy, argmax, (const float *)nullptr, (float *)dx);
+                }
+                OMNI_LAUNCH_CHECK();
+                return OMNI_OK;
+            }
 #define OMNI_POOL_BWD(T, R)                                                                                              \
     do {                                                                                                             \
         if (k == 3 && stride == 2)                                                                                   \

@@ -463,56 +463,70 @@ int launch_pack_khat_t(const ConvGeom &g, int dtype, const void *W, void *KhatT,
 // fp32 sum of its columns in bias_partials[f][block], reduced in block order by the second kernel.
 // ------------------------------------------------------------------------------------------------
 constexpr int PACK_VEC = 8;
-constexpr int PACK_COLS = 256 * PACK_VEC;
+constexpr int PACK_UNR = 4;                          // packs per thread
+constexpr int PACK_COLS = 256 * PACK_VEC * PACK_UNR;  // columns per workgroup
 
 template <typename T, typename U>
 __global__ __launch_bounds__(256) void pack_dyhat_kernel(ConvGeom g, const T *__restrict__ dY, U *__restrict__ out,
                                                          int64_t ld, float *__restrict__ bias_partials)
 {
-    int f = blockIdx.y;
-    int64_t m0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * PACK_VEC;
+    // PACK_UNR packs per thread, 256 packs apart.  Their loads are issued together and unconditionally: a
+    // pack that cannot be read with one load (it straddles two images or the end of the matrix) reads the
+    // first bytes of dY instead and is then assembled element by element.
+    const int f = blockIdx.y;
+    const bool can_vec = (int64_t)g.N * g.F * g.HoWo >= PACK_VEC;
     float sum = 0.f;
-    if (m0 < ld) {
-        uint32_t n, r;
-        g.div_HoWo.divmod(m0 < g.M ? (uint32_t)m0 : 0u, n, r);
-        VecOf<U, PACK_VEC> o;
-        if (m0 + PACK_VEC <= g.M && r + PACK_VEC <= (uint32_t)g.HoWo) {
-            // the 8 columns lie in one image: one load (element-aligned), two for fp32
-            __builtin_memcpy(&o, dY + ((int64_t)n * g.F + f) * g.HoWo + r, sizeof(o));
+    int64_t m0[PACK_UNR];
+    uint32_t n[PACK_UNR], r[PACK_UNR];
+    bool fast[PACK_UNR];
+    VecOf<U, PACK_VEC> o[PACK_UNR];
+#pragma unroll
+    for (int u = 0; u < PACK_UNR; ++u) {
+        m0[u] = (((int64_t)blockIdx.x * PACK_UNR + u) * 256 + threadIdx.x) * PACK_VEC;
+        g.div_HoWo.divmod(m0[u] < g.M ? (uint32_t)m0[u] : 0u, n[u], r[u]);
+        fast[u] = can_vec && m0[u] + PACK_VEC <= g.M && r[u] + PACK_VEC <= (uint32_t)g.HoWo;
+        const T *src = fast[u] ? dY + ((int64_t)n[u] * g.F + f) * g.HoWo + r[u] : dY;
+        if (can_vec) __builtin_memcpy(&o[u], src, sizeof(o[u]));
+    }
+#pragma unroll
+    for (int u = 0; u < PACK_UNR; ++u) {
+        if (m0[u] >= ld) continue;
+        if (fast[u]) {
 #pragma unroll
             for (int e = 0; e < PACK_VEC; ++e) {
                 T v;
-                __builtin_memcpy(&v, &o.v[e], sizeof(T));
+                __builtin_memcpy(&v, &o[u].v[e], sizeof(T));
                 sum += Elem<T>::to_f32(v);
             }
         } else {
+            uint32_t nn = n[u], rr = r[u];
 #pragma unroll
             for (int e = 0; e < PACK_VEC; ++e) {
                 U bits = 0;
-                if (m0 + e < g.M) {
-                    const T *src = dY + ((int64_t)n * g.F + f) * g.HoWo + r;
+                if (m0[u] + e < g.M) {
+                    const T *src = dY + ((int64_t)nn * g.F + f) * g.HoWo + rr;
                     bits = *reinterpret_cast<const U *>(src);
                     sum += Elem<T>::to_f32(*src);
                 }
-                o.v[e] = bits;
-                if (++r == (uint32_t)g.HoWo) {
-                    r = 0;
-                    ++n;
+                o[u].v[e] = bits;
+                if (++rr == (uint32_t)g.HoWo) {
+                    rr = 0;
+                    ++nn;
                 }
             }
         }
         // 8 x 4 bytes does not fit one 16-byte store: write two halves for fp32
         if constexpr (sizeof(U) == 2) {
-            *reinterpret_cast<VecOf<U, 8> *>(out + (int64_t)f * ld + m0) = o;
+            *reinterpret_cast<VecOf<U, 8> *>(out + (int64_t)f * ld + m0[u]) = o[u];
         } else {
             VecOf<U, 4> a, b;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                a.v[e] = o.v[e];
-                b.v[e] = o.v[4 + e];
+                a.v[e] = o[u].v[e];
+                b.v[e] = o[u].v[4 + e];
             }
-            *reinterpret_cast<VecOf<U, 4> *>(out + (int64_t)f * ld + m0) = a;
-            *reinterpret_cast<VecOf<U, 4> *>(out + (int64_t)f * ld + m0 + 4) = b;
+            *reinterpret_cast<VecOf<U, 4> *>(out + (int64_t)f * ld + m0[u]) = a;
+            *reinterpret_cast<VecOf<U, 4> *>(out + (int64_t)f * ld + m0[u] + 4) = b;
         }
     }
     if (bias_partials != nullptr) {
@@ -546,32 +560,43 @@ __global__ __launch_bounds__(256) void pack_dyhat_rows_kernel(ConvGeom g, FastDi
                                                               const bf16_t *__restrict__ dY, uint16_t *__restrict__ out,
                                                               int64_t ld, float *__restrict__ bias_partials)
 {
-    int f = blockIdx.y;
-    int64_t pack = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int f = blockIdx.y;
+    const bool can_vec = (int64_t)g.N * g.F * g.Ho * g.Wo >= 8;
     float sum = 0.f;
-    if (pack * 8 < ld) {
-        uint32_t row, i, n, oy;
-        div_p8.divmod((uint32_t)pack, row, i);
-        div_Ho.divmod(row, n, oy);
-        VecOf<uint16_t, 8> o;
-        const bool live = (int)n < g.N;
-        const bf16_t *src = dY + (((int64_t)(live ? n : 0) * g.F + f) * g.Ho + oy) * g.Wo + 8 * i;
-        if (live && 8 * (int)i + 8 <= g.Wo) {
-            __builtin_memcpy(&o, src, 16);  // element-aligned 16-byte load
+    int64_t pack[PACK_UNR];
+    uint32_t i[PACK_UNR];
+    const bf16_t *src[PACK_UNR];
+    bool live[PACK_UNR], fast[PACK_UNR];
+    VecOf<uint16_t, 8> o[PACK_UNR];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sum += bf16_to_f32(o.v[e]);
+    for (int u = 0; u < PACK_UNR; ++u) {
+        pack[u] = ((int64_t)blockIdx.x * PACK_UNR + u) * 256 + threadIdx.x;
+        uint32_t row, n, oy;
+        div_p8.divmod((uint32_t)(pack[u] * 8 < ld ? pack[u] : 0), row, i[u]);
+        div_Ho.divmod(row, n, oy);
+        live[u] = pack[u] * 8 < ld && (int)n < g.N;
+        src[u] = dY + (((int64_t)(live[u] ? n : 0) * g.F + f) * g.Ho + oy) * g.Wo + 8 * i[u];
+        fast[u] = can_vec && live[u] && 8 * (int)i[u] + 8 <= g.Wo;
+        if (can_vec) __builtin_memcpy(&o[u], fast[u] ? src[u] : dY, 16);  // element-aligned 16-byte loads, issued together
+    }
+#pragma unroll
+    for (int u = 0; u < PACK_UNR; ++u) {
+        if (pack[u] * 8 >= ld) continue;
+        if (fast[u]) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum += bf16_to_f32(o[u].v[e]);
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 uint16_t bits = 0;
-                if (live && 8 * (int)i + e < g.Wo) {
-                    bits = src[e];
+                if (live[u] && 8 * (int)i[u] + e < g.Wo) {
+                    bits = src[u][e];
                     sum += bf16_to_f32(bits);
                 }
-                o.v[e] = bits;
+                o[u].v[e] = bits;
             }
         }
-        *reinterpret_cast<VecOf<uint16_t, 8> *>(out + (int64_t)f * ld + pack * 8) = o;
+        *reinterpret_cast<VecOf<uint16_t, 8> *>(out + (int64_t)f * ld + pack[u] * 8) = o[u];
     }
     if (bias_partials != nullptr) {
         __shared__ float wave_sum[4];

@@ -29,9 +29,9 @@ MFMA_KERNELS = ("gemm", "conv_fused")          # kernel classes bound by the mat
 # workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by the readings for
 # the 256 MiB calibration copy below; the summary and its commands are profiles/*_hbm_traffic.md.
 MEASURED_HBM_BYTES_PER_LAUNCH = {
-    ("bf16", 256): {"gemm_wgrad": 271.5e6, "gemm_forward": 714.2e6, "conv_fused_forward": 129.4e6,
-                    "conv_fused_dgrad": 129.4e6, "lower": 671.6e6, "maxpool_backward": 143.2e6,
-                    "pack_dyhat": 145.5e6, "reduce_partials": 52.2e6, "maxpool_forward": 122.7e6},
+    ("bf16", 256): {"gemm_wgrad": 271.6e6, "gemm_forward": 714.2e6, "conv_fused_forward": 129.4e6,
+                    "conv_fused_dgrad": 129.4e6, "lower": 671.4e6, "maxpool_backward": 145.3e6,
+                    "pack_dyhat": 147.4e6, "reduce_partials": 52.2e6, "maxpool_forward": 122.7e6},
 }
 
 

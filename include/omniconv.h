@@ -64,6 +64,14 @@ typedef enum {
                                     OMNI_FLAG_DHAT_CACHED is also set): the product reads the entries of
                                     D-hat straight from X.  The workspace then holds no D-hat afterwards.
                                     Elsewhere the flag is ignored and the explicit path runs.            */
+#define OMNI_FLAG_SPLIT_K 8u     /* forward / backward_data, explicit path: when the result alone has too
+                                    few tiles to occupy the chip (few images per product: a small b_p of
+                                    Sec. III-B, or the fully connected layers run as whole-image
+                                    convolutions), split the product's reduction over the compute units:
+                                    fp32 partial results in the workspace, added in split order by a second
+                                    kernel that also applies bias / ReLU and stores.  Deterministic; differs
+                                    from the unsplit product by the fp32 rounding of another summation order.
+                                    Needs more workspace (omni_conv_workspace_bytes accounts for it).     */
 
 /*
  * A convolution layer (Sec. III-A, Eq. (conv_full); App. C adds stride and zero padding):
@@ -114,8 +122,10 @@ int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, 
  * lowered and multiplied at a time; App. C, Fig. (b), (c): the lowered data grows linearly with b_p and one
  * large product beats many small ones).  Runs omni_conv_forward's explicit path on consecutive groups of
  * b_p images (the last group may be smaller) through ONE workspace sized for b_p images:
- * workspace_bytes >= omni_conv_workspace_bytes of the same descriptor with N = b_p.  Every output element
- * is the same sum in the same order for every b_p, so Y is bit-identical to omni_conv_forward's.
+ * workspace_bytes >= omni_conv_workspace_bytes of the same descriptor with N = b_p (and, with
+ * OMNI_FLAG_SPLIT_K, also of the one with N = the smaller last group, N mod b_p).  Without OMNI_FLAG_SPLIT_K
+ * every output element is the same sum in the same order for every b_p, so Y is bit-identical to
+ * omni_conv_forward's; with it the split, hence the rounding, depends on the group's size.
  * 1 <= b_p <= N; for b_p < N a group of b_p images of X and of Y must be a multiple of 16 bytes (OMNI_MISALIGNED
  * otherwise).  OMNI_FLAG_FUSED is ignored: the knob is about D-hat's footprint.
  */

@@ -24,7 +24,7 @@ _lib = ctypes.CDLL(str(_LIB_PATH))
 
 F32, BF16 = 0, 1
 PASS_FORWARD, PASS_BACKWARD_DATA, PASS_BACKWARD_WEIGHTS = 0, 1, 2
-FLAG_RELU, FLAG_DHAT_CACHED, FLAG_FUSED = 1, 2, 4
+FLAG_RELU, FLAG_DHAT_CACHED, FLAG_FUSED, FLAG_SPLIT_K = 1, 2, 4, 8
 
 SYMBOLS = [
     "omni_conv_output_dims", "omni_conv_dhat_ld", "omni_conv_workspace_bytes", "omni_conv_fused_supported",

@@ -17,7 +17,7 @@ int make_geom(const omni_conv_desc *d, ConvGeom *g)
     int64_t ew = (int64_t)d->W + 2 * (int64_t)d->pad_w - d->kw;
     if (eh < 0 || ew < 0) return OMNI_INVALID_ARGUMENT;  // the window does not fit: empty output
     if (d->dtype != OMNI_F32 && d->dtype != OMNI_BF16) return OMNI_UNSUPPORTED;
-    if (d->flags & ~(OMNI_FLAG_RELU | OMNI_FLAG_DHAT_CACHED | OMNI_FLAG_FUSED)) return OMNI_UNSUPPORTED;
+    if (d->flags & ~(OMNI_FLAG_RELU | OMNI_FLAG_DHAT_CACHED | OMNI_FLAG_FUSED | OMNI_FLAG_SPLIT_K)) return OMNI_UNSUPPORTED;
     int64_t Ho = eh / d->stride_h + 1, Wo = ew / d->stride_w + 1;
     int64_t M = (int64_t)d->N * Ho * Wo;
     int64_t K = (int64_t)d->C * d->kh * d->kw;
@@ -29,6 +29,7 @@ int make_geom(const omni_conv_desc *d, ConvGeom *g)
     g->N = d->N; g->C = d->C; g->H = d->H; g->W = d->W; g->F = d->F;
     g->kh = d->kh; g->kw = d->kw; g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
     g->Ho = (int32_t)Ho; g->Wo = (int32_t)Wo; g->K = (int32_t)K; g->M = (int32_t)M; g->HoWo = (int32_t)(Ho * Wo);
+    g->flags = d->flags;
     g->div_Wo = FastDiv((uint32_t)Wo);
     g->div_HoWo = FastDiv((uint32_t)(Ho * Wo));
     g->div_kw = FastDiv((uint32_t)d->kw);
@@ -42,6 +43,27 @@ int make_geom(const omni_conv_desc *d, ConvGeom *g)
 
 static size_t align256(size_t b) { return (b + 255) / 256 * 256; }
 
+// OMNI_FLAG_SPLIT_K: a forward / data-gradient product of rows x cols results over a reduction of `red`
+// (a multiple of the LDS tile).  Split when its tiles fill at most half the compute units, into as many
+// chunks as bring the work items to about one per unit, each chunk at least four steps long.
+static void plan_split_k(const ConvGeom &g, int dtype, int64_t rows, int64_t cols, int64_t red, int *splits, int64_t *chunk)
+{
+    int64_t bk = gemm_red_tile(dtype);
+    *splits = 1;
+    *chunk = round_up(red, bk);
+    if (!(g.flags & OMNI_FLAG_SPLIT_K)) return;
+    int bm, bn;
+    gemm_split_tile((int)rows, (int)cols, &bm, &bn);
+    int64_t tiles = ((rows + bm - 1) / bm) * ((cols + bn - 1) / bn);
+    int64_t steps = (red + bk - 1) / bk;
+    if (tiles > 128 || steps < 8) return;
+    int64_t want = 256 / tiles, most = steps / 4;
+    int64_t n = want < most ? want : most;
+    if (n < 2) return;
+    *chunk = round_up((red + n - 1) / n, bk);
+    *splits = (int)((red + *chunk - 1) / *chunk);
+}
+
 void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w)
 {
     size_t e = elem_size(dtype);
@@ -50,7 +72,9 @@ void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w)
     w->Kp = round_up(g.K, 64);  // zero padded to whole reduction steps
     w->dhat = 0;
     w->khat = align256((size_t)g.K * w->ld * e);
-    w->total = w->khat + align256((size_t)w->Fp * w->Kp * e);
+    w->partials = w->khat + align256((size_t)w->Fp * w->Kp * e);
+    plan_split_k(g, dtype, g.F, w->ld, g.K, &w->splits, &w->chunk);
+    w->total = w->partials + align256(w->splits > 1 ? (size_t)w->splits * g.F * w->ld * sizeof(float) : 0);
     // the fused path keeps only its repacked weights here
     if (fused_supported(g, dtype, false) && fused_weight_bytes(g, false) > w->total) w->total = align256(fused_weight_bytes(g, false));
 }
@@ -64,7 +88,9 @@ void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w)
     w->ddhat = 0;
     w->dyhat = align256((size_t)g.K * w->ld * e);
     w->khat_t = w->dyhat + align256((size_t)g.F * w->ld * e);
-    w->total = w->khat_t + align256((size_t)w->Kp * w->Fp * e);
+    w->partials = w->khat_t + align256((size_t)w->Kp * w->Fp * e);
+    plan_split_k(g, dtype, g.K, w->ld, g.F, &w->splits, &w->chunk);
+    w->total = w->partials + align256(w->splits > 1 ? (size_t)w->splits * g.K * w->ld * sizeof(float) : 0);
     if (fused_supported(g, dtype, true) && fused_weight_bytes(g, true) > w->total) w->total = align256(fused_weight_bytes(g, true));
 }
 
@@ -222,7 +248,7 @@ int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, 
     if (st != OMNI_OK) return st;
     st = launch_pack_khat(g, desc->dtype, W, Khat, w.Fp, w.Kp, s);
     if (st != OMNI_OK) return st;
-    GemmFwdArgs a{Khat, w.Kp, Dhat, w.ld, bias, Y, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0};
+    GemmFwdArgs a{Khat, w.Kp, Dhat, w.ld, bias, Y, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0, (float *)(ws + w.partials), w.splits, w.chunk};
     return launch_gemm_forward(g, desc->dtype, a, s);
 }
 
@@ -249,6 +275,16 @@ int omni_conv_forward_partial(const omni_conv_desc *desc, int32_t b_p, const voi
     if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(workspace) || (bias && !aligned16(bias)))
         return OMNI_MISALIGNED;
     if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
+    if (desc->N % b_p != 0) {  // the smaller last group plans for itself (its split may differ): check it now too
+        omni_conv_desc last = part;
+        last.N = desc->N % b_p;
+        ForwardWs wl;
+        ConvGeom gl;
+        st = make_geom(&last, &gl);
+        if (st != OMNI_OK) return st;
+        plan_forward(gl, last.dtype, &wl);
+        if (workspace_bytes < wl.total) return OMNI_WORKSPACE_TOO_SMALL;
+    }
     for (int32_t n0 = 0; n0 < desc->N; n0 += b_p) {
         part.N = desc->N - n0 < b_p ? desc->N - n0 : b_p;
         st = omni_conv_forward(&part, (const char *)X + (size_t)n0 * x_image, W, bias, (char *)Y + (size_t)n0 * y_image,
@@ -281,7 +317,7 @@ int omni_conv_backward_data(const omni_conv_desc *desc, const void *dY, const vo
     if (st != OMNI_OK) return st;
     st = launch_pack_khat_t(g, desc->dtype, W, KhatT, w.Kp, w.Fp, s);
     if (st != OMNI_OK) return st;
-    GemmDgradArgs a{KhatT, w.Fp, dYhat, w.ld, dDhat};
+    GemmDgradArgs a{KhatT, w.Fp, dYhat, w.ld, dDhat, (float *)(ws + w.partials), w.splits, w.chunk};
     st = launch_gemm_dgrad(g, desc->dtype, a, s);
     if (st != OMNI_OK) return st;
     return launch_col2im(g, desc->dtype, dDhat, w.ld, dX, s);

@@ -70,6 +70,7 @@ struct ConvGeom {
     int32_t K;     // C*kh*kw   rows of D-hat
     int32_t M;     // N*Ho*Wo   columns of D-hat
     int32_t HoWo;  // Ho*Wo
+    uint32_t flags;  // the descriptor's OMNI_FLAG_* bits
     FastDiv div_Wo, div_HoWo, div_kw, div_khkw, div_W, div_HW, div_sh, div_sw;
 };
 
@@ -83,8 +84,10 @@ int make_geom(const omni_conv_desc *desc, ConvGeom *g);
 inline int64_t dhat_ld(const ConvGeom &g) { return round_up(g.M, 64); }
 
 // ---------------------------------------------------------------- workspace carving
-struct ForwardWs { size_t dhat, khat, total; int64_t ld, Fp, Kp; };
-struct BwdDataWs { size_t ddhat, dyhat, khat_t, total; int64_t ld, Kp, Fp; };
+// splits > 1 (OMNI_FLAG_SPLIT_K): the reduction is cut into `splits` chunks of `chunk` whose fp32 partial
+// results [splits][rows][ld] live at `partials`
+struct ForwardWs { size_t dhat, khat, partials, total; int64_t ld, Fp, Kp; int splits; int64_t chunk; };
+struct BwdDataWs { size_t ddhat, dyhat, khat_t, partials, total; int64_t ld, Kp, Fp; int splits; int64_t chunk; };
 // *_rows: the same plan for the row-padded dY-hat of the direct model gradient (reduction extent ld_rows)
 struct BwdWeightsWs {
     size_t dhat, dyhat, partials, bias_partials, total;
@@ -140,9 +143,10 @@ int launch_pack_dyhat_rows(const ConvGeom &g, const void *dY, void *dYhat, int64
                            int bias_blocks, float *dbias, hipStream_t s);
 
 // gemm.hip
-struct GemmFwdArgs { const void *Khat; int64_t ldk; const void *Dhat; int64_t ldd; const float *bias; void *Y; int relu; };
+// splits > 1: partial products into `partials`, then the ordered sum with the epilogue
+struct GemmFwdArgs { const void *Khat; int64_t ldk; const void *Dhat; int64_t ldd; const float *bias; void *Y; int relu; float *partials; int splits; int64_t chunk; };
 int launch_gemm_forward(const ConvGeom &g, int dtype, const GemmFwdArgs &a, hipStream_t s);
-struct GemmDgradArgs { const void *KhatT; int64_t ldk; const void *dYhat; int64_t ldd; void *dDhat; };
+struct GemmDgradArgs { const void *KhatT; int64_t ldk; const void *dYhat; int64_t ldd; void *dDhat; float *partials; int splits; int64_t chunk; };
 int launch_gemm_dgrad(const ConvGeom &g, int dtype, const GemmDgradArgs &a, hipStream_t s);
 // X_direct != null: D-hat is not in memory, its entries are read from X (wgrad_direct_supported layers)
 struct GemmWgradArgs { const void *dYhat; const void *Dhat; int64_t ldd; float *partials; int splits; int64_t chunk; float *dW; const void *X_direct; };
@@ -151,6 +155,7 @@ bool wgrad_direct_supported(const ConvGeom &g, int dtype);
 bool wgrad_direct_planes(const ConvGeom &g);  // its padded unit is the image plane, not the output row
 int gemm_red_tile(int dtype);  // reduction extent of one LDS tile (elements)
 void gemm_wgrad_tile(int F, int K, int *bm, int *bn);
+void gemm_split_tile(int rows, int cols, int *bm, int *bn);  // tile of a split forward / data-gradient product
 
 // implicit.hip: the convolution with lowering (forward) or col2im (data gradient) fused into the matrix
 // product; bf16, stride 1, shapes whose column tiles fit the kernel's LDS patch.  wt_scratch receives the

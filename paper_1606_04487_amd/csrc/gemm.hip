@@ -840,6 +840,20 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     if (l == 0 && i < count) out[i] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
 }
 
+// Ordered sum of the split partial results [splits][rows][cols] of a forward or data-gradient product,
+// handed to the product's own epilogue (address map, bias, ReLU, rounding).  One thread per result.
+template <typename Epi>
+__global__ __launch_bounds__(256) void reduce_store_kernel(const float *__restrict__ partials, int splits, int rows,
+                                                           int cols, Epi epi)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x, count = (int64_t)rows * cols;
+    if (idx >= count) return;
+    const int i = (int)(idx / cols), j = (int)(idx - (int64_t)i * cols);
+    float acc = 0.f;
+    for (int z = 0; z < splits; ++z) acc += partials[(int64_t)z * count + idx];
+    epi.store(i, epi.column(j), acc, epi.row_add(i), 0);
+}
+
 static GemmShape make_shape(int rows, int cols, int64_t red, int64_t chunk, int bm, int bn, int splits)
 {
     GemmShape s;
@@ -995,6 +1009,24 @@ static void launch_any(int tile, const T *A, int64_t lda, const T *B, int64_t ld
     }
 }
 
+// Tile of a split product: the 256 x 256 one where the result fills it about as well, else 128 x 128
+static int split_tile(int rows, int cols) { return pick_tile(rows, cols) == 6 ? 6 : 0; }
+void gemm_split_tile(int rows, int cols, int *bm, int *bn) { tile_dims(split_tile(rows, cols), bm, bn); }
+
+template <typename T, typename Epi>
+static void launch_split(const T *A, int64_t lda, const T *B, int64_t ldb, int rows, int cols, int64_t red, int64_t chunk,
+                         int splits, float *partials, const Epi &epi, hipStream_t s)
+{
+    PartialEpilogue pe{partials, rows, cols};
+    if (split_tile(rows, cols) == 6)
+        launch_cfg<T, Tile6, true, PartialEpilogue>(A, lda, B, ldb, rows, cols, red, chunk, splits, pe, s);
+    else
+        launch_cfg<T, Tile0, true, PartialEpilogue>(A, lda, B, ldb, rows, cols, red, chunk, splits, pe, s);
+    const int64_t count = (int64_t)rows * cols;
+    hipLaunchKernelGGL((reduce_store_kernel<Epi>), dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, partials, splits,
+                       rows, cols, epi);
+}
+
 template <typename T>
 static int run_forward(const ConvGeom &g, const GemmFwdArgs &a, hipStream_t s)
 {
@@ -1003,8 +1035,12 @@ static int run_forward(const ConvGeom &g, const GemmFwdArgs &a, hipStream_t s)
     FwdEpilogue<T> epi{(T *)a.Y, a.bias, g.F, g.M, g.HoWo, g.div_HoWo, a.relu};
     ProfScope prof(KID_GEMM_FWD, s, 2.0 * g.M * (double)g.K * g.F,
                    ((double)g.F * g.K + (double)g.K * g.M + (double)g.F * g.M) * sizeof(T));
-    launch_any<T, true, FwdEpilogue<T>>(pick_tile(g.F, (int)a.ldd), (const T *)a.Khat, a.ldk, (const T *)a.Dhat, a.ldd,
-                                        g.F, (int)a.ldd, g.K, round_up(g.K, BK), 1, epi, s);
+    if (a.splits > 1)
+        launch_split<T>((const T *)a.Khat, a.ldk, (const T *)a.Dhat, a.ldd, g.F, (int)a.ldd, g.K, a.chunk, a.splits, a.partials,
+                        epi, s);
+    else
+        launch_any<T, true, FwdEpilogue<T>>(pick_tile(g.F, (int)a.ldd), (const T *)a.Khat, a.ldk, (const T *)a.Dhat, a.ldd,
+                                            g.F, (int)a.ldd, g.K, round_up(g.K, BK), 1, epi, s);
     OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }
@@ -1021,8 +1057,12 @@ static int run_dgrad(const ConvGeom &g, const GemmDgradArgs &a, hipStream_t s)
     RowMajorEpilogue<T> epi{(T *)a.dDhat, a.ldd, g.K, (int)a.ldd};
     ProfScope prof(KID_GEMM_DGRAD, s, 2.0 * g.M * (double)g.K * g.F,
                    ((double)g.F * g.K + (double)g.K * g.M + (double)g.F * g.M) * sizeof(T));
-    launch_any<T, true, RowMajorEpilogue<T>>(pick_tile(g.K, (int)a.ldd), (const T *)a.KhatT, a.ldk, (const T *)a.dYhat,
-                                             a.ldd, g.K, (int)a.ldd, g.F, round_up(g.F, BK), 1, epi, s);
+    if (a.splits > 1)
+        launch_split<T>((const T *)a.KhatT, a.ldk, (const T *)a.dYhat, a.ldd, g.K, (int)a.ldd, g.F, a.chunk, a.splits,
+                        a.partials, epi, s);
+    else
+        launch_any<T, true, RowMajorEpilogue<T>>(pick_tile(g.K, (int)a.ldd), (const T *)a.KhatT, a.ldk, (const T *)a.dYhat,
+                                                 a.ldd, g.K, (int)a.ldd, g.F, round_up(g.F, BK), 1, epi, s);
     OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }

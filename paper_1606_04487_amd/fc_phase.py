@@ -21,16 +21,17 @@ def main():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--reps", type=int, default=10)
+    ap.add_argument("--no-split", action="store_true", help="do not split the reductions of the narrow products over the chip")
     args = ap.parse_args()
     dtype = B.BF16 if args.dtype == "bf16" else B.F32
     td = B.torch_dtype(dtype)
     N = args.batch
-    print(f"FC phase, batch {N}, {args.dtype}")
+    print(f"FC phase, batch {N}, {args.dtype}, reductions of narrow products {'not split' if args.no_split else 'split over the chip'}")
     print("| layer | GFLOP per pass | forward ms | data gradient ms | model gradient ms | TFLOP/s (all three) |")
     print("|---|---|---|---|---|---|")
     total_ms, total_flop = 0.0, 0.0
     for name, C, hk, F in FC_LAYERS:
-        d = B.conv_desc(N, C, hk, hk, F, hk, hk, 1, 0, dtype)
+        d = B.conv_desc(N, C, hk, hk, F, hk, hk, 1, 0, dtype, 0 if args.no_split else B.FLAG_SPLIT_K)
         X = torch.randn(N, C, hk, hk, device="cuda").to(td)
         W = (0.01 * torch.randn(F, C, hk, hk, device="cuda")).to(td)
         bias = torch.zeros(F, device="cuda")

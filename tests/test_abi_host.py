@@ -72,7 +72,7 @@ def test_workspace_sizes_grow_linearly_with_the_batch(B):
 @pytest.mark.parametrize("field,value,status", [
     ("N", 0, -1), ("C", -1, -1), ("F", 0, -1), ("kh", 0, -1), ("stride_h", 0, -1), ("pad_w", -1, -1),
     ("kh", 40, -1),                       # window larger than the padded image
-    ("dtype", 2, -2), ("flags", 8, -2), ("F", 70000, -2),
+    ("dtype", 2, -2), ("flags", 16, -2), ("F", 70000, -2),
 ])
 def test_bad_descriptors(B, field, value, status):
     d = B.conv_desc(2, 3, 32, 32, 8, 5, 5, 1, 2)
@@ -145,3 +145,17 @@ def test_partial_batching_workspace_is_linear_in_bp_and_checks_arguments():
     assert lib.omni_conv_forward_partial(ctypes.byref(d), 2, 16, 16, None, 16, 16, 64, None) == -3
     odd = B.conv_desc(4, 3, 5, 5, 2, 3, 3, 1, 1, B.BF16)    # one image = 150 bytes: groups would be misaligned
     assert lib.omni_conv_forward_partial(ctypes.byref(odd), 2, 16, 16, None, 16, 16, 1 << 40, None) == -4
+
+
+def test_split_k_flag_is_accepted_and_sized(B):
+    """OMNI_FLAG_SPLIT_K: accepted by the host checks; products with few columns get room for their partial sums."""
+    d0 = B.conv_desc(16, 64, 6, 6, 136, 6, 6, 1, 0, B.BF16)
+    d1 = d0.with_flags(B.FLAG_SPLIT_K)
+    assert B.conv_workspace_bytes(d1, B.PASS_FORWARD) > B.conv_workspace_bytes(d0, B.PASS_FORWARD)
+    assert B.conv_workspace_bytes(d1, B.PASS_BACKWARD_WEIGHTS) == B.conv_workspace_bytes(d0, B.PASS_BACKWARD_WEIGHTS)
+    big = B.conv_desc(256, 96, 27, 27, 256, 5, 5, 1, 2, B.BF16)     # fills the chip on its own: nothing changes
+    assert B.conv_workspace_bytes(big.with_flags(B.FLAG_SPLIT_K), B.PASS_FORWARD) == B.conv_workspace_bytes(big, B.PASS_FORWARD)
+    bad = d0.with_flags(16)
+    import ctypes
+    n = ctypes.c_size_t()
+    assert B._lib.omni_conv_workspace_bytes(ctypes.byref(bad), 0, ctypes.byref(n)) == -2

@@ -352,3 +352,34 @@ def test_fully_connected_as_convolution(B, cfg, dtype):
     dW, db = B.conv_backward_weights(d, Xg, dYg)
     assert rel_err(host(dW).reshape(F, -1), dY.reshape(N, F).astype(np.float64).T @ X.reshape(N, -1)) <= 1e-4
     assert rel_err(host(db), dY.reshape(N, F).sum(0)) <= 1e-4
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("cfg", [(16, 64, 6, 6, 136, 6, 6, 1, 1, 0, 0),      # FC6-like: 2304-long reduction, 16 columns
+                                 (24, 1200, 1, 1, 72, 1, 1, 1, 1, 0, 0),    # FC7/8-like
+                                 (1, 48, 13, 13, 64, 5, 5, 1, 1, 2, 2),     # one image per product (b_p = 1)
+                                 (4, 16, 4, 4, 1024, 3, 3, 1, 1, 1, 1)])    # many filters: the data gradient's reduction splits
+def test_split_reduction(B, cfg, dtype):
+    """OMNI_FLAG_SPLIT_K: products with few columns split their reduction over the chip.  Same bars as the
+    unsplit products against the oracle, agreement with them to rounding, deterministic, and the extra
+    workspace is accounted for."""
+    s, X, Wt, b, dY = make(cfg, dtype, 41)
+    N, C, H, W, F, kh, kw, sh, sw, ph, pw = cfg
+    plain = desc_of(B, cfg, dtype)
+    split = B.conv_desc(N, C, H, W, F, kh, kw, (sh, sw), (ph, pw), dtype, B.FLAG_SPLIT_K | B.FLAG_RELU)
+    assert B.conv_workspace_bytes(split, B.PASS_FORWARD) >= B.conv_workspace_bytes(plain, B.PASS_FORWARD)
+    Xg, Wg, bg, dYg = gpu(X, dtype), gpu(Wt, dtype), gpu(b), gpu(dY, dtype)
+    Y = B.conv_forward(split, Xg, Wg, bg)
+    ref = np.maximum(oracle.conv_forward(s, X, Wt, b), 0)
+    assert rel_err(host(Y), ref) <= TOL[dtype]
+    Y0 = B.conv_forward(plain.with_flags(B.FLAG_RELU), Xg, Wg, bg)
+    assert rel_err(host(Y), host(Y0)) <= (1e-5 if dtype == 0 else 1e-2)
+    assert torch.equal(Y, B.conv_forward(split, Xg, Wg, bg))
+    dX = B.conv_backward_data(split, dYg, Wg)
+    assert rel_err(host(dX), oracle.conv_backward_data(s, dY, Wt)) <= TOL[dtype]
+    assert rel_err(host(dX), host(B.conv_backward_data(plain, dYg, Wg))) <= (1e-5 if dtype == 0 else 1e-2)
+    assert torch.equal(dX, B.conv_backward_data(split, dYg, Wg))
+    # the model gradient ignores the flag
+    dW, _ = B.conv_backward_weights(split, Xg, dYg)
+    dW0, _ = B.conv_backward_weights(plain, Xg, dYg)
+    assert torch.equal(dW, dW0)

@@ -246,9 +246,13 @@ int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, 
 
     st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
     if (st != OMNI_OK) return st;
-    st = launch_pack_khat(g, desc->dtype, W, Khat, w.Fp, w.Kp, s);
-    if (st != OMNI_OK) return st;
-    GemmFwdArgs a{Khat, w.Kp, Dhat, w.ld, bias, Y, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0, (float *)(ws + w.partials), w.splits, w.chunk};
+    // K-hat is W with every row zero-padded to whole reduction steps: where there is nothing to pad, W itself
+    const bool w_is_khat = w.Kp == g.K && w.Fp == g.F;
+    if (!w_is_khat) {
+        st = launch_pack_khat(g, desc->dtype, W, Khat, w.Fp, w.Kp, s);
+        if (st != OMNI_OK) return st;
+    }
+    GemmFwdArgs a{w_is_khat ? W : Khat, w.Kp, Dhat, w.ld, bias, Y, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0, (float *)(ws + w.partials), w.splits, w.chunk};
     return launch_gemm_forward(g, desc->dtype, a, s);
 }
 

@@ -89,6 +89,13 @@ void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w)
     w->dyhat = align256((size_t)g.K * w->ld * e);
     w->khat_t = w->dyhat + align256((size_t)g.F * w->ld * e);
     w->partials = w->khat_t + align256((size_t)w->Kp * w->Fp * e);
+    if (dgrad_dense_supported(g)) {
+        // whole-image window: one product dX [N][K] = dY [N][F] * W [F][K]; the workspace holds only its partial sums
+        plan_split_k(g, dtype, g.N, g.K, g.F, &w->splits, &w->chunk);
+        w->partials = 0;
+        w->total = align256(w->splits > 1 ? (size_t)w->splits * g.N * g.K * sizeof(float) : 16);
+        return;
+    }
     plan_split_k(g, dtype, g.K, w->ld, g.F, &w->splits, &w->chunk);
     w->total = w->partials + align256(w->splits > 1 ? (size_t)w->splits * g.K * w->ld * sizeof(float) : 0);
     if (fused_supported(g, dtype, true) && fused_weight_bytes(g, true) > w->total) w->total = align256(fused_weight_bytes(g, true));
@@ -316,6 +323,9 @@ int omni_conv_backward_data(const omni_conv_desc *desc, const void *dY, const vo
     if ((desc->flags & OMNI_FLAG_FUSED) && fused_supported(g, desc->dtype, true) &&
         fused_weight_bytes(g, true) <= w.total)
         return launch_fused_conv(g, true, dY, W, nullptr, 0, dX, ws, s);
+
+    if (dgrad_dense_supported(g))
+        return launch_gemm_dgrad_dense(g, desc->dtype, dY, W, dX, (float *)(ws + w.partials), w.splits, w.chunk, s);
 
     st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, nullptr, 0, nullptr, s);
     if (st != OMNI_OK) return st;

@@ -148,6 +148,10 @@ struct GemmFwdArgs { const void *Khat; int64_t ldk; const void *Dhat; int64_t ld
 int launch_gemm_forward(const ConvGeom &g, int dtype, const GemmFwdArgs &a, hipStream_t s);
 struct GemmDgradArgs { const void *KhatT; int64_t ldk; const void *dYhat; int64_t ldd; void *dDhat; float *partials; int splits; int64_t chunk; };
 int launch_gemm_dgrad(const ConvGeom &g, int dtype, const GemmDgradArgs &a, hipStream_t s);
+// whole-image windows (fully connected layers): one product on the tensors as they are
+bool dgrad_dense_supported(const ConvGeom &g);
+int launch_gemm_dgrad_dense(const ConvGeom &g, int dtype, const void *dY, const void *W, void *dX, float *partials,
+                            int splits, int64_t chunk, hipStream_t s);
 // X_direct != null: D-hat is not in memory, its entries are read from X (wgrad_direct_supported layers)
 struct GemmWgradArgs { const void *dYhat; const void *Dhat; int64_t ldd; float *partials; int splits; int64_t chunk; float *dW; const void *X_direct; };
 int launch_gemm_wgrad(const ConvGeom &g, int dtype, const GemmWgradArgs &a, hipStream_t s);

@@ -1072,6 +1072,38 @@ int launch_gemm_dgrad(const ConvGeom &g, int dtype, const GemmDgradArgs &a, hipS
     return dtype == OMNI_BF16 ? run_dgrad<bf16_t>(g, a, s) : run_dgrad<float>(g, a, s);
 }
 
+// Data gradient of a layer whose window is the whole, unpadded image (a fully connected layer, Sec. II-C):
+// dX [N][K] = dY [N][F] * W [F][K] with all three tensors in their natural layouts -- dY's rows run along the
+// reduction, W's rows along the result's columns -- so nothing is packed, transposed or scattered back.
+bool dgrad_dense_supported(const ConvGeom &g)
+{
+    return g.Ho == 1 && g.Wo == 1 && g.ph == 0 && g.pw == 0 && g.kh == g.H && g.kw == g.W && g.F % 8 == 0 && g.K % 8 == 0;
+}
+
+template <typename T>
+static int run_dgrad_dense(const ConvGeom &g, const void *dY, const void *W, void *dX, float *partials, int splits,
+                           int64_t chunk, hipStream_t s)
+{
+    constexpr int BK = NPACK * Pack<T>::KP;
+    RowMajorEpilogue<T> epi{(T *)dX, (int64_t)g.K, g.N, g.K};
+    ProfScope prof(KID_GEMM_DGRAD, s, 2.0 * g.N * (double)g.K * g.F,
+                   ((double)g.F * g.K + (double)g.K * g.N + (double)g.F * g.N) * sizeof(T));
+    if (splits > 1)
+        launch_split<T>((const T *)dY, (int64_t)g.F, (const T *)W, (int64_t)g.K, g.N, g.K, g.F, chunk, splits, partials, epi, s);
+    else
+        launch_any<T, true, RowMajorEpilogue<T>>(pick_tile(g.N, g.K), (const T *)dY, (int64_t)g.F, (const T *)W, (int64_t)g.K,
+                                                 g.N, g.K, g.F, round_up(g.F, BK), 1, epi, s);
+    OMNI_LAUNCH_CHECK();
+    return OMNI_OK;
+}
+
+int launch_gemm_dgrad_dense(const ConvGeom &g, int dtype, const void *dY, const void *W, void *dX, float *partials,
+                            int splits, int64_t chunk, hipStream_t s)
+{
+    return dtype == OMNI_BF16 ? run_dgrad_dense<bf16_t>(g, dY, W, dX, partials, splits, chunk, s)
+                              : run_dgrad_dense<float>(g, dY, W, dX, partials, splits, chunk, s);
+}
+
 template <typename T>
 static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
 {

@@ -358,7 +358,8 @@ def test_fully_connected_as_convolution(B, cfg, dtype):
 @pytest.mark.parametrize("cfg", [(16, 64, 6, 6, 136, 6, 6, 1, 1, 0, 0),      # FC6-like: 2304-long reduction, 16 columns
                                  (24, 1200, 1, 1, 72, 1, 1, 1, 1, 0, 0),    # FC7/8-like
                                  (1, 48, 13, 13, 64, 5, 5, 1, 1, 2, 2),     # one image per product (b_p = 1)
-                                 (4, 16, 4, 4, 1024, 3, 3, 1, 1, 1, 1)])    # many filters: the data gradient's reduction splits
+                                 (4, 16, 4, 4, 1024, 3, 3, 1, 1, 1, 1),     # many filters: the data gradient's reduction splits
+                                 (8, 32, 2, 2, 2048, 2, 2, 1, 1, 0, 0)])    # whole-image window: the dense data gradient, split
 def test_split_reduction(B, cfg, dtype):
     """OMNI_FLAG_SPLIT_K: products with few columns split their reduction over the chip.  Same bars as the
     unsplit products against the oracle, agreement with them to rounding, deterministic, and the extra

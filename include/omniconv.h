@@ -104,15 +104,18 @@ int omni_conv_workspace_bytes(const omni_conv_desc *desc, int pass, size_t *byte
 /* Host only.  1 if the pass (omni_pass) of this layer runs fused under OMNI_FLAG_FUSED, 0 if it
  * falls back to the explicit path, negative status for a bad descriptor.  Fused forward and
  * backward_data: bf16, stride 1, reduced channels a multiple of 32, and the pixels needed by 256
- * consecutive output positions fit the kernel's LDS patch.  Fused backward_weights: bf16, stride 1,
- * output rows of at least 8 positions.  The workspace size of a pass does not depend on the flag. */
+ * consecutive output positions fit the kernel's LDS patch (and the layer is not one that backward_data
+ * handles as a single dense product, see there).  Fused backward_weights: bf16, stride 1, a result that
+ * fills 256 x 256 or 384 x 128 tiles.  The workspace size of a pass does not depend on OMNI_FLAG_FUSED. */
 int omni_conv_fused_supported(const omni_conv_desc *desc, int pass);
 
 /*
  * Forward pass (Sec. III-B: lower all N images, then a single GEMM; App. C: lifting is pure
  * addressing and costs no copy).  Steps: batched lowering of X into the workspace, reshaping of
- * W into a padded K-hat, one MFMA GEMM Y-hat[F x M] = K-hat[F x K] * D-hat[K x M] whose epilogue adds
- * bias (nullable, fp32[F]), applies ReLU if OMNI_FLAG_RELU and stores straight into Y [N][F][Ho][Wo].
+ * W into a padded K-hat (W itself where K needs no padding), one MFMA GEMM
+ * Y-hat[F x M] = K-hat[F x K] * D-hat[K x M] whose epilogue adds bias (nullable, fp32[F]), applies ReLU if
+ * OMNI_FLAG_RELU and stores straight into Y [N][F][Ho][Wo].  With OMNI_FLAG_SPLIT_K a product with few
+ * columns splits its reduction (see the flag).
  */
 int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, const float *bias,
                       void *Y, void *workspace, size_t workspace_bytes, void *hip_stream);
@@ -138,6 +141,9 @@ int omni_conv_forward_partial(const omni_conv_desc *desc, int32_t b_p, const voi
  * w.r.t. its input).  Steps: dY is packed into the matrix dY-hat [F][ld]; one MFMA GEMM
  * dD-hat[K x M] = K-hat^T[K x F] * dY-hat[F x M]; col2im sums the entries of dD-hat that were copies
  * of the same input pixel into dX [N][C][H][W] (gather form, fixed summation order).
+ * A layer whose window is the whole unpadded image (Ho = Wo = 1: a fully connected layer, Sec. II-C) with F
+ * and K multiples of 8 takes one product dX [N][K] = dY [N][F] * W [F][K] on the tensors as they are instead.
+ * OMNI_FLAG_SPLIT_K applies to either form.
  */
 int omni_conv_backward_data(const omni_conv_desc *desc, const void *dY, const void *W, void *dX,
                             void *workspace, size_t workspace_bytes, void *hip_stream);

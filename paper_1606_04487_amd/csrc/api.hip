@@ -362,15 +362,22 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
         st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
         if (st != OMNI_OK) return st;
     }
+    // with a split product the ordered reduction finishes the bias gradient too (one launch fewer)
     if (direct) {
-        st = launch_pack_dyhat_rows(g, dY, dYhat, w.ld_rows, dbias ? bias_partials : nullptr, w.bias_blocks_rows, dbias, s);
+        const bool defer = dbias != nullptr && w.splits_rows > 1;
+        st = launch_pack_dyhat_rows(g, dY, dYhat, w.ld_rows, dbias ? bias_partials : nullptr, w.bias_blocks_rows,
+                                    defer ? nullptr : dbias, s);
         if (st != OMNI_OK) return st;
-        GemmWgradArgs a{dYhat, nullptr, w.ld_rows, partials, w.splits_rows, w.chunk_rows, dW, X};
+        GemmWgradArgs a{dYhat, nullptr, w.ld_rows, partials, w.splits_rows, w.chunk_rows, dW, X,
+                        bias_partials, w.bias_blocks_rows, defer ? dbias : nullptr};
         return launch_gemm_wgrad(g, desc->dtype, a, s);
     }
-    st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, dbias ? bias_partials : nullptr, w.bias_blocks, dbias, s);
+    const bool defer = dbias != nullptr && w.splits > 1;
+    st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, dbias ? bias_partials : nullptr, w.bias_blocks,
+                           defer ? nullptr : dbias, s);
     if (st != OMNI_OK) return st;
-    GemmWgradArgs a{dYhat, Dhat, w.ld, partials, w.splits, w.chunk, dW, nullptr};
+    GemmWgradArgs a{dYhat, Dhat, w.ld, partials, w.splits, w.chunk, dW, nullptr, bias_partials, w.bias_blocks,
+                    defer ? dbias : nullptr};
     return launch_gemm_wgrad(g, desc->dtype, a, s);
 }
 

@@ -133,6 +133,7 @@ int launch_pack_khat(const ConvGeom &g, int dtype, const void *W, void *Khat, in
 int launch_pack_khat_t(const ConvGeom &g, int dtype, const void *W, void *KhatT, int64_t Kp, int64_t Fp, hipStream_t s);
 // dY [N][F][Ho][Wo] -> dY-hat [F][ld]; if bias_partials != null also writes per-block sums
 // [F][bias_blocks] and then reduces them into dbias.
+// (dbias == null with bias_partials != null: the per-block sums are left for the caller to reduce)
 int launch_pack_dyhat(const ConvGeom &g, int dtype, const void *dY, void *dYhat, int64_t ld,
                       float *bias_partials, int bias_blocks, float *dbias, hipStream_t s);
 int pack_dyhat_blocks(const ConvGeom &g);
@@ -153,7 +154,9 @@ bool dgrad_dense_supported(const ConvGeom &g);
 int launch_gemm_dgrad_dense(const ConvGeom &g, int dtype, const void *dY, const void *W, void *dX, float *partials,
                             int splits, int64_t chunk, hipStream_t s);
 // X_direct != null: D-hat is not in memory, its entries are read from X (wgrad_direct_supported layers)
-struct GemmWgradArgs { const void *dYhat; const void *Dhat; int64_t ldd; float *partials; int splits; int64_t chunk; float *dW; const void *X_direct; };
+// dbias != null (only with splits > 1): the ordered reduction also finishes the bias gradient from bias_partials
+struct GemmWgradArgs { const void *dYhat; const void *Dhat; int64_t ldd; float *partials; int splits; int64_t chunk; float *dW; const void *X_direct;
+                       const float *bias_partials; int bias_blocks; float *dbias; };
 int launch_gemm_wgrad(const ConvGeom &g, int dtype, const GemmWgradArgs &a, hipStream_t s);
 bool wgrad_direct_supported(const ConvGeom &g, int dtype);
 bool wgrad_direct_planes(const ConvGeom &g);  // its padded unit is the image plane, not the output row

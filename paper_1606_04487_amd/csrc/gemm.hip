@@ -818,11 +818,27 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const T *__restrict__ A,
 // Sum the per-split partial results into the final fp32 tensor, in a fixed order (deterministic): a
 // workgroup takes 64 consecutive elements; wavefront l adds splits l, l+4, l+8, ... in that order, four
 // loads in flight, and the four sums are then added as (s0 + s1) + (s2 + s3).
+// The launch may carry extra workgroups (blockIdx >= main_blocks) that finish the bias gradient: one
+// wavefront per filter adds that filter's per-block sums left by the dY packing kernel (strided per lane in
+// block order, then a fixed tree) -- the same arithmetic as bias_reduce_kernel, without a launch of its own.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partials, int splits,
-                                                              int64_t count, float *__restrict__ out)
+                                                              int64_t count, float *__restrict__ out, unsigned main_blocks,
+                                                              const float *__restrict__ bias_partials, int bias_blocks,
+                                                              int F, float *__restrict__ dbias)
 {
     __shared__ float part[4][64];
     const int c = threadIdx.x % 64, l = threadIdx.x / 64;
+    if (blockIdx.x >= main_blocks) {
+        const int f = (int)(blockIdx.x - main_blocks) * 4 + l;
+        if (f < F) {
+            float acc = 0.f;
+            for (int b = c; b < bias_blocks; b += 64) acc += bias_partials[(int64_t)f * bias_blocks + b];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+            if (c == 0) dbias[f] = acc;
+        }
+        return;
+    }
     const int64_t i = (int64_t)blockIdx.x * 64 + c;
     float acc = 0.f;
     if (i < count) {
@@ -1135,8 +1151,10 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
     if (a.splits > 1) {
         int64_t count = (int64_t)g.F * g.K;
         ProfScope prof(KID_REDUCE_PARTIALS, s, 0.0, 4.0 * count * (a.splits + 1));
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, s,
-                           a.partials, a.splits, count, a.dW);
+        const unsigned main_blocks = (unsigned)((count + 63) / 64);
+        const unsigned bias_wgs = a.dbias != nullptr ? (unsigned)((g.F + 3) / 4) : 0u;
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3(main_blocks + bias_wgs), dim3(256), 0, s, a.partials, a.splits, count,
+                           a.dW, main_blocks, a.bias_partials, a.bias_blocks, g.F, a.dbias);
         OMNI_LAUNCH_CHECK();
     }
     return OMNI_OK;

@@ -638,7 +638,7 @@ int launch_pack_dyhat_rows(const ConvGeom &geom, const void *dY, void *dYhat, in
                            FastDiv((uint32_t)g.Ho), (const bf16_t *)dY, (uint16_t *)dYhat, ld, bias_partials);
     }
     OMNI_LAUNCH_CHECK();
-    if (bias_partials != nullptr) {
+    if (bias_partials != nullptr && dbias != nullptr) {
         ProfScope prof(KID_BIAS_REDUCE, s, 0.0, 4.0 * g.F * (blocks + 1));
         hipLaunchKernelGGL(bias_reduce_kernel, dim3((unsigned)g.F), dim3(64), 0, s, bias_partials, blocks, dbias);
         OMNI_LAUNCH_CHECK();
@@ -662,7 +662,7 @@ int launch_pack_dyhat(const ConvGeom &g, int dtype, const void *dY, void *dYhat,
             hipLaunchKernelGGL((pack_dyhat_kernel<float, uint32_t>), grid, dim3(256), 0, s, g, (const float *)dY, (uint32_t *)dYhat, ld, bias_partials);
     }
     OMNI_LAUNCH_CHECK();
-    if (bias_partials != nullptr) {
+    if (bias_partials != nullptr && dbias != nullptr) {
         ProfScope prof(KID_BIAS_REDUCE, s, 0.0, 4.0 * g.F * (blocks + 1));
         hipLaunchKernelGGL(bias_reduce_kernel, dim3((unsigned)g.F), dim3(64), 0, s, bias_partials, blocks, dbias);
         OMNI_LAUNCH_CHECK();

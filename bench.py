@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--no-events", action="store_true", help="record no events at all (no kernel table, no roofline)")
     ap.add_argument("--table-steps", type=int, default=5, help="instrumented steps before the timed region")
     ap.add_argument("--overlap", action="store_true", help="model gradients on a second stream beside the data gradients")
+    ap.add_argument("--conv1-dgrad", action="store_true",
+                    help="also compute conv1's data gradient (the paper's FLOP rule, App. B, leaves it out; default: skipped)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -80,7 +82,7 @@ def main():
     torch.cuda.set_device(0)
     dtype = B.BF16 if args.dtype == "bf16" else B.F32
     layers = wl.caffenet_stack(args.batch)
-    stack = ConvStack(layers, dtype=dtype, ceil_mode=False, skip_first_dgrad=True, overlap_wgrad=args.overlap)
+    stack = ConvStack(layers, dtype=dtype, ceil_mode=False, skip_first_dgrad=not args.conv1_dgrad, overlap_wgrad=args.overlap)
     data = wl.stack_tensors(layers, seed=1, bf16=(dtype == B.BF16), pooled_out=stack.output_shape()[-2:])
     stack.set_parameters(data["W"], data["bias"])
     X = torch.from_numpy(data["X"]).cuda().to(B.torch_dtype(dtype))
@@ -123,7 +125,9 @@ def main():
 
     ms_per_step = 1e3 * dt / args.steps
     images_per_s = args.batch * args.steps / dt
-    flops_step = sum(3 * L.gemm_flops for L in layers) - layers[0].gemm_flops   # App. B rule: 1.6 TFLOP at 256
+    flops_step = sum(3 * L.gemm_flops for L in layers)   # App. B rule: 1.6 TFLOP at 256 without conv1's data gradient
+    if not args.conv1_dgrad:
+        flops_step -= layers[0].gemm_flops
     roof = None
     table = {}
     for name, k in table_kernels.items():
@@ -156,7 +160,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"caffenet_conv1-5_relu_pool_fwd+bwd+sgd_b{args.batch}_{args.dtype}",
-                   "global_batch": args.batch, "conv1_data_gradient": False},
+                   "global_batch": args.batch, "conv1_data_gradient": bool(args.conv1_dgrad)},
         "tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
         "mfma_frac_of_peak_whole_step": flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype],
         "roofline": roof, "cpu_baseline": cpu,

@@ -35,6 +35,17 @@ MEASURED_HBM_BYTES_PER_LAUNCH = {
 }
 
 
+def host_cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(sample_images: int):
     """The oracle, as it stands, on `sample_images` images of the same five layers (all three passes)."""
     import oracle
@@ -51,6 +62,7 @@ def cpu_baseline(sample_images: int):
             oracle.conv_backward_data(s, t["dY"], t["W"])
     dt = time.perf_counter() - t0
     return {"value": sample_images / dt, "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "host_cpu": host_cpu_model(), "host_logical_cpus": os.cpu_count(),
             "sample": f"{sample_images} images through conv1-conv5 forward, model gradient and data gradient "
                       f"(conv1's data gradient skipped), direct loops in fp64, {dt:.1f} s"}
 
@@ -115,11 +127,19 @@ def main():
     if dom is not None:
         B.profile_enable(True)
         B.profile_select(dom)
+    # one event between steps (on the stream the steps are launched on) for the median and the spread
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         stack.step(X, dOut, lr, mu)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    median_ms = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
+    mean_ms = sum(per_step) / len(per_step)
+    cv = (sum((t - mean_ms) ** 2 for t in per_step) / len(per_step)) ** 0.5 / mean_ms
     kernels = B.profile_summary() if dom is not None else {}
     B.profile_enable(False)
 
@@ -157,7 +177,7 @@ def main():
     out = {
         "metric": "conv fwd+bwd images/sec, CaffeNet-shaped conv stack, batch 256",
         "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "ms_per_step_median": median_ms, "ms_per_step_cv": cv, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"caffenet_conv1-5_relu_pool_fwd+bwd+sgd_b{args.batch}_{args.dtype}",
                    "global_batch": args.batch, "conv1_data_gradient": bool(args.conv1_dgrad)},

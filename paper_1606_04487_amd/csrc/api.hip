@@ -77,6 +77,7 @@ void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w)
     w->total = w->partials + align256(w->splits > 1 ? (size_t)w->splits * g.F * w->ld * sizeof(float) : 0);
     // the fused path keeps only its repacked weights here
     if (fused_supported(g, dtype, false) && fused_weight_bytes(g, false) > w->total) w->total = align256(fused_weight_bytes(g, false));
+    if (strided_supported(g, dtype) && strided_weight_bytes(g) > w->total) w->total = align256(strided_weight_bytes(g));
 }
 
 void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w)
@@ -220,6 +221,7 @@ int omni_conv_fused_supported(const omni_conv_desc *desc, int pass)
     if (pass == OMNI_PASS_FORWARD) {
         ForwardWs w;
         plan_forward(g, desc->dtype, &w);
+        if (strided_supported(g, desc->dtype) && strided_weight_bytes(g) <= w.total) return 1;
         return fused_supported(g, desc->dtype, false) && fused_weight_bytes(g, false) <= w.total ? 1 : 0;
     }
     if (pass == OMNI_PASS_BACKWARD_DATA) {
@@ -250,6 +252,8 @@ int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, 
     if ((desc->flags & OMNI_FLAG_FUSED) && fused_supported(g, desc->dtype, false) &&
         fused_weight_bytes(g, false) <= w.total)
         return launch_fused_conv(g, false, X, W, bias, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0, Y, ws, s);
+    if ((desc->flags & OMNI_FLAG_FUSED) && strided_supported(g, desc->dtype) && strided_weight_bytes(g) <= w.total)
+        return launch_strided_conv(g, X, W, bias, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0, Y, ws, s);
 
     st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
     if (st != OMNI_OK) return st;
@@ -358,10 +362,6 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
     float *partials = (float *)(ws + w.partials), *bias_partials = (float *)(ws + w.bias_partials);
 
     const bool direct = (desc->flags & OMNI_FLAG_FUSED) && !cached && wgrad_direct_supported(g, desc->dtype);
-    if (!cached && !direct) {
-        st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
-        if (st != OMNI_OK) return st;
-    }
     // with a split product the ordered reduction finishes the bias gradient too (one launch fewer)
     if (direct) {
         const bool defer = dbias != nullptr && w.splits_rows > 1;
@@ -376,6 +376,10 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
     st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, dbias ? bias_partials : nullptr, w.bias_blocks,
                            defer ? nullptr : dbias, s);
     if (st != OMNI_OK) return st;
+    if (!cached) {  // after the packing: dY is usually fresh in the last-level cache, which D-hat would flush
+        st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
+        if (st != OMNI_OK) return st;
+    }
     GemmWgradArgs a{dYhat, Dhat, w.ld, partials, w.splits, w.chunk, dW, nullptr, bias_partials, w.bias_blocks,
                     defer ? dbias : nullptr};
     return launch_gemm_wgrad(g, desc->dtype, a, s);

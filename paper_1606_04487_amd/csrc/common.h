@@ -108,7 +108,7 @@ inline size_t elem_size(int dtype) { return dtype == OMNI_BF16 ? 2 : 4; }
 // ---------------------------------------------------------------- optional event timing (profile.hip)
 enum KernelId {
     KID_LOWER = 0, KID_PACK_KHAT, KID_PACK_DYHAT, KID_BIAS_REDUCE, KID_GEMM_FWD, KID_GEMM_DGRAD, KID_GEMM_WGRAD,
-    KID_REDUCE_PARTIALS, KID_COL2IM, KID_SGD, KID_RELU, KID_POOL_FWD, KID_POOL_BWD, KID_FUSED_FWD, KID_FUSED_DGRAD,
+    KID_REDUCE_PARTIALS, KID_COL2IM, KID_SGD, KID_RELU, KID_POOL_FWD, KID_POOL_BWD, KID_FUSED_FWD, KID_FUSED_DGRAD, KID_STRIDED_FWD,
     KID_COUNT
 };
 // Brackets the launches made during its lifetime with two events on `s` when profiling is on.
@@ -171,6 +171,13 @@ bool fused_supported(const ConvGeom &g, int dtype, bool data_gradient);
 size_t fused_weight_bytes(const ConvGeom &g, bool data_gradient);
 int launch_fused_conv(const ConvGeom &g, bool data_gradient, const void *X, const void *W, const float *bias,
                       int relu, void *Y, void *wt_scratch, hipStream_t s);
+
+// strided.hip: the forward convolution of a layer with horizontal stride 4, no padding, at most 96 filters and
+// a short reduction (CaffeNet's conv1) without D-hat; bf16.  wt_scratch receives the repacked weights.
+bool strided_supported(const ConvGeom &g, int dtype);
+size_t strided_weight_bytes(const ConvGeom &g);
+int launch_strided_conv(const ConvGeom &g, const void *X, const void *W, const float *bias, int relu, void *Y,
+                        void *wt_scratch, hipStream_t s);
 
 // elementwise.hip
 int launch_sgd(int32_t n, float *const *W, float *const *V, const float *const *G, const int64_t *counts,

@@ -177,6 +177,59 @@ def test_fused_declines_and_falls_back(B):
         assert rel_err(got, oracle.conv_forward(s, X, Wt, None)) <= (TOL if dtype == 1 else 1e-4)
 
 
+# (N, C, H, W, F, kh, kw, sh): horizontal stride 4, no padding, few channels -- the conv1 kernel
+STRIDED_SHAPES = [
+    (2, 3, 35, 35, 8, 11, 11, 4),        # one tile per image, most of it beyond the image's last position
+    (3, 3, 227, 227, 96, 11, 11, 4),     # conv1 itself: six tiles per image, ragged last one, 25 reduction steps
+    (2, 2, 30, 41, 5, 3, 5, 2),          # window row of 5: the second group of 4 has one real column
+    (1, 1, 12, 9, 3, 2, 1, 1),           # 1-wide window, vertical stride 1, a single channel
+    (3, 4, 19, 23, 7, 4, 4, 3),          # window row of exactly one group
+    (5, 3, 99, 99, 64, 7, 7, 4),         # 576 positions: a full tile and a short one
+    (2, 3, 67, 131, 96, 11, 11, 4),      # non-square image
+]
+
+
+@pytest.mark.parametrize("cfg", STRIDED_SHAPES)
+def test_strided_forward(B, cfg):
+    N, C, H, W, F, kh, kw, sh = cfg
+    s = oracle.shape(N, C, H, W, F, kh, kw, (sh, 4), (0, 0))
+    rng = np.random.default_rng(17)
+    X = wl.to_bf16_values(rng.standard_normal((N, C, H, W)))
+    Wt = wl.to_bf16_values(0.05 * rng.standard_normal((F, C, kh, kw)))
+    b = (0.05 * rng.standard_normal(F)).astype(np.float32)
+    d = B.conv_desc(N, C, H, W, F, kh, kw, (sh, 4), (0, 0), BF16, B.FLAG_FUSED)
+    assert B.conv_fused_supported(d, B.PASS_FORWARD)
+    Xg, Wg, bg = gpu(X), gpu(Wt), gpu(b, False)
+    ref = oracle.conv_forward(s, X, Wt, b)
+    got = host(B.conv_forward(d, Xg, Wg, bg))
+    assert rel_err(got, ref) <= TOL
+    explicit = host(B.conv_forward(d.with_flags(0), Xg, Wg, bg))
+    assert rel_err(got, explicit) <= 1e-2          # one bf16 rounding step apart at most
+    assert np.mean(got == explicit) > 0.9
+    got_relu = host(B.conv_forward(d.with_flags(B.FLAG_FUSED | B.FLAG_RELU), Xg, Wg, None))
+    assert rel_err(got_relu, np.maximum(oracle.conv_forward(s, X, Wt, None), 0)) <= TOL and got_relu.min() >= 0
+    assert np.array_equal(got, host(B.conv_forward(d, Xg, Wg, bg)))   # deterministic
+    # pixels that only padded window columns reach never enter a sum: poison one of them
+    if kw % 4 != 0 and W > kw:
+        Xp = X.copy()
+        Xp[:, :, :, kw] = np.inf                   # column kw: the first window's first padded column
+        gotp = host(B.conv_forward(d, gpu(Xp), Wg, bg))
+        assert np.array_equal(gotp[:, :, :, 0], got[:, :, :, 0])
+
+
+def test_strided_declines(B):
+    # padding, more than 96 filters, a reduction beyond 400: the explicit path runs
+    for N, C, H, W, F, k, p in [(2, 3, 35, 35, 8, 11, 2), (2, 3, 35, 35, 97, 11, 0), (2, 40, 15, 15, 8, 3, 0)]:
+        d = B.conv_desc(N, C, H, W, F, k, k, (4, 4), (p, p), BF16, B.FLAG_FUSED)
+        assert not B.conv_fused_supported(d, B.PASS_FORWARD)
+        s = oracle.shape(N, C, H, W, F, k, k, (4, 4), (p, p))
+        rng = np.random.default_rng(4)
+        X = wl.to_bf16_values(rng.standard_normal((N, C, H, W)))
+        Wt = wl.to_bf16_values(0.05 * rng.standard_normal((F, C, k, k)))
+        got = host(B.conv_forward(d, gpu(X), gpu(Wt), None))
+        assert rel_err(got, oracle.conv_forward(s, X, Wt, None)) <= TOL
+
+
 def test_fused_stack_matches_explicit_stack(B):
     """The chained CIFAR-shaped stack in bf16: fused and explicit runs agree on outputs and gradients."""
     from paper_1606_04487_amd.stack import ConvStack

@@ -137,13 +137,29 @@ void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w)
         plan_splits(g, dtype, w->ld_rows, &w->splits_rows, &w->chunk_rows);
         w->bias_blocks_rows = pack_dyhat_rows_blocks(g);
     }
+    // the phase-split model gradient of a stride-4 layer: one result tile, so a workgroup per split
+    const bool phase = !direct && wgrad_phase_supported(g, dtype);
+    int64_t k_max = g.K;
+    size_t x4_bytes = 0;
+    if (phase) {
+        w->ld_rows = dyhat_rows_ld(g);
+        int64_t bk = gemm_red_tile(dtype), steps = (w->ld_rows + bk - 1) / bk;
+        int64_t splits = steps / 4 < 256 ? steps / 4 : 256;
+        if (splits < 1) splits = 1;
+        w->chunk_rows = round_up((w->ld_rows + splits - 1) / splits, bk);
+        w->splits_rows = (int)((w->ld_rows + w->chunk_rows - 1) / w->chunk_rows);
+        w->bias_blocks_rows = pack_dyhat_rows_blocks(g);
+        k_max = wgrad_phase_kp(g) > g.K ? wgrad_phase_kp(g) : g.K;
+        x4_bytes = (size_t)g.N * g.C * 4 * g.H * wgrad_phase_wp(g) * e;
+    }
     int64_t ld_max = w->ld > w->ld_rows ? w->ld : w->ld_rows;
     int splits_max = w->splits > w->splits_rows ? w->splits : w->splits_rows;
     int bb_max = w->bias_blocks > w->bias_blocks_rows ? w->bias_blocks : w->bias_blocks_rows;
     w->dhat = 0;
-    w->dyhat = align256((size_t)g.K * w->ld * e);
+    size_t dhat_bytes = (size_t)g.K * w->ld * e;
+    w->dyhat = align256(dhat_bytes > x4_bytes ? dhat_bytes : x4_bytes);
     w->partials = w->dyhat + align256((size_t)g.F * ld_max * e);
-    w->bias_partials = w->partials + align256(splits_max > 1 ? (size_t)splits_max * g.F * g.K * sizeof(float) : 0);
+    w->bias_partials = w->partials + align256(splits_max > 1 || phase ? (size_t)splits_max * g.F * k_max * sizeof(float) : 0);
     w->total = w->bias_partials + align256((size_t)g.F * bb_max * sizeof(float));
 }
 
@@ -229,7 +245,8 @@ int omni_conv_fused_supported(const omni_conv_desc *desc, int pass)
         plan_backward_data(g, desc->dtype, &w);
         return fused_supported(g, desc->dtype, true) && fused_weight_bytes(g, true) <= w.total ? 1 : 0;
     }
-    if (pass == OMNI_PASS_BACKWARD_WEIGHTS) return wgrad_direct_supported(g, desc->dtype) ? 1 : 0;
+    if (pass == OMNI_PASS_BACKWARD_WEIGHTS)
+        return wgrad_direct_supported(g, desc->dtype) || wgrad_phase_supported(g, desc->dtype) ? 1 : 0;
     return OMNI_INVALID_ARGUMENT;
 }
 
@@ -371,6 +388,15 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
         GemmWgradArgs a{dYhat, nullptr, w.ld_rows, partials, w.splits_rows, w.chunk_rows, dW, X,
                         bias_partials, w.bias_blocks_rows, defer ? dbias : nullptr};
         return launch_gemm_wgrad(g, desc->dtype, a, s);
+    }
+    if ((desc->flags & OMNI_FLAG_FUSED) && !cached && wgrad_phase_supported(g, desc->dtype)) {
+        // stride-4 layer: dY-hat row-padded, X split into its four phase images, the product reads those
+        st = launch_pack_dyhat_rows(g, dY, dYhat, w.ld_rows, dbias ? bias_partials : nullptr, w.bias_blocks_rows, nullptr, s);
+        if (st != OMNI_OK) return st;
+        st = launch_phase_split(g, wgrad_phase_wp(g), X, Dhat, s);
+        if (st != OMNI_OK) return st;
+        return launch_gemm_wgrad_phase(g, Dhat, dYhat, w.ld_rows, partials, w.splits_rows, w.chunk_rows, dW, bias_partials,
+                                       w.bias_blocks_rows, dbias, s);
     }
     const bool defer = dbias != nullptr && w.splits > 1;
     st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, dbias ? bias_partials : nullptr, w.bias_blocks,

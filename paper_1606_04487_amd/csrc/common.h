@@ -90,7 +90,7 @@ struct ForwardWs { size_t dhat, khat, partials, total; int64_t ld, Fp, Kp; int s
 struct BwdDataWs { size_t ddhat, dyhat, khat_t, partials, total; int64_t ld, Kp, Fp; int splits; int64_t chunk; };
 // *_rows: the same plan for the row-padded dY-hat of the direct model gradient (reduction extent ld_rows)
 struct BwdWeightsWs {
-    size_t dhat, dyhat, partials, bias_partials, total;
+    size_t dhat, dyhat, partials, bias_partials, total;  // dhat also holds X4 of the phase-split model gradient
     int64_t ld; int splits; int64_t chunk; int bias_blocks;
     int64_t ld_rows; int splits_rows; int64_t chunk_rows; int bias_blocks_rows;
 };
@@ -178,6 +178,16 @@ bool strided_supported(const ConvGeom &g, int dtype);
 size_t strided_weight_bytes(const ConvGeom &g);
 int launch_strided_conv(const ConvGeom &g, const void *X, const void *W, const float *bias, int relu, void *Y,
                         void *wt_scratch, hipStream_t s);
+
+// The model gradient of such a layer without D-hat: phase_split writes X4 [N][4C][H][WP] (strided.hip), the
+// product reads its lowered operand from X4 (gemm.hip).  dYhat is the row-padded dY-hat.
+bool wgrad_phase_supported(const ConvGeom &g, int dtype);
+int wgrad_phase_kp(const ConvGeom &g);  // columns of the phase-ordered gradient [F][K']
+int wgrad_phase_wp(const ConvGeom &g);  // row pitch of X4 in elements
+int launch_phase_split(const ConvGeom &g, int WP, const void *X, void *X4, hipStream_t s);
+int launch_gemm_wgrad_phase(const ConvGeom &g, const void *X4, const void *dYhat, int64_t ld, float *partials, int splits,
+                            int64_t chunk, float *dW, const float *bias_partials, int bias_blocks, float *dbias,
+                            hipStream_t s);
 
 // elementwise.hip
 int launch_sgd(int32_t n, float *const *W, float *const *V, const float *const *G, const int64_t *counts,

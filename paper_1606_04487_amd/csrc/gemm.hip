@@ -49,8 +49,9 @@ int gemm_red_tile(int dtype) { return dtype == OMNI_BF16 ? NPACK * 8 : NPACK * 4
 // r < rows and k < red; ld and red are multiples of the pack size and the base is 16-byte aligned.
 template <typename T, int TILE_ROWS, int NT> struct RedContigLoader {
     static constexpr int KP = Pack<T>::KP;
-    static constexpr int PER_THREAD = TILE_ROWS * NPACK / NT;
-    static_assert(TILE_ROWS * NPACK % NT == 0, "tile must divide over the threads");
+    static constexpr int TASKS = TILE_ROWS * NPACK;
+    static constexpr int PER_THREAD = (TASKS + NT - 1) / NT;
+    static constexpr bool RAGGED = TASKS % NT != 0;  // the last round of tasks covers only part of the threads
     uint4 regs[PER_THREAD];
 
     __device__ __forceinline__ void issue(const T *base, int64_t ld, int rows, int64_t red, int row0,
@@ -62,7 +63,7 @@ template <typename T, int TILE_ROWS, int NT> struct RedContigLoader {
             int g = t % NPACK, r = t / NPACK;
             int64_t k = k0 + (int64_t)g * KP;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (row0 + r < rows && k < red)
+            if ((!RAGGED || t < TASKS) && row0 + r < rows && k < red)
                 v = *reinterpret_cast<const uint4 *>(base + (int64_t)(row0 + r) * ld + k);
             regs[q] = v;
         }
@@ -73,7 +74,7 @@ template <typename T, int TILE_ROWS, int NT> struct RedContigLoader {
         for (int q = 0; q < PER_THREAD; ++q) {
             int t = tid + q * NT;
             int g = t % NPACK, r = t / NPACK;
-            lds[g * (TILE_ROWS + 1) + r] = regs[q];
+            if (!RAGGED || t < TASKS) lds[g * (TILE_ROWS + 1) + r] = regs[q];
         }
     }
 };
@@ -180,6 +181,7 @@ struct DirectSrc {
     FastDiv div_p8, div_Ho, div_khkw, div_kw;
     int32_t HoWo, KK;  // plane mode: output positions per image, window taps
     FastDiv div_W;
+    int32_t sh;        // row mode: vertical stride (input rows per output row)
 };
 
 // Plane mode.  When the output is as wide as the input (stride 1, 2*pw = kw - 1), output position q of an
@@ -294,10 +296,11 @@ template <int TILE_ROWS, int NT, int MODE> struct DirectLoader {
             const bool live = (int)row < d.rows;
             d.div_Ho.divmod(live ? row : 0u, n, oy);
             const int ox0 = 8 * (int)i;
-            const int base = (int)n * d.C * d.HW + (int)oy * d.W + ox0;
+            const int iy = (int)oy * d.sh;
+            const int base = (int)n * d.C * d.HW + iy * d.W + ox0;
 #pragma unroll
             for (int p = 0; p < PER_THREAD; ++p) {
-                bool ok = live && (unsigned)((int)oy + dky[p]) < (unsigned)d.H;
+                bool ok = live && (unsigned)(iy + dky[p]) < (unsigned)d.H;
                 uint32_t m = 1u;
                 if constexpr (!FIXED) {
                     const int ix = ox0 + dkx[p];
@@ -821,10 +824,16 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const T *__restrict__ A,
 // The launch may carry extra workgroups (blockIdx >= main_blocks) that finish the bias gradient: one
 // wavefront per filter adds that filter's per-block sums left by the dY packing kernel (strided per lane in
 // block order, then a fixed tree) -- the same arithmetic as bias_reduce_kernel, without a launch of its own.
+// PHASED: the partial results are [F][K'] in the phase-split order of a stride-4 layer (see
+// launch_gemm_wgrad_phase), K' index ((c * 4 + ph) * kh + ky) * kwq + kq standing for window column
+// kx = 4 kq + ph; entries with kx >= kw are padding and are dropped, the others go to [F][C][kh][kw].
+struct PhaseMap { int32_t C, kh, kw; FastDiv div_Kp, div_khkwq, div_kwq; };
+
+template <bool PHASED>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partials, int splits,
                                                               int64_t count, float *__restrict__ out, unsigned main_blocks,
                                                               const float *__restrict__ bias_partials, int bias_blocks,
-                                                              int F, float *__restrict__ dbias)
+                                                              int F, float *__restrict__ dbias, PhaseMap pm)
 {
     __shared__ float part[4][64];
     const int c = threadIdx.x % 64, l = threadIdx.x / 64;
@@ -853,7 +862,19 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     }
     part[l][c] = acc;
     __syncthreads();
-    if (l == 0 && i < count) out[i] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
+    if (l == 0 && i < count) {
+        const float sum = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
+        if constexpr (PHASED) {
+            uint32_t f, kp, cp, rem, ky, kq;
+            pm.div_Kp.divmod((uint32_t)i, f, kp);
+            pm.div_khkwq.divmod(kp, cp, rem);
+            pm.div_kwq.divmod(rem, ky, kq);
+            const int kx = 4 * (int)kq + (int)(cp % 4u);
+            if (kx < pm.kw) out[(((int64_t)f * pm.C + cp / 4u) * pm.kh + ky) * pm.kw + kx] = sum;
+        } else {
+            out[i] = sum;
+        }
+    }
 }
 
 // Ordered sum of the split partial results [splits][rows][cols] of a forward or data-gradient product,
@@ -1135,7 +1156,7 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
                 DirectSrc d{(const bf16_t *)a.X_direct, g.C, g.H, g.W, g.H * g.W, g.K, g.ph, g.pw,
                             planes ? g.N : g.N * g.Ho, (int32_t)((int64_t)g.N * g.C * g.H * g.W),
                             FastDiv((uint32_t)((unit + 7) / 8)), FastDiv((uint32_t)g.Ho), g.div_khkw, g.div_kw,
-                            g.Ho * g.Wo, planes ? g.kh * g.kw : 0, FastDiv((uint32_t)g.W)};
+                            g.Ho * g.Wo, planes ? g.kh * g.kw : 0, FastDiv((uint32_t)g.W), 1};
                 switch (pick_wgrad_tile(g.F, g.K)) {
                 case 9: launch_direct<Tile9>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s); break;
                 case 10: launch_direct<Tile10>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s); break;
@@ -1153,10 +1174,65 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
         ProfScope prof(KID_REDUCE_PARTIALS, s, 0.0, 4.0 * count * (a.splits + 1));
         const unsigned main_blocks = (unsigned)((count + 63) / 64);
         const unsigned bias_wgs = a.dbias != nullptr ? (unsigned)((g.F + 3) / 4) : 0u;
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3(main_blocks + bias_wgs), dim3(256), 0, s, a.partials, a.splits, count,
-                           a.dW, main_blocks, a.bias_partials, a.bias_blocks, g.F, a.dbias);
+        hipLaunchKernelGGL(reduce_partials_kernel<false>, dim3(main_blocks + bias_wgs), dim3(256), 0, s, a.partials, a.splits,
+                           count, a.dW, main_blocks, a.bias_partials, a.bias_blocks, g.F, a.dbias, PhaseMap{});
         OMNI_LAUNCH_CHECK();
     }
+    return OMNI_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Model gradient of a layer with horizontal stride 4 and no padding (CaffeNet's conv1) without D-hat.
+// The input is first split by x mod 4 into four phase images, X4 [N][C * 4][H][WP] with
+// X4(n, 4c + ph, y, xq) = X(n, c, y, 4 xq + ph) (zero where that column does not exist).  Window column
+// kx = 4 kq + ph of output column ox then meets phase image ph at xq = ox + kq: the layer is a convolution
+// of X4 with horizontal stride 1, 4C channels and a window of kh x ceil(kw / 4), which the row mode of
+// DirectLoader reads as it stands (8 consecutive output columns = 8 consecutive xq).  The result is
+// [F][K'] in that order, K' = 4C * kh * ceil(kw / 4), window columns beyond kw being padding; the ordered
+// reduction of the split partial results puts it back into [F][C][kh][kw].
+// One 96 x 512 result tile (8 wavefronts, 96 x 64 each) holds the whole gradient, so the launch is one
+// workgroup per split of the reduction.
+// ------------------------------------------------------------------------------------------------
+typedef Tile<96, 512, 1, 8, 1> TilePhase;
+
+static int phase_kwq(const ConvGeom &g) { return (g.kw + 3) / 4; }
+int wgrad_phase_kp(const ConvGeom &g) { return 4 * g.C * g.kh * phase_kwq(g); }
+int wgrad_phase_wp(const ConvGeom &g) { return (int)round_up((g.W + 3) / 4, 8); }
+
+bool wgrad_phase_supported(const ConvGeom &g, int dtype)
+{
+    if (dtype != OMNI_BF16 || g.sw != 4 || g.ph != 0 || g.pw != 0 || g.F > TilePhase::BM) return false;
+    if (wgrad_phase_kp(g) > TilePhase::BN) return false;
+    int64_t total4 = (int64_t)g.N * g.C * 4 * g.H * wgrad_phase_wp(g);
+    return total4 < 0x7fffffffll - 16 && total4 >= 8 && (int64_t)g.N * g.C * g.H * g.W < 0x7fffffffll - 64;
+}
+
+int launch_gemm_wgrad_phase(const ConvGeom &g, const void *X4, const void *dYhat, int64_t ld, float *partials, int splits,
+                            int64_t chunk, float *dW, const float *bias_partials, int bias_blocks, float *dbias,
+                            hipStream_t s)
+{
+    const int kwq = phase_kwq(g), Kp = wgrad_phase_kp(g), WP = wgrad_phase_wp(g);
+    PartialEpilogue epi{partials, g.F, Kp};
+    {
+        ProfScope prof(KID_GEMM_WGRAD, s, 2.0 * g.M * (double)g.K * g.F,
+                       ((double)g.N * g.C * 4 * g.H * WP + (double)g.F * g.M) * 2.0 + 4.0 * g.F * Kp * splits);
+        DirectSrc d{(const bf16_t *)X4, 4 * g.C, g.H, WP, g.H * WP, Kp, 0, 0, g.N * g.Ho,
+                    (int32_t)((int64_t)g.N * g.C * 4 * g.H * WP), FastDiv((uint32_t)((g.Wo + 7) / 8)), FastDiv((uint32_t)g.Ho),
+                    FastDiv((uint32_t)(g.kh * kwq)), FastDiv((uint32_t)kwq), g.Ho * g.Wo, 0, FastDiv((uint32_t)WP), g.sh};
+        GemmShape sh = make_shape(g.F, Kp, ld, chunk, TilePhase::BM, TilePhase::BN, splits);
+        sh.fast_store = epi.fits32() ? 1 : 0;
+        hipLaunchKernelGGL((gemm_kernel<bf16_t, TilePhase, false, PartialEpilogue, DIRECT_ROWS>), dim3(sh.per_xcd * 8),
+                           dim3(TilePhase::NT), 0, s, (const bf16_t *)dYhat, ld, (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
+    }
+    OMNI_LAUNCH_CHECK();
+    const int64_t count = (int64_t)g.F * Kp;
+    ProfScope prof(KID_REDUCE_PARTIALS, s, 0.0, 4.0 * count * (splits + 1));
+    const unsigned main_blocks = (unsigned)((count + 63) / 64);
+    const unsigned bias_wgs = dbias != nullptr ? (unsigned)((g.F + 3) / 4) : 0u;
+    PhaseMap pm{g.C, g.kh, g.kw, FastDiv((uint32_t)Kp), FastDiv((uint32_t)(g.kh * kwq)), FastDiv((uint32_t)kwq)};
+    hipLaunchKernelGGL(reduce_partials_kernel<true>, dim3(main_blocks + bias_wgs), dim3(256), 0, s, partials, splits, count,
+                       dW, main_blocks, bias_partials, bias_blocks, g.F, dbias, pm);
+    OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }
 

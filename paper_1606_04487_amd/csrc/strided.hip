@@ -321,7 +321,56 @@ static bool make_strided_geom(const ConvGeom &c, Geom *g)
     return true;
 }
 
+// X [planes][H][W] -> X4 [planes][4][H][WP]: X4(p, ph, y, xq) = X(p, y, 4 xq + ph), zero where 4 xq + ph >= W
+// (the phase images of the stride-4 model gradient).  One thread per 32 consecutive input columns of a row:
+// four 16-byte reads (element by element in a row's ragged last group), 16 half-word shuffles, one 16-byte
+// piece of every phase image.
+__global__ __launch_bounds__(256) void phase_split_kernel(const bf16_t *__restrict__ X, uint4 *__restrict__ X4, int planes,
+                                                          int H, int W, FastDiv div_G, FastDiv div_H)
+{
+    const int G = (int)div_G.d;  // groups per row = WP / 8
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)planes * H * G) return;
+    uint32_t row, gq, pl, y;
+    div_G.divmod((uint32_t)idx, row, gq);
+    div_H.divmod(row, pl, y);
+    const bf16_t *src = X + ((int64_t)row * W + 32 * (int)gq);
+    uint32_t w[16];
+    if (32 * (int)gq + 32 <= W) {
+        __builtin_memcpy(w, src, 64);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int x = 32 * (int)gq + 2 * k;
+            const uint32_t lo = x < W ? (uint32_t)src[2 * k] : 0u, hi = x + 1 < W ? (uint32_t)src[2 * k + 1] : 0u;
+            w[k] = lo | (hi << 16);
+        }
+    }
+#pragma unroll
+    for (int ph = 0; ph < 4; ++ph) {
+        uint32_t o[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const uint32_t a = w[4 * t + ph / 2], b = w[4 * t + 2 + ph / 2];  // elements 8t + ph and 8t + 4 + ph
+            o[t] = (ph % 2 == 0) ? ((a & 0xffffu) | (b << 16)) : ((a >> 16) | (b & 0xffff0000u));
+        }
+        X4[(((int64_t)pl * 4 + ph) * H + y) * G + gq] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
 }  // namespace strided
+
+int launch_phase_split(const ConvGeom &c, int WP, const void *X, void *X4, hipStream_t s)
+{
+    const int planes = c.N * c.C, G = WP / 8;
+    const int64_t total = (int64_t)planes * c.H * G;
+    if (total > 0x7fffffffll - 4096) return OMNI_UNSUPPORTED;
+    ProfScope prof(KID_LOWER, s, 0.0, 2.0 * ((double)planes * c.H * c.W + (double)planes * 4 * c.H * WP));
+    hipLaunchKernelGGL(strided::phase_split_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       (const bf16_t *)X, (uint4 *)X4, planes, c.H, c.W, FastDiv((uint32_t)G), FastDiv((uint32_t)c.H));
+    OMNI_LAUNCH_CHECK();
+    return OMNI_OK;
+}
 
 bool strided_supported(const ConvGeom &c, int dtype)
 {

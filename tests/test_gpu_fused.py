@@ -217,6 +217,29 @@ def test_strided_forward(B, cfg):
         assert np.array_equal(gotp[:, :, :, 0], got[:, :, :, 0])
 
 
+@pytest.mark.parametrize("cfg", STRIDED_SHAPES + [(2, 3, 40, 239, 96, 11, 11, 4),   # Wo = 58: the last pack of a row runs past X4's row
+                                                  (1, 16, 12, 30, 20, 2, 5, 3)])    # 16 channels, K' = 256
+def test_strided_backward_weights(B, cfg):
+    """Model gradient of a stride-4 layer from the four phase images of X (no D-hat): within the fp32-output
+    bar of the oracle, close to the explicit path, deterministic; window columns beyond kw are dropped."""
+    N, C, H, W, F, kh, kw, sh = cfg
+    s = oracle.shape(N, C, H, W, F, kh, kw, (sh, 4), (0, 0))
+    ho, wo = oracle.out_dims(s)
+    rng = np.random.default_rng(19)
+    X = wl.to_bf16_values(rng.standard_normal((N, C, H, W)))
+    dY = wl.to_bf16_values(rng.standard_normal((N, F, ho, wo)))
+    d = B.conv_desc(N, C, H, W, F, kh, kw, (sh, 4), (0, 0), BF16, B.FLAG_FUSED)
+    assert B.conv_fused_supported(d, B.PASS_BACKWARD_WEIGHTS)
+    Xg, dYg = gpu(X), gpu(dY)
+    dW, db = B.conv_backward_weights(d, Xg, dYg)
+    assert rel_err(host(dW), oracle.conv_backward_weights(s, X, dY)) <= 1e-4
+    assert rel_err(host(db), oracle.bias_grad(s, dY)) <= 1e-4
+    dW2, _ = B.conv_backward_weights(d.with_flags(0), Xg, dYg)
+    assert rel_err(host(dW), host(dW2)) <= 2e-5
+    again, db2 = B.conv_backward_weights(d, Xg, dYg)
+    assert torch.equal(dW, again) and torch.equal(db, db2)   # deterministic
+
+
 def test_strided_declines(B):
     # padding, more than 96 filters, a reduction beyond 400: the explicit path runs
     for N, C, H, W, F, k, p in [(2, 3, 35, 35, 8, 11, 2), (2, 3, 35, 35, 97, 11, 0), (2, 40, 15, 15, 8, 3, 0)]:

@@ -149,7 +149,7 @@ void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w)
         w->chunk_rows = round_up((w->ld_rows + splits - 1) / splits, bk);
         w->splits_rows = (int)((w->ld_rows + w->chunk_rows - 1) / w->chunk_rows);
         w->bias_blocks_rows = pack_dyhat_rows_blocks(g);
-        k_max = wgrad_phase_kp(g) > g.K ? wgrad_phase_kp(g) : g.K;
+        k_max = wgrad_phase_kp(g) + 1 > g.K ? wgrad_phase_kp(g) + 1 : g.K;  // + 1: the bias gradient's column
         x4_bytes = (size_t)g.N * g.C * 4 * g.H * wgrad_phase_wp(g) * e;
     }
     int64_t ld_max = w->ld > w->ld_rows ? w->ld : w->ld_rows;
@@ -390,13 +390,10 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
         return launch_gemm_wgrad(g, desc->dtype, a, s);
     }
     if ((desc->flags & OMNI_FLAG_FUSED) && !cached && wgrad_phase_supported(g, desc->dtype)) {
-        // stride-4 layer: dY-hat row-padded, X split into its four phase images, the product reads those
-        st = launch_pack_dyhat_rows(g, dY, dYhat, w.ld_rows, dbias ? bias_partials : nullptr, w.bias_blocks_rows, nullptr, s);
-        if (st != OMNI_OK) return st;
+        // stride-4 layer: X split into its four phase images; the product reads those and dY as they are
         st = launch_phase_split(g, wgrad_phase_wp(g), X, Dhat, s);
         if (st != OMNI_OK) return st;
-        return launch_gemm_wgrad_phase(g, Dhat, dYhat, w.ld_rows, partials, w.splits_rows, w.chunk_rows, dW, bias_partials,
-                                       w.bias_blocks_rows, dbias, s);
+        return launch_gemm_wgrad_phase(g, Dhat, dY, w.ld_rows, partials, w.splits_rows, w.chunk_rows, dW, dbias, s);
     }
     const bool defer = dbias != nullptr && w.splits > 1;
     st = launch_pack_dyhat(g, desc->dtype, dY, dYhat, w.ld, dbias ? bias_partials : nullptr, w.bias_blocks,

@@ -180,14 +180,14 @@ int launch_strided_conv(const ConvGeom &g, const void *X, const void *W, const f
                         void *wt_scratch, hipStream_t s);
 
 // The model gradient of such a layer without D-hat: phase_split writes X4 [N][4C][H][WP] (strided.hip), the
-// product reads its lowered operand from X4 (gemm.hip).  dYhat is the row-padded dY-hat.
+// product reads its lowered operand from X4 and its other operand from dY itself (gemm.hip); the bias
+// gradient comes out of the same product.
 bool wgrad_phase_supported(const ConvGeom &g, int dtype);
 int wgrad_phase_kp(const ConvGeom &g);  // columns of the phase-ordered gradient [F][K']
 int wgrad_phase_wp(const ConvGeom &g);  // row pitch of X4 in elements
 int launch_phase_split(const ConvGeom &g, int WP, const void *X, void *X4, hipStream_t s);
-int launch_gemm_wgrad_phase(const ConvGeom &g, const void *X4, const void *dYhat, int64_t ld, float *partials, int splits,
-                            int64_t chunk, float *dW, const float *bias_partials, int bias_blocks, float *dbias,
-                            hipStream_t s);
+int launch_gemm_wgrad_phase(const ConvGeom &g, const void *X4, const void *dY, int64_t ld, float *partials, int splits,
+                            int64_t chunk, float *dW, float *dbias, hipStream_t s);
 
 // elementwise.hip
 int launch_sgd(int32_t n, float *const *W, float *const *V, const float *const *G, const int64_t *counts,

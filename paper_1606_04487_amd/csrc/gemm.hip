@@ -182,6 +182,7 @@ struct DirectSrc {
     int32_t HoWo, KK;  // plane mode: output positions per image, window taps
     FastDiv div_W;
     int32_t sh;        // row mode: vertical stride (input rows per output row)
+    int32_t F, Wo;     // DIRECT_ROWS_ONES: dY is [N][F][Ho][Wo], read by DyLoader
 };
 
 // Plane mode.  When the output is as wide as the input (stride 1, 2*pw = kw - 1), output position q of an
@@ -191,7 +192,10 @@ struct DirectSrc {
 // are real pixels depends on (pack within the plane, tap) alone: a table in LDS, one byte per element,
 // built when the workgroup starts.  Row (pack j, tap KK) of the table is zero: result columns beyond K.
 constexpr int DIRECT_TAB = 2560;  // table entries (8 bytes each) a workgroup can hold beside its tiles
-enum { DIRECT_ROWS = 1, DIRECT_ROWS_FIXED = 2, DIRECT_PLANES = 3 };
+enum { DIRECT_ROWS = 1, DIRECT_ROWS_FIXED = 2, DIRECT_PLANES = 3, DIRECT_ROWS_ONES = 4 };
+// DIRECT_ROWS_ONES: row mode in which (a) row K of the operand -- the first result column beyond the gradient
+// -- is all ones, so that result column K is the sum of dY over every position: the bias gradient, from the
+// same MFMAs; and (b) the row operand is read from dY as it lies in memory (DyLoader), not from a packed copy.
 
 __device__ __forceinline__ void build_plane_table(const DirectSrc &d, uint2 *tab, int tid, int nt)
 {
@@ -219,10 +223,11 @@ __device__ __forceinline__ void build_plane_table(const DirectSrc &d, uint2 *tab
 // fall beside the image for a given window column -- is the same in every step: those masks are built once.
 template <int TILE_ROWS, int NT, int MODE> struct DirectLoader {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    static constexpr bool FIXED = MODE == DIRECT_ROWS_FIXED, PLANES = MODE == DIRECT_PLANES;
+    static constexpr bool FIXED = MODE == DIRECT_ROWS_FIXED, PLANES = MODE == DIRECT_PLANES, ONES = MODE == DIRECT_ROWS_ONES;
     static constexpr int PER_THREAD = TILE_ROWS * NPACK / NT;
     static_assert(TILE_ROWS * NPACK % NT == 0 && NT % NPACK == 0, "tile must divide over the threads");
     u32x4 v[PER_THREAD];
+    uint32_t ones[ONES ? PER_THREAD : 1];   // 0x3f803f80 (two bf16 ones) for the row of ones, else 0
     // rows: bits 0..7: which elements are real pixels (FIXED: bit 0: the input row exists).
     // bits 8..11: signed element shift (non-zero only where the 16 bytes had to be moved to stay inside
     // the tensor: first and last row of X)
@@ -254,6 +259,7 @@ template <int TILE_ROWS, int NT, int MODE> struct DirectLoader {
             if constexpr (PLANES) {
                 tap[q] = k < d.K ? (int)rem : d.KK;
             } else {
+                if constexpr (ONES) ones[q] = k == d.K ? 0x3f803f80u : 0u;
                 dky[q] = k < d.K ? (int)ky - d.ph : -(1 << 24);  // rows beyond K: no input row is ever valid
                 if constexpr (FIXED) {
                     const int ix = ox0 + dx;
@@ -351,9 +357,68 @@ template <int TILE_ROWS, int NT, int MODE> struct DirectLoader {
                 } else {
 #pragma unroll
                     for (int w = 0; w < 4; ++w) o[w] = a[w] & spread(masks[p], 2 * w);
+                    if constexpr (ONES) {
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) o[w] |= ones[p];  // the masks of a row beyond K are zero
+                    }
                 }
             }
             reinterpret_cast<u32x4 *>(lds)[g * (TILE_ROWS + 1) + r] = o;
+        }
+    }
+};
+
+// The row operand of the model gradient read from dY [N][F][Ho][Wo] itself: row f, padded column
+// ((n * Ho + oy) * P8 + i) * 8 + e is dY(n, f, oy, 8 i + e), zero for 8 i + e >= Wo and for columns beyond the
+// batch.  The 16 bytes of a row's ragged last pack are read so that they END at the row's end (always inside
+// the tensor, Wo >= 8) and are shifted down, which also zeroes the padding.
+template <int TILE_ROWS, int NT> struct DyLoader {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    static constexpr int TASKS = TILE_ROWS * NPACK;
+    static constexpr int PER_THREAD = (TASKS + NT - 1) / NT;
+    static constexpr bool RAGGED = TASKS % NT != 0;
+    u32x4 regs[PER_THREAD];
+    uint32_t okbits;
+    int back;  // elements the loads were moved back by
+
+    // m0: first padded column of this thread's packs (the same for all of them)
+    __device__ __forceinline__ void issue(const bf16_t *dY, const DirectSrc &d, int row0, int m0, int tid)
+    {
+        uint32_t row, i, n, oy;
+        d.div_p8.divmod((uint32_t)m0 >> 3, row, i);
+        const bool live = (int)row < d.rows;
+        d.div_Ho.divmod(live ? row : 0u, n, oy);
+        const int valid = d.Wo - 8 * (int)i < 8 ? d.Wo - 8 * (int)i : 8;
+        back = 8 - valid;
+        const int base = (int)n * d.F * d.HoWo + (int)oy * d.Wo + 8 * (int)i - back;
+        okbits = 0u;
+#pragma unroll
+        for (int q = 0; q < PER_THREAD; ++q) {
+            const int t = tid + q * NT;
+            const int f = row0 + t / NPACK;
+            const bool ok = live && f < d.F && (!RAGGED || t < TASKS);
+            const int e = ok ? base + f * d.HoWo : 0;
+            __builtin_memcpy(&regs[q], reinterpret_cast<const char *>(dY) + 2u * (uint32_t)e, 16);
+            okbits |= (ok ? 1u : 0u) << q;
+        }
+    }
+    __device__ __forceinline__ void commit(uint4 *lds, int tid) const
+    {
+#pragma unroll
+        for (int q = 0; q < PER_THREAD; ++q) {
+            const int t = tid + q * NT;
+            const int g = t % NPACK, r = t / NPACK;
+            u32x4 v = regs[q];
+            if (back) {
+                unsigned __int128 x = ((unsigned __int128)(((uint64_t)v[3] << 32) | v[2]) << 64) | (((uint64_t)v[1] << 32) | v[0]);
+                x >>= 16 * back;
+                const uint64_t lo = (uint64_t)x, hi = (uint64_t)(x >> 64);
+                v = u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+            }
+            const uint32_t keep = 0u - ((okbits >> q) & 1u);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) v[w] &= keep;
+            if (!RAGGED || t < TASKS) reinterpret_cast<u32x4 *>(lds)[g * (TILE_ROWS + 1) + r] = v;
         }
     }
 };
@@ -425,7 +490,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
 
-    RedContigLoader<T, BM, NT> la[PF];
+    constexpr bool DY_DIRECT = DIRECT == DIRECT_ROWS_ONES;  // the row operand comes from dY as it is
+    typename std::conditional<DY_DIRECT, DyLoader<BM, NT>, RedContigLoader<T, BM, NT>>::type la[PF];
     struct Unused {};  // only the column loader in use is instantiated: not every tile suits every loader
     typename std::conditional<!COL_OUTER && !DIRECT, RedContigLoader<T, BN, NT>, Unused>::type lb_red[PF];
     typename std::conditional<COL_OUTER, OuterContigLoader<T, BN, NT>, Unused>::type lb_out[PF];
@@ -441,7 +507,10 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
     }
 
     auto issue = [&](int set, int64_t k0) {
-        la[set].issue(A, lda, sh.rows, sh.red, row0, k0, tid);
+        if constexpr (DY_DIRECT)
+            la[set].issue(A, direct, row0, (int)k0 + (tid % NPACK) * 8, tid);
+        else
+            la[set].issue(A, lda, sh.rows, sh.red, row0, k0, tid);
         if constexpr (DIRECT)
             lb_dir[set].issue(direct, (int)k0 + (tid % NPACK) * 8, plane_tab);
         else if constexpr (COL_OUTER)
@@ -824,9 +893,10 @@ __global__ __launch_bounds__(256) void gemm_pipe_kernel(const T *__restrict__ A,
 // The launch may carry extra workgroups (blockIdx >= main_blocks) that finish the bias gradient: one
 // wavefront per filter adds that filter's per-block sums left by the dY packing kernel (strided per lane in
 // block order, then a fixed tree) -- the same arithmetic as bias_reduce_kernel, without a launch of its own.
-// PHASED: the partial results are [F][K'] in the phase-split order of a stride-4 layer (see
+// PHASED: the partial results are [F][K' + 1] in the phase-split order of a stride-4 layer (see
 // launch_gemm_wgrad_phase), K' index ((c * 4 + ph) * kh + ky) * kwq + kq standing for window column
-// kx = 4 kq + ph; entries with kx >= kw are padding and are dropped, the others go to [F][C][kh][kw].
+// kx = 4 kq + ph; entries with kx >= kw are padding and are dropped, the others go to [F][C][kh][kw];
+// column K' is the bias gradient.
 struct PhaseMap { int32_t C, kh, kw; FastDiv div_Kp, div_khkwq, div_kwq; };
 
 template <bool PHASED>
@@ -866,11 +936,15 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
         const float sum = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
         if constexpr (PHASED) {
             uint32_t f, kp, cp, rem, ky, kq;
-            pm.div_Kp.divmod((uint32_t)i, f, kp);
+            pm.div_Kp.divmod((uint32_t)i, f, kp);  // columns per row: K' + 1, the last one the bias gradient
             pm.div_khkwq.divmod(kp, cp, rem);
             pm.div_kwq.divmod(rem, ky, kq);
             const int kx = 4 * (int)kq + (int)(cp % 4u);
-            if (kx < pm.kw) out[(((int64_t)f * pm.C + cp / 4u) * pm.kh + ky) * pm.kw + kx] = sum;
+            if (kp + 1u == pm.div_Kp.d) {
+                if (dbias != nullptr) dbias[f] = sum;
+            } else if (kx < pm.kw) {
+                out[(((int64_t)f * pm.C + cp / 4u) * pm.kh + ky) * pm.kw + kx] = sum;
+            }
         } else {
             out[i] = sum;
         }
@@ -1156,7 +1230,7 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
                 DirectSrc d{(const bf16_t *)a.X_direct, g.C, g.H, g.W, g.H * g.W, g.K, g.ph, g.pw,
                             planes ? g.N : g.N * g.Ho, (int32_t)((int64_t)g.N * g.C * g.H * g.W),
                             FastDiv((uint32_t)((unit + 7) / 8)), FastDiv((uint32_t)g.Ho), g.div_khkw, g.div_kw,
-                            g.Ho * g.Wo, planes ? g.kh * g.kw : 0, FastDiv((uint32_t)g.W), 1};
+                            g.Ho * g.Wo, planes ? g.kh * g.kw : 0, FastDiv((uint32_t)g.W), 1, g.F, g.Wo};
                 switch (pick_wgrad_tile(g.F, g.K)) {
                 case 9: launch_direct<Tile9>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s); break;
                 case 10: launch_direct<Tile10>((const bf16_t *)a.dYhat, a.ldd, d, g.F, g.K, a.ldd, a.chunk, a.splits, epi, s); break;
@@ -1201,37 +1275,38 @@ int wgrad_phase_wp(const ConvGeom &g) { return (int)round_up((g.W + 3) / 4, 8); 
 
 bool wgrad_phase_supported(const ConvGeom &g, int dtype)
 {
-    if (dtype != OMNI_BF16 || g.sw != 4 || g.ph != 0 || g.pw != 0 || g.F > TilePhase::BM) return false;
-    if (wgrad_phase_kp(g) > TilePhase::BN) return false;
+    if (dtype != OMNI_BF16 || g.sw != 4 || g.ph != 0 || g.pw != 0 || g.F > TilePhase::BM || g.Wo < 8) return false;
+    if (wgrad_phase_kp(g) + 1 > TilePhase::BN) return false;  // + 1: the column of the bias gradient
     int64_t total4 = (int64_t)g.N * g.C * 4 * g.H * wgrad_phase_wp(g);
-    return total4 < 0x7fffffffll - 16 && total4 >= 8 && (int64_t)g.N * g.C * g.H * g.W < 0x7fffffffll - 64;
+    return total4 < 0x7fffffffll - 16 && total4 >= 8 && (int64_t)g.N * g.C * g.H * g.W < 0x7fffffffll - 64 &&
+           (int64_t)g.N * g.F * g.HoWo < 0x7fffffffll - 16;
 }
 
-int launch_gemm_wgrad_phase(const ConvGeom &g, const void *X4, const void *dYhat, int64_t ld, float *partials, int splits,
-                            int64_t chunk, float *dW, const float *bias_partials, int bias_blocks, float *dbias,
-                            hipStream_t s)
+// partials: [splits][F][K' + 1] floats; `ld` = the padded reduction extent (dyhat_rows_ld)
+int launch_gemm_wgrad_phase(const ConvGeom &g, const void *X4, const void *dY, int64_t ld, float *partials, int splits,
+                            int64_t chunk, float *dW, float *dbias, hipStream_t s)
 {
     const int kwq = phase_kwq(g), Kp = wgrad_phase_kp(g), WP = wgrad_phase_wp(g);
-    PartialEpilogue epi{partials, g.F, Kp};
+    PartialEpilogue epi{partials, g.F, Kp + 1};
     {
         ProfScope prof(KID_GEMM_WGRAD, s, 2.0 * g.M * (double)g.K * g.F,
-                       ((double)g.N * g.C * 4 * g.H * WP + (double)g.F * g.M) * 2.0 + 4.0 * g.F * Kp * splits);
+                       ((double)g.N * g.C * 4 * g.H * WP + (double)g.F * g.M) * 2.0 + 4.0 * g.F * (Kp + 1) * splits);
         DirectSrc d{(const bf16_t *)X4, 4 * g.C, g.H, WP, g.H * WP, Kp, 0, 0, g.N * g.Ho,
                     (int32_t)((int64_t)g.N * g.C * 4 * g.H * WP), FastDiv((uint32_t)((g.Wo + 7) / 8)), FastDiv((uint32_t)g.Ho),
-                    FastDiv((uint32_t)(g.kh * kwq)), FastDiv((uint32_t)kwq), g.Ho * g.Wo, 0, FastDiv((uint32_t)WP), g.sh};
-        GemmShape sh = make_shape(g.F, Kp, ld, chunk, TilePhase::BM, TilePhase::BN, splits);
+                    FastDiv((uint32_t)(g.kh * kwq)), FastDiv((uint32_t)kwq), g.Ho * g.Wo, 0, FastDiv((uint32_t)WP), g.sh,
+                    g.F, g.Wo};
+        GemmShape sh = make_shape(g.F, Kp + 1, ld, chunk, TilePhase::BM, TilePhase::BN, splits);
         sh.fast_store = epi.fits32() ? 1 : 0;
-        hipLaunchKernelGGL((gemm_kernel<bf16_t, TilePhase, false, PartialEpilogue, DIRECT_ROWS>), dim3(sh.per_xcd * 8),
-                           dim3(TilePhase::NT), 0, s, (const bf16_t *)dYhat, ld, (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
+        hipLaunchKernelGGL((gemm_kernel<bf16_t, TilePhase, false, PartialEpilogue, DIRECT_ROWS_ONES>), dim3(sh.per_xcd * 8),
+                           dim3(TilePhase::NT), 0, s, (const bf16_t *)dY, (int64_t)0, (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
     }
     OMNI_LAUNCH_CHECK();
-    const int64_t count = (int64_t)g.F * Kp;
+    const int64_t count = (int64_t)g.F * (Kp + 1);
     ProfScope prof(KID_REDUCE_PARTIALS, s, 0.0, 4.0 * count * (splits + 1));
     const unsigned main_blocks = (unsigned)((count + 63) / 64);
-    const unsigned bias_wgs = dbias != nullptr ? (unsigned)((g.F + 3) / 4) : 0u;
-    PhaseMap pm{g.C, g.kh, g.kw, FastDiv((uint32_t)Kp), FastDiv((uint32_t)(g.kh * kwq)), FastDiv((uint32_t)kwq)};
-    hipLaunchKernelGGL(reduce_partials_kernel<true>, dim3(main_blocks + bias_wgs), dim3(256), 0, s, partials, splits, count,
-                       dW, main_blocks, bias_partials, bias_blocks, g.F, dbias, pm);
+    PhaseMap pm{g.C, g.kh, g.kw, FastDiv((uint32_t)(Kp + 1)), FastDiv((uint32_t)(g.kh * kwq)), FastDiv((uint32_t)kwq)};
+    hipLaunchKernelGGL(reduce_partials_kernel<true>, dim3(main_blocks), dim3(256), 0, s, partials, splits, count, dW,
+                       main_blocks, (const float *)nullptr, 0, g.F, dbias, pm);
     OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }

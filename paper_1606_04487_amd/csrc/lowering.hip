@@ -567,6 +567,7 @@ __global__ __launch_bounds__(256) void pack_dyhat_rows_kernel(ConvGeom g, FastDi
     uint32_t i[PACK_UNR];
     const bf16_t *src[PACK_UNR];
     bool live[PACK_UNR], fast[PACK_UNR];
+    int back[PACK_UNR];
     VecOf<uint16_t, 8> o[PACK_UNR];
 #pragma unroll
     for (int u = 0; u < PACK_UNR; ++u) {
@@ -576,13 +577,23 @@ __global__ __launch_bounds__(256) void pack_dyhat_rows_kernel(ConvGeom g, FastDi
         div_Ho.divmod(row, n, oy);
         live[u] = pack[u] * 8 < ld && (int)n < g.N;
         src[u] = dY + (((int64_t)(live[u] ? n : 0) * g.F + f) * g.Ho + oy) * g.Wo + 8 * i[u];
-        fast[u] = can_vec && live[u] && 8 * (int)i[u] + 8 <= g.Wo;
-        if (can_vec) __builtin_memcpy(&o[u], fast[u] ? src[u] : dY, 16);  // element-aligned 16-byte loads, issued together
+        // a row's ragged last pack is read so that the 16 bytes END at the row's end (inside the tensor) and
+        // shifted down afterwards, which zeroes its padding
+        const int valid = g.Wo - 8 * (int)i[u];
+        back[u] = valid < 8 ? 8 - valid : 0;
+        fast[u] = can_vec && live[u] && (back[u] == 0 || g.Wo >= 8);
+        if (can_vec) __builtin_memcpy(&o[u], fast[u] ? src[u] - back[u] : dY, 16);  // element-aligned 16-byte loads, issued together
     }
 #pragma unroll
     for (int u = 0; u < PACK_UNR; ++u) {
         if (pack[u] * 8 >= ld) continue;
         if (fast[u]) {
+            if (back[u]) {
+                unsigned __int128 x;
+                __builtin_memcpy(&x, &o[u], 16);
+                x >>= 16 * back[u];
+                __builtin_memcpy(&o[u], &x, 16);
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) sum += bf16_to_f32(o[u].v[e]);
         } else {

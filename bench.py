@@ -24,14 +24,14 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
-MFMA_KERNELS = ("gemm", "conv_fused")          # kernel classes bound by the matrix cores
+MFMA_KERNELS = ("gemm", "conv_fused", "conv_strided")          # kernel classes bound by the matrix cores
 # HBM bytes per launch (fetched + written, averaged over the class's launches of one step) at the default
 # workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by the readings for
 # the 256 MiB calibration copy below; the summary and its commands are profiles/*_hbm_traffic.md.
 MEASURED_HBM_BYTES_PER_LAUNCH = {
-    ("bf16", 256): {"gemm_wgrad": 271.6e6, "gemm_forward": 714.2e6, "conv_fused_forward": 129.4e6,
-                    "conv_fused_dgrad": 129.4e6, "lower": 671.4e6, "maxpool_backward": 145.3e6,
-                    "pack_dyhat": 147.4e6, "reduce_partials": 52.2e6, "maxpool_forward": 121.4e6},
+    ("bf16", 256): {"gemm_wgrad": 180.2e6, "conv_fused_forward": 129.7e6, "conv_fused_dgrad": 129.7e6,
+                    "conv_strided_forward": 253.1e6, "lower": 169.8e6, "maxpool_backward": 145.3e6,
+                    "pack_dyhat": 104.1e6, "reduce_partials": 55.3e6, "maxpool_forward": 121.4e6},
 }
 
 

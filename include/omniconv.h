@@ -106,7 +106,12 @@ int omni_conv_workspace_bytes(const omni_conv_desc *desc, int pass, size_t *byte
  * backward_data: bf16, stride 1, reduced channels a multiple of 32, and the pixels needed by 256
  * consecutive output positions fit the kernel's LDS patch (and the layer is not one that backward_data
  * handles as a single dense product, see there).  Fused backward_weights: bf16, stride 1, a result that
- * fills 256 x 256 or 384 x 128 tiles.  The workspace size of a pass does not depend on OMNI_FLAG_FUSED. */
+ * fills 256 x 256 or 384 x 128 tiles.  Layers with horizontal stride 4, no padding and at most 96 filters
+ * (bf16; CaffeNet's conv1) run fused too: forward when C * kh * ceil(kw / 4) <= 100 and the input rows of 512
+ * output positions fit the kernel's LDS patch; backward_weights when 4 * C * kh * ceil(kw / 4) < 512 and
+ * Wo >= 8 (the input is split into its four column phases in the workspace and the product reads those and
+ * dY as they are; the bias gradient comes out of the same product).
+ * The workspace size of a pass does not depend on OMNI_FLAG_FUSED. */
 int omni_conv_fused_supported(const omni_conv_desc *desc, int pass);
 
 /*

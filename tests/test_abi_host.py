@@ -159,3 +159,22 @@ def test_split_k_flag_is_accepted_and_sized(B):
     import ctypes
     n = ctypes.c_size_t()
     assert B._lib.omni_conv_workspace_bytes(ctypes.byref(bad), 0, ctypes.byref(n)) == -2
+
+
+def test_which_passes_run_without_a_lowered_matrix(B):
+    """Host-side answers of omni_conv_fused_supported for the CaffeNet-shaped layers at batch 256 (bf16)
+    and for shapes the fused kernels must decline; the workspace size never depends on the flag."""
+    F, DG, WG = B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS
+    conv1 = B.conv_desc(256, 3, 227, 227, 96, 11, 11, 4, 0, B.BF16, B.FLAG_FUSED)
+    assert [B.conv_fused_supported(conv1, p) for p in (F, DG, WG)] == [True, False, True]
+    for C, H, Fo, k, p in [(96, 27, 256, 5, 2), (256, 13, 384, 3, 1), (384, 13, 384, 3, 1), (384, 13, 256, 3, 1)]:
+        d = B.conv_desc(256, C, H, H, Fo, k, k, 1, p, B.BF16, B.FLAG_FUSED)
+        assert all(B.conv_fused_supported(d, q) for q in (F, DG, WG))
+    # fp32, padding with stride 4, too many filters, a reduction beyond the kernel's weight tile, short rows
+    assert not B.conv_fused_supported(B.conv_desc(8, 3, 227, 227, 96, 11, 11, 4, 0, B.F32, B.FLAG_FUSED), F)
+    assert not B.conv_fused_supported(B.conv_desc(8, 3, 227, 227, 96, 11, 11, 4, 2, B.BF16, B.FLAG_FUSED), F)
+    assert not B.conv_fused_supported(B.conv_desc(8, 3, 227, 227, 128, 11, 11, 4, 0, B.BF16, B.FLAG_FUSED), WG)
+    assert not B.conv_fused_supported(B.conv_desc(8, 40, 35, 35, 8, 3, 3, 4, 0, B.BF16, B.FLAG_FUSED), F)
+    assert not B.conv_fused_supported(B.conv_desc(8, 3, 35, 35, 8, 11, 11, 4, 0, B.BF16, B.FLAG_FUSED), WG)   # Wo = 7
+    for p in (F, DG, WG):
+        assert B.conv_workspace_bytes(conv1, p) == B.conv_workspace_bytes(conv1.with_flags(0), p)

@@ -192,7 +192,7 @@ struct DirectSrc {
 // are real pixels depends on (pack within the plane, tap) alone: a table in LDS, one byte per element,
 // built when the workgroup starts.  Row (pack j, tap KK) of the table is zero: result columns beyond K.
 constexpr int DIRECT_TAB = 2560;  // table entries (8 bytes each) a workgroup can hold beside its tiles
-enum { DIRECT_ROWS = 1, DIRECT_ROWS_FIXED = 2, DIRECT_PLANES = 3, DIRECT_ROWS_ONES = 4 };
+enum { DIRECT_ROWS = 1, DIRECT_ROWS_FIXED = 2, DIRECT_PLANES = 3, DIRECT_ROWS_ONES = 4, DIRECT_PHASE3 = 5 };
 // DIRECT_ROWS_ONES: row mode in which (a) row K of the operand -- the first result column beyond the gradient
 // -- is all ones, so that result column K is the sum of dY over every position: the bias gradient, from the
 // same MFMAs; and (b) the row operand is read from dY as it lies in memory (DyLoader), not from a packed copy.
@@ -368,6 +368,67 @@ template <int TILE_ROWS, int NT, int MODE> struct DirectLoader {
     }
 };
 
+// DIRECT_PHASE3: the lowered operand of the phase-split stride-4 model gradient (launch_gemm_wgrad_phase) when a
+// window row has three groups (kw = 9 .. 12).  Rows 3t, 3t + 1, 3t + 2 of the operand are then the same ten
+// consecutive elements of phase image (c', ky) shifted by 0, 1 and 2: one 16-byte load and one 4-byte load
+// (both aligned: X4's rows are 16-byte multiples and a pack starts at a multiple of 8) serve three packs, and
+// only the K' / 3 real triples are loaded.  Nothing needs a mask: every address is inside X4 (8 * P8 + 2 <= WP),
+// columns beyond the batch meet zeros of the other operand, rows beyond K' + 1 are never written (their
+// results are columns the epilogue does not store), and row K' is the row of ones.
+template <int TILE_ROWS, int NT> struct Phase3Loader {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    static constexpr int ROUNDS = (TILE_ROWS / 3 + NT / NPACK - 1) / (NT / NPACK);  // triples per thread
+    u32x4 w[ROUNDS];
+    uint32_t x[ROUNDS];
+    int kbase[ROUNDS];  // element offset of the triple's input row from the pack's base; -1: no such triple
+
+    __device__ __forceinline__ void init(const DirectSrc &d, int, int tid)
+    {
+        const int kh = (int)d.div_khkw.d / 3;
+#pragma unroll
+        for (int q = 0; q < ROUNDS; ++q) {
+            const int tr = tid / NPACK + q * (NT / NPACK);
+            const int c = tr / kh, ky = tr - c * kh;
+            kbase[q] = 3 * tr < d.K ? c * d.HW + ky * d.W : -1;
+        }
+    }
+    __device__ __forceinline__ void issue(const DirectSrc &d, int m0, const uint2 *)
+    {
+        uint32_t row, i, n, oy;
+        d.div_p8.divmod((uint32_t)m0 >> 3, row, i);
+        const bool live = (int)row < d.rows;
+        d.div_Ho.divmod(live ? row : 0u, n, oy);
+        const int base = (int)n * d.C * d.HW + (int)oy * d.sh * d.W + 8 * (int)i;
+        const char *xb = reinterpret_cast<const char *>(d.X);
+#pragma unroll
+        for (int q = 0; q < ROUNDS; ++q) {
+            const int e = live && kbase[q] >= 0 ? base + kbase[q] : 0;
+            __builtin_memcpy(&w[q], xb + 2u * (uint32_t)e, 16);
+            __builtin_memcpy(&x[q], xb + 2u * (uint32_t)e + 16, 4);
+        }
+    }
+    __device__ __forceinline__ void commit(uint4 *lds, int tid) const
+    {
+        u32x4 *dst = reinterpret_cast<u32x4 *>(lds) + (tid % NPACK) * (TILE_ROWS + 1);
+#pragma unroll
+        for (int q = 0; q < ROUNDS; ++q) {
+            const int tr = tid / NPACK + q * (NT / NPACK);
+            if (kbase[q] >= 0) {
+                const u32x4 a = w[q];
+                dst[3 * tr] = a;
+                dst[3 * tr + 1] = u32x4{__builtin_amdgcn_alignbit(a[1], a[0], 16), __builtin_amdgcn_alignbit(a[2], a[1], 16),
+                                        __builtin_amdgcn_alignbit(a[3], a[2], 16), __builtin_amdgcn_alignbit(x[q], a[3], 16)};
+                dst[3 * tr + 2] = u32x4{a[1], a[2], a[3], x[q]};
+            }
+        }
+    }
+    // the row of ones (row K of the operand), rewritten with every tile by the first NPACK threads
+    __device__ __forceinline__ void commit_ones(uint4 *lds, int tid, int K) const
+    {
+        if (tid < NPACK) reinterpret_cast<u32x4 *>(lds)[tid * (TILE_ROWS + 1) + K] = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    }
+};
+
 // The row operand of the model gradient read from dY [N][F][Ho][Wo] itself: row f, padded column
 // ((n * Ho + oy) * P8 + i) * 8 + e is dY(n, f, oy, 8 i + e), zero for 8 i + e >= Wo and for columns beyond the
 // batch.  The 16 bytes of a row's ragged last pack are read so that they END at the row's end (always inside
@@ -490,12 +551,12 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
 
-    constexpr bool DY_DIRECT = DIRECT == DIRECT_ROWS_ONES;  // the row operand comes from dY as it is
+    constexpr bool DY_DIRECT = DIRECT == DIRECT_ROWS_ONES || DIRECT == DIRECT_PHASE3;  // the row operand comes from dY as it is
     typename std::conditional<DY_DIRECT, DyLoader<BM, NT>, RedContigLoader<T, BM, NT>>::type la[PF];
     struct Unused {};  // only the column loader in use is instantiated: not every tile suits every loader
     typename std::conditional<!COL_OUTER && !DIRECT, RedContigLoader<T, BN, NT>, Unused>::type lb_red[PF];
     typename std::conditional<COL_OUTER, OuterContigLoader<T, BN, NT>, Unused>::type lb_out[PF];
-    DirectLoader<BN, NT, DIRECT> lb_dir[DIRECT ? PF : 1];
+    typename std::conditional<DIRECT == DIRECT_PHASE3, Phase3Loader<BN, NT>, DirectLoader<BN, NT, DIRECT>>::type lb_dir[DIRECT ? PF : 1];
     __shared__ uint2 plane_tab[DIRECT == DIRECT_PLANES ? DIRECT_TAB : 1];
     if constexpr (DIRECT != 0) {
 #pragma unroll
@@ -520,9 +581,10 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_kernel(const T *__restrict__ A, 
     };
     auto commit = [&](int set, int buf) {
         la[set].commit(lds_a(buf), tid);
-        if constexpr (DIRECT)
+        if constexpr (DIRECT) {
             lb_dir[set].commit(lds_b(buf), tid);
-        else if constexpr (COL_OUTER)
+            if constexpr (DIRECT == DIRECT_PHASE3) lb_dir[set].commit_ones(lds_b(buf), tid, direct.K);
+        } else if constexpr (COL_OUTER)
             lb_out[set].commit(lds_b(buf), tid);
         else
             lb_red[set].commit(lds_b(buf), tid);
@@ -1297,8 +1359,14 @@ int launch_gemm_wgrad_phase(const ConvGeom &g, const void *X4, const void *dY, i
                     g.F, g.Wo};
         GemmShape sh = make_shape(g.F, Kp + 1, ld, chunk, TilePhase::BM, TilePhase::BN, splits);
         sh.fast_store = epi.fits32() ? 1 : 0;
-        hipLaunchKernelGGL((gemm_kernel<bf16_t, TilePhase, false, PartialEpilogue, DIRECT_ROWS_ONES>), dim3(sh.per_xcd * 8),
-                           dim3(TilePhase::NT), 0, s, (const bf16_t *)dY, (int64_t)0, (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
+        // three groups per window row and every pack's ten elements inside its row of X4: one load per three rows
+        const bool triples = kwq == 3 && 8 * ((g.Wo + 7) / 8) + 2 <= WP;
+        if (triples)
+            hipLaunchKernelGGL((gemm_kernel<bf16_t, TilePhase, false, PartialEpilogue, DIRECT_PHASE3>), dim3(sh.per_xcd * 8),
+                               dim3(TilePhase::NT), 0, s, (const bf16_t *)dY, (int64_t)0, (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
+        else
+            hipLaunchKernelGGL((gemm_kernel<bf16_t, TilePhase, false, PartialEpilogue, DIRECT_ROWS_ONES>), dim3(sh.per_xcd * 8),
+                               dim3(TilePhase::NT), 0, s, (const bf16_t *)dY, (int64_t)0, (const bf16_t *)nullptr, (int64_t)0, sh, epi, d);
     }
     OMNI_LAUNCH_CHECK();
     const int64_t count = (int64_t)g.F * (Kp + 1);

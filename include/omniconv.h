@@ -110,7 +110,10 @@ int omni_conv_workspace_bytes(const omni_conv_desc *desc, int pass, size_t *byte
  * (bf16; CaffeNet's conv1) run fused too: forward when C * kh * ceil(kw / 4) <= 100 and the input rows of 512
  * output positions fit the kernel's LDS patch; backward_weights when 4 * C * kh * ceil(kw / 4) < 512 and
  * Wo >= 8 (the input is split into its four column phases in the workspace and the product reads those and
- * dY as they are; the bias gradient comes out of the same product).
+ * dY as they are; the bias gradient comes out of the same product).  backward_data of any strided, unpadded
+ * bf16 layer with F a multiple of 32 runs as one fused stride-1 convolution over dY with C * stride_h *
+ * stride_w output channels (one per input channel and pixel phase) followed by the interleaving of the phase
+ * images into dX, provided that convolution meets the stride-1 conditions above.
  * The workspace size of a pass does not depend on OMNI_FLAG_FUSED. */
 int omni_conv_fused_supported(const omni_conv_desc *desc, int pass);
 

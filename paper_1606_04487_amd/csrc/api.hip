@@ -100,6 +100,7 @@ void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w)
     plan_split_k(g, dtype, g.K, w->ld, g.F, &w->splits, &w->chunk);
     w->total = w->partials + align256(w->splits > 1 ? (size_t)w->splits * g.K * w->ld * sizeof(float) : 0);
     if (fused_supported(g, dtype, true) && fused_weight_bytes(g, true) > w->total) w->total = align256(fused_weight_bytes(g, true));
+    if (strided_dgrad_supported(g, dtype) && strided_dgrad_bytes(g) > w->total) w->total = align256(strided_dgrad_bytes(g));
 }
 
 // Split the long reduction (extent ld) over the chip: one round of 256 x 256 workgroups on the 256 compute
@@ -243,6 +244,7 @@ int omni_conv_fused_supported(const omni_conv_desc *desc, int pass)
     if (pass == OMNI_PASS_BACKWARD_DATA) {
         BwdDataWs w;
         plan_backward_data(g, desc->dtype, &w);
+        if (strided_dgrad_supported(g, desc->dtype) && strided_dgrad_bytes(g) <= w.total) return 1;
         return fused_supported(g, desc->dtype, true) && fused_weight_bytes(g, true) <= w.total ? 1 : 0;
     }
     if (pass == OMNI_PASS_BACKWARD_WEIGHTS)
@@ -344,6 +346,8 @@ int omni_conv_backward_data(const omni_conv_desc *desc, const void *dY, const vo
     if ((desc->flags & OMNI_FLAG_FUSED) && fused_supported(g, desc->dtype, true) &&
         fused_weight_bytes(g, true) <= w.total)
         return launch_fused_conv(g, true, dY, W, nullptr, 0, dX, ws, s);
+    if ((desc->flags & OMNI_FLAG_FUSED) && strided_dgrad_supported(g, desc->dtype) && strided_dgrad_bytes(g) <= w.total)
+        return launch_strided_dgrad(g, dY, W, dX, ws, s);
 
     if (dgrad_dense_supported(g))
         return launch_gemm_dgrad_dense(g, desc->dtype, dY, W, dX, (float *)(ws + w.partials), w.splits, w.chunk, s);

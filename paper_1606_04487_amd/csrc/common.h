@@ -169,8 +169,9 @@ void gemm_split_tile(int rows, int cols, int *bm, int *bn);  // tile of a split 
 // repacked weights (fused_weight_bytes).
 bool fused_supported(const ConvGeom &g, int dtype, bool data_gradient);
 size_t fused_weight_bytes(const ConvGeom &g, bool data_gradient);
+// kid: kernel class the launch is timed under (-1: by data_gradient)
 int launch_fused_conv(const ConvGeom &g, bool data_gradient, const void *X, const void *W, const float *bias,
-                      int relu, void *Y, void *wt_scratch, hipStream_t s);
+                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid = -1);
 
 // strided.hip: the forward convolution of a layer with horizontal stride 4, no padding, at most 96 filters and
 // a short reduction (CaffeNet's conv1) without D-hat; bf16.  wt_scratch receives the repacked weights.
@@ -178,6 +179,13 @@ bool strided_supported(const ConvGeom &g, int dtype);
 size_t strided_weight_bytes(const ConvGeom &g);
 int launch_strided_conv(const ConvGeom &g, const void *X, const void *W, const float *bias, int relu, void *Y,
                         void *wt_scratch, hipStream_t s);
+
+// Data gradient of a strided, unpadded layer as one stride-1 convolution over dY with C*sh*sw output channels
+// (run by the fused kernel of implicit.hip) plus the interleaving of the phase images into dX; bf16.
+// `workspace` needs strided_dgrad_bytes().
+bool strided_dgrad_supported(const ConvGeom &g, int dtype);
+size_t strided_dgrad_bytes(const ConvGeom &g);
+int launch_strided_dgrad(const ConvGeom &g, const void *dY, const void *W, void *dX, void *workspace, hipStream_t s);
 
 // The model gradient of such a layer without D-hat: phase_split writes X4 [N][4C][H][WP] (strided.hip), the
 // product reads its lowered operand from X4 and its other operand from dY itself (gemm.hip); the bias

@@ -417,7 +417,7 @@ size_t fused_weight_bytes(const ConvGeom &c, bool data_gradient)
 }
 
 int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, const void *W, const float *bias,
-                      int relu, void *Y, void *wt_scratch, hipStream_t s)
+                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid)
 {
     using namespace fused;
     Geom g;
@@ -432,7 +432,7 @@ int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, cons
         OMNI_LAUNCH_CHECK();
     }
     FwdEpilogue<bf16_t> epi{(bf16_t *)Y, bias, g.F, g.M, g.HoWo, g.div_HoWo, relu};
-    ProfScope prof(data_gradient ? KID_FUSED_DGRAD : KID_FUSED_FWD, s, 2.0 * (double)c.M * c.K * c.F, 0.0);
+    ProfScope prof(kid >= 0 ? kid : (data_gradient ? KID_FUSED_DGRAD : KID_FUSED_FWD), s, 2.0 * (double)c.M * c.K * c.F, 0.0);
     dim3 grid((unsigned)(g.per_xcd * 8)), block(NT);
     if (g.bn == BN_WIDE)
         hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4, BN_WIDE, PATCH_WIDE>), grid, block, 0, s, (const bf16_t *)X,

@@ -372,6 +372,133 @@ int launch_phase_split(const ConvGeom &c, int WP, const void *X, void *X4, hipSt
     return OMNI_OK;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Data gradient of a strided, unpadded layer without dD-hat or a scatter step.  Input pixel
+// (y, x) = (sh yq + py, sw xq + px) receives dY(oy, ox) W(ky, kx) from the taps ky = py + sh kr, kx = px + sw kq
+// at oy = yq - kr, ox = xq - kq: for a fixed phase (py, px) that is a stride-1 correlation of dY (F channels) with
+// a window of ceil(kh / sh) x ceil(kw / sw) taps and full padding.  So the gradient is ONE stride-1 convolution
+// with C sh sw output channels (c, py, px), run by the fused stride-1 kernel (implicit.hip) on dY as it is, followed
+// by the interleaving of the phase images into dX (the inverse of phase_split).
+//   Wc[(c, py, px)][f][a][b] = W[f][c][py + sh (khq - 1 - a)][px + sw (kwq - 1 - b)]   (0 beyond the window)
+// ------------------------------------------------------------------------------------------------
+namespace strided {
+
+struct DgradPlan {
+    ConvGeom gs;        // the stride-1 convolution: input dY [N][F][Ho][Wo], output [N][C sh sw][Hq][Wq]
+    int khq, kwq, Hq, Wq, Co;
+    size_t wt, wc, x4, total;  // workspace regions: packed weights of the fused kernel, Wc, the phase images
+};
+
+static bool make_dgrad_plan(const ConvGeom &c, int dtype, DgradPlan *p)
+{
+    if (dtype != OMNI_BF16 || c.ph != 0 || c.pw != 0 || (c.sh == 1 && c.sw == 1)) return false;
+    p->khq = (c.kh + c.sh - 1) / c.sh, p->kwq = (c.kw + c.sw - 1) / c.sw;
+    p->Hq = c.Ho + p->khq - 1, p->Wq = c.Wo + p->kwq - 1;
+    int64_t co = (int64_t)c.C * c.sh * c.sw;
+    if (co > 65535) return false;
+    p->Co = (int)co;
+    omni_conv_desc d{};
+    d.N = c.N, d.C = c.F, d.H = c.Ho, d.W = c.Wo, d.F = p->Co, d.kh = p->khq, d.kw = p->kwq;
+    d.stride_h = d.stride_w = 1, d.pad_h = p->khq - 1, d.pad_w = p->kwq - 1, d.dtype = OMNI_BF16, d.flags = 0;
+    if (make_geom(&d, &p->gs) != OMNI_OK || p->gs.Ho != p->Hq || p->gs.Wo != p->Wq) return false;
+    if (!fused_supported(p->gs, OMNI_BF16, false)) return false;
+    if ((double)c.N * p->Co * p->Hq * p->Wq * 2.0 >= 4.0e9) return false;
+    auto al = [](size_t b) { return (b + 255) / 256 * 256; };
+    p->wt = 0;
+    p->wc = al(fused_weight_bytes(p->gs, false));
+    p->x4 = p->wc + al((size_t)p->Co * c.F * p->khq * p->kwq * 2);
+    p->total = p->x4 + al((size_t)c.N * p->Co * p->Hq * p->Wq * 2);
+    return true;
+}
+
+__global__ __launch_bounds__(256) void dgrad_phase_weights_kernel(const bf16_t *__restrict__ W, bf16_t *__restrict__ Wc, int C,
+                                                                  int F, int kh, int kw, int sh, int sw, int khq, int kwq)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int taps = khq * kwq, total = C * sh * sw * F * taps;
+    if (idx >= total) return;
+    const int tap = idx % taps, f = (idx / taps) % F, co = idx / (taps * F);
+    const int a = tap / kwq, b = tap - a * kwq;
+    const int px = co % sw, py = (co / sw) % sh, c = co / (sw * sh);
+    const int ky = py + sh * (khq - 1 - a), kx = px + sw * (kwq - 1 - b);
+    Wc[idx] = (ky < kh && kx < kw) ? W[((f * C + c) * kh + ky) * kw + kx] : (bf16_t)0;
+}
+
+// dX(n, c, y, x) = X4(n, (c sh + y % sh) sw + x % sw, y / sh, x / sw), zero where that entry does not exist (rows and
+// columns no window reaches).  One thread per 8 consecutive x of a row.
+__global__ __launch_bounds__(256) void phase_merge_kernel(const bf16_t *__restrict__ X4, bf16_t *__restrict__ dX, int planes,
+                                                          int H, int W, int sh, int sw, int Hq, int Wq, FastDiv div_G,
+                                                          FastDiv div_H, FastDiv div_sh, FastDiv div_sw)
+{
+    const int G = (int)div_G.d;  // 8-element groups per row
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)planes * H * G) return;
+    uint32_t row, gq, pl, y, yq, py;
+    div_G.divmod((uint32_t)idx, row, gq);
+    div_H.divmod(row, pl, y);
+    div_sh.divmod(y, yq, py);
+    const bf16_t *src = X4 + ((int64_t)(pl * sh + py) * sw * Hq + yq) * Wq;  // phase px adds px * Hq * Wq
+    const int64_t phase = (int64_t)Hq * Wq;
+    uint32_t v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int x = 8 * (int)gq + e;
+        uint32_t xq, px;
+        div_sw.divmod((uint32_t)x, xq, px);
+        v[e] = (x < W && (int)yq < Hq && (int)xq < Wq) ? (uint32_t)src[px * phase + xq] : 0u;
+    }
+    bf16_t *dst = dX + (int64_t)row * W + 8 * (int)gq;
+    if (8 * (int)gq + 8 <= W) {
+        const uint4 o = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+        __builtin_memcpy(dst, &o, 16);  // element-aligned 16-byte store
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (8 * (int)gq + e < W) dst[e] = (bf16_t)v[e];
+    }
+}
+
+}  // namespace strided
+
+bool strided_dgrad_supported(const ConvGeom &c, int dtype)
+{
+    strided::DgradPlan p;
+    return strided::make_dgrad_plan(c, dtype, &p);
+}
+
+size_t strided_dgrad_bytes(const ConvGeom &c)
+{
+    strided::DgradPlan p;
+    return strided::make_dgrad_plan(c, OMNI_BF16, &p) ? p.total : 0;
+}
+
+int launch_strided_dgrad(const ConvGeom &c, const void *dY, const void *W, void *dX, void *workspace, hipStream_t s)
+{
+    using namespace strided;
+    DgradPlan p;
+    if (!make_dgrad_plan(c, OMNI_BF16, &p)) return OMNI_UNSUPPORTED;
+    char *ws = (char *)workspace;
+    bf16_t *Wc = (bf16_t *)(ws + p.wc), *X4 = (bf16_t *)(ws + p.x4);
+    {
+        ProfScope prof(KID_PACK_KHAT, s, 0.0, 2.0 * (double)c.F * c.K * 2.0);
+        const int total = p.Co * c.F * p.khq * p.kwq;
+        hipLaunchKernelGGL(dgrad_phase_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t *)W, Wc,
+                           c.C, c.F, c.kh, c.kw, c.sh, c.sw, p.khq, p.kwq);
+        OMNI_LAUNCH_CHECK();
+    }
+    int st = launch_fused_conv(p.gs, false, dY, Wc, nullptr, 0, X4, ws + p.wt, s, KID_FUSED_DGRAD);
+    if (st != OMNI_OK) return st;
+    const int planes = c.N * c.C, G = (c.W + 7) / 8;
+    const int64_t total = (int64_t)planes * c.H * G;
+    if (total > 0x7fffffffll - 4096) return OMNI_UNSUPPORTED;
+    ProfScope prof(KID_COL2IM, s, 0.0, 2.0 * ((double)planes * c.H * c.W + (double)c.N * p.Co * p.Hq * p.Wq));
+    hipLaunchKernelGGL(phase_merge_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t *)X4, (bf16_t *)dX,
+                       planes, c.H, c.W, c.sh, c.sw, p.Hq, p.Wq, FastDiv((uint32_t)G), FastDiv((uint32_t)c.H),
+                       FastDiv((uint32_t)c.sh), FastDiv((uint32_t)c.sw));
+    OMNI_LAUNCH_CHECK();
+    return OMNI_OK;
+}
+
 bool strided_supported(const ConvGeom &c, int dtype)
 {
     strided::Geom g;

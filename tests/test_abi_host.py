@@ -166,7 +166,9 @@ def test_which_passes_run_without_a_lowered_matrix(B):
     and for shapes the fused kernels must decline; the workspace size never depends on the flag."""
     F, DG, WG = B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS
     conv1 = B.conv_desc(256, 3, 227, 227, 96, 11, 11, 4, 0, B.BF16, B.FLAG_FUSED)
-    assert [B.conv_fused_supported(conv1, p) for p in (F, DG, WG)] == [True, False, True]
+    assert [B.conv_fused_supported(conv1, p) for p in (F, DG, WG)] == [True, True, True]
+    # the strided data gradient needs F a multiple of 32 (it is the reduction of a stride-1 convolution over dY)
+    assert not B.conv_fused_supported(B.conv_desc(8, 3, 227, 227, 40, 11, 11, 4, 0, B.BF16, B.FLAG_FUSED), DG)
     for C, H, Fo, k, p in [(96, 27, 256, 5, 2), (256, 13, 384, 3, 1), (384, 13, 384, 3, 1), (384, 13, 256, 3, 1)]:
         d = B.conv_desc(256, C, H, H, Fo, k, k, 1, p, B.BF16, B.FLAG_FUSED)
         assert all(B.conv_fused_supported(d, q) for q in (F, DG, WG))

@@ -241,6 +241,39 @@ def test_strided_backward_weights(B, cfg):
     assert torch.equal(dW, again) and torch.equal(db, db2)   # deterministic
 
 
+# (N, C, H, W, F, kh, kw, sh, sw): strided, unpadded layers whose data gradient runs as one stride-1 convolution
+DGRAD_SHAPES = [
+    (3, 3, 227, 227, 96, 11, 11, 4, 4),   # conv1
+    (5, 3, 99, 99, 64, 7, 7, 4, 4),
+    (2, 3, 67, 131, 96, 11, 11, 4, 4),    # non-square
+    (2, 8, 21, 25, 32, 3, 5, 2, 4),       # different strides, window not a multiple of either
+    (3, 16, 30, 30, 64, 5, 5, 2, 2),      # stride 2; the last input row and column are reached by no window
+    (2, 4, 31, 33, 32, 3, 3, 4, 5),       # strides beyond the window: some phases have no tap at all
+    (1, 2, 20, 23, 32, 4, 4, 3, 3),
+    (2, 3, 35, 35, 40, 11, 11, 4, 4),     # F = 40: not a multiple of 32, the explicit path runs
+]
+
+
+@pytest.mark.parametrize("cfg", DGRAD_SHAPES)
+def test_strided_backward_data(B, cfg):
+    N, C, H, W, F, kh, kw, sh, sw = cfg
+    s = oracle.shape(N, C, H, W, F, kh, kw, (sh, sw), (0, 0))
+    ho, wo = oracle.out_dims(s)
+    rng = np.random.default_rng(23)
+    Wt = wl.to_bf16_values(0.05 * rng.standard_normal((F, C, kh, kw)))
+    dY = wl.to_bf16_values(rng.standard_normal((N, F, ho, wo)))
+    d = B.conv_desc(N, C, H, W, F, kh, kw, (sh, sw), (0, 0), BF16, B.FLAG_FUSED)
+    assert B.conv_fused_supported(d, B.PASS_BACKWARD_DATA) == (F % 32 == 0)
+    Wg, dYg = gpu(Wt), gpu(dY)
+    ref = oracle.conv_backward_data(s, dY, Wt)
+    got = host(B.conv_backward_data(d, dYg, Wg))
+    assert rel_err(got, ref) <= TOL
+    explicit = host(B.conv_backward_data(d.with_flags(0), dYg, Wg))
+    assert rel_err(got, explicit) <= 1e-2
+    assert np.all(got[ref == 0] == 0)              # pixels no window reaches are exactly zero
+    assert np.array_equal(got, host(B.conv_backward_data(d, dYg, Wg)))   # deterministic
+
+
 def test_strided_declines(B):
     # padding, more than 96 filters, a reduction beyond 400: the explicit path runs
     for N, C, H, W, F, k, p in [(2, 3, 35, 35, 8, 11, 2), (2, 3, 35, 35, 97, 11, 0), (2, 40, 15, 15, 8, 3, 0)]:

@@ -437,7 +437,7 @@ __global__ __launch_bounds__(256) void phase_merge_kernel(const bf16_t *__restri
     div_G.divmod((uint32_t)idx, row, gq);
     div_H.divmod(row, pl, y);
     div_sh.divmod(y, yq, py);
-    const bf16_t *src = X4 + ((int64_t)(pl * sh + py) * sw * Hq + yq) * Wq;  // phase px adds px * Hq * Wq
+    const bf16_t *src = X4 + (((int64_t)pl * sh + py) * sw * Hq + yq) * Wq;  // phase px adds px * Hq * Wq
     const int64_t phase = (int64_t)Hq * Wq;
     uint32_t v[8];
 #pragma unroll

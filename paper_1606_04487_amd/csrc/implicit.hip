@@ -19,11 +19,12 @@
 // order in registers on their way into LDS (8 channels x 8 pixels per thread).  Padding pixels are
 // zeroed once: the patch layout is the same for every chunk, and loads only ever write real pixels.
 //
-// Schedule: the weights of up to TG window taps are staged in LDS together, so a workgroup runs TG taps
-// (TG x 8 MFMAs per wavefront) between synchronisation points.  While it does, the next group's weights
-// and -- during a chunk's first group -- the next chunk's pixels are in flight into registers; at the
-// group's end one barrier retires the readers, the registers go to LDS, a second barrier publishes them.
-// Every request is therefore waited for at one place only, a whole group after it was issued.
+// Schedule: the weights of up to TG window taps are staged in LDS together, in one of two buffers, so a
+// workgroup runs TG taps (TG x 8 MFMAs per wavefront) between barriers.  While it does, the next group's
+// weights and -- during a chunk's first group -- the next chunk's pixels are in flight into registers.  The
+// weights go to the other buffer before the group's last tap (every wavefront left that buffer before the last
+// barrier), so those stores run under the other wavefronts' MFMAs and one barrier per group publishes them;
+// only the pixels, once per chunk, need a barrier of their own before they overwrite the patch.
 #include <cstdlib>
 #include <type_traits>
 
@@ -42,7 +43,7 @@ constexpr int NT = 512;          // 8 wavefronts
 constexpr int BN_NARROW = 256, PATCH_NARROW = 640;
 constexpr int BN_MID = 384, PATCH_MID = 800;
 constexpr int BN_WIDE = 512, PATCH_WIDE = 960;
-constexpr int TG = 9;            // window taps whose weights are staged in LDS together
+constexpr int TG = 5;            // window taps whose weights are staged in LDS together (two such buffers)
 constexpr int MAX_SLOTS = 8;     // images a column tile may touch
 constexpr uint32_t NO_PIX = 0xffffu;
 
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
     constexpr int TI = BM / WM / 32, TJ = BN / WN / 32;
     constexpr int LA = BM + 1;
     __shared__ uint4 patch[NG * PATCH_PIX];
-    __shared__ uint4 atile[TG * NG * LA];
+    __shared__ uint4 atile[2 * TG * NG * LA];
     __shared__ float lds_add[BM];
     __shared__ int slot_so[MAX_SLOTS], slot_ra[MAX_SLOTS], slot_p0[MAX_SLOTS], slot_ya[MAX_SLOTS], slot_len[MAX_SLOTS];
     __shared__ int total_pieces;
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
     // The weight tile of reduction step st = chunk * KK + tap is [g][Fp] packs, contiguous per g; this
     // thread moves pack (tid / BM, row0 + tid % BM) of each of a group's TG tiles.  Requests are
     // unconditional: steps past the group's (or the reduction's) end repeat a valid tile that nobody reads.
-    static_assert(TG == 9, "named staging registers below");
+    static_assert(TG <= 9, "named staging registers below");
     u32x4 a0, a1, a2, a3, a4, a5, a6, a7, a8;  // named so that each stays a register
     auto areg = [&](auto q) -> u32x4 & {
         constexpr int Q = decltype(q)::value;
@@ -229,8 +230,8 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
             areg(q) = wt[st * step_stride];
         });
     };
-    auto commit_a = [&]() {
-        static_for<0, TG>([&](auto q) { at[decltype(q)::value * (NG * LA)] = areg(q); });
+    auto commit_a = [&](int buf) {
+        static_for<0, TG>([&](auto q) { at[(buf * TG + decltype(q)::value) * (NG * LA)] = areg(q); });
     };
 
     f32x16 acc[TI][TJ];
@@ -241,8 +242,8 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
 
-    auto compute = [&](int slot, int tapoff) {
-        const uint4 *pa = atile + slot * (NG * LA) + wm * (BM / WM) + li;
+    auto compute = [&](int buf, int slot, int tapoff) {
+        const uint4 *pa = atile + (buf * TG + slot) * (NG * LA) + wm * (BM / WM) + li;
         int pix[TJ];
 #pragma unroll
         for (int u = 0; u < TJ; ++u) pix[u] = swz(pp0[u] + tapoff);
@@ -264,9 +265,9 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
     issue_patch(0);
     issue_a(0);
     commit_patch();
-    commit_a();
+    commit_a(0);
     __syncthreads();
-    int ky = 0, kx = 0;
+    int ky = 0, kx = 0, buf = 0;
     for (int chunk = 0; chunk < g.n_chunks; ++chunk) {
         const bool more_chunks = chunk + 1 < g.n_chunks;
         for (int t0 = 0; t0 < KK; t0 += TG) {
@@ -274,6 +275,8 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
             const bool last_group = t0 + TG >= KK;
             issue_a(chunk * KK + t0 + nt);                     // the next group (of this chunk or the next)
             if (t0 == 0 && more_chunks) issue_patch(chunk + 1);
+            // The next group's weights go to the other buffer (free since the last barrier) before this
+            // group's last tap, so that those stores run under the other wavefronts' MFMAs.
             if (TJ <= 2 && nt == TG) {
                 // a full group as straight-line code: the compiler may start a tap's LDS reads under the
                 // previous tap's MFMAs
@@ -283,18 +286,25 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
                     off[t] = ky * g.Wp + kx;
                     if (++kx == g.kw) kx = 0, ++ky;
                 }
-                static_for<0, TG>([&](auto q) { compute(decltype(q)::value, off[decltype(q)::value]); });
+                static_for<0, TG>([&](auto q) {
+                    constexpr int Q = decltype(q)::value;
+                    if constexpr (Q == TG - 1) commit_a(buf ^ 1);
+                    compute(buf, Q, off[Q]);
+                });
             } else {
                 for (int t = 0; t < nt; ++t) {
-                    compute(t, ky * g.Wp + kx);
+                    if (t == nt - 1) commit_a(buf ^ 1);
+                    compute(buf, t, ky * g.Wp + kx);
                     if (++kx == g.kw) kx = 0, ++ky;
                 }
             }
             if (last_group) ky = 0;
-            __syncthreads();  // every wavefront has read this group's weights (and, after a chunk's last group, its pixels)
-            commit_a();
-            if (last_group && more_chunks) commit_patch();
-            __syncthreads();
+            if (last_group && more_chunks) {
+                __syncthreads();  // every wavefront has read this chunk's pixels
+                commit_patch();
+            }
+            __syncthreads();      // this group's weights are free, the next group's (and chunk's pixels) are in LDS
+            buf ^= 1;
         }
     }
 

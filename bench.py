@@ -29,7 +29,7 @@ MFMA_KERNELS = ("gemm", "conv_fused", "conv_strided")          # kernel classes 
 # workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by the readings for
 # the 256 MiB calibration copy below; the summary and its commands are profiles/*_hbm_traffic.md.
 MEASURED_HBM_BYTES_PER_LAUNCH = {
-    ("bf16", 256): {"gemm_wgrad": 180.2e6, "conv_fused_forward": 129.7e6, "conv_fused_dgrad": 129.7e6,
+    ("bf16", 256): {"gemm_wgrad": 180.1e6, "conv_fused_forward": 100.0e6, "conv_fused_dgrad": 100.0e6,
                     "conv_strided_forward": 253.1e6, "lower": 169.8e6, "maxpool_backward": 145.3e6,
                     "pack_dyhat": 104.1e6, "reduce_partials": 55.3e6, "maxpool_forward": 121.4e6},
 }

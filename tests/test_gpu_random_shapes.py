@@ -1,0 +1,92 @@
+"""Seeded random layer shapes through all three passes with OMNI_FLAG_FUSED, against the fp64 oracle.
+
+The hand-picked shapes of the other GPU tests aim at known boundaries (tile edges, ragged packs, image
+straddles); this sweep draws window, stride, padding, channel and image sizes at random so that combinations
+nobody thought of still meet the same bar: bf16 storage, tensor-normalised error <= 2e-2 for the forward pass
+and the data gradient, <= 1e-4 for the fp32 model and bias gradients.  Whether a pass takes a fused kernel or
+the explicit path is the library's choice (`conv_fused_supported`); the sweep checks that both kinds occur.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1606_04487_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1606_04487_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def gpu(a, bf16=True):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if bf16 else t
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def rel_err(got, ref):
+    scale = np.max(np.abs(ref))
+    return np.max(np.abs(got - ref)) / (scale if scale > 0 else 1.0)
+
+
+def check(B, rng, cfg, relu):
+    N, C, H, W, F, kh, kw, sh, sw, ph, pw = cfg
+    s = oracle.shape(N, C, H, W, F, kh, kw, (sh, sw), (ph, pw))
+    ho, wo = oracle.out_dims(s)
+    X = wl.to_bf16_values(rng.standard_normal((N, C, H, W)))
+    Wt = wl.to_bf16_values(0.05 * rng.standard_normal((F, C, kh, kw)))
+    b = (0.05 * rng.standard_normal(F)).astype(np.float32)
+    dY = wl.to_bf16_values(rng.standard_normal((N, F, ho, wo)))
+    d = B.conv_desc(N, C, H, W, F, kh, kw, (sh, sw), (ph, pw), 1, B.FLAG_FUSED | (B.FLAG_RELU if relu else 0))
+    fused = [bool(B.conv_fused_supported(d, p)) for p in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS)]
+    Xg, Wg, bg, dYg = gpu(X), gpu(Wt), gpu(b, False), gpu(dY)
+    ref = oracle.conv_forward(s, X, Wt, b)
+    if relu:
+        ref = np.maximum(ref, 0)
+    assert rel_err(host(B.conv_forward(d, Xg, Wg, bg)), ref) <= 2e-2, ("forward", cfg)
+    assert rel_err(host(B.conv_backward_data(d, dYg, Wg)), oracle.conv_backward_data(s, dY, Wt)) <= 2e-2, ("backward_data", cfg)
+    dW, db = B.conv_backward_weights(d, Xg, dYg)
+    assert rel_err(host(dW), oracle.conv_backward_weights(s, X, dY)) <= 1e-4, ("backward_weights", cfg)
+    assert rel_err(host(db), oracle.bias_grad(s, dY)) <= 1e-4, ("bias_grad", cfg)
+    return fused
+
+
+def test_random_strided_unpadded_layers(B):
+    rng = np.random.default_rng(101)
+    seen = np.zeros((3, 2), dtype=int)
+    for it in range(60):
+        sh = int(rng.integers(1, 5))
+        sw = int(rng.choice([4, 4, 4, 2, 3, 5]))
+        kh, kw = int(rng.integers(1, 12)), int(rng.integers(1, 13))
+        C, F = int(rng.integers(1, 9)), int(rng.choice([1, 3, 8, 17, 32, 40, 64, 96]))
+        N = int(rng.integers(1, 5))
+        H = kh + sh * int(rng.integers(0, 14)) + int(rng.integers(0, sh))
+        W = kw + sw * int(rng.integers(0, 40)) + int(rng.integers(0, sw))
+        fused = check(B, rng, (N, C, H, W, F, kh, kw, sh, sw, 0, 0), relu=bool(it % 2))
+        for p in range(3):
+            seen[p, int(fused[p])] += 1
+    assert seen.min() > 0, seen   # every pass ran both fused and explicit somewhere in the sweep
+
+
+def test_random_stride1_layers(B):
+    rng = np.random.default_rng(202)
+    seen = np.zeros((3, 2), dtype=int)
+    for it in range(50):
+        kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        ph, pw = int(rng.integers(0, kh)), int(rng.integers(0, kw))
+        C, F = int(rng.choice([32, 64, 96, 8, 20])), int(rng.choice([8, 32, 40, 64, 130, 256, 384]))
+        N = int(rng.integers(1, 7))
+        H = max(kh - 2 * ph, 1) + int(rng.integers(0, 28))
+        W = max(kw - 2 * pw, 1) + int(rng.integers(0, 28))
+        fused = check(B, rng, (N, C, H, W, F, kh, kw, 1, 1, ph, pw), relu=bool(it % 2))
+        for p in range(3):
+            seen[p, int(fused[p])] += 1
+    assert seen.min() > 0, seen

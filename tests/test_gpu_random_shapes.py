@@ -37,22 +37,26 @@ def rel_err(got, ref):
     return np.max(np.abs(got - ref)) / (scale if scale > 0 else 1.0)
 
 
-def check(B, rng, cfg, relu):
+def check(B, rng, cfg, relu, dtype=1, flags=None):
     N, C, H, W, F, kh, kw, sh, sw, ph, pw = cfg
     s = oracle.shape(N, C, H, W, F, kh, kw, (sh, sw), (ph, pw))
     ho, wo = oracle.out_dims(s)
-    X = wl.to_bf16_values(rng.standard_normal((N, C, H, W)))
-    Wt = wl.to_bf16_values(0.05 * rng.standard_normal((F, C, kh, kw)))
+    bf16 = dtype == 1
+    tol = 2e-2 if bf16 else 1e-4
+    val = wl.to_bf16_values if bf16 else (lambda a: a.astype(np.float32))
+    X = val(rng.standard_normal((N, C, H, W)))
+    Wt = val(0.05 * rng.standard_normal((F, C, kh, kw)))
     b = (0.05 * rng.standard_normal(F)).astype(np.float32)
-    dY = wl.to_bf16_values(rng.standard_normal((N, F, ho, wo)))
-    d = B.conv_desc(N, C, H, W, F, kh, kw, (sh, sw), (ph, pw), 1, B.FLAG_FUSED | (B.FLAG_RELU if relu else 0))
+    dY = val(rng.standard_normal((N, F, ho, wo)))
+    flags = B.FLAG_FUSED if flags is None else flags
+    d = B.conv_desc(N, C, H, W, F, kh, kw, (sh, sw), (ph, pw), dtype, flags | (B.FLAG_RELU if relu else 0))
     fused = [bool(B.conv_fused_supported(d, p)) for p in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS)]
-    Xg, Wg, bg, dYg = gpu(X), gpu(Wt), gpu(b, False), gpu(dY)
+    Xg, Wg, bg, dYg = gpu(X, bf16), gpu(Wt, bf16), gpu(b, False), gpu(dY, bf16)
     ref = oracle.conv_forward(s, X, Wt, b)
     if relu:
         ref = np.maximum(ref, 0)
-    assert rel_err(host(B.conv_forward(d, Xg, Wg, bg)), ref) <= 2e-2, ("forward", cfg)
-    assert rel_err(host(B.conv_backward_data(d, dYg, Wg)), oracle.conv_backward_data(s, dY, Wt)) <= 2e-2, ("backward_data", cfg)
+    assert rel_err(host(B.conv_forward(d, Xg, Wg, bg)), ref) <= tol, ("forward", cfg)
+    assert rel_err(host(B.conv_backward_data(d, dYg, Wg)), oracle.conv_backward_data(s, dY, Wt)) <= tol, ("backward_data", cfg)
     dW, db = B.conv_backward_weights(d, Xg, dYg)
     assert rel_err(host(dW), oracle.conv_backward_weights(s, X, dY)) <= 1e-4, ("backward_weights", cfg)
     assert rel_err(host(db), oracle.bias_grad(s, dY)) <= 1e-4, ("bias_grad", cfg)
@@ -90,3 +94,19 @@ def test_random_stride1_layers(B):
         for p in range(3):
             seen[p, int(fused[p])] += 1
     assert seen.min() > 0, seen
+
+
+def test_random_explicit_layers(B):
+    """The paper's path as stated (lower, one GEMM, col2im), fp32 and bf16, any stride and padding, with and
+    without split reductions."""
+    rng = np.random.default_rng(303)
+    for it in range(40):
+        sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        kh, kw = int(rng.integers(1, 7)), int(rng.integers(1, 7))
+        ph, pw = int(rng.integers(0, kh)), int(rng.integers(0, kw))
+        C, F = int(rng.integers(1, 40)), int(rng.integers(1, 150))
+        N = int(rng.integers(1, 6))
+        H = max(kh - 2 * ph, 1) + int(rng.integers(0, 30))
+        W = max(kw - 2 * pw, 1) + int(rng.integers(0, 30))
+        flags = B.FLAG_SPLIT_K if it % 3 == 0 else 0
+        check(B, rng, (N, C, H, W, F, kh, kw, sh, sw, ph, pw), relu=bool(it % 2), dtype=it % 2, flags=flags)

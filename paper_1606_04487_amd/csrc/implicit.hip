@@ -57,6 +57,7 @@ struct Geom {
     int32_t Fp;              // F rounded up to the row tile
     int32_t tiles_f, tiles_m, n_items, per_xcd;
     int32_t bn;              // columns per workgroup: BN_NARROW, BN_MID or BN_WIDE
+    int32_t bm;              // filter rows per workgroup: 128, or 96 (with BN_WIDE) for layers of few filters
     FastDiv div_HoWo, div_Wo, div_W;
 };
 
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
                                                         Geom g, FwdEpilogue<bf16_t> epi)
 {
     static_assert(WM * WN * 64 == NT, "eight wavefronts");
-    static_assert(BM * NG == NT, "one 16-byte piece of a tap's weight tile per thread");
+    static_assert(BM * NG <= NT, "at most one 16-byte piece of a tap's weight tile per thread");
     constexpr int TI = BM / WM / 32, TJ = BN / WN / 32;
     constexpr int LA = BM + 1;
     __shared__ uint4 patch[NG * PATCH_PIX];
@@ -220,9 +221,11 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         else if constexpr (Q == 6) return a6; else if constexpr (Q == 7) return a7; else return a8;
     };
     const int KK = g.KK, n_steps = g.n_chunks * KK;
-    const u32x4 *wt = reinterpret_cast<const u32x4 *>(Wt) + (row0 + (tid / BM) * g.Fp + tid % BM);
+    const bool has_piece = tid < BM * NG;            // a 96-row tile has fewer pieces than threads
+    const int wtid = has_piece ? tid : BM * NG - 1;  // the others repeat the last one's (valid) requests
+    const u32x4 *wt = reinterpret_cast<const u32x4 *>(Wt) + (row0 + (wtid / BM) * g.Fp + wtid % BM);
     const int step_stride = NG * g.Fp;  // packs from one step's tile to the next
-    u32x4 *const at = reinterpret_cast<u32x4 *>(atile) + (tid / BM) * LA + tid % BM;
+    u32x4 *const at = reinterpret_cast<u32x4 *>(atile) + (wtid / BM) * LA + wtid % BM;
     auto issue_a = [&](int st0) {
         static_for<0, TG>([&](auto q) {
             int st = st0 + decltype(q)::value;
@@ -231,7 +234,8 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         });
     };
     auto commit_a = [&](int buf) {
-        static_for<0, TG>([&](auto q) { at[(buf * TG + decltype(q)::value) * (NG * LA)] = areg(q); });
+        if (BM * NG == NT || has_piece)
+            static_for<0, TG>([&](auto q) { at[(buf * TG + decltype(q)::value) * (NG * LA)] = areg(q); });
     };
 
     f32x16 acc[TI][TJ];
@@ -277,7 +281,7 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
             if (t0 == 0 && more_chunks) issue_patch(chunk + 1);
             // The next group's weights go to the other buffer (free since the last barrier) before this
             // group's last tap, so that those stores run under the other wavefronts' MFMAs.
-            if (TJ <= 2 && nt == TG) {
+            if (TJ <= 2 && TI <= 2 && nt == TG) {
                 // a full group as straight-line code: the compiler may start a tap's LDS reads under the
                 // previous tap's MFMAs
                 int off[TG];
@@ -339,8 +343,6 @@ __global__ void pack_weights_kernel(const bf16_t *__restrict__ W, uint4 *__restr
     Wt[p] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
 }
 
-static int row_tile(int) { return 128; }
-
 // The convolution as this kernel sees it; for the data gradient the layer's output gradient is the
 // input and the window is flipped.
 static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
@@ -362,9 +364,9 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
     if ((double)g->N * g->C * g->HW * 2.0 >= 4.0e9 || (double)M * g->F * 2.0 >= 4.0e9) return false;
     g->M = (int32_t)M;
     g->n_chunks = g->C / CH;
-    int bm = row_tile(g->F);
-    g->Fp = (int32_t)round_up(g->F, bm);
-    g->tiles_f = g->Fp / bm;
+    g->bm = 128;
+    g->Fp = (int32_t)round_up(g->F, 128);
+    g->tiles_f = g->Fp / 128;
     g->div_HoWo = FastDiv((uint32_t)g->HoWo);
     g->div_Wo = FastDiv((uint32_t)g->Wo);
     g->div_W = FastDiv((uint32_t)g->W);
@@ -403,6 +405,16 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
         int64_t items = (int64_t)g->tiles_f * ((g->M + t.bn - 1) / t.bn);
         double cost = (double)((items + 255) / 256) * t.bn * t.per_column;
         if (g->bn == 0 || cost < best) g->bn = t.bn, best = cost;
+    }
+    // A layer of at most 64 filters takes a 96-row tile (8 wavefronts of 96 x 64 on 512 columns): three quarters
+    // of the MFMAs for a few more fragment reads per MFMA.  (Measured: 48 filters 287 -> 192 us; with 96 filters
+    // the two tiles take the same time, the kernel being bound by its LDS reads, so those keep the 128-row tile.)
+    const char *eb = getenv("OMNI_FUSED_BM");  // tuning override: 128 keeps the 128-row tile, 96 forces the other up to 96 filters
+    const int f_max = (eb != nullptr && atoi(eb) == 96) ? 96 : 64;
+    if (g->F <= f_max && (eb == nullptr || atoi(eb) == 96) && (want == 0 || want == BN_WIDE) && fits(BN_WIDE, PATCH_WIDE)) {
+        int64_t items = (g->M + BN_WIDE - 1) / BN_WIDE;
+        double cost = (double)((items + 255) / 256) * BN_WIDE * 0.8;
+        if (g->bn == 0 || cost < best) g->bn = BN_WIDE, g->bm = 96, g->Fp = 96, g->tiles_f = 1, best = cost;
     }
     if (g->bn == 0) return false;
     g->tiles_m = (g->M + g->bn - 1) / g->bn;
@@ -444,7 +456,10 @@ int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, cons
     FwdEpilogue<bf16_t> epi{(bf16_t *)Y, bias, g.F, g.M, g.HoWo, g.div_HoWo, relu};
     ProfScope prof(kid >= 0 ? kid : (data_gradient ? KID_FUSED_DGRAD : KID_FUSED_FWD), s, 2.0 * (double)c.M * c.K * c.F, 0.0);
     dim3 grid((unsigned)(g.per_xcd * 8)), block(NT);
-    if (g.bn == BN_WIDE)
+    if (g.bm == 96)
+        hipLaunchKernelGGL((fused_conv_kernel<96, 1, 8, BN_WIDE, PATCH_WIDE>), grid, block, 0, s, (const bf16_t *)X,
+                           (const bf16_t *)wt_scratch, g, epi);
+    else if (g.bn == BN_WIDE)
         hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4, BN_WIDE, PATCH_WIDE>), grid, block, 0, s, (const bf16_t *)X,
                            (const bf16_t *)wt_scratch, g, epi);
     else if (g.bn == BN_MID)

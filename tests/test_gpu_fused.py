@@ -177,6 +177,19 @@ def test_fused_declines_and_falls_back(B):
         assert rel_err(got, oracle.conv_forward(s, X, Wt, None)) <= (TOL if dtype == 1 else 1e-4)
 
 
+@pytest.mark.parametrize("cfg", [(3, 64, 27, 27, 48, 5, 5, 2, 2), (6, 32, 13, 13, 40, 3, 3, 1, 1),
+                                 (2, 96, 27, 27, 96, 5, 5, 2, 2), (5, 32, 6, 6, 8, 1, 1, 0, 0)])
+@pytest.mark.parametrize("bm", ["96", "128"])
+def test_fused_row_tiles(B, cfg, bm, monkeypatch):
+    """Layers of few filters: the 96-row tile (forced up to 96 filters) and the 128-row tile agree with the oracle."""
+    monkeypatch.setenv("OMNI_FUSED_BM", bm)
+    s, X, Wt, b, dY = make(cfg, 29)
+    d = desc_of(B, cfg, B.FLAG_FUSED | B.FLAG_RELU)
+    assert B.conv_fused_supported(d, B.PASS_FORWARD)
+    got = host(B.conv_forward(d, gpu(X), gpu(Wt), gpu(b, False)))
+    assert rel_err(got, np.maximum(oracle.conv_forward(s, X, Wt, b), 0)) <= TOL
+
+
 # (N, C, H, W, F, kh, kw, sh): horizontal stride 4, no padding, few channels -- the conv1 kernel
 STRIDED_SHAPES = [
     (2, 3, 35, 35, 8, 11, 11, 4),        # one tile per image, most of it beyond the image's last position

@@ -15,6 +15,7 @@ class is bracketed by events -- its average launch duration in the roofline come
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -98,8 +99,11 @@ def main():
     data = wl.stack_tensors(layers, seed=1, bf16=(dtype == B.BF16), pooled_out=stack.output_shape()[-2:])
     stack.set_parameters(data["W"], data["bias"])
     X = torch.from_numpy(data["X"]).cuda().to(B.torch_dtype(dtype))
-    dOut = torch.from_numpy(data["dY"]).cuda().to(B.torch_dtype(dtype))
+    # the seeded N(0,1) draw times a power of two that keeps repeated updates from blowing the weights up
+    grad_scale = wl.step_upstream_scale(args.batch)
+    dOut = (torch.from_numpy(data["dY"]).cuda() * grad_scale).to(B.torch_dtype(dtype))
     lr, mu = 0.01, 0.9
+    W_start = [w.clone() for w in stack.W]
 
     # One plain device copy of known size (256 MiB read, 256 MiB written) before anything is timed: under
     # rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the counters' units.
@@ -173,6 +177,11 @@ def main():
                     "frac": ach / PEAK_HBM_GBS, "traffic": traffic, "avg_launch_ms": avg_ms,
                     "launches_per_step": k["launches"] / args.steps, "bytes_per_launch": k["bytes"] / k["launches"]}
 
+    # the tensors the timed steps ran on: finite, not degenerate, weights still where they were drawn
+    health = stack.tensor_health(W_start)
+    health["steps_run"] = args.warmup + (args.table_steps if table_kernels else 0) + args.steps
+    degenerate = stack.health_is_degenerate(health)
+
     cpu = cpu_baseline(args.cpu_sample) if args.cpu_sample > 0 else None
     out = {
         "metric": "conv fwd+bwd images/sec, CaffeNet-shaped conv stack, batch 256",
@@ -180,7 +189,9 @@ def main():
         "ms_per_step": ms_per_step, "ms_per_step_median": median_ms, "ms_per_step_cv": cv, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"caffenet_conv1-5_relu_pool_fwd+bwd+sgd_b{args.batch}_{args.dtype}",
-                   "global_batch": args.batch, "conv1_data_gradient": bool(args.conv1_dgrad)},
+                   "global_batch": args.batch, "conv1_data_gradient": bool(args.conv1_dgrad),
+                   "lr": lr, "momentum": mu, "upstream_gradient": f"N(0,1) draw x 2^{int(math.log2(grad_scale))}"},
+        "tensor_health": health,
         "tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
         "mfma_frac_of_peak_whole_step": flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype],
         "roofline": roof, "cpu_baseline": cpu,
@@ -188,6 +199,10 @@ def main():
         "kernels": table,
     }
     print(json.dumps(out))
+    if degenerate:
+        print("bench.py: the timed steps ran on non-finite or degenerate tensors (see tensor_health); "
+              "the figures above do not measure the stated workload.", file=sys.stderr)
+        sys.exit(3)
 
 
 if __name__ == "__main__":

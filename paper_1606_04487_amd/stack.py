@@ -142,3 +142,35 @@ class ConvStack:
         self.backward(dOut)
         self.sgd_step(lr, momentum, weight_decay)
         return out
+
+    # ------------------------------------------------------------------ state checks (plumbing, after a run)
+    def tensor_health(self, W_start: Optional[Sequence[torch.Tensor]] = None) -> dict:
+        """Finiteness and spread of the tensors the last step left: parameters, velocities, gradients, every
+        layer's output and the last data gradient.  Reads tensors back with torch; no part of a step."""
+        torch.cuda.synchronize()
+        last_dx = next((d for d in self.dXl if d is not None), None)
+        state = list(self.W) + list(self.b) + list(self.VW) + list(self.Vb) + list(self.dW) + list(self.db) + list(self.Y)
+        if last_dx is not None:
+            state.append(last_dx)
+        h = {
+            "finite": all(bool(torch.isfinite(t.float()).all()) for t in state),
+            "zero_fraction_Y": [round(float((y == 0).float().mean()), 4) for y in self.Y],
+            "max_abs_Y": [float(y.float().abs().max()) for y in self.Y],
+            "max_abs_W": [float(w.abs().max()) for w in self.W],
+            "std_W": [float(w.std()) for w in self.W],
+            "max_abs_dW": [float(g.abs().max()) for g in self.dW],
+        }
+        if W_start is not None:
+            h["max_abs_W_change"] = [float((w - w0).abs().max()) for w, w0 in zip(self.W, W_start)]
+        if last_dx is not None:
+            h["max_abs_dX_last"] = float(last_dx.float().abs().max())
+            h["zero_fraction_dX_last"] = round(float((last_dx == 0).float().mean()), 4)
+        return h
+
+    @staticmethod
+    def health_is_degenerate(h: dict, sigma: float = 0.01) -> bool:
+        """True if a step ran on tensors that no longer look like the workload: something not finite, a layer
+        whose ReLU output is (almost) all zero, vanished gradients, or weights that left N(0, sigma)."""
+        return (not h["finite"] or any(z > 0.9 for z in h["zero_fraction_Y"]) or any(m == 0.0 for m in h["max_abs_dW"])
+                or h.get("max_abs_dX_last", 1.0) == 0.0
+                or any(not (0.5 * sigma < sd < 2.0 * sigma) for sd in h["std_W"]))

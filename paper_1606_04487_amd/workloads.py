@@ -81,6 +81,20 @@ def caffenet_stack(N: int = 256) -> List[ConvLayer]:
     ]
 
 
+def step_upstream_scale(N: int) -> float:
+    """Power of two that the N(0,1) upstream gradient of a REPEATED training step is multiplied with.
+
+    The stack's objective <output, dOut> is linear in the output and multilinear in the layers' weights,
+    and the model gradients are summed over the batch (Sec. II-B), so momentum steps with the unscaled
+    draw grow the weights without bound: at batch 256 with lr 0.01 and momentum 0.9 every weight is NaN
+    after four steps.  Times 2^-18 / N (N rounded up to a power of two) one step moves a weight by about
+    1e-7 of its standard deviation, so tens of thousands of steps leave every tensor in the distribution it was
+    drawn from.  A power of two changes exponents only: the values keep the mantissas of the seeded draw
+    in fp32 and in bf16."""
+    import math
+    return 2.0 ** -(18 + max(0, math.ceil(math.log2(N))))
+
+
 def to_bf16_values(a: np.ndarray) -> np.ndarray:
     """Round a float32 array to the nearest bf16 value (ties to even); returned as float32."""
     import torch

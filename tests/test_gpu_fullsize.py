@@ -159,3 +159,31 @@ def test_caffenet_conv2_to_conv5_chained_batch256(B, dtype):
 def test_caffenet_full_stack_bf16_batch_sweep(B, N):
     # the configuration the bench times (N = 256), and the smaller batches of the sweep
     check_stack(B, wl.caffenet_stack(N), 1, False, "normal", seed=3, skip_first_dgrad=True)
+
+
+def test_repeated_steps_stay_finite_and_in_distribution(B):
+    # the bench's loop (forward, backward, momentum update on the same batch) at batch 16: thirty steps must
+    # leave every tensor finite, every layer's output alive and the weights where they were drawn
+    from paper_1606_04487_amd.stack import ConvStack
+    N = 16
+    layers = wl.caffenet_stack(N)
+    st = ConvStack(layers, dtype=1, ceil_mode=False, skip_first_dgrad=True)
+    data = wl.stack_tensors(layers, seed=1, bf16=True, pooled_out=st.output_shape()[-2:])
+    st.set_parameters(data["W"], data["bias"])
+    X = gpu(data["X"], 1)
+    dOut = (torch.from_numpy(data["dY"]).cuda() * wl.step_upstream_scale(N)).to(torch.bfloat16)
+    W0 = [w.clone() for w in st.W]
+    first = None
+    for step in range(30):
+        st.step(X, dOut, 0.01, 0.9)
+        if step == 0:
+            first = st.tensor_health(W0)
+    h = st.tensor_health(W0)
+    assert h["finite"] and not ConvStack.health_is_degenerate(h), h
+    assert all(0.3 < z < 0.7 for z in h["zero_fraction_Y"]), h      # ReLU of a zero-mean input: about half
+    assert all(c <= 0.01 * 0.01 for c in h["max_abs_W_change"]), h  # under a hundredth of sigma after 30 steps
+    assert all(c > 0 for c in h["max_abs_W_change"]), h             # but the update did move the weights
+    for a, b in zip(first["max_abs_Y"], h["max_abs_Y"]):
+        assert abs(a - b) <= 0.05 * a, (first, h)
+    del st
+    torch.cuda.empty_cache()

@@ -129,6 +129,25 @@ int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, 
                       void *Y, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * omni_conv_forward for callers that cannot allocate device memory and have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the
+ * workspace), same kernels and bit-identical results; the scratch is an array of OMNI_STATIC_SCRATCH_BYTES that
+ * is part of the library's device code, so every GPU the library runs on holds one copy of it from load time
+ * until the process ends.  The call itself allocates nothing and frees nothing (keep omni_profile_enable off:
+ * profiling creates events).  omni_conv_static_scratch_need (host only) tells how many bytes of scratch the path
+ * this descriptor takes would use: the repacked weights of a fused pass, or D-hat + K-hat (+ split partials) of
+ * the explicit path.  A layer that needs more than OMNI_STATIC_SCRATCH_BYTES is refused with
+ * OMNI_WORKSPACE_TOO_SMALL before anything is launched; use omni_conv_forward with a workspace for it.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on the same GPU (two streams, two threads)
+ * race on it and must be ordered by the caller.  Nothing in the array has to be zero beforehand: each call
+ * writes every byte it later reads, so the previous call's contents never matter.
+ */
+#define OMNI_STATIC_SCRATCH_BYTES (32u << 20)
+int omni_conv_static_scratch_need(const omni_conv_desc *desc, size_t *bytes);
+int omni_conv_forward_static(const omni_conv_desc *desc, const void *X, const void *W, const float *bias,
+                             void *Y, void *hip_stream);
+
+/*
  * Forward pass with partial batching (Sec. III-B, "Batching and Data Parallelism": b_p of the b images are
  * lowered and multiplied at a time; App. C, Fig. (b), (c): the lowered data grows linearly with b_p and one
  * large product beats many small ones).  Runs omni_conv_forward's explicit path on consecutive groups of

@@ -28,7 +28,7 @@ FLAG_RELU, FLAG_DHAT_CACHED, FLAG_FUSED, FLAG_SPLIT_K = 1, 2, 4, 8
 
 SYMBOLS = [
     "omni_conv_output_dims", "omni_conv_dhat_ld", "omni_conv_workspace_bytes", "omni_conv_fused_supported",
-    "omni_conv_forward", "omni_conv_forward_partial",
+    "omni_conv_forward", "omni_conv_forward_partial", "omni_conv_forward_static", "omni_conv_static_scratch_need",
     "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
     "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward", "omni_status_string", "omni_version",
@@ -63,6 +63,8 @@ _lib.omni_conv_output_dims.argtypes = [_dp, ctypes.POINTER(_i32), ctypes.POINTER
 _lib.omni_conv_dhat_ld.argtypes = [_dp, ctypes.POINTER(_i64)]
 _lib.omni_conv_fused_supported.argtypes = [_dp, ctypes.c_int]
 _lib.omni_conv_forward_partial.argtypes = [_dp, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.omni_conv_forward_static.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp]
+_lib.omni_conv_static_scratch_need.argtypes = [_dp, ctypes.POINTER(_sz)]
 _lib.omni_conv_workspace_bytes.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(_sz)]
 _lib.omni_conv_forward.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.omni_conv_backward_data.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -173,6 +175,22 @@ def conv_forward(desc: ConvDesc, X, W, bias=None, Y=None, workspace=None):
         workspace = alloc_workspace(desc, PASS_FORWARD, X.device)
     _check(_lib.omni_conv_forward(ctypes.byref(desc), _p(X), _p(W), _p(bias), _p(Y), _p(workspace),
                                   workspace.numel(), _stream()))
+    return Y
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def conv_static_scratch_need(desc: ConvDesc) -> int:
+    b = _sz()
+    _check(_lib.omni_conv_static_scratch_need(ctypes.byref(desc), ctypes.byref(b)))
+    return b.value
+
+
+def conv_forward_static(desc: ConvDesc, X, W, bias, Y):
+    """omni_conv_forward_static: the forward pass on the library's own static scratch; allocates nothing
+    (the caller passes the output tensor)."""
+    _check(_lib.omni_conv_forward_static(ctypes.byref(desc), _p(X), _p(W), _p(bias), _p(Y), _stream()))
     return Y
 
 

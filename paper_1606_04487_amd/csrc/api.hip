@@ -1,6 +1,8 @@
 // C ABI of the library: argument checks, workspace carving and the launch sequence of each pass.
 // Everything before the first launch is plain host code, so every error path can be exercised on a
 // machine without a GPU.
+#include <mutex>
+
 #include "common.h"
 
 namespace omni {
@@ -75,6 +77,7 @@ void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w)
     w->partials = w->khat + align256((size_t)w->Fp * w->Kp * e);
     plan_split_k(g, dtype, g.F, w->ld, g.K, &w->splits, &w->chunk);
     w->total = w->partials + align256(w->splits > 1 ? (size_t)w->splits * g.F * w->ld * sizeof(float) : 0);
+    w->explicit_total = w->total;
     // the fused path keeps only its repacked weights here
     if (fused_supported(g, dtype, false) && fused_weight_bytes(g, false) > w->total) w->total = align256(fused_weight_bytes(g, false));
     if (strided_supported(g, dtype) && strided_weight_bytes(g) > w->total) w->total = align256(strided_weight_bytes(g));
@@ -252,6 +255,34 @@ int omni_conv_fused_supported(const omni_conv_desc *desc, int pass)
     return OMNI_INVALID_ARGUMENT;
 }
 
+// The forward pass on checked arguments.  `avail` bytes of scratch at `ws`: each path checks what IT needs
+// (the fused kernels only their repacked weights, the explicit path D-hat, K-hat and the split partials).
+static int forward_on_scratch(const omni_conv_desc *desc, const ConvGeom &g, const ForwardWs &w, const void *X, const void *W,
+                              const float *bias, void *Y, char *ws, size_t avail, hipStream_t s)
+{
+    const int relu = (desc->flags & OMNI_FLAG_RELU) ? 1 : 0;
+    if ((desc->flags & OMNI_FLAG_FUSED) && fused_supported(g, desc->dtype, false)) {
+        if (avail < fused_weight_bytes(g, false)) return OMNI_WORKSPACE_TOO_SMALL;
+        return launch_fused_conv(g, false, X, W, bias, relu, Y, ws, s);
+    }
+    if ((desc->flags & OMNI_FLAG_FUSED) && strided_supported(g, desc->dtype)) {
+        if (avail < strided_weight_bytes(g)) return OMNI_WORKSPACE_TOO_SMALL;
+        return launch_strided_conv(g, X, W, bias, relu, Y, ws, s);
+    }
+    if (avail < w.explicit_total) return OMNI_WORKSPACE_TOO_SMALL;
+    void *Dhat = ws + w.dhat, *Khat = ws + w.khat;
+    int st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
+    if (st != OMNI_OK) return st;
+    // K-hat is W with every row zero-padded to whole reduction steps: where there is nothing to pad, W itself
+    const bool w_is_khat = w.Kp == g.K && w.Fp == g.F;
+    if (!w_is_khat) {
+        st = launch_pack_khat(g, desc->dtype, W, Khat, w.Fp, w.Kp, s);
+        if (st != OMNI_OK) return st;
+    }
+    GemmFwdArgs a{w_is_khat ? W : Khat, w.Kp, Dhat, w.ld, bias, Y, relu, (float *)(ws + w.partials), w.splits, w.chunk};
+    return launch_gemm_forward(g, desc->dtype, a, s);
+}
+
 int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, const float *bias, void *Y,
                       void *workspace, size_t workspace_bytes, void *hip_stream)
 {
@@ -264,26 +295,69 @@ int omni_conv_forward(const omni_conv_desc *desc, const void *X, const void *W, 
     ForwardWs w;
     plan_forward(g, desc->dtype, &w);
     if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
-    hipStream_t s = (hipStream_t)hip_stream;
-    char *ws = (char *)workspace;
-    void *Dhat = ws + w.dhat, *Khat = ws + w.khat;
+    return forward_on_scratch(desc, g, w, X, W, bias, Y, (char *)workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
 
-    if ((desc->flags & OMNI_FLAG_FUSED) && fused_supported(g, desc->dtype, false) &&
-        fused_weight_bytes(g, false) <= w.total)
-        return launch_fused_conv(g, false, X, W, bias, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0, Y, ws, s);
-    if ((desc->flags & OMNI_FLAG_FUSED) && strided_supported(g, desc->dtype) && strided_weight_bytes(g) <= w.total)
-        return launch_strided_conv(g, X, W, bias, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0, Y, ws, s);
+// ---------------------------------------------------------------- the forward pass on the library's own scratch
+// One array per GPU, part of the loaded code object: it exists from the moment the library is loaded on a
+// device until the process ends, and no call ever allocates it.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; kernels and copies get the device address looked up below.
+static __device__ __align__(256) unsigned char scratch[OMNI_STATIC_SCRATCH_BYTES];
 
-    st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
-    if (st != OMNI_OK) return st;
-    // K-hat is W with every row zero-padded to whole reduction steps: where there is nothing to pad, W itself
-    const bool w_is_khat = w.Kp == g.K && w.Fp == g.F;
-    if (!w_is_khat) {
-        st = launch_pack_khat(g, desc->dtype, W, Khat, w.Fp, w.Kp, s);
-        if (st != OMNI_OK) return st;
+static const int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices];  // per device: the address of that GPU's copy of the array
+
+// The current device's copy of the array (looked up once per device), or null if HIP refuses.
+static char *static_scratch_base()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
     }
-    GemmFwdArgs a{w_is_khat ? W : Khat, w.Kp, Dhat, w.ld, bias, Y, (desc->flags & OMNI_FLAG_RELU) ? 1 : 0, (float *)(ws + w.partials), w.splits, w.chunk};
-    return launch_gemm_forward(g, desc->dtype, a, s);
+    return (char *)g_scratch_ptr[dev];
+}
+
+int omni_conv_forward_static(const omni_conv_desc *desc, const void *X, const void *W, const float *bias, void *Y,
+                             void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (X == nullptr || W == nullptr || Y == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || (bias && !aligned16(bias))) return OMNI_MISALIGNED;
+    ForwardWs w;
+    plan_forward(g, desc->dtype, &w);
+    size_t need = 0;
+    st = omni_conv_static_scratch_need(desc, &need);
+    if (st != OMNI_OK) return st;
+    if (need > (size_t)OMNI_STATIC_SCRATCH_BYTES) return OMNI_WORKSPACE_TOO_SMALL;  // before any HIP call
+    char *ws = static_scratch_base();
+    if (ws == nullptr) return OMNI_HIP_ERROR;
+    // Nothing in the scratch has to start at zero: every path writes each byte it later reads (D-hat with its
+    // padded columns, K-hat with its padding, the repacked weights with their padded rows) in this very call.
+    return forward_on_scratch(desc, g, w, X, W, bias, Y, ws, (size_t)OMNI_STATIC_SCRATCH_BYTES, (hipStream_t)hip_stream);
+}
+
+int omni_conv_static_scratch_need(const omni_conv_desc *desc, size_t *bytes)
+{
+    if (bytes == nullptr) return OMNI_INVALID_ARGUMENT;
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    ForwardWs w;
+    plan_forward(g, desc->dtype, &w);
+    if ((desc->flags & OMNI_FLAG_FUSED) && fused_supported(g, desc->dtype, false)) *bytes = fused_weight_bytes(g, false);
+    else if ((desc->flags & OMNI_FLAG_FUSED) && strided_supported(g, desc->dtype)) *bytes = strided_weight_bytes(g);
+    else *bytes = w.explicit_total;
+    return OMNI_OK;
 }
 
 int omni_conv_forward_partial(const omni_conv_desc *desc, int32_t b_p, const void *X, const void *W,

@@ -86,7 +86,8 @@ inline int64_t dhat_ld(const ConvGeom &g) { return round_up(g.M, 64); }
 // ---------------------------------------------------------------- workspace carving
 // splits > 1 (OMNI_FLAG_SPLIT_K): the reduction is cut into `splits` chunks of `chunk` whose fp32 partial
 // results [splits][rows][ld] live at `partials`
-struct ForwardWs { size_t dhat, khat, partials, total; int64_t ld, Fp, Kp; int splits; int64_t chunk; };
+// explicit_total: what lowering + GEMM alone need (total also covers the fused kernels' repacked weights)
+struct ForwardWs { size_t dhat, khat, partials, total, explicit_total; int64_t ld, Fp, Kp; int splits; int64_t chunk; };
 struct BwdDataWs { size_t ddhat, dyhat, khat_t, partials, total; int64_t ld, Kp, Fp; int splits; int64_t chunk; };
 // *_rows: the same plan for the row-padded dY-hat of the direct model gradient (reduction extent ld_rows)
 struct BwdWeightsWs {

@@ -180,3 +180,20 @@ def test_which_passes_run_without_a_lowered_matrix(B):
     assert not B.conv_fused_supported(B.conv_desc(8, 3, 35, 35, 8, 11, 11, 4, 0, B.BF16, B.FLAG_FUSED), WG)   # Wo = 7
     for p in (F, DG, WG):
         assert B.conv_workspace_bytes(conv1, p) == B.conv_workspace_bytes(conv1.with_flags(0), p)
+
+
+def test_static_scratch_entry_refuses_on_the_host(B):
+    # argument and size checks of omni_conv_forward_static come before any HIP call
+    fake = ctypes.c_void_p(0x1000)
+    big = B.conv_desc(256, 96, 27, 27, 256, 5, 5, 1, 2, B.BF16)          # explicit path: D-hat of 900 MB
+    assert B.conv_static_scratch_need(big) > B.STATIC_SCRATCH_BYTES
+    assert B.raw().omni_conv_forward_static(ctypes.byref(big), fake, fake, None, fake, None) == -3
+    fused = big.with_flags(B.FLAG_FUSED)                                  # fused: only the repacked weights
+    assert 256 * 2400 * 2 <= B.conv_static_scratch_need(fused) <= B.STATIC_SCRATCH_BYTES
+    small = B.conv_desc(8, 3, 32, 32, 32, 5, 5, 1, 2, B.F32)
+    need = B.conv_static_scratch_need(small)
+    assert 75 * 8192 * 4 <= need <= B.conv_workspace_bytes(small, B.PASS_FORWARD) <= B.STATIC_SCRATCH_BYTES
+    assert B.raw().omni_conv_forward_static(ctypes.byref(small), None, fake, None, fake, None) == -1
+    assert B.raw().omni_conv_forward_static(ctypes.byref(small), ctypes.c_void_p(0x1004), fake, None, fake, None) == -4
+    bad = B.conv_desc(8, 3, 32, 32, 32, 5, 5, 1, 2, 7)
+    assert B.raw().omni_conv_forward_static(ctypes.byref(bad), fake, fake, None, fake, None) == -2

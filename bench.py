@@ -11,7 +11,14 @@ rate on a bounded sample of the same workload.
 Order of work: warm-up steps; a few instrumented steps with events around EVERY launch (they give the
 per-kernel table and name the dominant kernel class; the ~100 event records per step cost about a
 tenth of the step, so this pass is not the timed one); then the timed region, in which only the dominant
-class is bracketed by events -- its average launch duration in the roofline comes from there.
+class is bracketed by events -- its average launch duration in the roofline comes from there (when that
+class is one of the matrix-core classes, all of them are bracketed, so that the line also carries the
+rate of all the step's products together).
+
+The steps update the weights they run on.  The upstream gradient is the seeded N(0,1) draw times a power of
+two small enough that thousands of steps leave every tensor in its starting distribution; after the timed
+region the tensors are read back and checked (finite, ReLU outputs about half zero, weights still N(0, 0.01))
+and the run fails if they are not, so a figure from this script is a figure on the stated workload.
 """
 import argparse
 import json
@@ -26,14 +33,23 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
 MFMA_KERNELS = ("gemm", "conv_fused", "conv_strided")          # kernel classes bound by the matrix cores
-# HBM bytes per launch (fetched + written, averaged over the class's launches of one step) at the default
-# workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by the readings for
-# the 256 MiB calibration copy below; the summary and its commands are profiles/*_hbm_traffic.md.
-MEASURED_HBM_BYTES_PER_LAUNCH = {
-    ("bf16", 256): {"gemm_wgrad": 180.1e6, "conv_fused_forward": 100.0e6, "conv_fused_dgrad": 100.0e6,
-                    "conv_strided_forward": 253.1e6, "lower": 169.8e6, "maxpool_backward": 145.3e6,
-                    "pack_dyhat": 104.1e6, "reduce_partials": 55.3e6, "maxpool_forward": 121.4e6},
-}
+# HBM bytes per launch come from hbm_traffic.json in the package: rocprof_tables.py writes it from rocprofv3
+# --pmc FETCH_SIZE / WRITE_SIZE runs of this script (scaled by the readings for the 256 MiB calibration copy
+# below) together with a digest of the kernel sources; a table measured on other sources is not reported.
+
+
+def measured_traffic(workload: str):
+    """Kernel class -> measured HBM bytes per launch for this workload, or {} if none matches the built code."""
+    from paper_1606_04487_amd import rocprof_tables as rt
+    try:
+        entry = json.loads(rt.TRAFFIC_JSON.read_text()).get(workload)
+    except (OSError, ValueError):
+        return {}, "no traffic table"
+    if entry is None:
+        return {}, "no traffic table for this workload"
+    if entry.get("sources") != rt.sources_digest():
+        return {}, f"traffic table {entry.get('summary')} was measured on other kernel sources"
+    return entry["bytes_per_launch"], entry.get("summary")
 
 
 def host_cpu_model() -> str:
@@ -127,10 +143,11 @@ def main():
         B.profile_enable(False)
         dom = max(table_kernels, key=lambda n: table_kernels[n]["total_ms"])
 
-    # timed region: events around the dominant kernel class only
+    # timed region: events around the matrix-core kernel classes only (about 15 of a step's 45 launches)
+    mfma_classes = [n for n in table_kernels if n.startswith(MFMA_KERNELS)]
     if dom is not None:
         B.profile_enable(True)
-        B.profile_select(dom)
+        B.profile_select_many(mfma_classes if dom in mfma_classes else [dom])
     # one event between steps (on the stream the steps are launched on) for the median and the spread
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
@@ -152,29 +169,45 @@ def main():
     flops_step = sum(3 * L.gemm_flops for L in layers)   # App. B rule: 1.6 TFLOP at 256 without conv1's data gradient
     if not args.conv1_dgrad:
         flops_step -= layers[0].gemm_flops
-    roof = None
+    workload = f"caffenet_conv1-5_relu_pool_fwd+bwd+sgd_b{args.batch}_{args.dtype}"
+    traffic_table, traffic_src = measured_traffic(workload)
+    roof, roof_all = None, None
     table = {}
     for name, k in table_kernels.items():
         row = {"launches_per_step": k["launches"] / args.table_steps, "avg_ms": k["total_ms"] / k["launches"],
                "ms_per_step": k["total_ms"] / args.table_steps}
         if k["flops"] > 0 and name.startswith(MFMA_KERNELS):
             row["tflops"] = k["flops"] / (k["total_ms"] * 1e-3) / 1e12
-        row["gbs"] = k["bytes"] / (k["total_ms"] * 1e-3) / 1e9
+            row["frac_of_mfma_peak"] = row["tflops"] / PEAK_TFLOPS[args.dtype]
+        elif k["bytes"] > 0:
+            row["gbs"] = k["bytes"] / (k["total_ms"] * 1e-3) / 1e9
+            row["frac_of_hbm_peak"] = row["gbs"] / PEAK_HBM_GBS
         table[name] = row
+
+    def traffic_of(name):
+        return traffic_table.get("conv_fused" if name.startswith("conv_fused") else name)
+
     if dom is not None and dom in kernels:
         k = kernels[dom]                                   # the dominant class, timed inside the timed region
         avg_ms = k["total_ms"] / k["launches"]
-        traffic = MEASURED_HBM_BYTES_PER_LAUNCH.get((args.dtype, args.batch), {}).get(dom)
         if dom.startswith(MFMA_KERNELS):
             ach = k["flops"] / (k["total_ms"] * 1e-3) / 1e12
             roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_TFLOPS[args.dtype],
-                    "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS[args.dtype], "traffic": traffic,
-                    "avg_launch_ms": avg_ms, "launches_per_step": k["launches"] / args.steps,
+                    "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS[args.dtype], "traffic": traffic_of(dom),
+                    "traffic_source": traffic_src, "avg_launch_ms": avg_ms, "launches_per_step": k["launches"] / args.steps,
                     "flops_per_launch": k["flops"] / k["launches"]}
+            # every matrix-core class together (the products of all three passes of all five layers)
+            fl = sum(kernels[n]["flops"] for n in mfma_classes if n in kernels)
+            ms = sum(kernels[n]["total_ms"] for n in mfma_classes if n in kernels)
+            roof_all = {"kernels": sorted(n for n in mfma_classes if n in kernels), "bound": "mfma",
+                        "achieved": fl / (ms * 1e-3) / 1e12, "peak": PEAK_TFLOPS[args.dtype], "unit": "TFLOP/s",
+                        "frac": fl / (ms * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype], "ms_per_step": ms / args.steps,
+                        "per_class_frac": {n: kernels[n]["flops"] / (kernels[n]["total_ms"] * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype]
+                                           for n in mfma_classes if n in kernels}}
         else:
             ach = k["bytes"] / (k["total_ms"] * 1e-3) / 1e9
             roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": ach / PEAK_HBM_GBS, "traffic": traffic, "avg_launch_ms": avg_ms,
+                    "frac": ach / PEAK_HBM_GBS, "traffic": traffic_of(dom), "traffic_source": traffic_src, "avg_launch_ms": avg_ms,
                     "launches_per_step": k["launches"] / args.steps, "bytes_per_launch": k["bytes"] / k["launches"]}
 
     # the tensors the timed steps ran on: finite, not degenerate, weights still where they were drawn
@@ -188,13 +221,13 @@ def main():
         "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "ms_per_step_median": median_ms, "ms_per_step_cv": cv, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": f"caffenet_conv1-5_relu_pool_fwd+bwd+sgd_b{args.batch}_{args.dtype}",
+        "config": {"workload": workload,
                    "global_batch": args.batch, "conv1_data_gradient": bool(args.conv1_dgrad),
                    "lr": lr, "momentum": mu, "upstream_gradient": f"N(0,1) draw x 2^{int(math.log2(grad_scale))}"},
         "tensor_health": health,
         "tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
         "mfma_frac_of_peak_whole_step": flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype],
-        "roofline": roof, "cpu_baseline": cpu,
+        "roofline": roof, "roofline_all_mfma_kernels": roof_all, "cpu_baseline": cpu,
         "kernels_note": f"per-kernel table from {args.table_steps} instrumented steps before the timed region",
         "kernels": table,
     }

@@ -250,11 +250,13 @@ int omni_maxpool_relu_backward(int32_t dtype, int64_t planes, int32_t H, int32_t
  * Kernel classes are numbered 0 .. omni_profile_kernel_count()-1 and named by
  * omni_profile_kernel_name.  omni_profile_select(k) restricts recording to kernel class k (the two events
  * around a launch cost a few microseconds of stream time each, which adds up over a step's ~50 launches);
- * -1 records all again, and so does every omni_profile_enable call.  Host memory only; not thread-safe
- * against concurrent launches.
+ * -1 records all again, and so does every omni_profile_enable call.  omni_profile_select_mask records the
+ * classes whose bit (1 << kernel class) is set, e.g. all matrix-core classes.  Host memory only; not
+ * thread-safe against concurrent launches.
  */
 int omni_profile_enable(int on);
 int omni_profile_select(int kernel_id);
+int omni_profile_select_mask(uint64_t mask);
 int omni_profile_kernel_count(void);
 const char *omni_profile_kernel_name(int kernel_id);
 int omni_profile_summary(int kernel_id, int64_t *launches, double *total_ms, double *flops,

@@ -32,7 +32,7 @@ SYMBOLS = [
     "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
     "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward", "omni_status_string", "omni_version",
-    "omni_profile_enable", "omni_profile_select", "omni_profile_kernel_count", "omni_profile_kernel_name", "omni_profile_summary",
+    "omni_profile_enable", "omni_profile_select", "omni_profile_select_mask", "omni_profile_kernel_count", "omni_profile_kernel_name", "omni_profile_summary",
 ]
 
 
@@ -82,6 +82,7 @@ _lib.omni_maxpool_relu_backward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, 
 
 
 _lib.omni_profile_enable.argtypes = [ctypes.c_int]
+_lib.omni_profile_select_mask.argtypes = [ctypes.c_uint64]
 _lib.omni_profile_kernel_name.restype = ctypes.c_char_p
 _lib.omni_profile_kernel_name.argtypes = [ctypes.c_int]
 _lib.omni_profile_summary.argtypes = [ctypes.c_int, ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_double),
@@ -340,6 +341,15 @@ def profile_select(kernel_name: Optional[str]) -> None:
         return
     names = [_lib.omni_profile_kernel_name(i).decode() for i in range(_lib.omni_profile_kernel_count())]
     _check(_lib.omni_profile_select(names.index(kernel_name)))
+
+
+def profile_select_many(kernel_names) -> None:
+    """omni_profile_select_mask: record events for the named kernel classes only."""
+    names = [_lib.omni_profile_kernel_name(i).decode() for i in range(_lib.omni_profile_kernel_count())]
+    mask = 0
+    for n in kernel_names:
+        mask |= 1 << names.index(n)
+    _check(_lib.omni_profile_select_mask(ctypes.c_uint64(mask)))
 
 
 def profile_summary() -> dict:

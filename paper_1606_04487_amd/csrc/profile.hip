@@ -22,10 +22,11 @@ struct Record { int kid; hipEvent_t start, stop; double flops, bytes; };
 
 static std::mutex g_mu;
 static bool g_on = false;
-static int g_only = -1;  // record this kernel class only (-1: all)
+static uint64_t g_mask = ~0ull;  // kernel classes that are recorded (bit k = class k)
 static std::vector<Record> g_records;
 static std::vector<hipEvent_t> g_free;
 static const size_t kMaxRecords = 1u << 20;
+static_assert(KID_COUNT <= 64, "kernel classes fit the selection mask");
 
 bool profile_enabled() { return g_on; }
 
@@ -43,7 +44,7 @@ static hipEvent_t get_event()
 
 ProfScope::ProfScope(int kid, hipStream_t s, double flops, double bytes) : slot_(-1), stream_(s)
 {
-    if (!g_on || (g_only >= 0 && kid != g_only)) return;
+    if (!g_on || !((g_mask >> kid) & 1ull)) return;
     std::lock_guard<std::mutex> lock(g_mu);
     if (g_records.size() >= kMaxRecords) return;
     Record r{kid, get_event(), get_event(), flops, bytes};
@@ -75,7 +76,7 @@ int omni_profile_enable(int on)
     }
     g_records.clear();
     g_on = on != 0;
-    g_only = -1;
+    g_mask = ~0ull;
     return OMNI_OK;
 }
 
@@ -83,7 +84,14 @@ int omni_profile_select(int kernel_id)
 {
     if (kernel_id < -1 || kernel_id >= KID_COUNT) return OMNI_INVALID_ARGUMENT;
     std::lock_guard<std::mutex> lock(g_mu);
-    g_only = kernel_id;
+    g_mask = kernel_id < 0 ? ~0ull : (1ull << kernel_id);
+    return OMNI_OK;
+}
+
+int omni_profile_select_mask(uint64_t mask)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_mask = mask;
     return OMNI_OK;
 }
 

@@ -1,0 +1,219 @@
+"""Turn rocprofv3 CSV output of a bench run into the short tables kept under profiles/.
+
+Three sub-commands, each reading what one kind of rocprofv3 run wrote (`--output-format csv`):
+
+    stats     <kernel_stats.csv> <bench stdout>   per-class and per-kernel durations next to the library's own
+                                                   event timing (from the JSON line the profiled run printed)
+    traffic   <FETCH_SIZE csv> <WRITE_SIZE csv>    HBM bytes per kernel class, each counter scaled by what it read
+                                                   for the 256 MiB device copy bench.py makes first; also updates
+                                                   hbm_traffic.json beside this file, which bench.py reads for
+                                                   `roofline.traffic`
+    counters  <pmc csv> [<pmc csv> ...]            SQ counters of the matrix-core kernels
+
+Every table starts with the full command that produced its input.  Host-side text processing only.
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import hashlib
+import json
+import re
+from pathlib import Path
+
+HERE = Path(__file__).resolve().parent
+TRAFFIC_JSON = HERE / "hbm_traffic.json"
+CAL_KIB = 262144.0   # the calibration copy of bench.py: 256 MiB read, 256 MiB written
+
+
+def kernel_class(name: str):
+    """Kernel function name -> the library's timing class (the names omni_profile_kernel_name returns)."""
+    if "fused_conv_kernel" in name:
+        return "conv_fused"
+    if "strided_conv_kernel" in name:
+        return "conv_strided_forward"
+    if "PartialEpilogue" in name or "wgrad_kernel" in name:
+        return "gemm_wgrad"
+    if "FwdEpilogue" in name and "gemm" in name:
+        return "gemm_forward"
+    if "RowMajorEpilogue" in name:
+        return "gemm_dgrad"
+    for key, cls in (("phase_split", "lower"), ("phase_merge", "col2im"), ("lower_", "lower"), ("col2im", "col2im"),
+                     ("pack_dyhat", "pack_dyhat"), ("pack_weights", "pack_khat"), ("pack_strided_weights", "pack_khat"),
+                     ("dgrad_phase_weights", "pack_khat"), ("pack_khat", "pack_khat"), ("bias_reduce", "bias_reduce"),
+                     ("reduce_partials", "reduce_partials"), ("reduce_store", "reduce_partials"),
+                     ("maxpool_fwd", "maxpool_forward"), ("maxpool_bwd", "maxpool_backward"),
+                     ("maxpool_forward", "maxpool_forward"), ("maxpool_backward", "maxpool_backward"),
+                     ("relu", "relu"), ("sgd", "sgd"), ("lrn", "lrn"), ("dropout", "dropout")):
+        if key in name:
+            return cls
+    return None
+
+
+def short_name(name: str) -> str:
+    n = re.sub(r"\(.*", "", name).replace("void ", "").replace("omni::", "")
+    return n.replace("unsigned short", "bf16")
+
+
+def sources_digest() -> str:
+    """Hash of the kernel sources: a traffic table is only reported for the code it was measured on."""
+    h = hashlib.sha256()
+    for f in sorted((HERE / "csrc").glob("*")):
+        if f.suffix in (".hip", ".h"):
+            h.update(f.name.encode())
+            h.update(f.read_bytes())
+    return h.hexdigest()[:16]
+
+
+def last_json_line(path: str) -> dict:
+    lines = [l for l in open(path) if l.startswith("{")]
+    return json.loads(lines[-1])
+
+
+def cmd_stats(a) -> None:
+    rows = list(csv.DictReader(open(a.csv)))
+    bench = last_json_line(a.bench_out)
+    steps = a.steps
+    agg = collections.OrderedDict()
+    for r in rows:
+        c = kernel_class(r["Name"])
+        if c is None:
+            continue
+        e = agg.setdefault(c, [0, 0.0])
+        e[0] += int(r["Calls"])
+        e[1] += float(r["TotalDurationNs"])
+    ev = bench.get("kernels", {})
+    with open(a.out, "w") as f:
+        f.write(f"# rocprofv3 kernel statistics: {a.title}\n\n")
+        f.write(f"Command (run from /tmp with TMPDIR=/tmp on one MI355X):\n\n    {a.command}\n\n")
+        f.write(f"The run makes {steps} steps (warm-up + instrumented + timed); the table divides by {steps}.  `bench events` is the same\n"
+                "class timed by the library's own HIP events in that very run (the `kernels` table of the JSON line it printed).\n")
+        roof = bench.get("roofline")
+        if roof:
+            f.write(f"Dominant class of that run, timed inside the timed region: {roof['kernel']}, avg launch "
+                    f"{roof['avg_launch_ms'] * 1e3:.1f} us, {roof['achieved']:.0f} {roof['unit']} = {roof['frac']:.3f} of peak.\n")
+        f.write(f"\nbench line of the profiled run: {bench['ms_per_step']:.3f} ms/step, {bench['value']:.0f} {bench['unit']} (profiler attached)\n\n")
+        f.write("| kernel class | launches/step | rocprofv3 avg us/launch | rocprofv3 ms/step | bench events ms/step |\n|---|---|---|---|---|\n")
+        for c, (calls, ns) in sorted(agg.items(), key=lambda kv: -kv[1][1]):
+            if c == "conv_fused":
+                e = sum(ev.get(k, {}).get("ms_per_step", 0.0) for k in ("conv_fused_forward", "conv_fused_dgrad"))
+            else:
+                e = ev.get(c, {}).get("ms_per_step", float("nan"))
+            f.write(f"| {c} | {calls / steps:.1f} | {ns / calls / 1e3:.1f} | {ns / steps / 1e6:.3f} | {e:.3f} |\n")
+        tot = sum(v[1] for v in agg.values()) / steps / 1e6
+        f.write(f"\nSum of the library's kernels: {tot:.3f} ms/step.\n\n")
+        f.write("Per kernel (names shortened):\n\n| kernel | class | calls | avg us | % of GPU time |\n|---|---|---|---|---|\n")
+        for r in rows:
+            c = kernel_class(r["Name"])
+            if c is None:
+                continue
+            f.write(f"| {short_name(r['Name'])} | {c} | {r['Calls']} | {float(r['AverageNs']) / 1e3:.1f} | {r['Percentage']} |\n")
+    print(open(a.out).read())
+
+
+def read_counter(path: str):
+    per_class = collections.defaultdict(list)
+    cal = 0.0
+    for r in csv.DictReader(open(path)):
+        v = float(r["Counter_Value"])
+        if "copyBuffer" in r["Kernel_Name"]:
+            cal = max(cal, v)
+        c = kernel_class(r["Kernel_Name"])
+        if c:
+            per_class[c].append(v)
+    return per_class, cal
+
+
+def cmd_traffic(a) -> None:
+    fe, fcal = read_counter(a.fetch)
+    wr, wcal = read_counter(a.write)
+    if fcal <= 0 or wcal <= 0:
+        raise SystemExit("no calibration copy found in the counter files")
+    ff, wf = CAL_KIB / fcal, CAL_KIB / wcal
+    steps = a.steps
+    table = {}
+    with open(a.out, "w") as f:
+        f.write(f"# HBM traffic per kernel class (rocprofv3 --pmc): {a.title}\n\n")
+        f.write("Commands (each from /tmp with TMPDIR=/tmp on one MI355X; one counter per run):\n\n")
+        f.write(f"    {a.command.replace('COUNTER', 'FETCH_SIZE')}\n    {a.command.replace('COUNTER', 'WRITE_SIZE')}\n\n")
+        f.write("Calibration: the program first copies 256 MiB (262144 KiB) device to device; for that copy kernel FETCH_SIZE read "
+                f"{fcal:.1f} and WRITE_SIZE read {wcal:.1f}, so counter values are scaled by {ff:.4f} (fetch) and {wf:.4f} (write) to KiB.\n\n")
+        f.write("| kernel class | launches/step | fetched MB/launch | written MB/launch | total MB/step |\n|---|---|---|---|---|\n")
+        total = 0.0
+        for c in sorted(fe, key=lambda c: -(sum(fe[c]) * ff + sum(wr.get(c, [0])) * wf)):
+            n = len(fe[c])
+            fb = sum(fe[c]) * ff * 1024 / n / 1e6
+            wb = sum(wr.get(c, [0])) * wf * 1024 / max(len(wr.get(c, [0])), 1) / 1e6
+            f.write(f"| {c} | {n / steps:.1f} | {fb:.1f} | {wb:.1f} | {(fb + wb) * n / steps:.0f} |\n")
+            table[c] = round((fb + wb) * 1e6)
+            total += (fb + wb) * n / steps
+        f.write(f"\nAll classes together: {total / 1e3:.2f} GB of HBM traffic per step.\n")
+    print(open(a.out).read())
+    if a.workload:
+        store = json.loads(TRAFFIC_JSON.read_text()) if TRAFFIC_JSON.exists() else {}
+        store[a.workload] = {"sources": sources_digest(), "summary": str(Path(a.out).name),
+                             "bytes_per_launch": table, "fetch_scale": ff, "write_scale": wf}
+        TRAFFIC_JSON.write_text(json.dumps(store, indent=1, sort_keys=True) + "\n")
+
+
+def cmd_counters(a) -> None:
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    for path in a.csv:
+        for r in csv.DictReader(open(path)):
+            agg[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    rows = []
+    for k, d in agg.items():
+        v = {c: sum(x) / len(x) for c, x in d.items()}
+        if v.get("SQ_INSTS_MFMA", 0) > 0:
+            n = len(d["GRBM_GUI_ACTIVE"])
+            rows.append((v["GRBM_GUI_ACTIVE"] * n, short_name(k), n / a.steps, v))
+    rows.sort(key=lambda r: -r[0])
+    with open(a.out, "w") as f:
+        f.write(f"# SQ counters of the matrix-core kernels (rocprofv3 --pmc): {a.title}\n\n")
+        f.write("Commands (each from /tmp with TMPDIR=/tmp on one MI355X; one counter set per run):\n\n")
+        for c in a.command:
+            f.write(f"    {c}\n")
+        f.write("\nAverages per launch.  `MFMA busy` = SQ_VALU_MFMA_BUSY_CYCLES / SQ_BUSY_CYCLES / 32: the counter adds up the SIMDs of a\n"
+                "shader engine, so 32 (8 compute units x 4 SIMDs) is every matrix core busy all the time.  `LDS conflicts` =\n"
+                "SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE (share of LDS-active cycles lost to bank conflicts).  `waiting` =\n"
+                "SQ_WAIT_INST_ANY / SQ_WAVE_CYCLES.  `VALU/MFMA`, `LDS/MFMA` = instructions issued per MFMA instruction.\n\n")
+        f.write("| kernel | launches/step | GRBM_GUI_ACTIVE | MFMA insts | VALU/MFMA | LDS/MFMA | VMEM_RD insts | MFMA busy | LDS conflicts | waiting |\n"
+                "|---|---|---|---|---|---|---|---|---|---|\n")
+        for _, name, n, v in rows:
+            mb = v["SQ_VALU_MFMA_BUSY_CYCLES"] / v["SQ_BUSY_CYCLES"] / 32
+            f.write(f"| {name} | {n:.1f} | {v['GRBM_GUI_ACTIVE']:.0f} | {v['SQ_INSTS_MFMA']:.0f} | "
+                    f"{v['SQ_INSTS_VALU'] / v['SQ_INSTS_MFMA']:.1f} | {v['SQ_INSTS_LDS'] / v['SQ_INSTS_MFMA']:.2f} | {v['SQ_INSTS_VMEM_RD']:.0f} | "
+                    f"{mb:.2f} | {v['SQ_LDS_BANK_CONFLICT'] / max(v['SQ_LDS_IDX_ACTIVE'], 1):.2f} | "
+                    f"{v['SQ_WAIT_INST_ANY'] / v['SQ_WAVE_CYCLES']:.2f} |\n")
+        if a.reading:
+            f.write("\n" + a.reading + "\n")
+    print(open(a.out).read())
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="what", required=True)
+    s = sub.add_parser("stats")
+    s.add_argument("csv"), s.add_argument("bench_out")
+    s.add_argument("--steps", type=int, required=True), s.add_argument("--out", required=True)
+    s.add_argument("--title", required=True), s.add_argument("--command", required=True)
+    s.set_defaults(fn=cmd_stats)
+    t = sub.add_parser("traffic")
+    t.add_argument("fetch"), t.add_argument("write")
+    t.add_argument("--steps", type=int, required=True), t.add_argument("--out", required=True)
+    t.add_argument("--title", required=True), t.add_argument("--command", required=True, help="with COUNTER where the counter name goes")
+    t.add_argument("--workload", default="", help="key under which bench.py finds the table (its config.workload)")
+    t.set_defaults(fn=cmd_traffic)
+    c = sub.add_parser("counters")
+    c.add_argument("csv", nargs="+")
+    c.add_argument("--steps", type=int, required=True), c.add_argument("--out", required=True)
+    c.add_argument("--title", required=True), c.add_argument("--command", action="append", required=True)
+    c.add_argument("--reading", default="")
+    c.set_defaults(fn=cmd_counters)
+    a = ap.parse_args()
+    a.fn(a)
+
+
+if __name__ == "__main__":
+    main()

@@ -176,8 +176,7 @@ int omni_conv_backward_data(const omni_conv_desc *desc, const void *dY, const vo
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Model gradient, summed over the batch with no 1/N (Sec. II-B: "gradients from each tuple are
- * summed").  Steps: lowering of X (skipped with OMNI_FLAG_DHAT_CACHED), packing of dY, one MFMA
+ * Model gradient, summed over the images of the batch with no 1/N (Sec. II-B).  Steps: lowering of X (skipped with OMNI_FLAG_DHAT_CACHED), packing of dY, one MFMA
  * GEMM dK-hat[F x K] = dY-hat[F x M] * D-hat^T[M x K] split along M over the chip with a second,
  * ordered reduction stage.  dW is fp32 [F][C][kh][kw]; dbias (nullable) is fp32 [F] and receives
  * the plain sum of dY over images and pixels.

@@ -255,3 +255,63 @@ def conv_flops(N, C, H, W, F, kh, kw=None, stride=1, pad=0):
     s = shape(N, C, H, W, F, kh, kw, stride, pad)
     ho, wo = out_dims(s)
     return 2 * (s.N * ho * wo) * (s.C * s.kh * s.kw) * s.F
+
+
+def lrn_forward(x, size=5, alpha=1e-4, beta=0.75, k=1.0):
+    """Local response normalisation across channels of x [N][C][...]:
+    y = x * (k + alpha/size * sum over the channel window of x^2)^(-beta)."""
+    if size % 2 != 1:
+        raise ValueError("the channel window must have an odd size")
+    x, xp = _f32(x)
+    N, C = x.shape[:2]
+    plane = int(np.prod(x.shape[2:], dtype=np.int64))
+    y = np.empty(x.shape, dtype=np.float64)
+    _load().oc_lrn_forward(ctypes.c_int64(N), ctypes.c_int64(C), ctypes.c_int64(plane), ctypes.c_int32(size),
+                           ctypes.c_double(alpha), ctypes.c_double(beta), ctypes.c_double(k), xp, _ptr(y))
+    return y
+
+
+def lrn_backward(x, dy, size=5, alpha=1e-4, beta=0.75, k=1.0):
+    """Gradient of lrn_forward w.r.t. x given the gradient dy w.r.t. its output."""
+    if size % 2 != 1:
+        raise ValueError("the channel window must have an odd size")
+    x, xp = _f32(x)
+    dy, gp = _f32(dy)
+    N, C = x.shape[:2]
+    plane = int(np.prod(x.shape[2:], dtype=np.int64))
+    dx = np.empty(x.shape, dtype=np.float64)
+    _load().oc_lrn_backward(ctypes.c_int64(N), ctypes.c_int64(C), ctypes.c_int64(plane), ctypes.c_int32(size),
+                            ctypes.c_double(alpha), ctypes.c_double(beta), ctypes.c_double(k), xp, gp, _ptr(dx))
+    return dx
+
+
+def philox4x64(counter, key):
+    """One block of Philox4x64-10: four 64-bit words from a 4-word counter and a 2-word key."""
+    c = (ctypes.c_uint64 * 4)(*[int(v) for v in counter])
+    k = (ctypes.c_uint64 * 2)(*[int(v) for v in key])
+    out = (ctypes.c_uint64 * 4)()
+    _load().oc_philox4x64(c, k, out)
+    return [int(v) for v in out]
+
+
+def dropout_threshold(p):
+    lib = _load()
+    lib.oc_dropout_threshold.restype = ctypes.c_uint32
+    return int(lib.oc_dropout_threshold(ctypes.c_double(p)))
+
+
+def dropout_mask(count, p, seed, stream=0):
+    """uint8 keep-mask of `count` elements (1 = kept) for drop probability p."""
+    keep = np.empty(int(count), dtype=np.uint8)
+    _load().oc_dropout_mask(ctypes.c_int64(count), ctypes.c_double(p), ctypes.c_uint64(seed), ctypes.c_uint64(stream),
+                            _ptr(keep))
+    return keep
+
+
+def dropout_apply(x, p, seed, stream=0):
+    """keep ? x / (1 - p) : 0 elementwise over the flattened x; serves forward (x) and backward (dy)."""
+    x, xp = _f32(x)
+    y = np.empty(x.shape, dtype=np.float64)
+    _load().oc_dropout_apply(ctypes.c_int64(x.size), ctypes.c_double(p), ctypes.c_uint64(seed), ctypes.c_uint64(stream),
+                             xp, _ptr(y))
+    return y

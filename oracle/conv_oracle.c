@@ -26,6 +26,8 @@
  *   update ............. Sec. II-B, Eq. (update1), (update2).
  *   ReLU / max-pool .... named only (App. C, "Data Parallelism in non-GEMM Kernels"); the
  *                        tie and border rules are this build's readings.
+ *   normalisation, dropout  named in the same passage; formulas and the random generator are
+ *                        readings stated above the routines.
  *
  * Layouts: X [N][C][H][W], Wt [F][C][kh][kw], Y [N][F][Ho][Wo], all contiguous.
  * D-hat is row-major [C*kh*kw][N*Ho*Wo]: row (c*kh+ky)*kw+kx, column (n*Ho+oy)*Wo+ox.
@@ -399,5 +401,141 @@ void oc_sgd_momentum(int64_t count, const float *W0, const float *V0, const floa
         double v = mu * (double)V0[i] - lr * ((double)G[i] + lambda * (double)W0[i]);
         V1[i] = v;
         W1[i] = (double)W0[i] + v;
+    }
+}
+
+/*
+ * Local response normalisation across channels and dropout: the two remaining non-GEMM layers
+ * of the paper's CaffeNet runs (App. C, "Data Parallelism in non-GEMM Kernels" names them
+ * next to pooling and ReLU; the paper gives no formula).  Reading: the normalisation of the
+ * AlexNet network the paper trains, in the convention of the framework whose outputs the paper
+ * matches layer by layer (the window sum is scaled by alpha / size, and channels beyond the
+ * ends count as zero):
+ *     s[n,c,p] = k + (alpha / size) * sum_{|c' - c| <= (size-1)/2, 0 <= c' < C} x[n,c',p]^2     (size odd)
+ *     y[n,c,p] = x[n,c,p] * s[n,c,p]^(-beta)
+ * and its gradient
+ *     dx[n,c,p] = dy[n,c,p] * s[n,c,p]^(-beta)
+ *                 - (2 alpha beta / size) * x[n,c,p] * sum_{c' : c in window(c')} dy[n,c',p] * x[n,c',p] * s[n,c',p]^(-beta-1)
+ * x is [N][C][plane].
+ */
+static double lrn_scale(const float *x, int64_t C, int64_t plane, int64_t n, int64_t c, int64_t p,
+                        int32_t size, double alpha, double k)
+{
+    double acc = 0.0;
+    int64_t lo = c - (size - 1) / 2, hi = c + (size - 1) / 2;  /* size is odd */
+    for (int64_t cc = lo; cc <= hi; ++cc) {
+        if (cc < 0 || cc >= C)
+            continue;
+        double v = (double)x[(n * C + cc) * plane + p];
+        acc += v * v;
+    }
+    return k + alpha / (double)size * acc;
+}
+
+void oc_lrn_forward(int64_t N, int64_t C, int64_t plane, int32_t size, double alpha, double beta,
+                    double k, const float *x, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t c = 0; c < C; ++c)
+            for (int64_t p = 0; p < plane; ++p) {
+                double s = lrn_scale(x, C, plane, n, c, p, size, alpha, k);
+                y[(n * C + c) * plane + p] = (double)x[(n * C + c) * plane + p] * pow(s, -beta);
+            }
+}
+
+void oc_lrn_backward(int64_t N, int64_t C, int64_t plane, int32_t size, double alpha, double beta,
+                     double k, const float *x, const float *dy, double *dx)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t c = 0; c < C; ++c)
+            for (int64_t p = 0; p < plane; ++p) {
+                double xc = (double)x[(n * C + c) * plane + p];
+                double own = (double)dy[(n * C + c) * plane + p] *
+                             pow(lrn_scale(x, C, plane, n, c, p, size, alpha, k), -beta);
+                /* channels c' whose window contains c: the window is symmetric, so |c' - c| <= (size-1)/2 */
+                double cross = 0.0;
+                for (int64_t cc = c - (size - 1) / 2; cc <= c + (size - 1) / 2; ++cc) {
+                    if (cc < 0 || cc >= C)
+                        continue;
+                    double s = lrn_scale(x, C, plane, n, cc, p, size, alpha, k);
+                    cross += (double)dy[(n * C + cc) * plane + p] * (double)x[(n * C + cc) * plane + p] *
+                             pow(s, -beta - 1.0);
+                }
+                dx[(n * C + c) * plane + p] = own - 2.0 * alpha * beta / (double)size * xc * cross;
+            }
+}
+
+/*
+ * Dropout (training mode, as the framework the paper matches applies it): every element is
+ * kept with probability 1 - p and scaled by 1 / (1 - p), otherwise set to zero; the backward
+ * pass applies the same mask and scale to the gradient.  The random bits come from the
+ * counter-based generator Philox4x64-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers:
+ * as easy as 1, 2, 3", SC'11): block b = philox(counter = {b, 0, 0, 0}, key = {seed, stream})
+ * gives four 64-bit words = eight 32-bit draws (low half first); element i takes draw i mod 8 of
+ * block i / 8 and is kept iff draw >= threshold, threshold = floor(p * 2^32) (at most 2^32 - 1).
+ */
+static void mulhilo64(uint64_t a, uint64_t b, uint64_t *hi, uint64_t *lo)
+{
+    unsigned __int128 p = (unsigned __int128)a * (unsigned __int128)b;
+    *hi = (uint64_t)(p >> 64);
+    *lo = (uint64_t)p;
+}
+
+void oc_philox4x64(const uint64_t ctr[4], const uint64_t key[2], uint64_t out[4])
+{
+    const uint64_t M0 = 0xD2E7470EE14C6C93ull, M1 = 0xCA5A826395121157ull;   /* round multipliers */
+    const uint64_t W0 = 0x9E3779B97F4A7C15ull, W1 = 0xBB67AE8584CAA73Bull;   /* key increments */
+    uint64_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        uint64_t hi0, lo0, hi1, lo1;
+        mulhilo64(M0, c0, &hi0, &lo0);
+        mulhilo64(M1, c2, &hi1, &lo1);
+        uint64_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0, c1 = lo1, c2 = n2, c3 = lo0;
+        k0 += W0, k1 += W1;
+    }
+    out[0] = c0, out[1] = c1, out[2] = c2, out[3] = c3;
+}
+
+uint32_t oc_dropout_threshold(double p)
+{
+    double t = floor(p * 4294967296.0);
+    if (t < 0.0)
+        t = 0.0;
+    if (t > 4294967295.0)
+        t = 4294967295.0;
+    return (uint32_t)t;
+}
+
+/* keep[i] = 1 iff element i survives */
+void oc_dropout_mask(int64_t count, double p, uint64_t seed, uint64_t stream, uint8_t *keep)
+{
+    uint32_t thr = oc_dropout_threshold(p);
+    uint64_t key[2] = {seed, stream};
+    for (int64_t b = 0; b * 8 < count; ++b) {
+        uint64_t ctr[4] = {(uint64_t)b, 0, 0, 0}, w[4];
+        oc_philox4x64(ctr, key, w);
+        for (int j = 0; j < 8 && b * 8 + j < count; ++j) {
+            uint32_t draw = (uint32_t)(j & 1 ? w[j >> 1] >> 32 : w[j >> 1] & 0xffffffffull);
+            keep[b * 8 + j] = draw >= thr ? 1 : 0;
+        }
+    }
+}
+
+/* y = keep ? x / (1 - p) : 0.  The same routine maps dy to dx in the backward pass. */
+void oc_dropout_apply(int64_t count, double p, uint64_t seed, uint64_t stream, const float *x, double *y)
+{
+    uint32_t thr = oc_dropout_threshold(p);
+    uint64_t key[2] = {seed, stream};
+    double scale = 1.0 / (1.0 - p);
+    for (int64_t b = 0; b * 8 < count; ++b) {
+        uint64_t ctr[4] = {(uint64_t)b, 0, 0, 0}, w[4];
+        oc_philox4x64(ctr, key, w);
+        for (int j = 0; j < 8 && b * 8 + j < count; ++j) {
+            uint32_t draw = (uint32_t)(j & 1 ? w[j >> 1] >> 32 : w[j >> 1] & 0xffffffffull);
+            y[b * 8 + j] = draw >= thr ? (double)x[b * 8 + j] * scale : 0.0;
+        }
     }
 }

@@ -393,3 +393,114 @@ def test_workload_generators_are_seeded_and_distributed_as_stated():
     assert np.all((h["X"].view(np.uint32) & 0xFFFF) == 0)        # bf16-representable
     st = wl.stack_tensors(wl.cifar_stack(4), seed=1, x_dist="uniform", pooled_out=(4, 4))
     assert st["dY"].shape == (4, 64, 4, 4) and len(st["W"]) == 3
+
+
+# ---------------------------------------------------------------- normalisation across channels
+LRN_CASES = [(2, 7, 3, 4, 5, 1e-4, 0.75, 1.0), (1, 5, 2, 2, 3, 0.3, 0.5, 2.0), (2, 3, 1, 5, 5, 2.0, 0.75, 1.0),
+             (1, 9, 3, 3, 1, 0.7, 1.0, 0.5), (1, 12, 2, 3, 7, 0.05, 0.75, 1.0)]
+
+
+@pytest.mark.parametrize("N,C,H,W,size,alpha,beta,k", LRN_CASES)
+def test_lrn_matches_the_library_routine_and_its_autograd(N, C, H, W, size, alpha, beta, k):
+    x = _rand((N, C, H, W), 31) * 3.0
+    g = _rand((N, C, H, W), 32)
+    xt = torch.from_numpy(x.astype(np.float64)).requires_grad_(True)
+    yt = Fn.local_response_norm(xt, size, alpha=alpha, beta=beta, k=k)
+    yt.backward(torch.from_numpy(g.astype(np.float64)))
+    np.testing.assert_allclose(oracle.lrn_forward(x, size, alpha, beta, k), yt.detach().numpy(), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(oracle.lrn_backward(x, g, size, alpha, beta, k), xt.grad.numpy(), rtol=1e-10, atol=1e-13)
+
+
+def test_lrn_closed_forms():
+    # constant input a: a full window holds `size` copies of a^2, so y = a / (k + alpha a^2)^beta in the
+    # interior; the first and last channels see a window clipped to (size+1)/2 terms but still divide by size
+    a, size, alpha, beta, k, C = 1.5, 5, 0.2, 0.75, 1.0, 9
+    y = oracle.lrn_forward(np.full((2, C, 3, 3), a, dtype=np.float32), size, alpha, beta, k)
+    np.testing.assert_allclose(y[:, 2:C - 2], a / (k + alpha * a * a) ** beta, rtol=1e-14)
+    np.testing.assert_allclose(y[:, 0], a / (k + alpha / size * 3 * a * a) ** beta, rtol=1e-14)
+    np.testing.assert_allclose(y[:, 1], a / (k + alpha / size * 4 * a * a) ** beta, rtol=1e-14)
+    np.testing.assert_allclose(y[:, C - 1], y[:, 0], rtol=1e-15)
+    # a window of one channel with beta = 1: y = x / (k + alpha x^2), dy/dx = (k - alpha x^2) / (k + alpha x^2)^2
+    x = _rand((1, 4, 2, 3), 33) * 2.0
+    x64 = x.astype(np.float64)
+    np.testing.assert_allclose(oracle.lrn_forward(x, 1, 0.3, 1.0, 2.0), x64 / (2.0 + 0.3 * x64 ** 2), rtol=1e-14)
+    np.testing.assert_allclose(oracle.lrn_backward(x, np.ones_like(x), 1, 0.3, 1.0, 2.0),
+                               (2.0 - 0.3 * x64 ** 2) / (2.0 + 0.3 * x64 ** 2) ** 2, rtol=1e-12)
+    # alpha = 0: a plain scaling by k^-beta in both directions
+    np.testing.assert_allclose(oracle.lrn_forward(x, 5, 0.0, 0.75, 4.0), x64 * 4.0 ** -0.75, rtol=1e-14)
+    np.testing.assert_allclose(oracle.lrn_backward(x, x, 5, 0.0, 0.75, 4.0), x64 * 4.0 ** -0.75, rtol=1e-14)
+    with pytest.raises(ValueError):
+        oracle.lrn_forward(x, 4)
+
+
+def test_lrn_backward_by_central_differences():
+    N, C, H, W, size, alpha, beta, k = 1, 6, 2, 2, 5, 0.5, 0.75, 1.0
+    x = _rand((N, C, H, W), 34) * 2.0
+    g = _rand((N, C, H, W), 35).astype(np.float64)
+    dx = oracle.lrn_backward(x, g.astype(np.float32), size, alpha, beta, k)
+    g = g.astype(np.float32).astype(np.float64)
+    h = 2.0 ** -10                      # exactly representable steps of float32 inputs of this size
+    for idx in itertools.product(range(N), range(C), range(H), range(W)):
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        step = float(xp[idx]) - float(xm[idx])
+        fd = np.sum(g * (oracle.lrn_forward(xp, size, alpha, beta, k) - oracle.lrn_forward(xm, size, alpha, beta, k))) / step
+        assert abs(fd - dx[idx]) <= 1e-5 * max(1.0, abs(dx[idx])), (idx, fd, dx[idx])
+
+
+# ---------------------------------------------------------------- dropout and its generator
+def test_philox_blocks_match_numpys_generator():
+    # numpy's Philox bit generator is the same Philox4x64-10; it advances its counter before it
+    # produces a block, so its first four raw words are the block of counter + 1
+    for ctr, key in (([0, 0, 0, 0], [0, 0]), ([5, 0, 0, 0], [1, 2]), ([2 ** 64 - 2, 7, 0, 3], [123456789, 42]),
+                     ([41, 0, 0, 0], [2 ** 64 - 1, 2 ** 63])):
+        bg = np.random.Philox(counter=np.array(ctr, dtype=np.uint64), key=np.array(key, dtype=np.uint64))
+        nxt = list(ctr)
+        nxt[0] += 1
+        assert oracle.philox4x64(nxt, key) == [int(v) for v in bg.random_raw(4)]
+
+
+def _numpy_draws(count, seed, stream):
+    """The 32-bit draws of elements 0..count-1, taken from numpy's Philox: blocks 0, 1, 2, ... are what a
+    generator started one counter step before zero produces (counter all ones wraps to zero)."""
+    bg = np.random.Philox(counter=np.array([2 ** 64 - 1] * 4, dtype=np.uint64), key=np.array([seed, stream], dtype=np.uint64))
+    raw = bg.random_raw(4 * ((count + 7) // 8))
+    lo, hi = raw & np.uint64(0xffffffff), raw >> np.uint64(32)
+    return np.stack([lo, hi], axis=1).reshape(-1)[:count]
+
+
+@pytest.mark.parametrize("count,p,seed,stream", [(1000, 0.5, 1, 0), (37, 0.25, 7, 3), (4096, 0.9, 2 ** 40 + 5, 1), (8, 0.5, 0, 0)])
+def test_dropout_mask_is_draw_at_least_threshold(count, p, seed, stream):
+    draws = _numpy_draws(count, seed, stream)
+    thr = int(np.floor(p * 2.0 ** 32))
+    assert oracle.dropout_threshold(p) == thr
+    keep = oracle.dropout_mask(count, p, seed, stream)
+    assert np.array_equal(keep, (draws >= thr).astype(np.uint8))
+    x = _rand((count,), 40)
+    y = oracle.dropout_apply(x, p, seed, stream)
+    np.testing.assert_allclose(y, np.where(keep == 1, x.astype(np.float64) / (1.0 - p), 0.0), rtol=1e-15)
+
+
+def test_dropout_invariants():
+    n, p = 1 << 16, 0.5
+    x = _rand((n,), 41)
+    g = _rand((n,), 42)
+    keep = oracle.dropout_mask(n, p, 1)
+    # kept fraction within five standard deviations of 1 - p
+    assert abs(keep.mean() - (1 - p)) <= 5 * np.sqrt(p * (1 - p) / n)
+    # p = 0 keeps everything unscaled; the threshold saturates below 2^32
+    assert np.array_equal(oracle.dropout_apply(x, 0.0, 9), x.astype(np.float64))
+    assert oracle.dropout_threshold(0.0) == 0 and oracle.dropout_threshold(1.0) == 2 ** 32 - 1
+    # the map is diagonal, hence its own adjoint: <drop(x), g> = <x, drop(g)>
+    np.testing.assert_allclose(np.dot(oracle.dropout_apply(x, p, 1), g.astype(np.float64)),
+                               np.dot(x.astype(np.float64), oracle.dropout_apply(g, p, 1)), rtol=1e-12)
+    # scaling keeps the expectation: mean of y ~ mean of x for a constant input
+    y = oracle.dropout_apply(np.ones(n, dtype=np.float32), p, 1)
+    assert abs(y.mean() - 1.0) <= 5 * np.sqrt(p / (1 - p) / n)
+    # other seed or stream, other mask; same arguments, same mask
+    assert not np.array_equal(keep, oracle.dropout_mask(n, p, 2))
+    assert not np.array_equal(keep, oracle.dropout_mask(n, p, 1, 1))
+    assert np.array_equal(keep, oracle.dropout_mask(n, p, 1))
+    # a longer call extends a shorter one (element i depends on i, seed and stream only)
+    assert np.array_equal(oracle.dropout_mask(1001, p, 1), keep[:1001])

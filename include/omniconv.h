@@ -239,6 +239,30 @@ int omni_maxpool_relu_backward(int32_t dtype, int64_t planes, int32_t H, int32_t
                                const void *y_pooled, void *dx, void *hip_stream);
 
 /*
+ * Normalisation across channels and dropout: the other two non-GEMM layers of the paper's CaffeNet runs (App. C,
+ * "Data Parallelism in non-GEMM Kernels" names them beside pooling and ReLU; the paper prints no formula, the
+ * definitions are those of the AlexNet network it trains, in the convention of the framework it matches layer by
+ * layer).  x, y, dy, dx are [N][C][plane] (plane = H*W) of `dtype`.
+ *   lrn_forward : s = k + (alpha / size) * sum_{|c' - c| <= size/2, 0 <= c' < C} x[n,c',p]^2;  y = x * s^(-beta).
+ *       size odd, at most 9 (OMNI_UNSUPPORTED otherwise).  scale (nullable, fp32 [N][C][plane]) receives s; the
+ *       backward pass needs it.  Arithmetic in fp32, one rounding on store.
+ *   lrn_backward: dx = dy * s^(-beta) - (2 alpha beta / size) * x * sum_{|c' - c| <= size/2} dy[c'] x[c'] s[c']^(-beta-1).
+ *   dropout_forward : y[i] = keep(i) ? x[i] / (1 - p) : 0, 0 <= p < 1.  keep(i) comes from the counter-based
+ *       generator Philox4x64-10: block i / 8 (counter {i / 8, 0, 0, 0}, key {seed, stream_id}) yields four 64-bit
+ *       words = eight 32-bit draws, low half first; element i is kept iff draw i mod 8 >= floor(p * 2^32).  No mask
+ *       is stored: dropout_backward (dx[i] = keep(i) ? dy[i] / (1 - p) : 0) regenerates it from the same
+ *       (p, seed, stream_id).  In place allowed.
+ */
+int omni_lrn_forward(int32_t dtype, int64_t N, int32_t C, int64_t plane, int32_t size, float alpha, float beta,
+                     float k, const void *x, void *y, float *scale, void *hip_stream);
+int omni_lrn_backward(int32_t dtype, int64_t N, int32_t C, int64_t plane, int32_t size, float alpha, float beta,
+                      float k, const void *x, const void *dy, const float *scale, void *dx, void *hip_stream);
+int omni_dropout_forward(int32_t dtype, int64_t count, float p, uint64_t seed, uint64_t stream_id,
+                         const void *x, void *y, void *hip_stream);
+int omni_dropout_backward(int32_t dtype, int64_t count, float p, uint64_t seed, uint64_t stream_id,
+                          const void *dy, void *dx, void *hip_stream);
+
+/*
  * Per-kernel timing (the paper times with a wall clock, App. C "Experiment Setup"; on a GPU the
  * equivalent is an event pair on the stream).  omni_profile_enable(1) clears earlier records and
  * makes every later launch of the library record a start and a stop event on its stream, tagged

@@ -31,7 +31,8 @@ SYMBOLS = [
     "omni_conv_forward", "omni_conv_forward_partial", "omni_conv_forward_static", "omni_conv_static_scratch_need",
     "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
-    "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward", "omni_status_string", "omni_version",
+    "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward",
+    "omni_lrn_forward", "omni_lrn_backward", "omni_dropout_forward", "omni_dropout_backward", "omni_status_string", "omni_version",
     "omni_profile_enable", "omni_profile_select", "omni_profile_select_mask", "omni_profile_kernel_count", "omni_profile_kernel_name", "omni_profile_summary",
 ]
 
@@ -79,6 +80,11 @@ _lib.omni_pool_output_dim.argtypes = [_i32, _i32, _i32, _i32]
 _lib.omni_maxpool_forward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.omni_maxpool_backward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.omni_maxpool_relu_backward.argtypes = [_i32, _i64, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
+_f, _u64 = ctypes.c_float, ctypes.c_uint64
+_lib.omni_lrn_forward.argtypes = [_i32, _i64, _i32, _i64, _i32, _f, _f, _f, _vp, _vp, _vp, _vp]
+_lib.omni_lrn_backward.argtypes = [_i32, _i64, _i32, _i64, _i32, _f, _f, _f, _vp, _vp, _vp, _vp, _vp]
+_lib.omni_dropout_forward.argtypes = [_i32, _i64, _f, _u64, _u64, _vp, _vp, _vp]
+_lib.omni_dropout_backward.argtypes = [_i32, _i64, _f, _u64, _u64, _vp, _vp, _vp]
 
 
 _lib.omni_profile_enable.argtypes = [ctypes.c_int]
@@ -326,6 +332,43 @@ def maxpool_relu_backward(dy, argmax, y_pooled, H: int, W: int, k: int = 3, stri
         dx = torch.empty(tuple(dy.shape[:-2]) + (H, W), dtype=dy.dtype, device=dy.device)
     _check(_lib.omni_maxpool_relu_backward(dtype_code(dy.dtype), planes, H, W, k, stride, int(ceil_mode), _p(dy),
                                            _p(argmax), _p(y_pooled), _p(dx), _stream()))
+    return dx
+
+
+def lrn_forward(x, size: int = 5, alpha: float = 1e-4, beta: float = 0.75, k: float = 1.0, y=None, scale=None,
+                want_scale: bool = True):
+    """omni_lrn_forward over x [N][C][...]; returns (y, scale) -- scale (fp32) is what lrn_backward needs."""
+    N, C = x.shape[:2]
+    plane = x.numel() // (N * C) if N * C else 0
+    y = torch.empty_like(x) if y is None else y
+    if scale is None and want_scale:
+        scale = torch.empty(x.shape, dtype=torch.float32, device=x.device)
+    _check(_lib.omni_lrn_forward(dtype_code(x.dtype), N, C, plane, size, alpha, beta, k, _p(x), _p(y), _p(scale), _stream()))
+    return y, scale
+
+
+def lrn_backward(x, dy, scale, size: int = 5, alpha: float = 1e-4, beta: float = 0.75, k: float = 1.0, dx=None):
+    """omni_lrn_backward: gradient w.r.t. the normalisation's input."""
+    N, C = x.shape[:2]
+    plane = x.numel() // (N * C) if N * C else 0
+    dx = torch.empty_like(x) if dx is None else dx
+    _check(_lib.omni_lrn_backward(dtype_code(x.dtype), N, C, plane, size, alpha, beta, k, _p(x), _p(dy), _p(scale), _p(dx),
+                                  _stream()))
+    return dx
+
+
+def dropout_forward(x, p: float, seed: int, stream_id: int = 0, y=None):
+    """omni_dropout_forward: keep with probability 1 - p, scale by 1 / (1 - p); the mask is a function of
+    (p, seed, stream_id, element index)."""
+    y = torch.empty_like(x) if y is None else y
+    _check(_lib.omni_dropout_forward(dtype_code(x.dtype), x.numel(), p, seed, stream_id, _p(x), _p(y), _stream()))
+    return y
+
+
+def dropout_backward(dy, p: float, seed: int, stream_id: int = 0, dx=None):
+    """omni_dropout_backward: the same mask and scale applied to the gradient."""
+    dx = torch.empty_like(dy) if dx is None else dx
+    _check(_lib.omni_dropout_backward(dtype_code(dy.dtype), dy.numel(), p, seed, stream_id, _p(dy), _p(dx), _stream()))
     return dx
 
 

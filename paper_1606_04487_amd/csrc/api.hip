@@ -1,6 +1,7 @@
 // C ABI of the library: argument checks, workspace carving and the launch sequence of each pass.
 // Everything before the first launch is plain host code, so every error path can be exercised on a
 // machine without a GPU.
+#include <cmath>
 #include <mutex>
 
 #include "common.h"
@@ -593,6 +594,69 @@ int omni_maxpool_relu_backward(int32_t dtype, int64_t planes, int32_t H, int32_t
     if (dy == nullptr || argmax == nullptr || y == nullptr || dx == nullptr) return OMNI_INVALID_ARGUMENT;
     if (!aligned16(dy) || !aligned16(y) || !aligned16(dx)) return OMNI_MISALIGNED;
     return launch_maxpool_bwd(dtype, planes, H, W, k, stride, ceil_mode, dy, argmax, y, dx, (hipStream_t)hip_stream);
+}
+
+static int check_lrn(int32_t dtype, int64_t N, int32_t C, int64_t plane, int32_t size, float alpha, float beta, float k)
+{
+    if (check_dtype(dtype) != OMNI_OK) return OMNI_UNSUPPORTED;
+    if (N < 0 || C <= 0 || plane <= 0 || size <= 0 || !(k > 0.f) || !(alpha >= 0.f) || !(beta >= 0.f)) return OMNI_INVALID_ARGUMENT;
+    if (size % 2 != 1 || size > 9) return OMNI_UNSUPPORTED;  // symmetric window, held in registers
+    if (plane > 0x7fffffffll - 4096 || (double)N * (double)plane > 2147479551.0) return OMNI_UNSUPPORTED;
+    return OMNI_OK;
+}
+
+int omni_lrn_forward(int32_t dtype, int64_t N, int32_t C, int64_t plane, int32_t size, float alpha, float beta, float k,
+                     const void *x, void *y, float *scale, void *hip_stream)
+{
+    int st = check_lrn(dtype, N, C, plane, size, alpha, beta, k);
+    if (st != OMNI_OK) return st;
+    if (N == 0) return OMNI_OK;
+    if (x == nullptr || y == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(x) || !aligned16(y) || (scale && !aligned16(scale))) return OMNI_MISALIGNED;
+    return launch_lrn(dtype, false, N, C, plane, size, alpha, beta, k, x, nullptr, scale, y, (hipStream_t)hip_stream);
+}
+
+int omni_lrn_backward(int32_t dtype, int64_t N, int32_t C, int64_t plane, int32_t size, float alpha, float beta, float k,
+                      const void *x, const void *dy, const float *scale, void *dx, void *hip_stream)
+{
+    int st = check_lrn(dtype, N, C, plane, size, alpha, beta, k);
+    if (st != OMNI_OK) return st;
+    if (N == 0) return OMNI_OK;
+    if (x == nullptr || dy == nullptr || scale == nullptr || dx == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(scale) || !aligned16(dx)) return OMNI_MISALIGNED;
+    return launch_lrn(dtype, true, N, C, plane, size, alpha, beta, k, x, dy, const_cast<float *>(scale), dx,
+                      (hipStream_t)hip_stream);
+}
+
+// floor(p * 2^32), at most 2^32 - 1: an element is kept iff its 32-bit draw is at least this
+static uint32_t dropout_threshold(float p)
+{
+    double t = floor((double)p * 4294967296.0);
+    return t > 4294967295.0 ? 4294967295u : (uint32_t)t;
+}
+
+static int dropout_call(int32_t dtype, int64_t count, float p, uint64_t seed, uint64_t stream_id, const void *in, void *out,
+                        void *hip_stream)
+{
+    if (check_dtype(dtype) != OMNI_OK) return OMNI_UNSUPPORTED;
+    if (count < 0 || !(p >= 0.f) || !(p < 1.f)) return OMNI_INVALID_ARGUMENT;
+    if (count == 0) return OMNI_OK;
+    if (in == nullptr || out == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(in) || !aligned16(out)) return OMNI_MISALIGNED;
+    return launch_dropout(dtype, count, dropout_threshold(p), 1.0f / (1.0f - p), seed, stream_id, in, out,
+                          (hipStream_t)hip_stream);
+}
+
+int omni_dropout_forward(int32_t dtype, int64_t count, float p, uint64_t seed, uint64_t stream_id, const void *x, void *y,
+                         void *hip_stream)
+{
+    return dropout_call(dtype, count, p, seed, stream_id, x, y, hip_stream);
+}
+
+int omni_dropout_backward(int32_t dtype, int64_t count, float p, uint64_t seed, uint64_t stream_id, const void *dy, void *dx,
+                          void *hip_stream)
+{
+    return dropout_call(dtype, count, p, seed, stream_id, dy, dx, hip_stream);
 }
 
 }  // extern "C"

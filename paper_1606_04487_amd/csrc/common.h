@@ -110,6 +110,7 @@ inline size_t elem_size(int dtype) { return dtype == OMNI_BF16 ? 2 : 4; }
 enum KernelId {
     KID_LOWER = 0, KID_PACK_KHAT, KID_PACK_DYHAT, KID_BIAS_REDUCE, KID_GEMM_FWD, KID_GEMM_DGRAD, KID_GEMM_WGRAD,
     KID_REDUCE_PARTIALS, KID_COL2IM, KID_SGD, KID_RELU, KID_POOL_FWD, KID_POOL_BWD, KID_FUSED_FWD, KID_FUSED_DGRAD, KID_STRIDED_FWD,
+    KID_LRN, KID_DROPOUT,
     KID_COUNT
 };
 // Brackets the launches made during its lifetime with two events on `s` when profiling is on.
@@ -206,5 +207,12 @@ int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
                        const void *x, void *y, uint8_t *argmax, hipStream_t s);
 int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
                        const void *dy, const uint8_t *argmax, const void *y, void *dx, hipStream_t s);
+
+
+// normdrop.hip: normalisation across channels (x, dy, out [N][C][plane]; scale fp32, same shape) and dropout
+int launch_lrn(int dtype, bool backward, int64_t N, int32_t C, int64_t plane, int32_t size, float alpha, float beta, float k,
+               const void *x, const void *dy, float *scale, void *out, hipStream_t s);
+int launch_dropout(int dtype, int64_t count, uint32_t threshold, float scale, uint64_t seed, uint64_t stream_id, const void *x,
+                   void *y, hipStream_t s);
 
 }  // namespace omni

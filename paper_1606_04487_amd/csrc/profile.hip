@@ -16,6 +16,7 @@ namespace omni {
 static const char *const kNames[KID_COUNT] = {
     "lower", "pack_khat", "pack_dyhat", "bias_reduce", "gemm_forward", "gemm_dgrad", "gemm_wgrad",
     "reduce_partials", "col2im", "sgd", "relu", "maxpool_forward", "maxpool_backward", "conv_fused_forward", "conv_fused_dgrad", "conv_strided_forward",
+    "lrn", "dropout",
 };
 
 struct Record { int kid; hipEvent_t start, stop; double flops, bytes; };

@@ -197,3 +197,25 @@ def test_static_scratch_entry_refuses_on_the_host(B):
     assert B.raw().omni_conv_forward_static(ctypes.byref(small), ctypes.c_void_p(0x1004), fake, None, fake, None) == -4
     bad = B.conv_desc(8, 3, 32, 32, 32, 5, 5, 1, 2, 7)
     assert B.raw().omni_conv_forward_static(ctypes.byref(bad), fake, fake, None, fake, None) == -2
+
+
+def test_lrn_and_dropout_argument_checks(B):
+    fake = ctypes.c_void_p(0x1000)
+    L = B.raw()
+    f = ctypes.c_float
+    # even or oversized windows, bad dtype, non-positive k
+    assert L.omni_lrn_forward(0, 2, 8, 9, 4, f(1e-4), f(0.75), f(1.0), fake, fake, None, None) == -2
+    assert L.omni_lrn_forward(0, 2, 8, 9, 11, f(1e-4), f(0.75), f(1.0), fake, fake, None, None) == -2
+    assert L.omni_lrn_forward(5, 2, 8, 9, 5, f(1e-4), f(0.75), f(1.0), fake, fake, None, None) == -2
+    assert L.omni_lrn_forward(0, 2, 8, 9, 5, f(1e-4), f(0.75), f(0.0), fake, fake, None, None) == -1
+    assert L.omni_lrn_forward(0, 2, 0, 9, 5, f(1e-4), f(0.75), f(1.0), fake, fake, None, None) == -1
+    assert L.omni_lrn_forward(0, 2, 8, 9, 5, f(1e-4), f(0.75), f(1.0), None, fake, None, None) == -1
+    assert L.omni_lrn_forward(0, 0, 8, 9, 5, f(1e-4), f(0.75), f(1.0), None, None, None, None) == 0      # empty batch
+    assert L.omni_lrn_backward(0, 2, 8, 9, 5, f(1e-4), f(0.75), f(1.0), fake, fake, None, fake, None) == -1  # scale required
+    assert L.omni_lrn_backward(0, 2, 8, 9, 5, f(1e-4), f(0.75), f(1.0), fake, fake, ctypes.c_void_p(0x1004), fake, None) == -4
+    for p_bad in (1.0, 1.5, -0.1, float("nan")):
+        assert L.omni_dropout_forward(0, 16, f(p_bad), 1, 0, fake, fake, None) == -1
+    assert L.omni_dropout_forward(0, -1, f(0.5), 1, 0, fake, fake, None) == -1
+    assert L.omni_dropout_forward(0, 0, f(0.5), 1, 0, None, None, None) == 0
+    assert L.omni_dropout_backward(1, 16, f(0.5), 1, 0, fake, None, None) == -1
+    assert L.omni_dropout_backward(3, 16, f(0.5), 1, 0, fake, fake, None) == -2

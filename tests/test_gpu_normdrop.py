@@ -1,0 +1,104 @@
+"""GPU parity of the normalisation and dropout layers (App. C, "Data Parallelism in non-GEMM Kernels")
+against the CPU oracle, element by element.  Dropout's keep-mask is integer work (a counter-based generator
+and a threshold) and must agree bit for bit; the kept values and the normalisation are floating point."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1606_04487_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1606_04487_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def gpu(a, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if dtype == 1 else t
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+# (N, C, H, W, size, alpha, beta, k): CaffeNet's two normalisation layers at a reduced batch, ragged shapes,
+# windows wider than the channel count, one channel, a large alpha that makes the scale matter
+LRN_SHAPES = [
+    (8, 96, 27, 27, 5, 1e-4, 0.75, 1.0), (8, 256, 13, 13, 5, 1e-4, 0.75, 1.0),
+    (3, 7, 5, 9, 5, 0.5, 0.75, 1.0), (2, 3, 4, 4, 7, 1.0, 0.5, 2.0), (5, 1, 3, 3, 3, 0.3, 0.75, 1.0),
+    (1, 33, 1, 1, 9, 2.0, 1.0, 0.5), (2, 16, 17, 3, 1, 0.7, 0.75, 1.0), (300, 4, 1, 2, 3, 0.1, 0.75, 1.0),
+]
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("N,C,H,W,size,alpha,beta,k", LRN_SHAPES)
+def test_lrn_forward_and_backward(B, N, C, H, W, size, alpha, beta, k, dtype):
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32) * 2.0
+    g = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    if dtype == 1:
+        x, g = wl.to_bf16_values(x), wl.to_bf16_values(g)
+    xg, gg = gpu(x, dtype), gpu(g, dtype)
+    y, scale = B.lrn_forward(xg, size, alpha, beta, k)
+    dx = B.lrn_backward(xg, gg, scale, size, alpha, beta, k)
+    y_only, none = B.lrn_forward(xg, size, alpha, beta, k, want_scale=False)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(y_only, y)
+    # float32 parameters reach the kernel; hand the oracle the same values
+    a32, b32, k32 = float(np.float32(alpha)), float(np.float32(beta)), float(np.float32(k))
+    ref_y = oracle.lrn_forward(x, size, a32, b32, k32)
+    ref_dx = oracle.lrn_backward(x, g, size, a32, b32, k32)
+    x64 = x.astype(np.float64)
+    ref_s = ref_y * 0 + k32
+    for c in range(C):
+        lo, hi = max(0, c - size // 2), min(C, c + size // 2 + 1)
+        ref_s[:, c] = k32 + a32 / size * np.sum(x64[:, lo:hi] ** 2, axis=1)     # closed form of the window sum
+    assert np.all(np.abs(host(scale) - ref_s) <= 2e-6 * np.abs(ref_s))
+    tol = 2e-5 if dtype == 0 else 2.0 ** -8          # fp32 pow and a few flops; bf16: one rounding on store
+    assert np.all(np.abs(host(y) - ref_y) <= tol * np.abs(ref_y) + 1e-30)
+    # the gradient is a difference of two terms: bound the error by the terms' magnitudes, not by the result
+    own = np.abs(g.astype(np.float64)) * ref_s ** -b32
+    mag = own + np.abs(ref_dx - g.astype(np.float64) * ref_s ** -b32)
+    assert np.all(np.abs(host(dx) - ref_dx) <= tol * mag + 1e-30)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("count,p,seed,stream_id", [(256 * 4096, 0.5, 1, 0), (1000003, 0.5, 7, 2), (7, 0.25, 3, 1), (8, 0.9, 2 ** 40 + 5, 0),
+                                                    (4099, 0.0, 5, 0), (65537, 0.999, 11, 2 ** 63)])
+def test_dropout_mask_bit_exact_and_values(B, count, p, seed, stream_id, dtype):
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal(count).astype(np.float32) + 3.0      # no zeros: the mask is visible in y
+    g = rng.standard_normal(count).astype(np.float32) + 3.0
+    if dtype == 1:
+        x, g = wl.to_bf16_values(x), wl.to_bf16_values(g)
+    y = B.dropout_forward(gpu(x, dtype), p, seed, stream_id)
+    dx = B.dropout_backward(gpu(g, dtype), p, seed, stream_id)
+    torch.cuda.synchronize()
+    p32 = float(np.float32(p))
+    keep = oracle.dropout_mask(count, p32, seed, stream_id)
+    assert np.array_equal((host(y) != 0).astype(np.uint8), keep)          # integer work: bit-exact
+    assert np.array_equal((host(dx) != 0).astype(np.uint8), keep)
+    tol = 2e-7 if dtype == 0 else 2.0 ** -8
+    for got, src in ((y, x), (dx, g)):
+        ref = oracle.dropout_apply(src, p32, seed, stream_id)
+        assert np.all(np.abs(host(got) - ref) <= tol * np.abs(ref))
+    if p == 0.0:
+        assert np.array_equal(host(y), x.astype(np.float64))
+
+
+def test_dropout_in_place_and_determinism(B):
+    x = torch.randn(100001, device="cuda")
+    a = B.dropout_forward(x, 0.5, 9, 1)
+    b = x.clone()
+    B.dropout_forward(b, 0.5, 9, 1, y=b)
+    c = B.dropout_forward(x, 0.5, 9, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(a, c)
+    assert not torch.equal(a, B.dropout_forward(x, 0.5, 10, 1))
+    assert B.dropout_forward(torch.empty(0, device="cuda"), 0.5, 1).numel() == 0

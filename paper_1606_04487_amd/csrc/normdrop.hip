@@ -15,11 +15,16 @@ template <> __device__ __forceinline__ void st_f32<bf16_t>(bf16_t *p, float v) {
 
 // ------------------------------------------------------------------------------------------------
 // Normalisation: s = k + alpha/size * sum_{|c'-c| <= size/2} x[c']^2,  y = x * s^-beta.
-// One thread per (image, pixel) walks the channels; consecutive threads hold consecutive pixels, so every
-// access of a wavefront is one contiguous run of a channel plane.  The window's squares live in registers
-// (a shift register of HALF*2+1 values), so x is read once.  s is optionally stored (fp32) for the backward
-// pass, which needs it at every channel of the window.
+// One thread per (image, pixel, block of LRN_CB channels) walks its channels; consecutive threads hold
+// consecutive pixels, so every access of a wavefront is one contiguous run of a channel plane.  The window's
+// squares live in registers (a shift register of HALF*2+1 values), so x is read once plus the block's halo.
+// s is optionally stored (fp32) for the backward pass, which needs it at every channel of the window.
+// s^-beta = exp2(-beta * log2(s)) on the hardware's exp2 / log2 units (s >= k > 0).
 // ------------------------------------------------------------------------------------------------
+constexpr int LRN_CB = 8;  // channels per thread
+
+__device__ __forceinline__ float pow_neg(float s, float beta) { return __builtin_amdgcn_exp2f(-beta * __builtin_amdgcn_logf(s)); }
+
 template <typename T, int HALF>
 __global__ __launch_bounds__(256) void lrn_forward_kernel(const T *__restrict__ x, T *__restrict__ y, float *__restrict__ scale,
                                                           int64_t pixels, int32_t C, int64_t plane, FastDiv div_plane,
@@ -35,14 +40,16 @@ __global__ __launch_bounds__(256) void lrn_forward_kernel(const T *__restrict__ 
     for (int j = 0; j < 2 * HALF + 1; ++j) sq[j] = 0.f;
 #pragma unroll
     for (int j = 0; j <= HALF; ++j) xv[j] = 0.f;
-    // preload channels 0 .. HALF-1 into the upper half of the window
+    // preload channels c0 - HALF .. c0 + HALF - 1: the window of channel c0 minus its newest member
+    const int c0 = blockIdx.y * LRN_CB, c1 = c0 + LRN_CB < C ? c0 + LRN_CB : C;
 #pragma unroll
-    for (int j = 0; j < HALF; ++j) {
-        float v = j < C ? ld_f32(x + base + (int64_t)j * plane) : 0.f;
-        xv[j + 1] = v;
-        sq[HALF + 1 + j] = v * v;
+    for (int j = 0; j < 2 * HALF; ++j) {
+        int cc = c0 - HALF + j;
+        float v = (cc >= 0 && cc < C) ? ld_f32(x + base + (int64_t)cc * plane) : 0.f;
+        sq[j + 1] = v * v;
+        if (j >= HALF) xv[j - HALF + 1] = v;
     }
-    for (int c = 0; c < C; ++c) {
+    for (int c = c0; c < c1; ++c) {
         // shift the window by one channel and take in channel c + HALF
 #pragma unroll
         for (int j = 0; j < 2 * HALF; ++j) sq[j] = sq[j + 1];
@@ -56,7 +63,7 @@ __global__ __launch_bounds__(256) void lrn_forward_kernel(const T *__restrict__ 
         for (int j = 0; j < 2 * HALF + 1; ++j) acc += sq[j];
         float s = k + alpha_over_size * acc;
         if (scale != nullptr) scale[base + (int64_t)c * plane] = s;
-        st_f32(y + base + (int64_t)c * plane, xv[0] * powf(s, -beta));
+        st_f32(y + base + (int64_t)c * plane, xv[0] * pow_neg(s, beta));
     }
 }
 
@@ -78,18 +85,23 @@ __global__ __launch_bounds__(256) void lrn_backward_kernel(const T *__restrict__
 #pragma unroll
     for (int j = 0; j <= HALF; ++j) xv[j] = 0.f, own[j] = 0.f;
     auto take = [&](int c, float &xo, float &oo, float &ro) {
-        if (c < C) {
+        if (c >= 0 && c < C) {
             int64_t i = base + (int64_t)c * plane;
             float xx = ld_f32(x + i), g = ld_f32(dy + i), s = scale[i];
-            float pw = powf(s, -beta);
+            float pw = pow_neg(s, beta);
             xo = xx, oo = g * pw, ro = g * xx * pw / s;
         } else {
             xo = 0.f, oo = 0.f, ro = 0.f;
         }
     };
+    const int c0 = blockIdx.y * LRN_CB, c1 = c0 + LRN_CB < C ? c0 + LRN_CB : C;
 #pragma unroll
-    for (int j = 0; j < HALF; ++j) take(j, xv[j + 1], own[j + 1], r[HALF + 1 + j]);
-    for (int c = 0; c < C; ++c) {
+    for (int j = 0; j < 2 * HALF; ++j) {
+        float xo, oo;
+        take(c0 - HALF + j, xo, oo, r[j + 1]);
+        if (j >= HALF) xv[j - HALF + 1] = xo, own[j - HALF + 1] = oo;
+    }
+    for (int c = c0; c < c1; ++c) {
 #pragma unroll
         for (int j = 0; j < 2 * HALF; ++j) r[j] = r[j + 1];
 #pragma unroll
@@ -108,7 +120,7 @@ static int lrn_launch(bool backward, int64_t N, int32_t C, int64_t plane, int32_
 {
     const int64_t pixels = N * plane;
     const double elems = (double)pixels * C, e = sizeof(T);
-    dim3 grid((unsigned)((pixels + 255) / 256)), block(256);
+    dim3 grid((unsigned)((pixels + 255) / 256), (unsigned)((C + LRN_CB - 1) / LRN_CB)), block(256);
     FastDiv dp((uint32_t)plane);
     if (!backward) {
         ProfScope prof(KID_LRN, s, 0.0, elems * (2.0 * e + (scale ? 4.0 : 0.0)));

@@ -38,10 +38,15 @@ class ConvStack:
         # the model gradient then reads its lowered operand straight from X (or lowers X itself where it
         # cannot) instead of finding D-hat cached by the forward pass
         extra = B.FLAG_FUSED if fused else 0
-        self.desc = [B.conv_desc(L.N, L.C, L.H, L.W, L.F, L.k, L.k, L.s, L.p, dtype, B.FLAG_RELU | extra)
+        # fully connected layers (whole-image windows) have few columns: split their reductions over the chip
+        # (and take the explicit path, whose products on W and dY as they lie need no lowering there)
+        self.desc = [B.conv_desc(L.N, L.C, L.H, L.W, L.F, L.k, L.k, L.s, L.p, dtype,
+                                 (B.FLAG_RELU if L.relu else 0) | (B.FLAG_SPLIT_K if L.Ho * L.Wo == 1 else extra))
                      for L in self.layers]
+        self.dropout_seed = 1
         self.fwd_fused = [fused and B.conv_fused_supported(d, B.PASS_FORWARD) for d in self.desc]
-        self.desc_wgrad = [d.with_flags(B.FLAG_FUSED if ff else B.FLAG_DHAT_CACHED) for d, ff in zip(self.desc, self.fwd_fused)]
+        self.desc_wgrad = [d.with_flags((B.FLAG_FUSED if ff else B.FLAG_DHAT_CACHED) | (d.flags & B.FLAG_SPLIT_K))
+                           for d, ff in zip(self.desc, self.fwd_fused)]
         # parameters: fp32 masters, velocity, gradients; bf16 copies of W for the bf16 passes
         self.W = [torch.zeros((L.F, L.C, L.k, L.k), dtype=torch.float32, device=device) for L in self.layers]
         self.b = [torch.zeros((L.F,), dtype=torch.float32, device=device) for L in self.layers]
@@ -63,6 +68,7 @@ class ConvStack:
         # activations
         self.X: List[Optional[torch.Tensor]] = [None] * len(self.layers)
         self.Y, self.P, self.A, self.dYc, self.dXl = [], [], [], [], []
+        self.Nrm, self.Sc, self.Dr, self.gN, self.gD = [], [], [], [], []   # normalised / scale / dropped; their gradients
         for i, (L, d) in enumerate(zip(self.layers, self.desc)):
             ho, wo = B.conv_output_dims(d)
             self.Y.append(torch.empty((L.N, L.F, ho, wo), dtype=self.tdtype, device=device))
@@ -74,6 +80,12 @@ class ConvStack:
             else:
                 self.P.append(None)
                 self.A.append(None)
+            out = self.P[-1] if L.pool_after else self.Y[-1]
+            self.Nrm.append(torch.empty_like(out) if L.lrn_after else None)
+            self.Sc.append(torch.empty(out.shape, dtype=torch.float32, device=device) if L.lrn_after else None)
+            self.gN.append(torch.empty_like(out) if L.lrn_after else None)
+            self.Dr.append(torch.empty_like(out) if L.dropout_after > 0 else None)
+            self.gD.append(torch.empty_like(out) if L.dropout_after > 0 else None)
             need_dx = not (i == 0 and skip_first_dgrad)
             self.dXl.append(torch.empty((L.N, L.C, L.H, L.W), dtype=self.tdtype, device=device) if need_dx else None)
 
@@ -91,6 +103,8 @@ class ConvStack:
         last = self.P[-1] if self.P[-1] is not None else self.Y[-1]
         return tuple(last.shape)
 
+    LRN = (5, 1e-4, 0.75, 1.0)   # channel window, alpha, beta, k of the network's normalisation layers
+
     # ------------------------------------------------------------------ passes
     def forward(self, X: torch.Tensor) -> torch.Tensor:
         cur = X
@@ -101,17 +115,33 @@ class ConvStack:
             if L.pool_after:
                 B.maxpool_forward(cur, 3, 2, self.ceil_mode, self.P[i], self.A[i])
                 cur = self.P[i]
+            if L.lrn_after:
+                B.lrn_forward(cur, *self.LRN, y=self.Nrm[i], scale=self.Sc[i])
+                cur = self.Nrm[i]
+            if L.dropout_after > 0:
+                B.dropout_forward(cur, L.dropout_after, self.dropout_seed, i, y=self.Dr[i])
+                cur = self.Dr[i]
         return cur
 
     def backward(self, dOut: torch.Tensor) -> Optional[torch.Tensor]:
         g = dOut
         for i in reversed(range(len(self.layers))):
             L, Y = self.layers[i], self.Y[i]
-            if L.pool_after:
+            if L.dropout_after > 0:
+                B.dropout_backward(g, L.dropout_after, self.dropout_seed, i, dx=self.gD[i])
+                g = self.gD[i]
+            if L.lrn_after:
+                B.lrn_backward(self.P[i] if L.pool_after else Y, g, self.Sc[i], *self.LRN, dx=self.gN[i])
+                g = self.gN[i]
+            if L.pool_after and L.relu:
                 B.maxpool_relu_backward(g, self.A[i], self.P[i], Y.shape[-2], Y.shape[-1], 3, 2, self.ceil_mode,
                                         self.dYc[i])
-            else:
+            elif L.pool_after:
+                B.maxpool_backward(g, self.A[i], Y.shape[-2], Y.shape[-1], 3, 2, self.ceil_mode, dx=self.dYc[i])
+            elif L.relu:
                 B.relu_backward(Y, g, self.dYc[i])
+            else:
+                self.dYc[i] = g     # no layer between the convolution and the incoming gradient
             if self.side is not None:
                 self.side.wait_stream(torch.cuda.current_stream())
                 with torch.cuda.stream(self.side):

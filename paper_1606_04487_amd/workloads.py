@@ -30,6 +30,9 @@ class ConvLayer:
     s: int = 1
     p: int = 0
     pool_after: bool = False      # 3x3 stride-2 max-pool follows the ReLU
+    relu: bool = True             # ReLU on the layer's output (the last fully connected layer has none)
+    lrn_after: bool = False       # normalisation across 5 channels follows the pool (alpha 1e-4, beta 0.75, k 1)
+    dropout_after: float = 0.0    # drop probability of a dropout layer that follows (0: none)
 
     @property
     def Ho(self) -> int:
@@ -93,6 +96,20 @@ def step_upstream_scale(N: int) -> float:
     in fp32 and in bf16."""
     import math
     return 2.0 ** -(18 + max(0, math.ceil(math.log2(N))))
+
+
+def caffenet_full(N: int = 256) -> List[ConvLayer]:
+    """The whole CaffeNet-shaped network (Sec. II-C: conv phase, then FC phase): conv1..conv5 as above with the
+    two normalisation layers after the first two pools, then FC6 (the convolution whose 6 x 6 window covers the
+    whole 256 x 6 x 6 image), FC7 and FC8 (1 x 1 convolutions on 1 x 1 images), dropout 0.5 after FC6 and FC7."""
+    conv = caffenet_stack(N)
+    conv[0] = replace(conv[0], lrn_after=True)
+    conv[1] = replace(conv[1], lrn_after=True)
+    return conv + [
+        ConvLayer("fc6", N, 256, 6, 6, 4096, 6, 1, 0, dropout_after=0.5),
+        ConvLayer("fc7", N, 4096, 1, 1, 4096, 1, 1, 0, dropout_after=0.5),
+        ConvLayer("fc8", N, 4096, 1, 1, 1000, 1, 1, 0, relu=False),
+    ]
 
 
 def to_bf16_values(a: np.ndarray) -> np.ndarray:

@@ -102,3 +102,71 @@ def test_dropout_in_place_and_determinism(B):
     assert torch.equal(a, b) and torch.equal(a, c)
     assert not torch.equal(a, B.dropout_forward(x, 0.5, 10, 1))
     assert B.dropout_forward(torch.empty(0, device="cuda"), 0.5, 1).numel() == 0
+
+
+def test_whole_caffenet_iteration_small_batch_stage_by_stage(B):
+    # conv1..conv5 with pools and normalisation layers, FC6..FC8 with dropout, at batch 4 in bf16: every stage's
+    # output and gradient against the oracle applied to what that stage received on the GPU
+    from paper_1606_04487_amd.stack import ConvStack
+    N, dtype, tol = 4, 1, 2e-2
+    layers = wl.caffenet_full(N)
+    st = ConvStack(layers, dtype=dtype, ceil_mode=False, skip_first_dgrad=True)
+    data = wl.stack_tensors(layers, seed=4, bf16=True, pooled_out=st.output_shape()[-2:])
+    st.set_parameters(data["W"], data["bias"])
+    X, dOut = gpu(data["X"], dtype), gpu(data["dY"], dtype)
+    out = st.forward(X)
+    st.backward(dOut)
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (N, 1000, 1, 1)
+    h32 = lambda t: t.detach().float().cpu().numpy()
+
+    def close(got, ref, what, limit=tol):
+        e = np.max(np.abs(h32(got).astype(np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-30)
+        assert e <= limit, (what, e)
+
+    size, alpha, beta, k = ConvStack.LRN
+    a32 = float(np.float32(alpha))
+    g = dOut
+    for i in reversed(range(len(layers))):
+        L = layers[i]
+        s = oracle.shape(L.N, L.C, L.H, L.W, L.F, L.k, L.k, L.s, L.p)
+        Xi, Wi, Yg = h32(st.X[i]), h32(st.Wc[i]), h32(st.Y[i])
+        y_ref = oracle.conv_forward(s, Xi, Wi, data["bias"][i])
+        close(st.Y[i], np.maximum(y_ref, 0) if L.relu else y_ref, ("forward", L.name))
+        cur = Yg
+        if L.pool_after:
+            Pref, Aref = oracle.maxpool_forward(Yg, 3, 2, False)
+            assert np.array_equal(h32(st.P[i]).astype(np.float64), Pref), ("pool", L.name)
+            cur = h32(st.P[i])
+        if L.lrn_after:
+            close(st.Nrm[i], oracle.lrn_forward(cur, size, a32, beta, k), ("lrn", L.name), 2.0 ** -8)
+            lrn_in, cur = cur, h32(st.Nrm[i])
+        if L.dropout_after > 0:
+            keep = oracle.dropout_mask(cur.size, L.dropout_after, st.dropout_seed, i).reshape(cur.shape)
+            # ReLU zeros hide the mask where the input is zero: compare where it is not
+            assert np.array_equal((h32(st.Dr[i]) != 0)[cur != 0], keep[cur != 0] == 1), ("dropout mask", L.name)
+            close(st.Dr[i], oracle.dropout_apply(cur, L.dropout_after, st.dropout_seed, i), ("dropout", L.name), 2.0 ** -8)
+        # backward, in reverse order of the forward stages
+        gh = h32(g)
+        if L.dropout_after > 0:
+            close(st.gD[i], oracle.dropout_apply(gh, L.dropout_after, st.dropout_seed, i), ("dropout backward", L.name), 2.0 ** -8)
+            gh = h32(st.gD[i])
+        if L.lrn_after:
+            close(st.gN[i], oracle.lrn_backward(lrn_in, gh, size, a32, beta, k), ("lrn backward", L.name), 2.0 ** -7)
+            gh = h32(st.gN[i])
+        if L.pool_after:
+            gh = oracle.maxpool_backward(gh, Aref, L.Ho, L.Wo)
+        ref_g = oracle.relu_backward(Yg, np.ones_like(Yg)) * gh if L.relu else gh.astype(np.float64)
+        close(st.dYc[i], ref_g, ("relu/pool backward", L.name), 2.0 ** -8)
+        Gg = h32(st.dYc[i])
+        close(st.dW[i], oracle.conv_backward_weights(s, Xi, Gg), ("backward_weights", L.name), 1e-4)
+        close(st.db[i], oracle.bias_grad(s, Gg), ("bias gradient", L.name), 1e-4)
+        if st.dXl[i] is None:
+            break
+        close(st.dXl[i], oracle.conv_backward_data(s, Gg, Wi), ("backward_data", L.name))
+        g = st.dXl[i]
+    st.sgd_step(0.01, 0.9)
+    torch.cuda.synchronize()
+    assert all(bool(torch.isfinite(w).all()) for w in st.W)
+    del st
+    torch.cuda.empty_cache()

@@ -285,6 +285,17 @@ const char *omni_profile_kernel_name(int kernel_id);
 int omni_profile_summary(int kernel_id, int64_t *launches, double *total_ms, double *flops,
                          double *bytes);
 
+/*
+ * Tile overrides for tuning sweeps and tests -- not for production callers: the library chooses its tiles from
+ * the layer's shape.  Process-wide, host only, not thread-safe against concurrent calls.
+ *   OMNI_TUNE_GEMM_TILE: index of the GEMM tile configuration (-1: choose)
+ *   OMNI_TUNE_FUSED_BN : column tile of the fused convolution: 256, 384 or 512 (0: choose)
+ *   OMNI_TUNE_FUSED_BM : row tile of the fused convolution: 96 or 128 (0: choose)
+ * An override that does not fit a layer is ignored for that layer.
+ */
+enum { OMNI_TUNE_GEMM_TILE = 0, OMNI_TUNE_FUSED_BN = 1, OMNI_TUNE_FUSED_BM = 2 };
+int omni_tuning_set(int knob, int value);
+
 /* Host only.  Static string for a status code. */
 const char *omni_status_string(int status);
 

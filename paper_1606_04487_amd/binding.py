@@ -32,7 +32,7 @@ SYMBOLS = [
     "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
     "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward",
-    "omni_lrn_forward", "omni_lrn_backward", "omni_dropout_forward", "omni_dropout_backward", "omni_status_string", "omni_version",
+    "omni_lrn_forward", "omni_lrn_backward", "omni_dropout_forward", "omni_dropout_backward", "omni_status_string", "omni_version", "omni_tuning_set",
     "omni_profile_enable", "omni_profile_select", "omni_profile_select_mask", "omni_profile_kernel_count", "omni_profile_kernel_name", "omni_profile_summary",
 ]
 
@@ -98,6 +98,14 @@ _lib.omni_profile_summary.argtypes = [ctypes.c_int, ctypes.POINTER(_i64), ctypes
 def raw():
     """The ctypes library handle (for tests of the error paths)."""
     return _lib
+
+
+TUNE_GEMM_TILE, TUNE_FUSED_BN, TUNE_FUSED_BM = 0, 1, 2
+
+
+def tuning_set(knob: int, value: int) -> None:
+    """omni_tuning_set: tile overrides for sweeps and tests."""
+    _check(_lib.omni_tuning_set(int(knob), int(value)))
 
 
 def status_string(status: int) -> str:

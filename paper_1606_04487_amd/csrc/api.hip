@@ -189,6 +189,22 @@ const char *omni_status_string(int status)
 
 const char *omni_version(void) { return "0.1"; }
 
+int omni_tuning_set(int knob, int value)
+{
+    switch (knob) {
+    case OMNI_TUNE_GEMM_TILE: set_gemm_tile_override(value); return OMNI_OK;
+    case OMNI_TUNE_FUSED_BN:
+        if (value != 0 && value != 256 && value != 384 && value != 512) return OMNI_INVALID_ARGUMENT;
+        set_fused_tile_override(value, -1);
+        return OMNI_OK;
+    case OMNI_TUNE_FUSED_BM:
+        if (value != 0 && value != 96 && value != 128) return OMNI_INVALID_ARGUMENT;
+        set_fused_tile_override(-1, value);
+        return OMNI_OK;
+    default: return OMNI_INVALID_ARGUMENT;
+    }
+}
+
 int omni_conv_output_dims(const omni_conv_desc *desc, int32_t *Ho, int32_t *Wo)
 {
     if (Ho == nullptr || Wo == nullptr) return OMNI_INVALID_ARGUMENT;

@@ -199,6 +199,10 @@ int launch_phase_split(const ConvGeom &g, int WP, const void *X, void *X4, hipSt
 int launch_gemm_wgrad_phase(const ConvGeom &g, const void *X4, const void *dY, int64_t ld, float *partials, int splits,
                             int64_t chunk, float *dW, float *dbias, hipStream_t s);
 
+// tile overrides for sweeps (omni_tuning_set); -1 leaves a value as it is
+void set_gemm_tile_override(int tile);
+void set_fused_tile_override(int bn, int bm);
+
 // elementwise.hip
 int launch_sgd(int32_t n, float *const *W, float *const *V, const float *const *G, const int64_t *counts,
                void *const *shadow, float lr, float mu, float wd, hipStream_t s);

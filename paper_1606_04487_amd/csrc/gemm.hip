@@ -1053,7 +1053,7 @@ static GemmShape make_shape(int rows, int cols, int64_t red, int64_t chunk, int 
     return s;
 }
 
-// Tile configurations compiled in.  Index = OMNI_GEMM_TILE environment override (for tuning runs) or
+// Tile configurations compiled in.  Index = the tuning override (omni_tuning_set, for sweeps) or
 // the choice of pick_tile().
 typedef Tile<128, 128, 2, 2, 1> Tile0;
 typedef Tile<128, 128, 2, 2, 2> Tile1;
@@ -1068,12 +1068,9 @@ typedef Tile<192, 256, 2, 4, 1> Tile9;
 typedef Tile<384, 128, 4, 2, 1> Tile10;
 constexpr int N_TILES = 11;
 
-static int tile_override()
-{
-    const char *e = getenv("OMNI_GEMM_TILE");
-    int v = e ? atoi(e) : -1;
-    return (v >= 0 && v < N_TILES) ? v : -1;
-}
+static int g_tile_override = -1;  // omni_tuning_set(OMNI_TUNE_GEMM_TILE, ...): sweeps and tests only
+void set_gemm_tile_override(int v) { g_tile_override = (v >= 0 && v < N_TILES) ? v : -1; }
+static int tile_override() { return g_tile_override; }
 
 // Tile choice: the 256 x 256 tile halves the operand traffic per flop, so it wins whenever the result
 // fills its tiles about as well as it fills 128 x 128 ones (measured on the CaffeNet-shaped layers: 256

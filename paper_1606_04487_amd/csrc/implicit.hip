@@ -47,6 +47,8 @@ constexpr int TG = 5;            // window taps whose weights are staged in LDS 
 constexpr int MAX_SLOTS = 8;     // images a column tile may touch
 constexpr uint32_t NO_PIX = 0xffffu;
 
+static int g_fused_bn = 0, g_fused_bm = 0;  // omni_tuning_set(OMNI_TUNE_FUSED_*): sweeps and tests only
+
 struct Geom {
     int32_t N, C, H, W;      // input  [N][C][H][W]
     int32_t F, Ho, Wo;       // output [N][F][Ho][Wo],  Ho = H + 2*ph - kh + 1
@@ -394,8 +396,7 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
     // Among the tiles that fit, the one with the least estimated time: rounds of the 256 compute units
     // times the tile's width, the narrower tiles a few per cent dearer per column (their weights are
     // staged for fewer columns, and they read more LDS fragments per MFMA).
-    const char *e = getenv("OMNI_FUSED_BN");  // tuning override: 256, 384 or 512
-    int want = e != nullptr ? atoi(e) : 0;
+    const int want = g_fused_bn;  // tuning override: 256, 384 or 512 (0: choose)
     const struct { int bn, patch; double per_column; } tiles[3] = {
         {BN_WIDE, PATCH_WIDE, 1.0}, {BN_MID, PATCH_MID, 1.03}, {BN_NARROW, PATCH_NARROW, 1.06}};
     double best = 0.0;
@@ -409,9 +410,9 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
     // A layer of at most 64 filters takes a 96-row tile (8 wavefronts of 96 x 64 on 512 columns): three quarters
     // of the MFMAs for a few more fragment reads per MFMA.  (Measured: 48 filters 287 -> 192 us; with 96 filters
     // the two tiles take the same time, the kernel being bound by its LDS reads, so those keep the 128-row tile.)
-    const char *eb = getenv("OMNI_FUSED_BM");  // tuning override: 128 keeps the 128-row tile, 96 forces the other up to 96 filters
-    const int f_max = (eb != nullptr && atoi(eb) == 96) ? 96 : 64;
-    if (g->F <= f_max && (eb == nullptr || atoi(eb) == 96) && (want == 0 || want == BN_WIDE) && fits(BN_WIDE, PATCH_WIDE)) {
+    const int bm_want = g_fused_bm;  // tuning override: 128 keeps the 128-row tile, 96 forces the other up to 96 filters
+    const int f_max = bm_want == 96 ? 96 : 64;
+    if (g->F <= f_max && (bm_want == 0 || bm_want == 96) && (want == 0 || want == BN_WIDE) && fits(BN_WIDE, PATCH_WIDE)) {
         int64_t items = (g->M + BN_WIDE - 1) / BN_WIDE;
         double cost = (double)((items + 255) / 256) * BN_WIDE * 0.8;
         if (g->bn == 0 || cost < best) g->bn = BN_WIDE, g->bm = 96, g->Fp = 96, g->tiles_f = 1, best = cost;
@@ -424,6 +425,12 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
 }
 
 }  // namespace fused
+
+void set_fused_tile_override(int bn, int bm)
+{
+    if (bn >= 0) fused::g_fused_bn = bn;
+    if (bm >= 0) fused::g_fused_bm = bm;
+}
 
 bool fused_supported(const ConvGeom &c, int dtype, bool data_gradient)
 {

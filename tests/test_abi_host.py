@@ -219,3 +219,18 @@ def test_lrn_and_dropout_argument_checks(B):
     assert L.omni_dropout_forward(0, 0, f(0.5), 1, 0, None, None, None) == 0
     assert L.omni_dropout_backward(1, 16, f(0.5), 1, 0, fake, None, None) == -1
     assert L.omni_dropout_backward(3, 16, f(0.5), 1, 0, fake, fake, None) == -2
+
+
+def test_tuning_overrides_are_checked(B):
+    L = B.raw()
+    assert L.omni_tuning_set(B.TUNE_FUSED_BN, 300) == -1
+    assert L.omni_tuning_set(B.TUNE_FUSED_BM, 64) == -1
+    assert L.omni_tuning_set(9, 0) == -1
+    # a forced column tile changes which layers run fused, and resetting restores the library's choice
+    d = B.conv_desc(4, 256, 13, 13, 384, 3, 3, 1, 1, B.BF16, B.FLAG_FUSED)
+    assert B.conv_fused_supported(d, B.PASS_FORWARD)
+    for bn in (256, 384, 512, 0):
+        B.tuning_set(B.TUNE_FUSED_BN, bn)
+        assert B.conv_fused_supported(d, B.PASS_FORWARD)
+    B.tuning_set(B.TUNE_GEMM_TILE, 3)
+    B.tuning_set(B.TUNE_GEMM_TILE, -1)

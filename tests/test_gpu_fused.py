@@ -27,6 +27,20 @@ def B():
     return binding
 
 
+@pytest.fixture
+def tuning(B):
+    """Sets tile overrides through omni_tuning_set and puts the library's own choice back afterwards."""
+    touched = []
+
+    def set_knob(knob, value):
+        touched.append(knob)
+        B.tuning_set(knob, value)
+
+    yield set_knob
+    for knob in touched:
+        B.tuning_set(knob, -1 if knob == B.TUNE_GEMM_TILE else 0)
+
+
 def gpu(a, bf16=True):
     t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
     return t.to(torch.bfloat16) if bf16 else t
@@ -113,10 +127,10 @@ def test_fused_backward_data(B, cfg):
 
 @pytest.mark.parametrize("bn", ["256", "384", "512"])
 @pytest.mark.parametrize("cfg", [FUSED_SHAPES[1], FUSED_SHAPES[2], FUSED_SHAPES[8], (7, 64, 13, 13, 96, 3, 3, 1, 1)])
-def test_fused_every_column_tile(B, cfg, bn, monkeypatch):
+def test_fused_every_column_tile(B, cfg, bn, tuning):
     """Each of the kernel's column-tile widths, forced through the tuning override, on both fused passes
     (a width whose patch does not fit a shape is skipped by the library, which then declines)."""
-    monkeypatch.setenv("OMNI_FUSED_BN", bn)
+    tuning(B.TUNE_FUSED_BN, int(bn))
     s, X, Wt, b, dY = make(cfg, 21)
     d = desc_of(B, cfg, B.FLAG_FUSED | B.FLAG_RELU)
     ran = 0
@@ -180,9 +194,9 @@ def test_fused_declines_and_falls_back(B):
 @pytest.mark.parametrize("cfg", [(3, 64, 27, 27, 48, 5, 5, 2, 2), (6, 32, 13, 13, 40, 3, 3, 1, 1),
                                  (2, 96, 27, 27, 96, 5, 5, 2, 2), (5, 32, 6, 6, 8, 1, 1, 0, 0)])
 @pytest.mark.parametrize("bm", ["96", "128"])
-def test_fused_row_tiles(B, cfg, bm, monkeypatch):
+def test_fused_row_tiles(B, cfg, bm, tuning):
     """Layers of few filters: the 96-row tile (forced up to 96 filters) and the 128-row tile agree with the oracle."""
-    monkeypatch.setenv("OMNI_FUSED_BM", bm)
+    tuning(B.TUNE_FUSED_BM, int(bm))
     s, X, Wt, b, dY = make(cfg, 29)
     d = desc_of(B, cfg, B.FLAG_FUSED | B.FLAG_RELU)
     assert B.conv_fused_supported(d, B.PASS_FORWARD)

@@ -170,3 +170,28 @@ def test_whole_caffenet_iteration_small_batch_stage_by_stage(B):
     assert all(bool(torch.isfinite(w).all()) for w in st.W)
     del st
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("g", [2, 4, 8])
+def test_implicit_momentum_recursion_through_the_gpu_update(B, g):
+    """Sec. IV-C, Theorem 1: g asynchronous groups without explicit momentum behave in expectation like momentum
+    SGD with momentum 1 - 1/g and step eta / g.  That recursion, iterated through omni_sgd_momentum_step on a
+    quadratic loss (gradients formed on the host from the GPU's current model), must follow the model's own
+    reference trajectory."""
+    from paper_1606_04487_amd import async_model as am
+    A = np.array([[1.0, 0.2], [0.2, 0.5]])
+    w_star, w0 = np.array([1.0, -2.0]), np.array([4.0, 3.0])
+    eta, steps = 0.4, 80
+    # many independent copies of the 2-parameter problem in one tensor, so the launch is not trivially small
+    copies = 4096
+    W = torch.from_numpy(np.tile(w0, copies).astype(np.float32)).cuda()
+    V = torch.zeros_like(W)
+    ref = am.implicit_momentum_reference(A, w_star, w0, eta, g, steps)
+    for t in range(steps):
+        w_host = W.cpu().numpy().astype(np.float64).reshape(copies, 2)
+        grad = ((w_host - w_star) @ A.T).astype(np.float32).reshape(-1)
+        B.sgd_momentum_step([W], [V], [torch.from_numpy(grad).cuda()], eta / g, 1.0 - 1.0 / g, 0.0)
+        got = W.cpu().numpy().reshape(copies, 2)
+        assert np.max(np.abs(got - ref[t + 1])) <= 2e-4 * max(1.0, np.max(np.abs(ref[t + 1]))), (g, t)
+    # (tests/test_async_model.py checks on the CPU that the asynchronous simulation obeys this recursion step by step)
+    assert np.linalg.norm(ref[-1] - w_star) < 0.5 * np.linalg.norm(w0 - w_star)

@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--no-events", action="store_true", help="record no events at all (no kernel table, no roofline)")
     ap.add_argument("--table-steps", type=int, default=5, help="instrumented steps before the timed region")
     ap.add_argument("--overlap", action="store_true", help="model gradients on a second stream beside the data gradients")
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5],
+                    help="workload configuration: 5 (default) is the CaffeNet-shaped stack the metric is quoted on; 1-4 are the "
+                         "single layer, the CIFAR-style stack, conv1 alone and conv2-conv5 alone (per-pass times and oracle errors)")
     ap.add_argument("--conv1-dgrad", action="store_true",
                     help="also compute conv1's data gradient (the paper's FLOP rule, App. B, leaves it out; default: skipped)")
     args = ap.parse_args()
@@ -109,6 +112,14 @@ def main():
     from paper_1606_04487_amd.stack import ConvStack
 
     torch.cuda.set_device(0)
+    if args.config != 5:
+        from paper_1606_04487_amd import config_bench
+        rec = config_bench.run_config(args.config, max(args.steps, 1))
+        print(json.dumps({
+            "metric": "conv fwd+bwd images/sec", "value": rec.pop("value"), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic",
+            "dtype": "f32" if args.config != 4 else "f32+bf16", "config": {"workload": rec.pop("workload")}, **rec}))
+        return
     dtype = B.BF16 if args.dtype == "bf16" else B.F32
     layers = wl.caffenet_stack(args.batch)
     stack = ConvStack(layers, dtype=dtype, ceil_mode=False, skip_first_dgrad=not args.conv1_dgrad, overlap_wgrad=args.overlap)

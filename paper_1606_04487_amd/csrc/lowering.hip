@@ -327,7 +327,11 @@ struct Col2imPlan {
     int pitch;   // LDS elements per row segment (multiple of the vector width)
 };
 
-template <typename T>
+// KH, KW > 0: stride 1 and a window known at compile time.  Pixel (iy, ix) then receives tap (ky, kx) from output
+// position (iy + ph - ky, ix + pw - kx), i.e. from LDS element  base - ky * Wo - kx  of row ky * KW + kx: one
+// address per pixel, constant offsets per tap, and the taps that fall outside the output are masked instead of
+// being skipped by loops with data-dependent bounds (the vector ALU, not memory, is what bounded this kernel).
+template <typename T, int KH, int KW>
 __global__ __launch_bounds__(256) void col2im_lds_kernel(ConvGeom g, Col2imPlan p, const T *__restrict__ D,
                                                          int64_t ld, T *__restrict__ dX)
 {
@@ -348,9 +352,26 @@ __global__ __launch_bounds__(256) void col2im_lds_kernel(ConvGeom g, Col2imPlan 
     const int64_t row_slots = ld / VEC;
     uint4 *dst = reinterpret_cast<uint4 *>(col2im_smem);
     const int pitch_slots = p.pitch / VEC;
-    for (int i = tid; i < khkw * slots; i += 256) {
-        int r = i / slots, v = i - r * slots;
-        dst[r * pitch_slots + v] = src[r * row_slots + v];
+    {
+        // batches of loads into registers, then into LDS: a plain copy loop waits for each load before it
+        // issues the next one, and a workgroup's whole segment is only about ten loads per thread
+        constexpr int BATCH = 12;
+        const int total = khkw * slots;
+        for (int i0 = tid; i0 < total; i0 += 256 * BATCH) {
+            uint4 regs[BATCH];
+            int where[BATCH];
+            // branch-free: indices past the end repeat the last slot (the same bytes land in the same place twice)
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                int i = i0 + 256 * u;
+                i = i < total ? i : total - 1;
+                const int r = i / slots, v = i - r * slots;
+                regs[u] = src[r * row_slots + v];
+                where[u] = r * pitch_slots + v;
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) dst[where[u]] = regs[u];
+        }
     }
     __syncthreads();
 
@@ -359,14 +380,33 @@ __global__ __launch_bounds__(256) void col2im_lds_kernel(ConvGeom g, Col2imPlan 
         uint32_t inb, pix, iy, ix;
         g.div_HW.divmod((uint32_t)px, inb, pix);
         g.div_W.divmod(pix, iy, ix);
-        const T *base = seg + skew + (int)inb * g.HoWo;
         float acc = 0.f;
-        const TapRange ry = tap_range((int)iy, g.ph, g.kh, g.sh, g.Ho, g.div_sh);
-        const TapRange rx = tap_range((int)ix, g.pw, g.kw, g.sw, g.Wo, g.div_sw);
-        for (int ky = ry.first, oy = ry.o_first; ky <= ry.last; ky += g.sh, --oy) {
-            const T *row = base + ky * g.kw * p.pitch + oy * g.Wo;
-            for (int kx = rx.first, ox = rx.o_first; kx <= rx.last; kx += g.sw, --ox)
-                acc += Elem<T>::to_f32(row[kx * p.pitch + ox]);
+        if constexpr (KH > 0) {
+            const int oy0 = (int)iy + g.ph, ox0 = (int)ix + g.pw;     // output position of tap (0, 0)
+            const int base = skew + (int)inb * g.HoWo + oy0 * g.Wo + ox0;
+            bool vx[KW];
+#pragma unroll
+            for (int kx = 0; kx < KW; ++kx) vx[kx] = (unsigned)(ox0 - kx) < (unsigned)g.Wo;
+#pragma unroll
+            for (int ky = 0; ky < KH; ++ky) {
+                const bool vy = (unsigned)(oy0 - ky) < (unsigned)g.Ho;
+#pragma unroll
+                for (int kx = 0; kx < KW; ++kx) {
+                    const bool ok = vy && vx[kx];
+                    const int idx = ok ? (ky * KW + kx) * p.pitch + base - ky * g.Wo - kx : 0;
+                    const float v = Elem<T>::to_f32(seg[idx]);
+                    acc += ok ? v : 0.f;
+                }
+            }
+        } else {
+            const T *base = seg + skew + (int)inb * g.HoWo;
+            const TapRange ry = tap_range((int)iy, g.ph, g.kh, g.sh, g.Ho, g.div_sh);
+            const TapRange rx = tap_range((int)ix, g.pw, g.kw, g.sw, g.Wo, g.div_sw);
+            for (int ky = ry.first, oy = ry.o_first; ky <= ry.last; ky += g.sh, --oy) {
+                const T *row = base + ky * g.kw * p.pitch + oy * g.Wo;
+                for (int kx = rx.first, ox = rx.o_first; kx <= rx.last; kx += g.sw, --ox)
+                    acc += Elem<T>::to_f32(row[kx * p.pitch + ox]);
+            }
         }
         dX[((int64_t)(n0 + inb) * g.C + c) * hw + pix] = Elem<T>::from_f32(acc);
     }
@@ -376,7 +416,7 @@ static bool make_col2im_plan(const ConvGeom &g, size_t elem, int64_t ld, Col2imP
 {
     const int vec = (int)(16 / elem);
     if (ld % vec != 0 || g.C > 65535) return false;
-    const size_t budget = 40 * 1024, hard_limit = 64 * 1024;
+    const size_t budget = 40 * 1024, hard_limit = 80 * 1024;  // two workgroups per compute unit at the limit
     const int khkw = g.kh * g.kw;
     size_t per_image = (size_t)khkw * g.HoWo * elem;
     int nb = (int)(budget / per_image);
@@ -398,10 +438,20 @@ int launch_col2im(const ConvGeom &g, int dtype, const void *dDhat, int64_t ld, v
     size_t lds = 0;
     if (make_col2im_plan(g, elem_size(dtype), ld, &plan, &lds)) {
         dim3 grid((unsigned)plan.groups, (unsigned)g.C, 1);
-        if (dtype == OMNI_BF16)
-            hipLaunchKernelGGL(col2im_lds_kernel<bf16_t>, grid, dim3(256), lds, s, g, plan, (const bf16_t *)dDhat, ld, (bf16_t *)dX);
-        else
-            hipLaunchKernelGGL(col2im_lds_kernel<float>, grid, dim3(256), lds, s, g, plan, (const float *)dDhat, ld, (float *)dX);
+        const bool unit = g.sh == 1 && g.sw == 1;
+#define OMNI_COL2IM_CASE(KH, KW)                                                                                              \
+    do {                                                                                                                      \
+        if (dtype == OMNI_BF16)                                                                                               \
+            hipLaunchKernelGGL((col2im_lds_kernel<bf16_t, KH, KW>), grid, dim3(256), lds, s, g, plan, (const bf16_t *)dDhat,   \
+                               ld, (bf16_t *)dX);                                                                              \
+        else                                                                                                                  \
+            hipLaunchKernelGGL((col2im_lds_kernel<float, KH, KW>), grid, dim3(256), lds, s, g, plan, (const float *)dDhat, ld, \
+                               (float *)dX);                                                                                   \
+    } while (0)
+        if (unit && g.kh == 3 && g.kw == 3) OMNI_COL2IM_CASE(3, 3);
+        else if (unit && g.kh == 5 && g.kw == 5) OMNI_COL2IM_CASE(5, 5);
+        else OMNI_COL2IM_CASE(0, 0);
+#undef OMNI_COL2IM_CASE
         OMNI_LAUNCH_CHECK();
         return OMNI_OK;
     }

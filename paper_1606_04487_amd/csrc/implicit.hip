@@ -58,6 +58,7 @@ struct Geom {
     int32_t n_chunks;        // C / CH
     int32_t Fp;              // F rounded up to the row tile
     int32_t tiles_f, tiles_m, n_items, per_xcd;
+    int32_t splits, chunks_per_split;  // the reduction's chunks cut into `splits` ranges (1: not split)
     int32_t bn;              // columns per workgroup: BN_NARROW, BN_MID or BN_WIDE
     int32_t bm;              // filter rows per workgroup: 128, or 96 (with BN_WIDE) for layers of few filters
     FastDiv div_HoWo, div_Wo, div_W;
@@ -103,9 +104,13 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
     }
 }
 
-template <int BM, int WM, int WN, int BN, int PATCH_PIX>
+// Epi: FwdEpilogue<bf16_t> (bias, ReLU, rounding, store into Y), or PartialEpilogue when few column tiles
+// exist (small batches): the reduction's chunks are then split over `g.splits` workgroups per tile, each
+// leaving its raw fp32 sums in a slice [F][M] of the scratch, which reduce_store_kernel adds in split order
+// and hands to the forward epilogue.
+template <int BM, int WM, int WN, int BN, int PATCH_PIX, typename Epi>
 __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Wt,
-                                                        Geom g, FwdEpilogue<bf16_t> epi)
+                                                        Geom g, Epi epi)
 {
     static_assert(WM * WN * 64 == NT, "eight wavefronts");
     static_assert(BM * NG <= NT, "at most one 16-byte piece of a tap's weight tile per thread");
@@ -120,7 +125,11 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
     const int xcd = blockIdx.x % 8, slot_id = blockIdx.x / 8;
     const int item = xcd * g.per_xcd + slot_id;  // contiguous ranges of tiles per XCD, row tiles fastest
     if (item >= g.n_items) return;
-    const int tm = item / g.tiles_f, tf = item - tm * g.tiles_f;
+    const int n_tiles = g.tiles_f * g.tiles_m;
+    const int z = item / n_tiles, tile_id = item - z * n_tiles;   // splits of one tile are far apart in time
+    const int chunk_lo = z * g.chunks_per_split;
+    const int chunk_hi = chunk_lo + g.chunks_per_split < g.n_chunks ? chunk_lo + g.chunks_per_split : g.n_chunks;
+    const int tm = tile_id / g.tiles_f, tf = tile_id - tm * g.tiles_f;
     const int row0 = tf * BM, col0 = tm * BN;
     const int m_last = (col0 + BN < g.M ? col0 + BN : g.M) - 1;
     const int n0 = (int)g.div_HoWo.div((uint32_t)col0);
@@ -142,7 +151,8 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         total_pieces = p0;
     }
     for (int i = tid; i < NG * PATCH_PIX; i += NT) patch[i] = make_uint4(0, 0, 0, 0);
-    for (int i = tid; i < BM; i += NT) lds_add[i] = epi.row_add(row0 + i);
+    if constexpr (Epi::HAS_ROW_ADD)
+        for (int i = tid; i < BM; i += NT) lds_add[i] = epi.row_add(row0 + i);
     __syncthreads();
 
     // patch pixel of each of this lane's columns at tap (0, 0)
@@ -268,14 +278,14 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         }
     };
 
-    issue_patch(0);
-    issue_a(0);
+    issue_patch(chunk_lo);
+    issue_a(chunk_lo * KK);
     commit_patch();
     commit_a(0);
     __syncthreads();
     int ky = 0, kx = 0, buf = 0;
-    for (int chunk = 0; chunk < g.n_chunks; ++chunk) {
-        const bool more_chunks = chunk + 1 < g.n_chunks;
+    for (int chunk = chunk_lo; chunk < chunk_hi; ++chunk) {
+        const bool more_chunks = chunk + 1 < chunk_hi;
         for (int t0 = 0; t0 < KK; t0 += TG) {
             const int nt = KK - t0 < TG ? KK - t0 : TG;
             const bool last_group = t0 + TG >= KK;
@@ -317,7 +327,7 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
     // every wavefront is past the loop's last barrier: the weight tiles become staging space
     constexpr int STRIP = 16 * staged_pitch(TJ);
     static_assert((NT / 64) * STRIP <= (int)sizeof(atile), "staging strips fit in the weight tiles");
-    store_tile_staged<TI, TJ, 16>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, 0, epi,
+    store_tile_staged<TI, TJ, 16>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, z, epi,
                                   reinterpret_cast<char *>(atile) + wave * STRIP, lds_add, row0);
 }
 
@@ -419,7 +429,17 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
     }
     if (g->bn == 0) return false;
     g->tiles_m = (g->M + g->bn - 1) / g->bn;
-    g->n_items = g->tiles_f * g->tiles_m;
+    // Few tiles (small batches): cut the reduction into ranges of chunks so that about one workgroup per
+    // compute unit exists; the ranges' fp32 sums are added in a fixed order afterwards.
+    const int n_tiles = g->tiles_f * g->tiles_m;
+    g->splits = 1;
+    if (n_tiles <= 128 && g->n_chunks >= 2 && (double)g->F * g->M * 4.0 * 16.0 < 4.0e9) {
+        int want = 256 / n_tiles;
+        g->splits = want < g->n_chunks ? want : g->n_chunks;
+    }
+    g->chunks_per_split = (g->n_chunks + g->splits - 1) / g->splits;
+    g->splits = (g->n_chunks + g->chunks_per_split - 1) / g->chunks_per_split;
+    g->n_items = n_tiles * g->splits;
     g->per_xcd = (g->n_items + 7) / 8;
     return true;
 }
@@ -438,11 +458,17 @@ bool fused_supported(const ConvGeom &c, int dtype, bool data_gradient)
     return dtype == OMNI_BF16 && fused::make_fused_geom(c, data_gradient, &g);
 }
 
+static size_t fused_packed_bytes(const fused::Geom &g)
+{
+    return ((size_t)g.n_chunks * g.KK * fused::NG * g.Fp * 16 + 255) / 256 * 256;
+}
+
+// the repacked weights, then (split reductions only) the fp32 partial results [splits][F][M]
 size_t fused_weight_bytes(const ConvGeom &c, bool data_gradient)
 {
     fused::Geom g;
     if (!fused::make_fused_geom(c, data_gradient, &g)) return 0;
-    return (size_t)g.n_chunks * g.KK * fused::NG * g.Fp * 16;
+    return fused_packed_bytes(g) + (g.splits > 1 ? (size_t)g.splits * g.F * g.M * sizeof(float) : 0);
 }
 
 int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, const void *W, const float *bias,
@@ -463,18 +489,28 @@ int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, cons
     FwdEpilogue<bf16_t> epi{(bf16_t *)Y, bias, g.F, g.M, g.HoWo, g.div_HoWo, relu};
     ProfScope prof(kid >= 0 ? kid : (data_gradient ? KID_FUSED_DGRAD : KID_FUSED_FWD), s, 2.0 * (double)c.M * c.K * c.F, 0.0);
     dim3 grid((unsigned)(g.per_xcd * 8)), block(NT);
-    if (g.bm == 96)
-        hipLaunchKernelGGL((fused_conv_kernel<96, 1, 8, BN_WIDE, PATCH_WIDE>), grid, block, 0, s, (const bf16_t *)X,
-                           (const bf16_t *)wt_scratch, g, epi);
-    else if (g.bn == BN_WIDE)
-        hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4, BN_WIDE, PATCH_WIDE>), grid, block, 0, s, (const bf16_t *)X,
-                           (const bf16_t *)wt_scratch, g, epi);
-    else if (g.bn == BN_MID)
-        hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4, BN_MID, PATCH_MID>), grid, block, 0, s, (const bf16_t *)X,
-                           (const bf16_t *)wt_scratch, g, epi);
-    else
-        hipLaunchKernelGGL((fused_conv_kernel<128, 2, 4, BN_NARROW, PATCH_NARROW>), grid, block, 0, s, (const bf16_t *)X,
-                           (const bf16_t *)wt_scratch, g, epi);
+    float *partials = reinterpret_cast<float *>(reinterpret_cast<char *>(wt_scratch) + fused_packed_bytes(g));
+    PartialEpilogue pe{partials, g.F, g.M};
+#define OMNI_FUSED_LAUNCH(BM_, WM_, WN_, BN_, PATCH_)                                                                       \
+    do {                                                                                                                    \
+        if (g.splits > 1)                                                                                                   \
+            hipLaunchKernelGGL((fused_conv_kernel<BM_, WM_, WN_, BN_, PATCH_, PartialEpilogue>), grid, block, 0, s,          \
+                               (const bf16_t *)X, (const bf16_t *)wt_scratch, g, pe);                                       \
+        else                                                                                                                \
+            hipLaunchKernelGGL((fused_conv_kernel<BM_, WM_, WN_, BN_, PATCH_, FwdEpilogue<bf16_t>>), grid, block, 0, s,      \
+                               (const bf16_t *)X, (const bf16_t *)wt_scratch, g, epi);                                      \
+    } while (0)
+    if (g.bm == 96) OMNI_FUSED_LAUNCH(96, 1, 8, BN_WIDE, PATCH_WIDE);
+    else if (g.bn == BN_WIDE) OMNI_FUSED_LAUNCH(128, 2, 4, BN_WIDE, PATCH_WIDE);
+    else if (g.bn == BN_MID) OMNI_FUSED_LAUNCH(128, 2, 4, BN_MID, PATCH_MID);
+    else OMNI_FUSED_LAUNCH(128, 2, 4, BN_NARROW, PATCH_NARROW);
+#undef OMNI_FUSED_LAUNCH
+    OMNI_LAUNCH_CHECK();
+    if (g.splits > 1) {
+        const int64_t count = (int64_t)g.F * g.M;
+        hipLaunchKernelGGL((reduce_store_kernel<FwdEpilogue<bf16_t>>), dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s,
+                           partials, g.splits, g.F, g.M, epi);
+    }
     OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }

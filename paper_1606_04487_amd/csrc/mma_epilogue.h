@@ -263,4 +263,18 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][TJ], int i_w
     }
 }
 
+// Ordered sum of the split partial results [splits][rows][cols] of a forward or data-gradient product,
+// handed to the product's own epilogue (address map, bias, ReLU, rounding).  One thread per result.
+template <typename Epi>
+__global__ __launch_bounds__(256) void reduce_store_kernel(const float *__restrict__ partials, int splits, int rows,
+                                                           int cols, Epi epi)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x, count = (int64_t)rows * cols;
+    if (idx >= count) return;
+    const int i = (int)(idx / cols), j = (int)(idx - (int64_t)i * cols);
+    float acc = 0.f;
+    for (int z = 0; z < splits; ++z) acc += partials[(int64_t)z * count + idx];
+    epi.store(i, epi.column(j), acc, epi.row_add(i), 0);
+}
+
 }  // namespace omni

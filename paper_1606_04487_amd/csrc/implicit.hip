@@ -238,16 +238,32 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
     const u32x4 *wt = reinterpret_cast<const u32x4 *>(Wt) + (row0 + (wtid / BM) * g.Fp + wtid % BM);
     const int step_stride = NG * g.Fp;  // packs from one step's tile to the next
     u32x4 *const at = reinterpret_cast<u32x4 *>(atile) + (wtid / BM) * LA + wtid % BM;
-    auto issue_a = [&](int st0) {
+    // Tiles whose pieces are one per thread (BM * NG == NT, BM a multiple of 64) go from global memory straight
+    // into LDS: a wavefront's 64 pieces are 64 consecutive packs of one channel pack, in memory and in the tile,
+    // so one global-to-LDS load per tap and wavefront (LDS address = a wave-uniform base + lane * 16) replaces a
+    // load into registers, the registers themselves and an LDS store.  The loads are asynchronous: they are waited
+    // for (memory counter at zero) before the barrier that publishes the buffer.
+    constexpr bool DMA = BM * NG == NT && BM % 64 == 0;
+    u32x4 *const at_wave = reinterpret_cast<u32x4 *>(atile) + __builtin_amdgcn_readfirstlane((wave * 64 / BM) * LA + (wave * 64) % BM);
+    auto issue_a = [&](int st0, int buf) {
         static_for<0, TG>([&](auto q) {
             int st = st0 + decltype(q)::value;
             st = st < n_steps ? st : n_steps - 1;
-            areg(q) = wt[st * step_stride];
+            if constexpr (DMA)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wt + st * step_stride),
+                                                 (__attribute__((address_space(3))) void *)(at_wave + (buf * TG + decltype(q)::value) * (NG * LA)),
+                                                 16, 0, 0);
+            else
+                areg(q) = wt[st * step_stride];
         });
     };
     auto commit_a = [&](int buf) {
-        if (BM * NG == NT || has_piece)
-            static_for<0, TG>([&](auto q) { at[(buf * TG + decltype(q)::value) * (NG * LA)] = areg(q); });
+        if constexpr (!DMA)
+            if (has_piece)
+                static_for<0, TG>([&](auto q) { at[(buf * TG + decltype(q)::value) * (NG * LA)] = areg(q); });
+    };
+    auto wait_a = [&]() {
+        if constexpr (DMA) __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0) only: the tiles are in LDS
     };
 
     f32x16 acc[TI][TJ];
@@ -258,30 +274,35 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][u][v] = 0.f;
 
-    auto compute = [&](int buf, int slot, int tapoff) {
-        const uint4 *pa = atile + (buf * TG + slot) * (NG * LA) + wm * (BM / WM) + li;
-        int pix[TJ];
+    // A tap is two slabs of MFMAs (channel packs 0, 1 and 2, 3 of the chunk).  The fragments of a slab are read
+    // from LDS one slab ahead, into the other of two register sets, so that a wavefront's LDS latency runs
+    // under its own MFMAs and not only under the other wavefront's.
+    uint4 fa0[TI], fb0[TJ], fa1[TI], fb1[TJ];
+    int pix[TJ];
+    auto set_pix = [&](int tapoff) {
 #pragma unroll
         for (int u = 0; u < TJ; ++u) pix[u] = swz(pp0[u] + tapoff);
+    };
+    auto load_frag = [&](uint4 (&fa)[TI], uint4 (&fb)[TJ], int buf, int slot, int s2) {
+        const int g2 = 2 * s2 + h;
+        const uint4 *pa = atile + (buf * TG + slot) * (NG * LA) + wm * (BM / WM) + li + g2 * LA;
 #pragma unroll
-        for (int s = 0; s < NG / 2; ++s) {
-            const int g2 = 2 * s + h;
-            uint4 a[TI], b[TJ];
+        for (int t = 0; t < TI; ++t) fa[t] = pa[32 * t];
 #pragma unroll
-            for (int t = 0; t < TI; ++t) a[t] = pa[g2 * LA + 32 * t];
+        for (int u = 0; u < TJ; ++u) fb[u] = patch[g2 * PATCH_PIX + pix[u]];
+    };
+    auto mma_frag = [&](const uint4 (&fa)[TI], const uint4 (&fb)[TJ]) {
 #pragma unroll
-            for (int u = 0; u < TJ; ++u) b[u] = patch[g2 * PATCH_PIX + pix[u]];
+        for (int t = 0; t < TI; ++t)
 #pragma unroll
-            for (int t = 0; t < TI; ++t)
-#pragma unroll
-                for (int u = 0; u < TJ; ++u) Mma<bf16_t>::run(a[t], b[u], acc[t][u]);
-        }
+            for (int u = 0; u < TJ; ++u) Mma<bf16_t>::run(fa[t], fb[u], acc[t][u]);
     };
 
     issue_patch(chunk_lo);
-    issue_a(chunk_lo * KK);
+    issue_a(chunk_lo * KK, 0);
     commit_patch();
     commit_a(0);
+    wait_a();
     __syncthreads();
     int ky = 0, kx = 0, buf = 0;
     for (int chunk = chunk_lo; chunk < chunk_hi; ++chunk) {
@@ -289,36 +310,29 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         for (int t0 = 0; t0 < KK; t0 += TG) {
             const int nt = KK - t0 < TG ? KK - t0 : TG;
             const bool last_group = t0 + TG >= KK;
-            issue_a(chunk * KK + t0 + nt);                     // the next group (of this chunk or the next)
+            issue_a(chunk * KK + t0 + nt, buf ^ 1);            // the next group (of this chunk or the next)
             if (t0 == 0 && more_chunks) issue_patch(chunk + 1);
             // The next group's weights go to the other buffer (free since the last barrier) before this
             // group's last tap, so that those stores run under the other wavefronts' MFMAs.
-            if (TJ <= 2 && TI <= 2 && nt == TG) {
-                // a full group as straight-line code: the compiler may start a tap's LDS reads under the
-                // previous tap's MFMAs
-                int off[TG];
-#pragma unroll
-                for (int t = 0; t < TG; ++t) {
-                    off[t] = ky * g.Wp + kx;
-                    if (++kx == g.kw) kx = 0, ++ky;
+            set_pix(ky * g.Wp + kx);
+            load_frag(fa0, fb0, buf, 0, 0);
+            for (int t = 0; t < nt; ++t) {
+                load_frag(fa1, fb1, buf, t, 1);
+                if (t == nt - 1) commit_a(buf ^ 1);
+                mma_frag(fa0, fb0);
+                if (++kx == g.kw) kx = 0, ++ky;
+                if (t + 1 < nt) {
+                    set_pix(ky * g.Wp + kx);
+                    load_frag(fa0, fb0, buf, t + 1, 0);
                 }
-                static_for<0, TG>([&](auto q) {
-                    constexpr int Q = decltype(q)::value;
-                    if constexpr (Q == TG - 1) commit_a(buf ^ 1);
-                    compute(buf, Q, off[Q]);
-                });
-            } else {
-                for (int t = 0; t < nt; ++t) {
-                    if (t == nt - 1) commit_a(buf ^ 1);
-                    compute(buf, t, ky * g.Wp + kx);
-                    if (++kx == g.kw) kx = 0, ++ky;
-                }
+                mma_frag(fa1, fb1);
             }
             if (last_group) ky = 0;
             if (last_group && more_chunks) {
                 __syncthreads();  // every wavefront has read this chunk's pixels
                 commit_patch();
             }
+            wait_a();
             __syncthreads();      // this group's weights are free, the next group's (and chunk's pixels) are in LDS
             buf ^= 1;
         }

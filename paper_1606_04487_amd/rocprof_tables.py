@@ -1,7 +1,8 @@
 """Turn rocprofv3 CSV output of a bench run into the short tables kept under profiles/.
 
-Three sub-commands, each reading what one kind of rocprofv3 run wrote (`--output-format csv`):
+Four sub-commands, each reading what one kind of rocprofv3 run wrote (`--output-format csv`):
 
+    movement  <FETCH_SIZE csv> <WRITE_SIZE csv> <stdout>  lowering / col2im alone (movement_bench): per layer times and traffic
     stats     <kernel_stats.csv> <bench stdout>   per-class and per-kernel durations next to the library's own
                                                    event timing (from the JSON line the profiled run printed)
     traffic   <FETCH_SIZE csv> <WRITE_SIZE csv>    HBM bytes per kernel class, each counter scaled by what it read
@@ -157,6 +158,49 @@ def cmd_traffic(a) -> None:
         TRAFFIC_JSON.write_text(json.dumps(store, indent=1, sort_keys=True) + "\n")
 
 
+def cmd_movement(a) -> None:
+    """Lowering / col2im on their own: movement_bench's event table next to the traffic of each launch.
+    The counter files list dispatches in launch order; movement_bench launches, per dtype and layer,
+    (warmup + iters) pairs of (lower, col2im)."""
+    def launches(path):
+        rows = list(csv.DictReader(open(path)))
+        cal = max(float(r["Counter_Value"]) for r in rows if "copyBuffer" in r["Kernel_Name"])
+        seq = [(kernel_class(r["Kernel_Name"]), short_name(r["Kernel_Name"]), float(r["Counter_Value"])) for r in rows
+               if kernel_class(r["Kernel_Name"]) in ("lower", "col2im")]
+        return seq, cal
+    fe, fcal = launches(a.fetch)
+    wr, wcal = launches(a.write)
+    ff, wf = CAL_KIB / fcal, CAL_KIB / wcal
+    events = [json.loads(l) for l in open(a.bench_out) if l.startswith("{")]
+    per = 2 * (a.warmup + a.iters)
+    with open(a.out, "w") as f:
+        f.write(f"# Batched lowering and col2im on their own against the HBM roofline: {a.title}\n\n")
+        f.write("Commands (from /tmp with TMPDIR=/tmp on one MI355X):\n\n")
+        for c in a.command:
+            f.write(f"    {c}\n")
+        f.write("\n`us` and `GB/s` come from the first command's own output (HIP events around each launch; rocprofv3's kernel trace of the\n"
+                "same run agrees, see the second table); `fetched` / `written` are FETCH_SIZE / WRITE_SIZE of one launch of that layer, scaled by the\n"
+                f"readings for the 256 MiB calibration copy ({ff:.4f} and {wf:.4f}).  Algorithmic bytes: the input once plus the lowered matrix once,\n"
+                "(N C H W + K ld) e.  Peak: 8000 GB/s.\n\n")
+        f.write("| kernel | layer | dtype | algorithmic MB | us | GB/s | of peak | fetched MB | written MB | kernel |\n|---|---|---|---|---|---|---|---|---|---|\n")
+        for i, r in enumerate(events):
+            blk, which = i // 2, (0 if r["kernel"] == "lower" else 1)
+            j = blk * per + 2 * a.warmup + which            # first timed launch of this (dtype, layer, kernel)
+            fmb = fe[j][2] * ff * 1024 / 1e6 if j < len(fe) else float("nan")
+            wmb = wr[j][2] * wf * 1024 / 1e6 if j < len(wr) else float("nan")
+            assert j >= len(fe) or fe[j][0] == r["kernel"], (i, j, fe[j], r["kernel"])
+            f.write(f"| {r['kernel']} | {r['layer']} | {r['dtype']} | {r['algorithmic_bytes'] / 1e6:.0f} | {r['avg_launch_ms'] * 1e3:.1f} | "
+                    f"{r['gbs']:.0f} | {r['frac_of_hbm_peak']:.2f} | {fmb:.0f} | {wmb:.0f} | {fe[j][1] if j < len(fe) else ''} |\n")
+        if a.stats:
+            f.write("\nrocprofv3 kernel statistics of the timed run (all layers and both dtypes together per kernel):\n\n| kernel | calls | avg us |\n|---|---|---|\n")
+            for r in csv.DictReader(open(a.stats)):
+                if kernel_class(r["Name"]) in ("lower", "col2im"):
+                    f.write(f"| {short_name(r['Name'])} | {r['Calls']} | {float(r['AverageNs']) / 1e3:.1f} |\n")
+        if a.reading:
+            f.write("\n" + a.reading + "\n")
+    print(open(a.out).read())
+
+
 def cmd_counters(a) -> None:
     agg = collections.defaultdict(lambda: collections.defaultdict(list))
     for path in a.csv:
@@ -211,6 +255,12 @@ def main() -> None:
     c.add_argument("--title", required=True), c.add_argument("--command", action="append", required=True)
     c.add_argument("--reading", default="")
     c.set_defaults(fn=cmd_counters)
+    m = sub.add_parser("movement")
+    m.add_argument("fetch"), m.add_argument("write"), m.add_argument("bench_out")
+    m.add_argument("--stats", default=""), m.add_argument("--iters", type=int, default=2), m.add_argument("--warmup", type=int, default=1)
+    m.add_argument("--out", required=True), m.add_argument("--title", required=True)
+    m.add_argument("--command", action="append", required=True), m.add_argument("--reading", default="")
+    m.set_defaults(fn=cmd_movement)
     a = ap.parse_args()
     a.fn(a)
 

@@ -317,6 +317,72 @@ __global__ __launch_bounds__(256) void col2im_kernel(ConvGeom g, const T *__rest
     dX[(int64_t)plane * g.H * g.W + pix] = Elem<T>::from_f32(acc);
 }
 
+// Strided layers whose segments do not fit in LDS (CaffeNet's conv1: 11 x 11 window, stride 4).  With stride S an
+// input pixel meets only the taps of its own residue class, kx = (ix + pw) mod S + S*j, and for one such tap the
+// pixels ix, ix + S, ix + 2S, ... of a row read consecutive columns of one row of dD-hat.  So a thread takes the S
+// consecutive pixels S*b .. S*b + S - 1 of an input row and neighbouring lanes take neighbouring b: every load
+// instruction of a wavefront then reads one run of consecutive elements (the per-pixel form above reads S runs with
+// gaps, and fetched three times the matrix on conv1), and every thread stores S consecutive pixels at once.
+// At most JY x JX taps per pixel (ceil(kh / S), ceil(kw / S)), all issued together with the absent ones masked;
+// each pixel's terms are added in ascending (ky, kx), as above.
+template <typename T, int S, int JY, int JX>
+__global__ __launch_bounds__(256) void col2im_strided_kernel(ConvGeom g, const T *__restrict__ D, int64_t ld,
+                                                             T *__restrict__ dX, uint32_t plane0, uint32_t count,
+                                                             FastDiv div_rows, FastDiv div_bw)
+{
+    // One launch covers `count` < 2^31 (plane, row, group of S pixels) triples starting at plane plane0.
+    const uint32_t local = blockIdx.x * 256u + threadIdx.x;
+    if (local >= count) return;
+    uint32_t pl, rest, iy, b;
+    div_rows.divmod(local, pl, rest);  // rows of groups per plane: H * ceil(W / S)
+    div_bw.divmod(rest, iy, b);
+    const uint32_t plane = plane0 + pl;
+    const uint32_t n = plane / (uint32_t)g.C, c = plane - n * (uint32_t)g.C;
+    const TapRange ry = tap_range((int)iy, g.ph, g.kh, S, g.Ho, g.div_sh);
+    TapRange rx[S];
+#pragma unroll
+    for (int px = 0; px < S; ++px) {
+        const int ix = S * (int)b + px;
+        rx[px] = tap_range(ix < g.W ? ix : g.W - 1, g.pw, g.kw, S, g.Wo, g.div_sw);
+        if (ix >= g.W) rx[px].last = -1;
+    }
+    float v[JY][S][JX];
+    bool ok[JY][S][JX];
+#pragma unroll
+    for (int jy = 0; jy < JY; ++jy) {
+        const int ky = ry.first + jy * S, oy = ry.o_first - jy;
+        const bool vy = ky <= ry.last;
+        const int64_t col0 = ((int64_t)n * g.Ho + oy) * g.Wo;
+#pragma unroll
+        for (int px = 0; px < S; ++px)
+#pragma unroll
+            for (int jx = 0; jx < JX; ++jx) {
+                const int kx = rx[px].first + jx * S, ox = rx[px].o_first - jx;
+                ok[jy][px][jx] = vy && kx <= rx[px].last;
+                const int64_t at = ok[jy][px][jx] ? (((int64_t)c * g.kh + ky) * g.kw + kx) * ld + col0 + ox : 0;
+                v[jy][px][jx] = Elem<T>::to_f32(D[at]);
+            }
+    }
+    T res[S];
+#pragma unroll
+    for (int px = 0; px < S; ++px) {
+        float acc = 0.f;
+#pragma unroll
+        for (int jy = 0; jy < JY; ++jy)
+#pragma unroll
+            for (int jx = 0; jx < JX; ++jx) acc += ok[jy][px][jx] ? v[jy][px][jx] : 0.f;
+        res[px] = Elem<T>::from_f32(acc);
+    }
+    T *out = dX + ((int64_t)plane * g.H + iy) * g.W + S * (int64_t)b;
+    if (S * (int)b + S <= g.W) {
+        __builtin_memcpy(out, res, sizeof(res));  // element-aligned store of S pixels
+    } else {
+#pragma unroll
+        for (int px = 0; px < S; ++px)
+            if (S * (int)b + px < g.W) out[px] = res[px];
+    }
+}
+
 // LDS-staged variant.  A workgroup takes channel c of a group of nb images.  Step 1 copies, for each of
 // the kh*kw rows of that channel, the column range of the group from dD-hat into LDS with 16-byte loads
 // (all loads are in flight together).  Step 2 is the same gather as above, served from LDS: one thread
@@ -453,6 +519,28 @@ int launch_col2im(const ConvGeom &g, int dtype, const void *dDhat, int64_t ld, v
         else OMNI_COL2IM_CASE(0, 0);
 #undef OMNI_COL2IM_CASE
         OMNI_LAUNCH_CHECK();
+        return OMNI_OK;
+    }
+    // strided layers: the form whose loads are contiguous per wavefront, when the window has at most 3 x 3 taps per pixel
+    const int S = g.sh;
+    if (g.sh == g.sw && (S == 2 || S == 4) && (g.kh + S - 1) / S <= 3 && (g.kw + S - 1) / S <= 3) {
+        const int64_t bw = (g.W + S - 1) / S, rows = (int64_t)g.H * bw;
+        const int64_t per_launch = (0x7fffffffll - 4096) / rows;
+        const FastDiv div_rows((uint32_t)rows), div_bw((uint32_t)bw);
+        for (int64_t p0 = 0; p0 < planes; p0 += per_launch) {
+            const int64_t np = planes - p0 < per_launch ? planes - p0 : per_launch;
+            const uint32_t count = (uint32_t)(np * rows);
+            dim3 grid((count + 255u) / 256u);
+#define OMNI_COL2IM_STRIDED(T_, S_)                                                                                       \
+    hipLaunchKernelGGL((col2im_strided_kernel<T_, S_, 3, 3>), grid, dim3(256), 0, s, g, (const T_ *)dDhat, ld, (T_ *)dX,   \
+                       (uint32_t)p0, count, div_rows, div_bw)
+            if (dtype == OMNI_BF16 && S == 4) OMNI_COL2IM_STRIDED(bf16_t, 4);
+            else if (dtype == OMNI_BF16) OMNI_COL2IM_STRIDED(bf16_t, 2);
+            else if (S == 4) OMNI_COL2IM_STRIDED(float, 4);
+            else OMNI_COL2IM_STRIDED(float, 2);
+#undef OMNI_COL2IM_STRIDED
+            OMNI_LAUNCH_CHECK();
+        }
         return OMNI_OK;
     }
     int64_t planes_per_launch = (0x7fffffffll - 4096) / hw;

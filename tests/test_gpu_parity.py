@@ -110,6 +110,50 @@ def test_col2im(B, cfg, dtype):
     assert rel_err(host(got), oracle.col2im(s, Z)) <= TOL[dtype]
 
 
+# Strided layers whose per-image segments exceed what the LDS-staged kernel holds (or whose leading dimension is
+# not a multiple of the vector width) take the form with S pixels per thread: strides 2 and 4, windows with one to
+# three taps per pixel and direction, widths that are not multiples of the stride, padding.
+STRIDED = [
+    (2, 2, 65, 65, 1, 7, 7, 2, 2, 3, 3),
+    (1, 2, 115, 113, 1, 11, 11, 4, 4, 0, 0),
+    (1, 2, 137, 135, 1, 3, 3, 2, 2, 1, 1),
+    (2, 3, 40, 38, 1, 5, 12, 4, 4, 2, 5),
+    (3, 2, 21, 23, 1, 4, 4, 4, 4, 0, 0),
+    (2, 2, 19, 18, 1, 2, 6, 2, 2, 0, 2),
+]
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("cfg", STRIDED)
+def test_col2im_strided(B, cfg, dtype):
+    s, *_ = make(cfg, dtype, 4)
+    d = desc_of(B, cfg, dtype)
+    ho, wo = oracle.out_dims(s)
+    K, M = s.C * s.kh * s.kw, s.N * ho * wo
+    rng = np.random.default_rng(5)
+    Zi = rng.integers(-3, 4, size=(K, M)).astype(np.float32)      # integer data: sums are exact
+    ref = oracle.col2im(s, Zi)
+    for pad in (0, 3):
+        Zp = np.concatenate([Zi, np.full((K, pad), 7.0, np.float32)], axis=1) if pad else Zi
+        got = B.col2im(d, gpu(Zp, dtype), ld=M + pad)
+        assert np.array_equal(host(got), ref), (cfg, pad)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("cfg", STRIDED + [(1, 2, 150, 9, 1, 3, 3, 1, 1, 1, 1), (1, 1, 97, 200, 1, 5, 5, 1, 1, 2, 2)])
+def test_lower_large_planes(B, cfg, dtype):
+    """Planes too large for whole images per workgroup: bands of output rows, narrow bands with the threads split
+    into row groups."""
+    s, X, *_ = make(cfg, dtype, 6)
+    d = desc_of(B, cfg, dtype)
+    ref = oracle.lower(s, X)
+    M = ref.shape[1]
+    for pad in (0, 16, 3):
+        got = host(B.lower(d, gpu(X, dtype), ld=M + pad)).astype(np.float32)
+        assert np.array_equal(got[:, :M].view(np.uint32), ref.view(np.uint32)), (cfg, pad)
+        assert np.all(got[:, M:].view(np.uint32) == 0)
+
+
 # ------------------------------------------------------------------------------------ the three passes
 
 @pytest.mark.parametrize("dtype", [0, 1])

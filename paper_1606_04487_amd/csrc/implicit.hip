@@ -417,9 +417,28 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
         }
         return true;
     };
-    // Among the tiles that fit, the one with the least estimated time: rounds of the 256 compute units
-    // times the tile's width, the narrower tiles a few per cent dearer per column (their weights are
+    // Few tiles (small batches): the reduction is cut into ranges of chunks so that about one workgroup per
+    // compute unit exists; the ranges' fp32 sums are added in a fixed order afterwards.
+    auto splits_for = [&](int64_t n_tiles, int64_t F_rows) {
+        int splits = 1;
+        if (n_tiles <= 128 && g->n_chunks >= 2 && (double)F_rows * g->M * 4.0 * 16.0 < 4.0e9) {
+            int want = (int)(256 / n_tiles);
+            splits = want < g->n_chunks ? want : g->n_chunks;
+        }
+        const int per = (g->n_chunks + splits - 1) / splits;
+        return (g->n_chunks + per - 1) / per;
+    };
+    // Among the tiles that fit, the one with the least estimated time: rounds of the 256 compute units times the
+    // tile's width times what a workgroup does per column -- the chunks of the reduction it walks plus its fixed
+    // part (prologue and epilogue cost about as much as 14 window taps; a split reduction also writes fp32 partial
+    // sums that are added afterwards) -- the narrower tiles a few per cent dearer per column (their weights are
     // staged for fewer columns, and they read more LDS fragments per MFMA).
+    auto estimate = [&](int64_t tiles, int bn, double per_column, int64_t F_rows) {
+        const int splits = splits_for(tiles, F_rows);
+        const int per = (g->n_chunks + splits - 1) / splits;
+        const double fixed = 14.0 / g->KK + (splits > 1 ? 0.5 : 0.0);
+        return (double)((tiles * splits + 255) / 256) * bn * per_column * (per + fixed);
+    };
     const int want = g_fused_bn;  // tuning override: 256, 384 or 512 (0: choose)
     const struct { int bn, patch; double per_column; } tiles[3] = {
         {BN_WIDE, PATCH_WIDE, 1.0}, {BN_MID, PATCH_MID, 1.03}, {BN_NARROW, PATCH_NARROW, 1.06}};
@@ -427,8 +446,7 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
     g->bn = 0;
     for (const auto &t : tiles) {
         if ((want != 0 && want != t.bn) || !fits(t.bn, t.patch)) continue;
-        int64_t items = (int64_t)g->tiles_f * ((g->M + t.bn - 1) / t.bn);
-        double cost = (double)((items + 255) / 256) * t.bn * t.per_column;
+        const double cost = estimate((int64_t)g->tiles_f * ((g->M + t.bn - 1) / t.bn), t.bn, t.per_column, g->F);
         if (g->bn == 0 || cost < best) g->bn = t.bn, best = cost;
     }
     // A layer of at most 64 filters takes a 96-row tile (8 wavefronts of 96 x 64 on 512 columns): three quarters
@@ -437,20 +455,13 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
     const int bm_want = g_fused_bm;  // tuning override: 128 keeps the 128-row tile, 96 forces the other up to 96 filters
     const int f_max = bm_want == 96 ? 96 : 64;
     if (g->F <= f_max && (bm_want == 0 || bm_want == 96) && (want == 0 || want == BN_WIDE) && fits(BN_WIDE, PATCH_WIDE)) {
-        int64_t items = (g->M + BN_WIDE - 1) / BN_WIDE;
-        double cost = (double)((items + 255) / 256) * BN_WIDE * 0.8;
+        const double cost = estimate((g->M + BN_WIDE - 1) / BN_WIDE, BN_WIDE, 0.8, g->F);
         if (g->bn == 0 || cost < best) g->bn = BN_WIDE, g->bm = 96, g->Fp = 96, g->tiles_f = 1, best = cost;
     }
     if (g->bn == 0) return false;
     g->tiles_m = (g->M + g->bn - 1) / g->bn;
-    // Few tiles (small batches): cut the reduction into ranges of chunks so that about one workgroup per
-    // compute unit exists; the ranges' fp32 sums are added in a fixed order afterwards.
     const int n_tiles = g->tiles_f * g->tiles_m;
-    g->splits = 1;
-    if (n_tiles <= 128 && g->n_chunks >= 2 && (double)g->F * g->M * 4.0 * 16.0 < 4.0e9) {
-        int want = 256 / n_tiles;
-        g->splits = want < g->n_chunks ? want : g->n_chunks;
-    }
+    g->splits = splits_for(n_tiles, g->F);
     g->chunks_per_split = (g->n_chunks + g->splits - 1) / g->splits;
     g->splits = (g->n_chunks + g->chunks_per_split - 1) / g->chunks_per_split;
     g->n_items = n_tiles * g->splits;

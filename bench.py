@@ -8,6 +8,9 @@ tensors already resident in HBM.  Prints ONE JSON line with images/s, the roofli
 kernel (timed with HIP events on the launch stream inside the timed region) and the CPU oracle's
 rate on a bounded sample of the same workload.
 
+After the timed region the same K steps are replayed as one captured HIP graph and reported beside it
+(`graph_replay`: launch gaps removed; the headline value stays the eager one, whose kernels carry the events).
+
 Order of work: warm-up steps; a few instrumented steps with events around EVERY launch (they give the
 per-kernel table and name the dominant kernel class; the ~100 event records per step cost about a
 tenth of the step, so this pass is not the timed one); then the timed region, in which only the dominant
@@ -95,6 +98,9 @@ def main():
     ap.add_argument("--no-events", action="store_true", help="record no events at all (no kernel table, no roofline)")
     ap.add_argument("--table-steps", type=int, default=5, help="instrumented steps before the timed region")
     ap.add_argument("--overlap", action="store_true", help="model gradients on a second stream beside the data gradients")
+    ap.add_argument("--no-graph", action="store_true", help="skip the graph replay after the timed region (profiler runs)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step as one captured HIP graph (no events inside: the roofline block then comes from the instrumented steps)")
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5],
                     help="workload configuration: 5 (default) is the CaffeNet-shaped stack the metric is quoted on; 1-4 are the "
                          "single layer, the CIFAR-style stack, conv1 alone and conv2-conv5 alone (per-pass times and oracle errors)")
@@ -161,10 +167,19 @@ def main():
         B.profile_select_many(mfma_classes if dom in mfma_classes else [dom])
     # one event between steps (on the stream the steps are launched on) for the median and the spread
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    run_step = lambda: stack.step(X, dOut, lr, mu)
+    if args.graph:
+        # the same launches, recorded once and replayed: nothing in a step allocates, clears memory or waits
+        B.profile_enable(False)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            stack.step(X, dOut, lr, mu)
+        torch.cuda.synchronize()
+        run_step = graph.replay
     t0 = time.perf_counter()
     marks[0].record()
     for i in range(args.steps):
-        stack.step(X, dOut, lr, mu)
+        run_step()
         marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -174,6 +189,8 @@ def main():
     cv = (sum((t - mean_ms) ** 2 for t in per_step) / len(per_step)) ** 0.5 / mean_ms
     kernels = B.profile_summary() if dom is not None else {}
     B.profile_enable(False)
+    if args.graph:
+        kernels = table_kernels      # eager launches of the instrumented steps: a replayed graph carries no events
 
     ms_per_step = 1e3 * dt / args.steps
     images_per_s = args.batch * args.steps / dt
@@ -201,29 +218,49 @@ def main():
     if dom is not None and dom in kernels:
         k = kernels[dom]                                   # the dominant class, timed inside the timed region
         avg_ms = k["total_ms"] / k["launches"]
+        timed_steps = args.table_steps if args.graph else args.steps
         if dom.startswith(MFMA_KERNELS):
             ach = k["flops"] / (k["total_ms"] * 1e-3) / 1e12
             roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_TFLOPS[args.dtype],
                     "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS[args.dtype], "traffic": traffic_of(dom),
-                    "traffic_source": traffic_src, "avg_launch_ms": avg_ms, "launches_per_step": k["launches"] / args.steps,
+                    "traffic_source": traffic_src, "avg_launch_ms": avg_ms, "launches_per_step": k["launches"] / timed_steps,
                     "flops_per_launch": k["flops"] / k["launches"]}
             # every matrix-core class together (the products of all three passes of all five layers)
             fl = sum(kernels[n]["flops"] for n in mfma_classes if n in kernels)
             ms = sum(kernels[n]["total_ms"] for n in mfma_classes if n in kernels)
             roof_all = {"kernels": sorted(n for n in mfma_classes if n in kernels), "bound": "mfma",
                         "achieved": fl / (ms * 1e-3) / 1e12, "peak": PEAK_TFLOPS[args.dtype], "unit": "TFLOP/s",
-                        "frac": fl / (ms * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype], "ms_per_step": ms / args.steps,
+                        "frac": fl / (ms * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype], "ms_per_step": ms / timed_steps,
                         "per_class_frac": {n: kernels[n]["flops"] / (kernels[n]["total_ms"] * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype]
                                            for n in mfma_classes if n in kernels}}
         else:
             ach = k["bytes"] / (k["total_ms"] * 1e-3) / 1e9
             roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": ach / PEAK_HBM_GBS, "traffic": traffic_of(dom), "traffic_source": traffic_src, "avg_launch_ms": avg_ms,
-                    "launches_per_step": k["launches"] / args.steps, "bytes_per_launch": k["bytes"] / k["launches"]}
+                    "launches_per_step": k["launches"] / timed_steps, "bytes_per_launch": k["bytes"] / k["launches"]}
+
+    # beside the timed region: the same K steps replayed as one captured HIP graph (launch gaps removed; no
+    # per-kernel events are possible inside a replay, so the headline value and the roofline stay the eager ones)
+    graph_extra, extra_steps = None, 0
+    if not args.graph and not args.overlap and not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            stack.step(X, dOut, lr, mu)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter() - tg
+        extra_steps = args.steps + 1
+        graph_extra = {"ms_per_step": 1e3 * tg / args.steps, "value": args.batch * args.steps / tg, "unit": "images/s", "steps": args.steps,
+                       "note": "the step captured once and replayed as a HIP graph, timed after the eager region; same kernels, bit-identical results"}
 
     # the tensors the timed steps ran on: finite, not degenerate, weights still where they were drawn
     health = stack.tensor_health(W_start)
-    health["steps_run"] = args.warmup + (args.table_steps if table_kernels else 0) + args.steps
+    health["steps_run"] = args.warmup + (args.table_steps if table_kernels else 0) + args.steps + extra_steps
     degenerate = stack.health_is_degenerate(health)
 
     cpu = cpu_baseline(args.cpu_sample) if args.cpu_sample > 0 else None
@@ -233,12 +270,12 @@ def main():
         "ms_per_step": ms_per_step, "ms_per_step_median": median_ms, "ms_per_step_cv": cv, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": workload,
-                   "global_batch": args.batch, "conv1_data_gradient": bool(args.conv1_dgrad),
+                   "global_batch": args.batch, "conv1_data_gradient": bool(args.conv1_dgrad), "launch": "hip graph replay" if args.graph else "eager",
                    "lr": lr, "momentum": mu, "upstream_gradient": f"N(0,1) draw x 2^{int(math.log2(grad_scale))}"},
         "tensor_health": health,
         "tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
         "mfma_frac_of_peak_whole_step": flops_step / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[args.dtype],
-        "roofline": roof, "roofline_all_mfma_kernels": roof_all, "cpu_baseline": cpu,
+        "roofline": roof, "roofline_all_mfma_kernels": roof_all, "cpu_baseline": cpu, "graph_replay": graph_extra,
         "kernels_note": f"per-kernel table from {args.table_steps} instrumented steps before the timed region",
         "kernels": table,
     }

@@ -356,3 +356,37 @@ def test_second_stream_model_gradient_is_identical(B):
         for a, b in zip(res[0][k], res[1][k]):
             assert torch.equal(a, b)
     assert torch.equal(res[0][3], res[1][3])
+
+
+@pytest.mark.parametrize("which", ["cifar", "caffenet"])
+def test_step_replayed_as_a_hip_graph_is_identical(B, which):
+    """A step allocates nothing, clears no memory and waits for nothing, so it can be captured once and replayed
+    as a HIP graph (what `bench.py --graph` times).  Every replay, with eager launches and synchronisations of the
+    program's own between the replays, must leave exactly what the same number of eager steps leaves."""
+    from paper_1606_04487_amd.stack import ConvStack
+    if which == "cifar":
+        layers, ceil, pooled = wl.cifar_stack(16), True, (4, 4)
+    else:
+        layers, ceil, pooled = wl.caffenet_stack(8), False, (6, 6)
+    t = wl.stack_tensors(layers, seed=9, bf16=True, pooled_out=pooled)
+    X = gpu(t["X"])
+    dOut = (gpu(t["dY"]).float() * wl.step_upstream_scale(layers[0].N)).to(torch.bfloat16)
+    eager = ConvStack(layers, dtype=B.BF16, ceil_mode=ceil, skip_first_dgrad=False)
+    replayed = ConvStack(layers, dtype=B.BF16, ceil_mode=ceil, skip_first_dgrad=False)
+    for st in (eager, replayed):
+        st.set_parameters(t["W"], t["bias"])
+        st.step(X, dOut, 0.01, 0.9)          # step 1 eager on both (also warms the capture up)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        replayed.step(X, dOut, 0.01, 0.9)    # recorded, not run
+    torch.cuda.synchronize()
+    for it in range(4):
+        eager.step(X, dOut, 0.01, 0.9)       # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ("W", "b", "VW", "dW", "db", "Y", "dYc"):
+            for a, b in zip(getattr(eager, name), getattr(replayed, name)):
+                assert torch.equal(a, b), (which, it, name)
+        assert torch.equal(eager.dXl[0], replayed.dXl[0]), (which, it)

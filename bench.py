@@ -239,28 +239,32 @@ def main():
                     "frac": ach / PEAK_HBM_GBS, "traffic": traffic_of(dom), "traffic_source": traffic_src, "avg_launch_ms": avg_ms,
                     "launches_per_step": k["launches"] / timed_steps, "bytes_per_launch": k["bytes"] / k["launches"]}
 
-    # beside the timed region: the same K steps replayed as one captured HIP graph (launch gaps removed; no
-    # per-kernel events are possible inside a replay, so the headline value and the roofline stay the eager ones)
-    graph_extra, extra_steps = None, 0
-    if not args.graph and not args.overlap and not args.no_graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            stack.step(X, dOut, lr, mu)
-        torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
-        tg = time.perf_counter()
-        for _ in range(args.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        tg = time.perf_counter() - tg
-        extra_steps = args.steps + 1
-        graph_extra = {"ms_per_step": 1e3 * tg / args.steps, "value": args.batch * args.steps / tg, "unit": "images/s", "steps": args.steps,
-                       "note": "the step captured once and replayed as a HIP graph, timed after the eager region; same kernels, bit-identical results"}
-
     # the tensors the timed steps ran on: finite, not degenerate, weights still where they were drawn
     health = stack.tensor_health(W_start)
-    health["steps_run"] = args.warmup + (args.table_steps if table_kernels else 0) + args.steps + extra_steps
+    health["steps_run"] = args.warmup + (args.table_steps if table_kernels else 0) + args.steps
+
+    # beside the timed region: the same K steps replayed as one captured HIP graph (launch gaps removed; no
+    # per-kernel events are possible inside a replay, so the headline value and the roofline stay the eager ones)
+    graph_extra = None
+    if not args.graph and not args.overlap and not args.no_graph:
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                stack.step(X, dOut, lr, mu)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            tg = time.perf_counter()
+            for _ in range(args.steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            tg = time.perf_counter() - tg
+            after = stack.tensor_health(W_start)
+            graph_extra = {"ms_per_step": 1e3 * tg / args.steps, "value": args.batch * args.steps / tg, "unit": "images/s", "steps": args.steps,
+                           "tensors_finite_after": after["finite"] and not stack.health_is_degenerate(after),
+                           "note": "the step captured once and replayed as a HIP graph, timed after the eager region; same kernels, bit-identical results"}
+        except Exception as exc:  # the eager figures above stand on their own
+            graph_extra = {"error": f"{type(exc).__name__}: {exc}"}
     degenerate = stack.health_is_degenerate(health)
 
     cpu = cpu_baseline(args.cpu_sample) if args.cpu_sample > 0 else None

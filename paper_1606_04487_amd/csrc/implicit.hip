@@ -150,9 +150,6 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         }
         total_pieces = p0;
     }
-    for (int i = tid; i < NG * PATCH_PIX; i += NT) patch[i] = make_uint4(0, 0, 0, 0);
-    if constexpr (Epi::HAS_ROW_ADD)
-        for (int i = tid; i < BM; i += NT) lds_add[i] = epi.row_add(row0 + i);
     __syncthreads();
 
     // patch pixel of each of this lane's columns at tap (0, 0)
@@ -298,8 +295,14 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
             for (int u = 0; u < TJ; ++u) Mma<bf16_t>::run(fa[t], fb[u], acc[t][u]);
     };
 
+    // The first chunk's pixels and weights are requested before the patch is cleared, so that the clearing (the
+    // padding stays zero for the whole kernel: loads only ever write real pixels) runs under their latency.
     issue_patch(chunk_lo);
     issue_a(chunk_lo * KK, 0);
+    for (int i = tid; i < NG * PATCH_PIX; i += NT) patch[i] = make_uint4(0, 0, 0, 0);
+    if constexpr (Epi::HAS_ROW_ADD)
+        for (int i = tid; i < BM; i += NT) lds_add[i] = epi.row_add(row0 + i);
+    __syncthreads();
     commit_patch();
     commit_a(0);
     wait_a();

@@ -100,7 +100,7 @@ def raw():
     return _lib
 
 
-TUNE_GEMM_TILE, TUNE_FUSED_BN, TUNE_FUSED_BM = 0, 1, 2
+TUNE_GEMM_TILE, TUNE_FUSED_BN, TUNE_FUSED_BM, TUNE_WGRAD_SPLITS, TUNE_WGRAD_PATCH = 0, 1, 2, 3, 4
 
 
 def tuning_set(knob: int, value: int) -> None:

@@ -157,8 +157,15 @@ void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w)
         k_max = wgrad_phase_kp(g) + 1 > g.K ? wgrad_phase_kp(g) + 1 : g.K;  // + 1: the bias gradient's column
         x4_bytes = (size_t)g.N * g.C * 4 * g.H * wgrad_phase_wp(g) * e;
     }
+    // the LDS-patch model gradient: its own split count over images, always through the partial sums
+    w->splits_patch = !phase && wgrad_patch_supported(g, dtype) ? wgrad_patch_splits(g) : 0;
+    if (w->splits_patch > 0) {
+        w->ld_rows = dyhat_rows_ld(g);
+        w->bias_blocks_rows = pack_dyhat_rows_blocks(g);
+    }
     int64_t ld_max = w->ld > w->ld_rows ? w->ld : w->ld_rows;
     int splits_max = w->splits > w->splits_rows ? w->splits : w->splits_rows;
+    if (w->splits_patch > 0 && splits_max < w->splits_patch + 1) splits_max = w->splits_patch + 1;  // + 1: kept even when it is 1
     int bb_max = w->bias_blocks > w->bias_blocks_rows ? w->bias_blocks : w->bias_blocks_rows;
     w->dhat = 0;
     size_t dhat_bytes = (size_t)g.K * w->ld * e;
@@ -200,6 +207,14 @@ int omni_tuning_set(int knob, int value)
     case OMNI_TUNE_FUSED_BM:
         if (value != 0 && value != 96 && value != 128) return OMNI_INVALID_ARGUMENT;
         set_fused_tile_override(-1, value);
+        return OMNI_OK;
+    case OMNI_TUNE_WGRAD_SPLITS:
+        if (value < 0) return OMNI_INVALID_ARGUMENT;
+        set_wgrad_patch_override(value, -1);
+        return OMNI_OK;
+    case OMNI_TUNE_WGRAD_PATCH:
+        if (value != 0 && value != 1) return OMNI_INVALID_ARGUMENT;
+        set_wgrad_patch_override(-1, value);
         return OMNI_OK;
     default: return OMNI_INVALID_ARGUMENT;
     }
@@ -268,7 +283,7 @@ int omni_conv_fused_supported(const omni_conv_desc *desc, int pass)
         return fused_supported(g, desc->dtype, true) && fused_weight_bytes(g, true) <= w.total ? 1 : 0;
     }
     if (pass == OMNI_PASS_BACKWARD_WEIGHTS)
-        return wgrad_direct_supported(g, desc->dtype) || wgrad_phase_supported(g, desc->dtype) ? 1 : 0;
+        return wgrad_patch_supported(g, desc->dtype) || wgrad_direct_supported(g, desc->dtype) || wgrad_phase_supported(g, desc->dtype) ? 1 : 0;
     return OMNI_INVALID_ARGUMENT;
 }
 
@@ -473,6 +488,14 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
     void *Dhat = ws + w.dhat, *dYhat = ws + w.dyhat;
     float *partials = (float *)(ws + w.partials), *bias_partials = (float *)(ws + w.bias_partials);
 
+    if ((desc->flags & OMNI_FLAG_FUSED) && !cached && w.splits_patch > 0) {
+        // 3 x 3 layer on small planes: dY as a plane-padded matrix, the lowered operand from an LDS copy of X
+        st = launch_pack_dyhat_rows(g, dY, dYhat, w.ld_rows, dbias ? bias_partials : nullptr, w.bias_blocks_rows, nullptr, s);
+        if (st != OMNI_OK) return st;
+        st = launch_wgrad_patch(g, X, dYhat, w.ld_rows, partials, w.splits_patch, s);
+        if (st != OMNI_OK) return st;
+        return launch_wgrad_reduce(g, partials, w.splits_patch, dW, bias_partials, w.bias_blocks_rows, dbias, s);
+    }
     const bool direct = (desc->flags & OMNI_FLAG_FUSED) && !cached && wgrad_direct_supported(g, desc->dtype);
     // with a split product the ordered reduction finishes the bias gradient too (one launch fewer)
     if (direct) {

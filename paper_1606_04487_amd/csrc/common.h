@@ -94,6 +94,7 @@ struct BwdWeightsWs {
     size_t dhat, dyhat, partials, bias_partials, total;  // dhat also holds X4 of the phase-split model gradient
     int64_t ld; int splits; int64_t chunk; int bias_blocks;
     int64_t ld_rows; int splits_rows; int64_t chunk_rows; int bias_blocks_rows;
+    int splits_patch;  // > 0: the layer's fused model gradient is wgrad_patch.hip's, over this many image ranges
 };
 void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w);
 void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w);
@@ -199,9 +200,22 @@ int launch_phase_split(const ConvGeom &g, int WP, const void *X, void *X4, hipSt
 int launch_gemm_wgrad_phase(const ConvGeom &g, const void *X4, const void *dY, int64_t ld, float *partials, int splits,
                             int64_t chunk, float *dW, float *dbias, hipStream_t s);
 
+// wgrad_patch.hip: the model gradient of a 3 x 3, stride-1, same-size layer on small planes (bf16) with the
+// lowered operand read from an LDS copy of the input planes; dY-hat in the plane-padded layout of
+// launch_pack_dyhat_rows, partial sums [splits][F][K] (splits = wgrad_patch_splits) for launch_wgrad_reduce.
+bool wgrad_patch_supported(const ConvGeom &g, int dtype);
+int wgrad_patch_splits(const ConvGeom &g);
+int launch_wgrad_patch(const ConvGeom &g, const void *X, const void *dYhat, int64_t ld, float *partials, int splits,
+                       hipStream_t s);
+// gemm.hip: ordered sum of the split partial results [splits][F][K] into dW; with dbias != null the same launch
+// finishes the bias gradient from the per-block sums of the dY packing kernel
+int launch_wgrad_reduce(const ConvGeom &g, const float *partials, int splits, float *dW, const float *bias_partials,
+                        int bias_blocks, float *dbias, hipStream_t s);
+
 // tile overrides for sweeps (omni_tuning_set); -1 leaves a value as it is
 void set_gemm_tile_override(int tile);
 void set_fused_tile_override(int bn, int bm);
+void set_wgrad_patch_override(int max_splits, int off);
 
 // elementwise.hip
 int launch_sgd(int32_t n, float *const *W, float *const *V, const float *const *G, const int64_t *counts,

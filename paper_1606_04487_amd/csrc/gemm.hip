@@ -1298,15 +1298,20 @@ static int run_wgrad(const ConvGeom &g, const GemmWgradArgs &a, hipStream_t s)
         }
     }
     OMNI_LAUNCH_CHECK();
-    if (a.splits > 1) {
-        int64_t count = (int64_t)g.F * g.K;
-        ProfScope prof(KID_REDUCE_PARTIALS, s, 0.0, 4.0 * count * (a.splits + 1));
-        const unsigned main_blocks = (unsigned)((count + 63) / 64);
-        const unsigned bias_wgs = a.dbias != nullptr ? (unsigned)((g.F + 3) / 4) : 0u;
-        hipLaunchKernelGGL(reduce_partials_kernel<false>, dim3(main_blocks + bias_wgs), dim3(256), 0, s, a.partials, a.splits,
-                           count, a.dW, main_blocks, a.bias_partials, a.bias_blocks, g.F, a.dbias, PhaseMap{});
-        OMNI_LAUNCH_CHECK();
-    }
+    if (a.splits > 1) return launch_wgrad_reduce(g, a.partials, a.splits, a.dW, a.bias_partials, a.bias_blocks, a.dbias, s);
+    return OMNI_OK;
+}
+
+int launch_wgrad_reduce(const ConvGeom &g, const float *partials, int splits, float *dW, const float *bias_partials,
+                        int bias_blocks, float *dbias, hipStream_t s)
+{
+    int64_t count = (int64_t)g.F * g.K;
+    ProfScope prof(KID_REDUCE_PARTIALS, s, 0.0, 4.0 * count * (splits + 1));
+    const unsigned main_blocks = (unsigned)((count + 63) / 64);
+    const unsigned bias_wgs = dbias != nullptr ? (unsigned)((g.F + 3) / 4) : 0u;
+    hipLaunchKernelGGL(reduce_partials_kernel<false>, dim3(main_blocks + bias_wgs), dim3(256), 0, s, partials, splits, count, dW,
+                       main_blocks, bias_partials, bias_blocks, g.F, dbias, PhaseMap{});
+    OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }
 

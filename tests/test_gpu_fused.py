@@ -170,6 +170,39 @@ def test_fused_backward_weights(B, cfg):
     assert torch.equal(dW, again)                  # deterministic
 
 
+# 3 x 3 layers on 13 x 13 planes whose channels fill the LDS-patch model gradient's 128 x 64 tiles
+PATCH_SHAPES = [(1, 64, 13, 13, 128, 3, 3, 1, 1), (2, 64, 13, 13, 128, 3, 3, 1, 1), (7, 128, 13, 13, 256, 3, 3, 1, 1),
+                (12, 64, 13, 13, 384, 3, 3, 1, 1), (5, 192, 13, 13, 128, 3, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("splits", [0, 1, 2, 3])
+@pytest.mark.parametrize("cfg", PATCH_SHAPES)
+def test_patch_backward_weights(B, cfg, splits, tuning):
+    """Model gradient with the lowered operand read from an LDS copy of the input planes: image ranges of one
+    image, of whole pairs and with an odd last image (splits caps the number of ranges, so one workgroup walks
+    several images), against the oracle and against the direct-loader path; deterministic."""
+    print("patch wgrad", cfg, "splits", splits, flush=True)
+    s, X, Wt, b, dY = make(cfg, 17)
+    d = desc_of(B, cfg, B.FLAG_FUSED)
+    tuning(B.TUNE_WGRAD_SPLITS, splits)
+    Xg, dYg = gpu(X), gpu(dY)
+    dW, db = B.conv_backward_weights(d, Xg, dYg)
+    ref = oracle.conv_backward_weights(s, X, dY)
+    assert rel_err(host(dW), ref) <= 1e-4
+    assert rel_err(host(db), oracle.bias_grad(s, dY)) <= 1e-4
+    again, _ = B.conv_backward_weights(d, Xg, dYg)
+    assert torch.equal(dW, again)
+    tuning(B.TUNE_WGRAD_PATCH, 1)                  # the same layer through the direct loader
+    dW2, _ = B.conv_backward_weights(d, Xg, dYg)
+    assert rel_err(host(dW), host(dW2)) <= 2e-5
+    # every tap of every (filter, channel) pair is held to the bar on its own, so that a wrong mask or shift of
+    # one tap cannot hide behind the tensor's maximum
+    got = host(dW)
+    for ky in range(3):
+        for kx in range(3):
+            assert rel_err(got[:, :, ky, kx], ref[:, :, ky, kx]) <= 1e-4, (ky, kx)
+
+
 def test_fused_declines_and_falls_back(B):
     # stride 2, channels not a multiple of 32, fp32: the flag is accepted and the explicit path runs
     for cfg, dtype in [((2, 32, 9, 9, 8, 3, 3, 2, 2, 1, 1), 1), ((2, 20, 9, 9, 8, 3, 3, 1, 1, 1, 1), 1),

@@ -179,7 +179,12 @@ template <typename PL> __global__ __launch_bounds__(NT) void wgrad_patch_kernel(
 #pragma unroll
         for (int fi = 0; fi < 4; ++fi) A[fi] = *reinterpret_cast<const uint4 *>(yp + fi * (16 * YP * 16));
 #pragma unroll
-        for (int j = 0; j < 5; ++j) R[j] = *reinterpret_cast<const uint4 *>(xp + j * 16);
+        for (int j = 0; j < 5; ++j) {
+            // whole 16-byte reads (one bank group per lane, 16 lanes at a time): read as single words the compiler
+            // fetches only the words a tap uses, and the row pitch then puts four lanes on every bank
+            R[j] = *reinterpret_cast<const uint4 *>(xp + j * 16);
+            asm volatile("" : "+v"(R[j].x), "+v"(R[j].y), "+v"(R[j].z), "+v"(R[j].w));
+        }
         M0 = *reinterpret_cast<const uint4 *>(mp);
         M2 = *reinterpret_cast<const uint4 *>(mp + 16);
         static_for<0, TAPS>([&](auto tt) {

@@ -186,6 +186,31 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
                                void *hip_stream);
 
 /*
+ * Repacked weights as an object of the caller's (App. C: the model, unlike the data, needs no replication -- it
+ * only changes once per step).  With OMNI_FLAG_FUSED the forward pass and the data gradient read the weights in
+ * kernel-specific orders, which omni_conv_forward / omni_conv_backward_data write into their workspace on every
+ * call.  A caller whose weights change once per training step can instead keep those copies itself:
+ *   omni_conv_packed_weights_bytes: bytes of the copy that `pass` (OMNI_PASS_FORWARD or OMNI_PASS_BACKWARD_DATA) of
+ *       this layer reads; 0 when that pass does not read repacked weights (then the *_packed calls below return
+ *       OMNI_UNSUPPORTED for it and the plain entry points are the ones to call).  Host only.
+ *   omni_conv_pack_weights: ONE launch that writes the copies of n layer-and-pass pairs (n <= 16): descs is a host
+ *       array of n descriptors, passes of n pass ids, W and packed host arrays of n device pointers (W[i] the
+ *       layer's bf16 weights [F][C][kh][kw], packed[i] the caller's buffer of omni_conv_packed_weights_bytes).
+ *       An entry whose pass reads no repacked weights is OMNI_UNSUPPORTED (nothing is launched).
+ *   omni_conv_forward_packed / omni_conv_backward_data_packed: omni_conv_forward / omni_conv_backward_data with
+ *       `packed` (as written by omni_conv_pack_weights for the same descriptor and pass) in place of W; results are
+ *       bit-identical to the plain entry points'.  Workspace as for the plain entry points.
+ * All pointers 16-byte aligned; the copies stay valid until W changes.
+ */
+int omni_conv_packed_weights_bytes(const omni_conv_desc *desc, int pass, size_t *bytes);
+int omni_conv_pack_weights(int32_t n, const omni_conv_desc *descs, const int32_t *passes, const void *const *W,
+                           void *const *packed, void *hip_stream);
+int omni_conv_forward_packed(const omni_conv_desc *desc, const void *X, const void *packed, const float *bias,
+                             void *Y, void *workspace, size_t workspace_bytes, void *hip_stream);
+int omni_conv_backward_data_packed(const omni_conv_desc *desc, const void *dY, const void *packed, void *dX,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Momentum SGD over a list of parameter tensors in one launch sequence
  * (Sec. II-B, Eq. (update2) then Eq. (update1)):
  *     V <- momentum * V - lr * (G + weight_decay * W);    W <- W + V

@@ -30,6 +30,7 @@ SYMBOLS = [
     "omni_conv_output_dims", "omni_conv_dhat_ld", "omni_conv_workspace_bytes", "omni_conv_fused_supported",
     "omni_conv_forward", "omni_conv_forward_partial", "omni_conv_forward_static", "omni_conv_static_scratch_need",
     "omni_conv_backward_data", "omni_conv_backward_weights", "omni_sgd_momentum_step", "omni_lower",
+    "omni_conv_packed_weights_bytes", "omni_conv_pack_weights", "omni_conv_forward_packed", "omni_conv_backward_data_packed",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
     "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward",
     "omni_lrn_forward", "omni_lrn_backward", "omni_dropout_forward", "omni_dropout_backward", "omni_status_string", "omni_version", "omni_tuning_set",
@@ -70,6 +71,10 @@ _lib.omni_conv_workspace_bytes.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(_sz
 _lib.omni_conv_forward.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.omni_conv_backward_data.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.omni_conv_backward_weights.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.omni_conv_packed_weights_bytes.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(_sz)]
+_lib.omni_conv_pack_weights.argtypes = [_i32, _vp, _vp, _vp, _vp, _vp]
+_lib.omni_conv_forward_packed.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.omni_conv_backward_data_packed.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.omni_sgd_momentum_step.argtypes = [_i32, _vp, _vp, _vp, _vp, _vp, ctypes.c_float, ctypes.c_float,
                                         ctypes.c_float, _vp]
 _lib.omni_lower.argtypes = [_dp, _vp, _vp, _i64, _vp]
@@ -231,6 +236,48 @@ def conv_backward_data(desc: ConvDesc, dY, W, dX=None, workspace=None):
         workspace = alloc_workspace(desc, PASS_BACKWARD_DATA, dY.device)
     _check(_lib.omni_conv_backward_data(ctypes.byref(desc), _p(dY), _p(W), _p(dX), _p(workspace),
                                         workspace.numel(), _stream()))
+    return dX
+
+
+def conv_packed_weights_bytes(desc: ConvDesc, which: int) -> int:
+    """omni_conv_packed_weights_bytes: bytes of the repacked weights that pass `which` reads (0: none)."""
+    b = _sz()
+    _check(_lib.omni_conv_packed_weights_bytes(ctypes.byref(desc), which, ctypes.byref(b)))
+    return b.value
+
+
+def conv_pack_weights(descs: Sequence[ConvDesc], passes: Sequence[int], W: Sequence[torch.Tensor],
+                      packed: Sequence[torch.Tensor]) -> None:
+    """omni_conv_pack_weights: the repacked weights of several layer-and-pass pairs in one launch."""
+    n = len(descs)
+    if not (len(passes) == n and len(W) == n and len(packed) == n):
+        raise ValueError("descs, passes, W and packed must have equal length")
+    darr = (ConvDesc * max(n, 1))(*descs)
+    parr = (_i32 * max(n, 1))(*passes)
+    arr = _vp * max(n, 1)
+    _check(_lib.omni_conv_pack_weights(n, darr, parr, arr(*[_p(t) for t in W]), arr(*[_p(t) for t in packed]), _stream()))
+
+
+def conv_forward_packed(desc: ConvDesc, X, packed, bias=None, Y=None, workspace=None):
+    """omni_conv_forward_packed: omni_conv_forward reading weights repacked by conv_pack_weights."""
+    ho, wo = conv_output_dims(desc)
+    if Y is None:
+        Y = torch.empty((desc.N, desc.F, ho, wo), dtype=torch_dtype(desc.dtype), device=X.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, PASS_FORWARD, X.device)
+    _check(_lib.omni_conv_forward_packed(ctypes.byref(desc), _p(X), _p(packed), _p(bias), _p(Y), _p(workspace),
+                                         workspace.numel(), _stream()))
+    return Y
+
+
+def conv_backward_data_packed(desc: ConvDesc, dY, packed, dX=None, workspace=None):
+    """omni_conv_backward_data_packed: omni_conv_backward_data reading weights repacked by conv_pack_weights."""
+    if dX is None:
+        dX = torch.empty((desc.N, desc.C, desc.H, desc.W), dtype=torch_dtype(desc.dtype), device=dY.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, PASS_BACKWARD_DATA, dY.device)
+    _check(_lib.omni_conv_backward_data_packed(ctypes.byref(desc), _p(dY), _p(packed), _p(dX), _p(workspace),
+                                               workspace.numel(), _stream()))
     return dX
 
 

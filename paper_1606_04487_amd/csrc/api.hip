@@ -5,6 +5,7 @@
 #include <mutex>
 
 #include "common.h"
+#include "pack_jobs.h"
 
 namespace omni {
 
@@ -290,17 +291,18 @@ int omni_conv_fused_supported(const omni_conv_desc *desc, int pass)
 // The forward pass on checked arguments.  `avail` bytes of scratch at `ws`: each path checks what IT needs
 // (the fused kernels only their repacked weights, the explicit path D-hat, K-hat and the split partials).
 static int forward_on_scratch(const omni_conv_desc *desc, const ConvGeom &g, const ForwardWs &w, const void *X, const void *W,
-                              const float *bias, void *Y, char *ws, size_t avail, hipStream_t s)
+                              const float *bias, void *Y, char *ws, size_t avail, hipStream_t s, const void *prepacked = nullptr)
 {
     const int relu = (desc->flags & OMNI_FLAG_RELU) ? 1 : 0;
     if ((desc->flags & OMNI_FLAG_FUSED) && fused_supported(g, desc->dtype, false)) {
         if (avail < fused_weight_bytes(g, false)) return OMNI_WORKSPACE_TOO_SMALL;
-        return launch_fused_conv(g, false, X, W, bias, relu, Y, ws, s);
+        return launch_fused_conv(g, false, X, W, bias, relu, Y, ws, s, -1, prepacked);
     }
     if ((desc->flags & OMNI_FLAG_FUSED) && strided_supported(g, desc->dtype)) {
         if (avail < strided_weight_bytes(g)) return OMNI_WORKSPACE_TOO_SMALL;
-        return launch_strided_conv(g, X, W, bias, relu, Y, ws, s);
+        return launch_strided_conv(g, X, W, bias, relu, Y, ws, s, prepacked);
     }
+    if (prepacked != nullptr) return OMNI_UNSUPPORTED;  // the explicit path reads W itself
     if (avail < w.explicit_total) return OMNI_WORKSPACE_TOO_SMALL;
     void *Dhat = ws + w.dhat, *Khat = ws + w.khat;
     int st = launch_lower(g, desc->dtype, X, Dhat, w.ld, s);
@@ -466,6 +468,89 @@ int omni_conv_backward_data(const omni_conv_desc *desc, const void *dY, const vo
     st = launch_gemm_dgrad(g, desc->dtype, a, s);
     if (st != OMNI_OK) return st;
     return launch_col2im(g, desc->dtype, dDhat, w.ld, dX, s);
+}
+
+// Which repacking (if any) `pass` of this layer reads with OMNI_FLAG_FUSED: fills `job` (when not null) and `bytes`.
+static bool packed_weights_job(const omni_conv_desc *desc, const ConvGeom &g, int pass, const void *W, void *packed, PackJob *job,
+                               size_t *bytes)
+{
+    *bytes = 0;
+    if (!(desc->flags & OMNI_FLAG_FUSED)) return false;
+    if (pass == OMNI_PASS_FORWARD) {
+        if (fused_supported(g, desc->dtype, false)) return fused_pack_job(g, false, W, packed, job, bytes);
+        if (strided_supported(g, desc->dtype)) return strided_pack_job(g, W, packed, job, bytes);
+        return false;
+    }
+    if (pass == OMNI_PASS_BACKWARD_DATA && fused_supported(g, desc->dtype, true)) return fused_pack_job(g, true, W, packed, job, bytes);
+    return false;
+}
+
+int omni_conv_packed_weights_bytes(const omni_conv_desc *desc, int pass, size_t *bytes)
+{
+    if (bytes == nullptr) return OMNI_INVALID_ARGUMENT;
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (pass != OMNI_PASS_FORWARD && pass != OMNI_PASS_BACKWARD_DATA) return OMNI_INVALID_ARGUMENT;
+    packed_weights_job(desc, g, pass, nullptr, nullptr, nullptr, bytes);
+    return OMNI_OK;
+}
+
+int omni_conv_pack_weights(int32_t n, const omni_conv_desc *descs, const int32_t *passes, const void *const *W,
+                           void *const *packed, void *hip_stream)
+{
+    if (n < 0 || n > MAX_PACK_JOBS) return OMNI_INVALID_ARGUMENT;
+    if (n == 0) return OMNI_OK;
+    if (descs == nullptr || passes == nullptr || W == nullptr || packed == nullptr) return OMNI_INVALID_ARGUMENT;
+    PackJobTable t;
+    t.n = n;
+    t.first_block[0] = 0;
+    for (int i = 0; i < n; ++i) {
+        ConvGeom g;
+        int st = make_geom(&descs[i], &g);
+        if (st != OMNI_OK) return st;
+        if (passes[i] != OMNI_PASS_FORWARD && passes[i] != OMNI_PASS_BACKWARD_DATA) return OMNI_INVALID_ARGUMENT;
+        if (W[i] == nullptr || packed[i] == nullptr) return OMNI_INVALID_ARGUMENT;
+        if (!aligned16(W[i]) || !aligned16(packed[i])) return OMNI_MISALIGNED;
+        size_t bytes;
+        if (!packed_weights_job(&descs[i], g, passes[i], W[i], packed[i], &t.job[i], &bytes)) return OMNI_UNSUPPORTED;
+        t.first_block[i + 1] = t.first_block[i] + (t.job[i].total + 255) / 256;
+    }
+    return launch_pack_jobs(t, (hipStream_t)hip_stream);
+}
+
+int omni_conv_forward_packed(const omni_conv_desc *desc, const void *X, const void *packed, const float *bias, void *Y,
+                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (X == nullptr || packed == nullptr || Y == nullptr || workspace == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(X) || !aligned16(packed) || !aligned16(Y) || !aligned16(workspace) || (bias && !aligned16(bias)))
+        return OMNI_MISALIGNED;
+    size_t pbytes;
+    if (!packed_weights_job(desc, g, OMNI_PASS_FORWARD, nullptr, nullptr, nullptr, &pbytes)) return OMNI_UNSUPPORTED;
+    ForwardWs w;
+    plan_forward(g, desc->dtype, &w);
+    if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
+    return forward_on_scratch(desc, g, w, X, nullptr, bias, Y, (char *)workspace, workspace_bytes, (hipStream_t)hip_stream, packed);
+}
+
+int omni_conv_backward_data_packed(const omni_conv_desc *desc, const void *dY, const void *packed, void *dX, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (dY == nullptr || packed == nullptr || dX == nullptr || workspace == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(dY) || !aligned16(packed) || !aligned16(dX) || !aligned16(workspace)) return OMNI_MISALIGNED;
+    size_t pbytes;
+    if (!packed_weights_job(desc, g, OMNI_PASS_BACKWARD_DATA, nullptr, nullptr, nullptr, &pbytes)) return OMNI_UNSUPPORTED;
+    BwdDataWs w;
+    plan_backward_data(g, desc->dtype, &w);
+    if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
+    if (fused_weight_bytes(g, true) > w.total) return OMNI_UNSUPPORTED;
+    return launch_fused_conv(g, true, dY, nullptr, nullptr, 0, dX, workspace, (hipStream_t)hip_stream, -1, packed);
 }
 
 int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const void *dY, float *dW, float *dbias,

@@ -174,14 +174,14 @@ bool fused_supported(const ConvGeom &g, int dtype, bool data_gradient);
 size_t fused_weight_bytes(const ConvGeom &g, bool data_gradient);
 // kid: kernel class the launch is timed under (-1: by data_gradient)
 int launch_fused_conv(const ConvGeom &g, bool data_gradient, const void *X, const void *W, const float *bias,
-                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid = -1);
+                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid = -1, const void *prepacked = nullptr);
 
 // strided.hip: the forward convolution of a layer with horizontal stride 4, no padding, at most 96 filters and
 // a short reduction (CaffeNet's conv1) without D-hat; bf16.  wt_scratch receives the repacked weights.
 bool strided_supported(const ConvGeom &g, int dtype);
 size_t strided_weight_bytes(const ConvGeom &g);
 int launch_strided_conv(const ConvGeom &g, const void *X, const void *W, const float *bias, int relu, void *Y,
-                        void *wt_scratch, hipStream_t s);
+                        void *wt_scratch, hipStream_t s, const void *prepacked = nullptr);
 
 // Data gradient of a strided, unpadded layer as one stride-1 convolution over dY with C*sh*sw output channels
 // (run by the fused kernel of implicit.hip) plus the interleaving of the phase images into dX; bf16.

@@ -30,6 +30,7 @@
 
 #include "common.h"
 #include "mma_epilogue.h"
+#include "pack_jobs.h"
 
 namespace omni {
 namespace fused {
@@ -350,26 +351,14 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
 
 // Weights [out][in][kh][kw] (forward) or [in][out][kh][kw] read flipped (data gradient) -> the kernel's
 // order [chunk][tap][g][Fp][8]: pack (chunk, tap, g, row) = input channels chunk*32 + 8g .. +7 of output
-// channel `row` at window tap `tap`; rows beyond F are zero.  One thread per pack.
-__global__ void pack_weights_kernel(const bf16_t *__restrict__ W, uint4 *__restrict__ Wt, int F, int Fp, int KK,
-                                    int n_chunks, int64_t stride_out, int64_t stride_in, int flip)
+// channel `row` at window tap `tap`; rows beyond F are zero.  One thread per pack (pack_one, pack_jobs.h); a launch
+// carries a table of such jobs, block b belonging to the job whose block range holds it.
+__global__ __launch_bounds__(256) void pack_jobs_kernel(PackJobTable t)
 {
-    int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t total = (int64_t)n_chunks * KK * NG * Fp;
-    if (p >= total) return;
-    int row = (int)(p % Fp);
-    int64_t t = p / Fp;
-    int gq = (int)(t % NG);
-    t /= NG;
-    int tap = (int)(t % KK), chunk = (int)(t / KK);
-    uint32_t v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        int c = chunk * CH + gq * 8 + j;
-        int src_tap = flip ? KK - 1 - tap : tap;
-        v[j] = row < F ? (uint32_t)W[row * stride_out + c * stride_in + src_tap] : 0u;
-    }
-    Wt[p] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+    int j = 0;
+    while (j + 1 < t.n && (int64_t)blockIdx.x >= t.first_block[j + 1]) ++j;
+    const int64_t p = ((int64_t)blockIdx.x - t.first_block[j]) * 256 + threadIdx.x;
+    if (p < t.job[j].total) pack_one(t.job[j], p);
 }
 
 // The convolution as this kernel sees it; for the data gradient the layer's output gradient is the
@@ -499,21 +488,53 @@ size_t fused_weight_bytes(const ConvGeom &c, bool data_gradient)
     return fused_packed_bytes(g) + (g.splits > 1 ? (size_t)g.splits * g.F * g.M * sizeof(float) : 0);
 }
 
+static void fill_fused_job(const fused::Geom &g, bool data_gradient, const void *W, void *packed, PackJob *job)
+{
+    job->kind = 0;
+    job->W = (const bf16_t *)W, job->Wt = (uint4 *)packed;
+    job->total = (int64_t)g.n_chunks * g.KK * fused::NG * g.Fp;
+    job->F = g.F, job->Fp = g.Fp, job->KK = g.KK, job->n_chunks = g.n_chunks, job->flip = data_gradient ? 1 : 0;
+    job->stride_out = data_gradient ? g.KK : (int64_t)g.C * g.KK;
+    job->stride_in = data_gradient ? (int64_t)g.F * g.KK : g.KK;
+    job->C = job->kh = job->kw = job->kwq = job->groups = job->BM = 0;
+}
+
+bool fused_pack_job(const ConvGeom &c, bool data_gradient, const void *W, void *packed, PackJob *job, size_t *bytes)
+{
+    fused::Geom g;
+    *bytes = 0;
+    if (!fused::make_fused_geom(c, data_gradient, &g)) return false;
+    *bytes = fused_packed_bytes(g);
+    if (job != nullptr) fill_fused_job(g, data_gradient, W, packed, job);
+    return true;
+}
+
+int launch_pack_jobs(const PackJobTable &t, hipStream_t s)
+{
+    if (t.n <= 0) return OMNI_OK;
+    double bytes = 0.0;
+    for (int j = 0; j < t.n; ++j) bytes += 2.0 * 16.0 * (double)t.job[j].total;
+    ProfScope prof(KID_PACK_KHAT, s, 0.0, bytes);
+    hipLaunchKernelGGL(fused::pack_jobs_kernel, dim3((unsigned)t.first_block[t.n]), dim3(256), 0, s, t);
+    OMNI_LAUNCH_CHECK();
+    return OMNI_OK;
+}
+
+// `prepacked` != null: the repacked weights already exist there (fused_pack_job) and W is not read
 int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, const void *W, const float *bias,
-                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid)
+                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid, const void *prepacked)
 {
     using namespace fused;
     Geom g;
     if (!make_fused_geom(c, data_gradient, &g)) return OMNI_UNSUPPORTED;
-    {
-        ProfScope prof(KID_PACK_KHAT, s, 0.0, 2.0 * (double)c.F * c.K * 2.0);
-        int64_t total = (int64_t)g.n_chunks * g.KK * NG * g.Fp;
-        int64_t so = data_gradient ? g.KK : (int64_t)g.C * g.KK, si = data_gradient ? (int64_t)g.F * g.KK : g.KK;
-        hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                           (const bf16_t *)W, (uint4 *)wt_scratch, g.F, g.Fp, g.KK, g.n_chunks, so, si,
-                           data_gradient ? 1 : 0);
-        OMNI_LAUNCH_CHECK();
+    if (prepacked == nullptr) {
+        PackJobTable t;
+        fill_fused_job(g, data_gradient, W, wt_scratch, &t.job[0]);
+        t.first_block[0] = 0, t.first_block[1] = (t.job[0].total + 255) / 256, t.n = 1;
+        int st = launch_pack_jobs(t, s);
+        if (st != OMNI_OK) return st;
     }
+    const bf16_t *wt = (const bf16_t *)(prepacked != nullptr ? prepacked : wt_scratch);
     FwdEpilogue<bf16_t> epi{(bf16_t *)Y, bias, g.F, g.M, g.HoWo, g.div_HoWo, relu};
     ProfScope prof(kid >= 0 ? kid : (data_gradient ? KID_FUSED_DGRAD : KID_FUSED_FWD), s, 2.0 * (double)c.M * c.K * c.F, 0.0);
     dim3 grid((unsigned)(g.per_xcd * 8)), block(NT);
@@ -523,10 +544,10 @@ int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, cons
     do {                                                                                                                    \
         if (g.splits > 1)                                                                                                   \
             hipLaunchKernelGGL((fused_conv_kernel<BM_, WM_, WN_, BN_, PATCH_, PartialEpilogue>), grid, block, 0, s,          \
-                               (const bf16_t *)X, (const bf16_t *)wt_scratch, g, pe);                                       \
+                               (const bf16_t *)X, wt, g, pe);                                       \
         else                                                                                                                \
             hipLaunchKernelGGL((fused_conv_kernel<BM_, WM_, WN_, BN_, PATCH_, FwdEpilogue<bf16_t>>), grid, block, 0, s,      \
-                               (const bf16_t *)X, (const bf16_t *)wt_scratch, g, epi);                                      \
+                               (const bf16_t *)X, wt, g, epi);                                      \
     } while (0)
     if (g.bm == 96) OMNI_FUSED_LAUNCH(96, 1, 8, BN_WIDE, PATCH_WIDE);
     else if (g.bn == BN_WIDE) OMNI_FUSED_LAUNCH(128, 2, 4, BN_WIDE, PATCH_WIDE);

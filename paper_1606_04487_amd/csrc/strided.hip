@@ -19,6 +19,7 @@
 // 16-byte stores), which borrows the patch's LDS space.
 #include "common.h"
 #include "mma_epilogue.h"
+#include "pack_jobs.h"
 
 namespace omni {
 namespace strided {
@@ -262,28 +263,9 @@ __global__ __launch_bounds__(NT) void strided_conv_kernel(const bf16_t *__restri
     }
 }
 
-// W [F][C][kh][kw] -> [pack p][row f (96)] 16-byte packs: pack p holds groups 2p and 2p + 1, group
-// (c, ky, j) the window columns 4j .. 4j + 3 (zero beyond kw, beyond the last group and for rows beyond F).
-__global__ void pack_strided_weights_kernel(const bf16_t *__restrict__ W, uint4 *__restrict__ Wt, Geom g)
-{
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= 2 * g.steps * BM) return;
-    const int p = idx / BM, f = idx - p * BM;
-    uint32_t v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int gi = 2 * p + j / 4, i = j % 4;
-        v[j] = 0u;
-        if (gi < g.groups && f < g.F) {
-            uint32_t c, rem, ky, kq;
-            g.div_khkwq.divmod((uint32_t)gi, c, rem);
-            g.div_kwq.divmod(rem, ky, kq);
-            const int kx = 4 * (int)kq + i;
-            if (kx < g.kw) v[j] = (uint32_t)W[((f * g.C + (int)c) * g.kh + (int)ky) * g.kw + kx];
-        }
-    }
-    Wt[idx] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
-}
+// The kernel's weights: W [F][C][kh][kw] -> [pack p][row f (96)] 16-byte packs: pack p holds groups 2p and 2p + 1,
+// group (c, ky, j) the window columns 4j .. 4j + 3 (zero beyond kw, beyond the last group and for rows beyond F);
+// written by pack_one (pack_jobs.h), kind 1.
 
 static bool make_strided_geom(const ConvGeom &c, Geom *g)
 {
@@ -512,23 +494,44 @@ size_t strided_weight_bytes(const ConvGeom &c)
     return (size_t)2 * g.steps * strided::BM * 16;
 }
 
+static void fill_strided_job(const strided::Geom &g, const void *W, void *packed, PackJob *job)
+{
+    job->kind = 1;
+    job->W = (const bf16_t *)W, job->Wt = (uint4 *)packed;
+    job->total = (int64_t)2 * g.steps * strided::BM;
+    job->F = g.F, job->Fp = job->KK = job->n_chunks = job->flip = 0, job->stride_out = job->stride_in = 0;
+    job->C = g.C, job->kh = g.kh, job->kw = g.kw, job->kwq = g.kwq, job->groups = g.groups, job->BM = strided::BM;
+}
+
+bool strided_pack_job(const ConvGeom &c, const void *W, void *packed, PackJob *job, size_t *bytes)
+{
+    strided::Geom g;
+    *bytes = 0;
+    if (!strided::make_strided_geom(c, &g)) return false;
+    *bytes = strided_weight_bytes(c);
+    if (job != nullptr) fill_strided_job(g, W, packed, job);
+    return true;
+}
+
+// `prepacked` != null: the repacked weights already exist there (strided_pack_job) and W is not read
 int launch_strided_conv(const ConvGeom &c, const void *X, const void *W, const float *bias, int relu, void *Y,
-                        void *wt_scratch, hipStream_t s)
+                        void *wt_scratch, hipStream_t s, const void *prepacked)
 {
     using namespace strided;
     Geom g;
     if (!make_strided_geom(c, &g)) return OMNI_UNSUPPORTED;
-    {
-        ProfScope prof(KID_PACK_KHAT, s, 0.0, 2.0 * (double)c.F * c.K * 2.0);
-        int total = 2 * g.steps * BM;
-        hipLaunchKernelGGL(pack_strided_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                           (const bf16_t *)W, (uint4 *)wt_scratch, g);
-        OMNI_LAUNCH_CHECK();
+    if (prepacked == nullptr) {
+        PackJobTable t;
+        fill_strided_job(g, W, wt_scratch, &t.job[0]);
+        t.first_block[0] = 0, t.first_block[1] = (t.job[0].total + 255) / 256, t.n = 1;
+        int st = launch_pack_jobs(t, s);
+        if (st != OMNI_OK) return st;
     }
+    const uint4 *wt = (const uint4 *)(prepacked != nullptr ? prepacked : wt_scratch);
     ProfScope prof(KID_STRIDED_FWD, s, 2.0 * (double)c.M * c.K * c.F,
                    2.0 * ((double)c.N * c.C * c.H * c.W + (double)c.M * c.F));
     hipLaunchKernelGGL(strided_conv_kernel, dim3((unsigned)(g.n_items < 256 ? g.n_items : 256)), dim3(NT), 0, s, (const bf16_t *)X,
-                       (const uint4 *)wt_scratch, (bf16_t *)Y, bias, relu, g);
+                       wt, (bf16_t *)Y, bias, relu, g);
     OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }

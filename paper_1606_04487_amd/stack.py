@@ -65,6 +65,14 @@ class ConvStack:
             if not (i == 0 and skip_first_dgrad):
                 bwd_bytes = max(bwd_bytes, B.conv_workspace_bytes(d, B.PASS_BACKWARD_DATA))
         self.ws_bwd = torch.empty(max(bwd_bytes, 16), dtype=torch.uint8, device=device)
+        # Repacked weights of the fused forward / data-gradient kernels, owned here and rewritten by ONE launch
+        # whenever the weights change (set_parameters, sgd_step) instead of by every forward / backward call.
+        self.packed_fwd, self.packed_bwd = [], []
+        for i, d in enumerate(self.desc):
+            nf = B.conv_packed_weights_bytes(d, B.PASS_FORWARD)
+            nb = 0 if (i == 0 and skip_first_dgrad) else B.conv_packed_weights_bytes(d, B.PASS_BACKWARD_DATA)
+            self.packed_fwd.append(torch.empty(nf, dtype=torch.uint8, device=device) if nf else None)
+            self.packed_bwd.append(torch.empty(nb, dtype=torch.uint8, device=device) if nb else None)
         # activations
         self.X: List[Optional[torch.Tensor]] = [None] * len(self.layers)
         self.Y, self.P, self.A, self.dYc, self.dXl = [], [], [], [], []
@@ -98,6 +106,15 @@ class ConvStack:
                 self.Wc[i].copy_(self.W[i])       # plumbing: the inputs are bf16-representable already
             self.VW[i].zero_()
             self.Vb[i].zero_()
+        self.repack_weights()
+
+    def repack_weights(self) -> None:
+        """The fused kernels' copies of the current weights, all layers and both passes in launches of up to 16."""
+        jobs = [(self.desc[i], B.PASS_FORWARD, self.Wc[i], p) for i, p in enumerate(self.packed_fwd) if p is not None]
+        jobs += [(self.desc[i], B.PASS_BACKWARD_DATA, self.Wc[i], p) for i, p in enumerate(self.packed_bwd) if p is not None]
+        for k in range(0, len(jobs), 16):
+            d, ps, w, out = zip(*jobs[k:k + 16])
+            B.conv_pack_weights(d, ps, w, out)
 
     def output_shape(self):
         last = self.P[-1] if self.P[-1] is not None else self.Y[-1]
@@ -110,7 +127,10 @@ class ConvStack:
         cur = X
         for i, L in enumerate(self.layers):
             self.X[i] = cur
-            B.conv_forward(self.desc[i], cur, self.Wc[i], self.b[i], self.Y[i], self.ws_layer[i])
+            if self.packed_fwd[i] is not None:
+                B.conv_forward_packed(self.desc[i], cur, self.packed_fwd[i], self.b[i], self.Y[i], self.ws_layer[i])
+            else:
+                B.conv_forward(self.desc[i], cur, self.Wc[i], self.b[i], self.Y[i], self.ws_layer[i])
             cur = self.Y[i]
             if L.pool_after:
                 B.maxpool_forward(cur, 3, 2, self.ceil_mode, self.P[i], self.A[i])
@@ -153,7 +173,10 @@ class ConvStack:
             if self.dXl[i] is None:
                 g = None
                 break
-            B.conv_backward_data(self.desc[i], self.dYc[i], self.Wc[i], self.dXl[i], self.ws_bwd)
+            if self.packed_bwd[i] is not None:
+                B.conv_backward_data_packed(self.desc[i], self.dYc[i], self.packed_bwd[i], self.dXl[i], self.ws_bwd)
+            else:
+                B.conv_backward_data(self.desc[i], self.dYc[i], self.Wc[i], self.dXl[i], self.ws_bwd)
             g = self.dXl[i]
         if self.side is not None:
             torch.cuda.current_stream().wait_stream(self.side)
@@ -165,6 +188,7 @@ class ConvStack:
             shadow = list(self.Wc) + [None] * len(self.b)
         B.sgd_momentum_step(self.W + self.b, self.VW + self.Vb, self.dW + self.db, lr, momentum,
                             weight_decay, shadow)
+        self.repack_weights()
 
     def step(self, X: torch.Tensor, dOut: torch.Tensor, lr: float, momentum: float,
              weight_decay: float = 0.0) -> torch.Tensor:

@@ -221,6 +221,50 @@ def test_lrn_and_dropout_argument_checks(B):
     assert L.omni_dropout_backward(3, 16, f(0.5), 1, 0, fake, fake, None) == -2
 
 
+def test_packed_weights_argument_checks(B):
+    """Sizes and error paths of the repacked-weights object (host code only: nothing is launched)."""
+    L = B.raw()
+    fake = ctypes.c_void_p(0x1000)
+    fused = B.conv_desc(4, 256, 13, 13, 384, 3, 3, 1, 1, B.BF16, B.FLAG_FUSED)
+    plain = B.conv_desc(4, 256, 13, 13, 384, 3, 3, 1, 1, B.BF16, 0)
+    conv1 = B.conv_desc(2, 3, 227, 227, 96, 11, 11, 4, 0, B.BF16, B.FLAG_FUSED)
+    f32 = B.conv_desc(4, 256, 13, 13, 384, 3, 3, 1, 1, B.F32, B.FLAG_FUSED)
+    # [chunk][tap][pack][row][8] bf16 with the rows rounded up to the 128-row tile, rounded up to 256 bytes
+    assert B.conv_packed_weights_bytes(fused, B.PASS_FORWARD) == (256 // 32) * 9 * 4 * 384 * 16
+    assert B.conv_packed_weights_bytes(fused, B.PASS_BACKWARD_DATA) == (384 // 32) * 9 * 4 * 256 * 16
+    assert B.conv_packed_weights_bytes(conv1, B.PASS_FORWARD) > 0
+    assert B.conv_packed_weights_bytes(conv1, B.PASS_BACKWARD_DATA) == 0      # its data gradient repacks by itself
+    for d in (plain, f32):
+        assert B.conv_packed_weights_bytes(d, B.PASS_FORWARD) == 0
+        assert B.conv_packed_weights_bytes(d, B.PASS_BACKWARD_DATA) == 0
+    n = ctypes.c_size_t()
+    assert L.omni_conv_packed_weights_bytes(ctypes.byref(fused), B.PASS_BACKWARD_WEIGHTS, ctypes.byref(n)) == -1
+    assert L.omni_conv_packed_weights_bytes(ctypes.byref(fused), B.PASS_FORWARD, None) == -1
+    # the launch: counts, null and misaligned entries, a pass without repacked weights
+    descs = (B.ConvDesc * 2)(fused, plain)
+    passes = (ctypes.c_int32 * 2)(B.PASS_FORWARD, B.PASS_FORWARD)
+    ptrs = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    assert L.omni_conv_pack_weights(0, None, None, None, None, None) == 0
+    assert L.omni_conv_pack_weights(17, descs, passes, ptrs, ptrs, None) == -1
+    assert L.omni_conv_pack_weights(-1, descs, passes, ptrs, ptrs, None) == -1
+    assert L.omni_conv_pack_weights(1, descs, passes, None, ptrs, None) == -1
+    assert L.omni_conv_pack_weights(2, descs, passes, ptrs, ptrs, None) == -2   # entry 1 reads W itself
+    odd = (ctypes.c_void_p * 2)(0x1004, 0x2000)
+    assert L.omni_conv_pack_weights(1, descs, passes, odd, ptrs, None) == -4
+    nul = (ctypes.c_void_p * 2)(0, 0x2000)
+    assert L.omni_conv_pack_weights(1, descs, passes, nul, ptrs, None) == -1
+    bad_pass = (ctypes.c_int32 * 2)(B.PASS_BACKWARD_WEIGHTS, 0)
+    assert L.omni_conv_pack_weights(1, descs, bad_pass, ptrs, ptrs, None) == -1
+    # the packed entry points refuse layers and passes without repacked weights, and check like the plain ones
+    assert L.omni_conv_forward_packed(ctypes.byref(plain), fake, fake, None, fake, fake, 1 << 40, None) == -2
+    assert L.omni_conv_backward_data_packed(ctypes.byref(conv1), fake, fake, fake, fake, 1 << 40, None) == -2
+    assert L.omni_conv_forward_packed(ctypes.byref(fused), fake, None, None, fake, fake, 1 << 40, None) == -1
+    assert L.omni_conv_forward_packed(ctypes.byref(fused), fake, ctypes.c_void_p(0x1008), None, fake, fake, 1 << 40, None) == -4
+    assert L.omni_conv_forward_packed(ctypes.byref(fused), fake, fake, None, fake, fake, 16, None) == -3
+    assert L.omni_conv_backward_data_packed(ctypes.byref(fused), fake, fake, None, fake, 1 << 40, None) == -1
+    assert L.omni_conv_backward_data_packed(ctypes.byref(fused), fake, fake, fake, fake, 16, None) == -3
+
+
 def test_tuning_overrides_are_checked(B):
     L = B.raw()
     assert L.omni_tuning_set(B.TUNE_FUSED_BN, 300) == -1

@@ -203,6 +203,39 @@ def test_patch_backward_weights(B, cfg, splits, tuning):
             assert rel_err(got[:, :, ky, kx], ref[:, :, ky, kx]) <= 1e-4, (ky, kx)
 
 
+def test_packed_weights_entry_points_are_identical(B):
+    """The caller-owned repacked weights: nine layer-and-pass pairs written by ONE launch, then the *_packed entry
+    points against the plain ones, bit for bit (stride-1 layers both passes, the stride-4 layer forward)."""
+    cfgs = [(3, 32, 13, 13, 64, 3, 3, 1, 1, 1), (2, 96, 27, 27, 256, 5, 5, 2, 2, 1), (5, 64, 13, 13, 384, 3, 3, 1, 1, 1),
+            (2, 64, 9, 11, 128, 3, 2, 0, 1, 1), (2, 3, 67, 67, 96, 11, 11, 0, 0, 4)]
+    rng = np.random.default_rng(23)
+    jobs, cases = [], []
+    for (N, C, H, W, F, kh, kw, ph, pw, st) in cfgs:
+        d = B.conv_desc(N, C, H, W, F, kh, kw, st, (ph, pw), B.BF16, B.FLAG_FUSED | B.FLAG_RELU)
+        ho, wo = B.conv_output_dims(d)
+        X = gpu(rng.standard_normal((N, C, H, W)))
+        Wt = gpu(0.05 * rng.standard_normal((F, C, kh, kw)))
+        bias = torch.from_numpy(rng.standard_normal(F).astype(np.float32)).cuda()
+        dY = gpu(rng.standard_normal((N, F, ho, wo)))
+        for which in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA):
+            nbytes = B.conv_packed_weights_bytes(d, which)
+            if nbytes == 0:
+                assert st == 4 and which == B.PASS_BACKWARD_DATA
+                continue
+            buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            jobs.append((d, which, Wt, buf))
+            cases.append((d, which, X, Wt, bias, dY, buf))
+    assert len(jobs) == 9
+    print("packed weights:", len(jobs), "jobs in one launch", flush=True)
+    B.conv_pack_weights(*zip(*jobs))
+    for d, which, X, Wt, bias, dY, buf in cases:
+        print("packed entry point", d.N, d.C, d.H, d.F, d.kh, "pass", which, flush=True)
+        if which == B.PASS_FORWARD:
+            assert torch.equal(B.conv_forward_packed(d, X, buf, bias), B.conv_forward(d, X, Wt, bias))
+        else:
+            assert torch.equal(B.conv_backward_data_packed(d, dY, buf), B.conv_backward_data(d, dY, Wt))
+
+
 def test_fused_declines_and_falls_back(B):
     # stride 2, channels not a multiple of 32, fp32: the flag is accepted and the explicit path runs
     for cfg, dtype in [((2, 32, 9, 9, 8, 3, 3, 2, 2, 1, 1), 1), ((2, 20, 9, 9, 8, 3, 3, 1, 1, 1, 1), 1),

@@ -105,7 +105,7 @@ def raw():
     return _lib
 
 
-TUNE_GEMM_TILE, TUNE_FUSED_BN, TUNE_FUSED_BM, TUNE_WGRAD_SPLITS, TUNE_WGRAD_PATCH = 0, 1, 2, 3, 4
+TUNE_GEMM_TILE, TUNE_FUSED_BN, TUNE_FUSED_BM, TUNE_WGRAD_SPLITS, TUNE_WGRAD_PATCH, TUNE_FUSED_PITCH = 0, 1, 2, 3, 4, 5
 
 
 def tuning_set(knob: int, value: int) -> None:

@@ -215,6 +215,7 @@ int launch_wgrad_reduce(const ConvGeom &g, const float *partials, int splits, fl
 // tile overrides for sweeps (omni_tuning_set); -1 leaves a value as it is
 void set_gemm_tile_override(int tile);
 void set_fused_tile_override(int bn, int bm);
+void set_fused_pitch_override(int bare);
 void set_wgrad_patch_override(int max_splits, int off);
 
 // elementwise.hip

@@ -270,6 +270,8 @@ def test_tuning_overrides_are_checked(B):
     assert L.omni_tuning_set(B.TUNE_FUSED_BN, 300) == -1
     assert L.omni_tuning_set(B.TUNE_FUSED_BM, 64) == -1
     assert L.omni_tuning_set(9, 0) == -1
+    assert L.omni_tuning_set(B.TUNE_FUSED_PITCH, 2) == -1 and L.omni_tuning_set(B.TUNE_WGRAD_SPLITS, -1) == -1
+    assert L.omni_tuning_set(B.TUNE_WGRAD_PATCH, 2) == -1
     # a forced column tile changes which layers run fused, and resetting restores the library's choice
     d = B.conv_desc(4, 256, 13, 13, 384, 3, 3, 1, 1, B.BF16, B.FLAG_FUSED)
     assert B.conv_fused_supported(d, B.PASS_FORWARD)

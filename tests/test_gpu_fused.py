@@ -145,6 +145,28 @@ def test_fused_every_column_tile(B, cfg, bn, tuning):
     assert ran > 0 or bn != "256"
 
 
+@pytest.mark.parametrize("bare", [0, 1])
+@pytest.mark.parametrize("cfg", [FUSED_SHAPES[0], FUSED_SHAPES[1], (5, 96, 27, 27, 64, 5, 5, 2, 2), (9, 64, 13, 13, 128, 3, 3, 1, 1),
+                                 (3, 32, 20, 22, 96, 3, 4, 1, 1)])
+def test_fused_patch_pitch(B, cfg, bare, tuning):
+    """The LDS patch with the bare padded row width and with the pitch that keeps fragment reads free of bank
+    conflicts: the same sums in the same order, so the two agree bit for bit, and both meet the oracle."""
+    print("fused patch pitch", cfg, "bare" if bare else "conflict-free", flush=True)
+    s, X, Wt, b, dY = make(cfg, 29)
+    d = desc_of(B, cfg, B.FLAG_FUSED | B.FLAG_RELU)
+    tuning(B.TUNE_FUSED_PITCH, bare)
+    Y = B.conv_forward(d, gpu(X), gpu(Wt), torch.from_numpy(b).cuda())
+    assert rel_err(host(Y), np.maximum(oracle.conv_forward(s, X, Wt, b), 0.0)) <= TOL
+    tuning(B.TUNE_FUSED_PITCH, 1 - bare)
+    assert torch.equal(Y, B.conv_forward(d, gpu(X), gpu(Wt), torch.from_numpy(b).cuda()))
+    if B.conv_fused_supported(d, B.PASS_BACKWARD_DATA):
+        tuning(B.TUNE_FUSED_PITCH, bare)
+        dX = B.conv_backward_data(d, gpu(dY), gpu(Wt))
+        assert rel_err(host(dX), oracle.conv_backward_data(s, dY, Wt)) <= TOL
+        tuning(B.TUNE_FUSED_PITCH, 1 - bare)
+        assert torch.equal(dX, B.conv_backward_data(d, gpu(dY), gpu(Wt)))
+
+
 @pytest.mark.parametrize("cfg", FUSED_SHAPES + [(3, 5, 13, 13, 7, 3, 3, 1, 1), (2, 20, 27, 27, 130, 5, 5, 2, 2),
                                                 (2, 3, 9, 30, 4, 3, 5, 2, 4), (2, 30, 13, 13, 250, 3, 3, 1, 1),
                                                 (3, 29, 9, 11, 256, 3, 2, 0, 1), (1, 57, 27, 27, 200, 5, 5, 2, 2),

@@ -51,8 +51,15 @@ template <int H_, int W_> struct Plane {
     static constexpr int P8 = (HW + 7) / 8;          // 16-byte groups per plane
     static constexpr int TAIL = HW - 8 * (P8 - 1);   // real elements of a plane's last group
     static constexpr int MG = 2;                     // zero groups on either side of a plane in xbuf
-    static constexpr int XP = (P8 + 2 * MG) | 1;     // row pitches in groups: odd, so that the 16 rows read by
-    static constexpr int YP = P8 | 1;                // a lane group fall into 16 different bank groups
+    // Row pitches in groups.  A lane of a fragment read takes row lane % 16 at group lane / 16, and the LDS serves
+    // the 64 lanes of a 16-byte read in four passes of 16 (lanes 0-3, 12-15, 20-27 | 4-11, 16-19, 28-31 | the same of
+    // the upper half), a pass being free of bank conflicts when its 16-byte slots differ mod 16.  With slot =
+    // pitch * row + group that holds exactly for pitch = 2, 6, 10 or 14 mod 16 (an odd pitch, which spreads any 16
+    // CONSECUTIVE lanes over all slots, puts two lanes on half of the slots of every pass: measured twice the cycles).
+    static constexpr int conflict_free_pitch(int n) { return n % 4 == 2 ? n : n + (6 - n % 4) % 4; }
+    static constexpr int XP = conflict_free_pitch(P8 + 2 * MG);
+    static constexpr int YP = conflict_free_pitch(P8);
+    static_assert(XP % 4 == 2 && YP % 4 == 2 && XP >= P8 + 2 * MG && YP >= P8, "pitches");
     static constexpr int Y_ITERS = (FT * YP + NT - 1) / NT;
     static constexpr int Y_BUF = Y_ITERS * NT;       // groups per ybuf buffer (every thread writes one per iteration)
     static constexpr int X_PIECES = CT * P8;

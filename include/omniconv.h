@@ -318,8 +318,8 @@ int omni_profile_summary(int kernel_id, int64_t *launches, double *total_ms, dou
  *   OMNI_TUNE_FUSED_BM : row tile of the fused convolution: 96 or 128 (0: choose)
  *   OMNI_TUNE_FUSED_PITCH : 1 keeps the fused convolution's LDS patch at the bare padded row width, 0 lets it take the
  *                           pitch that keeps fragment reads free of bank conflicts where the patch still fits
- *   OMNI_TUNE_WGRAD_SPLITS: most image ranges the LDS-patch model gradient splits its reduction into (0: choose)
- *   OMNI_TUNE_WGRAD_PATCH : 1 switches the LDS-patch model gradient off (its layers take the direct loader), 0 on
+ *   OMNI_TUNE_WGRAD_SPLITS: most ranges the LDS-patch model gradients split their reduction into (0: choose)
+ *   OMNI_TUNE_WGRAD_PATCH : 1 switches the LDS-patch model gradients off (their layers take the direct loader), 0 on
  * An override that does not fit a layer is ignored for that layer.
  */
 enum { OMNI_TUNE_GEMM_TILE = 0, OMNI_TUNE_FUSED_BN = 1, OMNI_TUNE_FUSED_BM = 2, OMNI_TUNE_WGRAD_SPLITS = 3, OMNI_TUNE_WGRAD_PATCH = 4,

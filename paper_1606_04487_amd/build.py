@@ -15,7 +15,7 @@ HERE = Path(__file__).resolve().parent
 ROOT = HERE.parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libomniconv.so"
-SOURCES = ["api.hip", "lowering.hip", "elementwise.hip", "gemm.hip", "implicit.hip", "strided.hip", "wgrad_patch.hip", "normdrop.hip", "profile.hip"]
+SOURCES = ["api.hip", "lowering.hip", "elementwise.hip", "gemm.hip", "implicit.hip", "strided.hip", "wgrad_patch.hip", "wgrad_wide.hip", "normdrop.hip", "profile.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          f"-I{ROOT / 'include'}", f"-I{CSRC}"]

@@ -164,8 +164,14 @@ void plan_backward_weights(const ConvGeom &g, int dtype, BwdWeightsWs *w)
         w->ld_rows = dyhat_rows_ld(g);
         w->bias_blocks_rows = pack_dyhat_rows_blocks(g);
     }
+    w->splits_wide = !phase && w->splits_patch == 0 && wgrad_wide_supported(g, dtype) ? wgrad_wide_splits(g) : 0;
+    if (w->splits_wide > 0) {
+        w->ld_rows = dyhat_rows_ld(g);
+        w->bias_blocks_rows = pack_dyhat_rows_blocks(g);
+    }
     int64_t ld_max = w->ld > w->ld_rows ? w->ld : w->ld_rows;
     int splits_max = w->splits > w->splits_rows ? w->splits : w->splits_rows;
+    if (w->splits_wide > 0 && splits_max < w->splits_wide + 1) splits_max = w->splits_wide + 1;
     if (w->splits_patch > 0 && splits_max < w->splits_patch + 1) splits_max = w->splits_patch + 1;  // + 1: kept even when it is 1
     int bb_max = w->bias_blocks > w->bias_blocks_rows ? w->bias_blocks : w->bias_blocks_rows;
     w->dhat = 0;
@@ -216,10 +222,12 @@ int omni_tuning_set(int knob, int value)
     case OMNI_TUNE_WGRAD_SPLITS:
         if (value < 0) return OMNI_INVALID_ARGUMENT;
         set_wgrad_patch_override(value, -1);
+        set_wgrad_wide_override(value, -1);
         return OMNI_OK;
     case OMNI_TUNE_WGRAD_PATCH:
         if (value != 0 && value != 1) return OMNI_INVALID_ARGUMENT;
         set_wgrad_patch_override(-1, value);
+        set_wgrad_wide_override(-1, value);
         return OMNI_OK;
     default: return OMNI_INVALID_ARGUMENT;
     }
@@ -288,7 +296,7 @@ int omni_conv_fused_supported(const omni_conv_desc *desc, int pass)
         return fused_supported(g, desc->dtype, true) && fused_weight_bytes(g, true) <= w.total ? 1 : 0;
     }
     if (pass == OMNI_PASS_BACKWARD_WEIGHTS)
-        return wgrad_patch_supported(g, desc->dtype) || wgrad_direct_supported(g, desc->dtype) || wgrad_phase_supported(g, desc->dtype) ? 1 : 0;
+        return wgrad_patch_supported(g, desc->dtype) || wgrad_wide_supported(g, desc->dtype) || wgrad_direct_supported(g, desc->dtype) || wgrad_phase_supported(g, desc->dtype) ? 1 : 0;
     return OMNI_INVALID_ARGUMENT;
 }
 
@@ -584,6 +592,12 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
         st = launch_wgrad_patch(g, X, dYhat, w.ld_rows, partials, w.splits_patch, s);
         if (st != OMNI_OK) return st;
         return launch_wgrad_reduce(g, partials, w.splits_patch, dW, bias_partials, w.bias_blocks_rows, dbias, s);
+    }
+    if ((desc->flags & OMNI_FLAG_FUSED) && !cached && w.splits_wide > 0) {
+        // 5-wide window: dY as a plane-padded matrix, the lowered operand from LDS copies of windows of X's planes
+        st = launch_pack_dyhat_rows(g, dY, dYhat, w.ld_rows, dbias ? bias_partials : nullptr, w.bias_blocks_rows, nullptr, s);
+        if (st != OMNI_OK) return st;
+        return launch_wgrad_wide(g, X, dYhat, w.ld_rows, partials, w.splits_wide, dW, bias_partials, w.bias_blocks_rows, dbias, s);
     }
     const bool direct = (desc->flags & OMNI_FLAG_FUSED) && !cached && wgrad_direct_supported(g, desc->dtype);
     // with a split product the ordered reduction finishes the bias gradient too (one launch fewer)

@@ -95,6 +95,7 @@ struct BwdWeightsWs {
     int64_t ld; int splits; int64_t chunk; int bias_blocks;
     int64_t ld_rows; int splits_rows; int64_t chunk_rows; int bias_blocks_rows;
     int splits_patch;  // > 0: the layer's fused model gradient is wgrad_patch.hip's, over this many image ranges
+    int splits_wide;   // > 0: ... is wgrad_wide.hip's, over this many ranges of stages
 };
 void plan_forward(const ConvGeom &g, int dtype, ForwardWs *w);
 void plan_backward_data(const ConvGeom &g, int dtype, BwdDataWs *w);
@@ -207,6 +208,13 @@ bool wgrad_patch_supported(const ConvGeom &g, int dtype);
 int wgrad_patch_splits(const ConvGeom &g);
 int launch_wgrad_patch(const ConvGeom &g, const void *X, const void *dYhat, int64_t ld, float *partials, int splits,
                        hipStream_t s);
+// wgrad_wide.hip: the same for a 5-wide window on planes too large for LDS (one window row per workgroup, stages of
+// 128 positions); partial sums [splits][kh][F][C][kw], added in order by its own reduction (with the bias gradient)
+bool wgrad_wide_supported(const ConvGeom &g, int dtype);
+int wgrad_wide_splits(const ConvGeom &g);
+int launch_wgrad_wide(const ConvGeom &g, const void *X, const void *dYhat, int64_t ld, float *partials, int splits, float *dW,
+                      const float *bias_partials, int bias_blocks, float *dbias, hipStream_t s);
+void set_wgrad_wide_override(int max_splits, int off);
 // gemm.hip: ordered sum of the split partial results [splits][F][K] into dW; with dbias != null the same launch
 // finishes the bias gradient from the per-block sums of the dY packing kernel
 int launch_wgrad_reduce(const ConvGeom &g, const float *partials, int splits, float *dW, const float *bias_partials,

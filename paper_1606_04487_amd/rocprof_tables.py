@@ -34,7 +34,7 @@ def kernel_class(name: str):
         return "conv_fused"
     if "strided_conv_kernel" in name:
         return "conv_strided_forward"
-    if "PartialEpilogue" in name or "wgrad_kernel" in name or "wgrad_patch_kernel" in name:
+    if "PartialEpilogue" in name or "wgrad_kernel" in name or "wgrad_patch_kernel" in name or "wgrad_wide_kernel" in name:
         return "gemm_wgrad"
     if "FwdEpilogue" in name and "gemm" in name:
         return "gemm_forward"
@@ -43,7 +43,7 @@ def kernel_class(name: str):
     for key, cls in (("phase_split", "lower"), ("phase_merge", "col2im"), ("lower_", "lower"), ("col2im", "col2im"),
                      ("pack_dyhat", "pack_dyhat"), ("pack_weights", "pack_khat"), ("pack_jobs", "pack_khat"), ("pack_strided_weights", "pack_khat"),
                      ("dgrad_phase_weights", "pack_khat"), ("pack_khat", "pack_khat"), ("bias_reduce", "bias_reduce"),
-                     ("reduce_partials", "reduce_partials"), ("reduce_store", "reduce_partials"),
+                     ("reduce_partials", "reduce_partials"), ("reduce_wide", "reduce_partials"), ("reduce_store", "reduce_partials"),
                      ("maxpool_fwd", "maxpool_forward"), ("maxpool_bwd", "maxpool_backward"),
                      ("maxpool_forward", "maxpool_forward"), ("maxpool_backward", "maxpool_backward"),
                      ("relu", "relu"), ("sgd", "sgd"), ("lrn", "lrn"), ("dropout", "dropout")):

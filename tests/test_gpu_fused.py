@@ -258,6 +258,41 @@ def test_packed_weights_entry_points_are_identical(B):
             assert torch.equal(B.conv_backward_data_packed(d, dY, buf), B.conv_backward_data(d, dY, Wt))
 
 
+# 5-wide windows, same-size output, channels a multiple of 96, filters of 128, planes of whole 32-position slabs:
+# the LDS-patch model gradient with one window row per workgroup
+WIDE_SHAPES = [(2, 96, 27, 27, 128, 5, 5, 2, 2), (3, 96, 8, 12, 256, 5, 5, 2, 2), (1, 192, 16, 16, 128, 5, 5, 2, 2),
+               (2, 96, 12, 8, 128, 3, 5, 1, 2), (5, 96, 4, 15, 128, 7, 5, 3, 2), (1, 96, 24, 32, 128, 5, 5, 2, 2)]
+
+
+@pytest.mark.parametrize("splits", [0, 1, 3])
+@pytest.mark.parametrize("cfg", WIDE_SHAPES)
+def test_wide_patch_backward_weights(B, cfg, splits, tuning):
+    """Model gradient of 5-wide windows from LDS copies of plane windows (row offsets of every residue mod 8, window
+    heights 3 to 7, planes with and without a ragged last group, two channel tiles, last stages of fewer slabs; one
+    range of stages, three, or one round of workgroups), against the oracle tap by tap and against the direct-loader
+    path; the bias gradient; deterministic."""
+    print("wide patch wgrad", cfg, "splits", splits, flush=True)
+    N, C, H, W, F, kh, kw, ph, pw = cfg
+    s, X, Wt, b, dY = make(cfg, 19)
+    d = desc_of(B, cfg, B.FLAG_FUSED)
+    tuning(B.TUNE_WGRAD_SPLITS, splits)
+    Xg, dYg = gpu(X), gpu(dY)
+    dW, db = B.conv_backward_weights(d, Xg, dYg)
+    ref = oracle.conv_backward_weights(s, X, dY)
+    got = host(dW)
+    assert rel_err(got, ref) <= 1e-4
+    assert rel_err(host(db), oracle.bias_grad(s, dY)) <= 1e-4
+    scale = np.max(np.abs(ref))
+    for ky in range(kh):
+        for kx in range(kw):
+            assert np.max(np.abs(got[:, :, ky, kx] - ref[:, :, ky, kx])) <= 1e-4 * scale, (ky, kx)
+    again, _ = B.conv_backward_weights(d, Xg, dYg)
+    assert torch.equal(dW, again)
+    tuning(B.TUNE_WGRAD_PATCH, 1)                  # the same layer without this kernel
+    dW2, _ = B.conv_backward_weights(d, Xg, dYg)
+    assert rel_err(got, host(dW2)) <= 2e-5
+
+
 def test_fused_declines_and_falls_back(B):
     # stride 2, channels not a multiple of 32, fp32: the flag is accepted and the explicit path runs
     for cfg, dtype in [((2, 32, 9, 9, 8, 3, 3, 2, 2, 1, 1), 1), ((2, 20, 9, 9, 8, 3, 3, 1, 1, 1, 1), 1),

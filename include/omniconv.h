@@ -264,6 +264,41 @@ int omni_maxpool_relu_backward(int32_t dtype, int64_t planes, int32_t H, int32_t
                                const void *y_pooled, void *dx, void *hip_stream);
 
 /*
+ * The output gradient in the form the model gradient multiplies (Sec. III-B: the batch's output as ONE matrix whose
+ * columns run over all images' positions; Sec. II-B: its gradient is the left operand of the model-gradient product).
+ * With OMNI_FLAG_FUSED, bf16, the model gradient of the same-size stride-1 layers reads dY as the "rows" matrix
+ *     dY_rows [F][ld] bf16:  dY_rows[f][n * plane_pitch + j] = dY[n][f][j],  j < Ho*Wo;  zero for Ho*Wo <= j < plane_pitch,
+ * which omni_conv_backward_weights writes into its workspace on every call.  The layer that PRODUCES dY (the ReLU
+ * and/or pooling layer behind the convolution) can write that form directly, and both backward passes read it:
+ *   omni_conv_dy_rows_layout: ld and plane_pitch (elements) for this layer, plane_pitch = Ho*Wo rounded up to 8 and
+ *       ld = N * plane_pitch; OMNI_UNSUPPORTED when the layer's model gradient does not read the rows form (then the
+ *       plain entry points are the ones to call).  Host only.
+ *   omni_relu_backward_rows: dx_rows = rows form of (y > 0 ? dy : 0) for dense y, dy [N][C][plane] (bf16, 8 <= plane
+ *       <= 2048, C <= 65535; ld a multiple of 8, >= N * (plane rounded up to 8)); plane_sums (nullable) is fp32
+ *       [C][N] and receives the sum of every plane's stored values -- the partial sums of the bias gradient.
+ *   omni_maxpool_backward_rows: omni_maxpool_backward (y == NULL) or omni_maxpool_relu_backward (y = the pooled
+ *       values) writing dx in the rows form of the [N][C][H][W] gradient, same plane_sums; bf16, 3 x 3 windows at
+ *       stride 2 on planes of at most about 100 x 100, OMNI_UNSUPPORTED otherwise.
+ *   omni_conv_backward_weights_rows: omni_conv_backward_weights reading dY_rows (not modified); dbias, if wanted, is
+ *       the ordered sum of plane_sums over the images, so plane_sums must then be given.  dW is bit-identical to the
+ *       plain entry point's.  Workspace as for OMNI_PASS_BACKWARD_WEIGHTS.
+ *   omni_conv_backward_data_rows: omni_conv_backward_data_packed reading dY_rows; dX is bit-identical.  Workspace as
+ *       for OMNI_PASS_BACKWARD_DATA.
+ * Columns of dx_rows beyond N * plane_pitch are never written.  All pointers 16-byte aligned.
+ */
+int omni_conv_dy_rows_layout(const omni_conv_desc *desc, int64_t *ld, int64_t *plane_pitch);
+int omni_relu_backward_rows(int32_t dtype, int32_t N, int32_t C, int64_t plane, const void *y, const void *dy,
+                            void *dx_rows, int64_t ld, float *plane_sums, void *hip_stream);
+int omni_maxpool_backward_rows(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t W, int32_t k, int32_t stride,
+                               int32_t ceil_mode, const void *dy, const uint8_t *argmax, const void *y, void *dx_rows,
+                               int64_t ld, float *plane_sums, void *hip_stream);
+int omni_conv_backward_weights_rows(const omni_conv_desc *desc, const void *X, const void *dY_rows,
+                                    const float *plane_sums, float *dW, float *dbias, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream);
+int omni_conv_backward_data_rows(const omni_conv_desc *desc, const void *dY_rows, const void *packed, void *dX,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Normalisation across channels and dropout: the other two non-GEMM layers of the paper's CaffeNet runs (App. C,
  * "Data Parallelism in non-GEMM Kernels" names them beside pooling and ReLU; the paper prints no formula, the
  * definitions are those of the AlexNet network it trains, in the convention of the framework it matches layer by

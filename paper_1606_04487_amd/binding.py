@@ -33,6 +33,8 @@ SYMBOLS = [
     "omni_conv_packed_weights_bytes", "omni_conv_pack_weights", "omni_conv_forward_packed", "omni_conv_backward_data_packed",
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
     "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward",
+    "omni_conv_dy_rows_layout", "omni_relu_backward_rows", "omni_maxpool_backward_rows", "omni_conv_backward_weights_rows",
+    "omni_conv_backward_data_rows",
     "omni_lrn_forward", "omni_lrn_backward", "omni_dropout_forward", "omni_dropout_backward", "omni_status_string", "omni_version", "omni_tuning_set",
     "omni_profile_enable", "omni_profile_select", "omni_profile_select_mask", "omni_profile_kernel_count", "omni_profile_kernel_name", "omni_profile_summary",
 ]
@@ -75,6 +77,11 @@ _lib.omni_conv_packed_weights_bytes.argtypes = [_dp, ctypes.c_int, ctypes.POINTE
 _lib.omni_conv_pack_weights.argtypes = [_i32, _vp, _vp, _vp, _vp, _vp]
 _lib.omni_conv_forward_packed.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.omni_conv_backward_data_packed.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.omni_conv_dy_rows_layout.argtypes = [_dp, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
+_lib.omni_relu_backward_rows.argtypes = [_i32, _i32, _i32, _i64, _vp, _vp, _vp, _i64, _vp, _vp]
+_lib.omni_maxpool_backward_rows.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i64, _vp, _vp]
+_lib.omni_conv_backward_weights_rows.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.omni_conv_backward_data_rows.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.omni_sgd_momentum_step.argtypes = [_i32, _vp, _vp, _vp, _vp, _vp, ctypes.c_float, ctypes.c_float,
                                         ctypes.c_float, _vp]
 _lib.omni_lower.argtypes = [_dp, _vp, _vp, _i64, _vp]
@@ -388,6 +395,73 @@ def maxpool_relu_backward(dy, argmax, y_pooled, H: int, W: int, k: int = 3, stri
     _check(_lib.omni_maxpool_relu_backward(dtype_code(dy.dtype), planes, H, W, k, stride, int(ceil_mode), _p(dy),
                                            _p(argmax), _p(y_pooled), _p(dx), _stream()))
     return dx
+
+
+def conv_dy_rows_layout(desc: ConvDesc):
+    """omni_conv_dy_rows_layout: (ld, plane_pitch) of the rows form of dY this layer's model gradient reads, or None
+    when it reads no such form."""
+    ld, pitch = _i64(0), _i64(0)
+    st = _lib.omni_conv_dy_rows_layout(ctypes.byref(desc), ctypes.byref(ld), ctypes.byref(pitch))
+    if st == -2:
+        return None
+    _check(st)
+    return ld.value, pitch.value
+
+
+def _rows_out(dx_rows, plane_sums, N, C, plane, ld, want_sums, device):
+    if ld is None:
+        ld = N * ((plane + 7) // 8 * 8)
+    if dx_rows is None:
+        dx_rows = torch.zeros((C, ld), dtype=torch.bfloat16, device=device)
+    if plane_sums is None and want_sums:
+        plane_sums = torch.empty((C, N), dtype=torch.float32, device=device)
+    return dx_rows, plane_sums, ld
+
+
+def relu_backward_rows(y, dy, dx_rows=None, plane_sums=None, ld=None, want_sums=True):
+    """omni_relu_backward_rows: ReLU backward of [N][C][...] tensors written as the rows matrix [C][ld]; returns
+    (dx_rows, plane_sums [C][N])."""
+    N, C = y.shape[:2]
+    plane = y.numel() // (N * C) if N * C else 0
+    dx_rows, plane_sums, ld = _rows_out(dx_rows, plane_sums, N, C, plane, ld, want_sums, y.device)
+    _check(_lib.omni_relu_backward_rows(dtype_code(y.dtype), N, C, plane, _p(y), _p(dy), _p(dx_rows), ld, _p(plane_sums),
+                                        _stream()))
+    return dx_rows, plane_sums
+
+
+def maxpool_backward_rows(dy, argmax, y_pooled, H: int, W: int, k: int = 3, stride: int = 2, ceil_mode: bool = True,
+                          dx_rows=None, plane_sums=None, ld=None, want_sums=True):
+    """omni_maxpool_backward_rows: max-pool backward (times the ReLU's gradient when y_pooled is given) of dy
+    [N][C][Ho][Wo], written as the rows matrix [C][ld] of the [N][C][H][W] gradient; returns (dx_rows, plane_sums)."""
+    N, C = dy.shape[:2]
+    dx_rows, plane_sums, ld = _rows_out(dx_rows, plane_sums, N, C, H * W, ld, want_sums, dy.device)
+    _check(_lib.omni_maxpool_backward_rows(dtype_code(dy.dtype), N, C, H, W, k, stride, int(ceil_mode), _p(dy), _p(argmax),
+                                           _p(y_pooled), _p(dx_rows), ld, _p(plane_sums), _stream()))
+    return dx_rows, plane_sums
+
+
+def conv_backward_weights_rows(desc: ConvDesc, X, dY_rows, plane_sums, dW=None, dbias=None, workspace=None, want_dbias=True):
+    """omni_conv_backward_weights_rows: omni_conv_backward_weights reading dY in its rows form."""
+    if dW is None:
+        dW = torch.empty((desc.F, desc.C, desc.kh, desc.kw), dtype=torch.float32, device=X.device)
+    if dbias is None and want_dbias:
+        dbias = torch.empty((desc.F,), dtype=torch.float32, device=X.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, PASS_BACKWARD_WEIGHTS, X.device)
+    _check(_lib.omni_conv_backward_weights_rows(ctypes.byref(desc), _p(X), _p(dY_rows), _p(plane_sums), _p(dW), _p(dbias),
+                                                _p(workspace), workspace.numel(), _stream()))
+    return dW, dbias
+
+
+def conv_backward_data_rows(desc: ConvDesc, dY_rows, packed, dX=None, workspace=None):
+    """omni_conv_backward_data_rows: omni_conv_backward_data_packed reading dY in its rows form."""
+    if dX is None:
+        dX = torch.empty((desc.N, desc.C, desc.H, desc.W), dtype=torch_dtype(desc.dtype), device=dY_rows.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, PASS_BACKWARD_DATA, dY_rows.device)
+    _check(_lib.omni_conv_backward_data_rows(ctypes.byref(desc), _p(dY_rows), _p(packed), _p(dX), _p(workspace),
+                                             workspace.numel(), _stream()))
+    return dX
 
 
 def lrn_forward(x, size: int = 5, alpha: float = 1e-4, beta: float = 0.75, k: float = 1.0, y=None, scale=None,

@@ -629,6 +629,75 @@ int omni_conv_backward_weights(const omni_conv_desc *desc, const void *X, const 
     return launch_gemm_wgrad(g, desc->dtype, a, s);
 }
 
+// Whether the layer's model gradient reads dY in the rows form, and that form's extents.
+static bool dy_rows_layout(const omni_conv_desc *desc, const ConvGeom &g, const BwdWeightsWs &w, int64_t *ld, int64_t *pitch)
+{
+    if (!(desc->flags & OMNI_FLAG_FUSED) || (desc->flags & OMNI_FLAG_DHAT_CACHED)) return false;
+    if (w.splits_patch <= 0 && w.splits_wide <= 0) return false;
+    const int64_t p = ((int64_t)g.Ho * g.Wo + 7) / 8 * 8;
+    if (w.ld_rows != (int64_t)g.N * p) return false;  // no round-up at the rows' ends: every element belongs to a plane
+    *ld = w.ld_rows, *pitch = p;
+    return true;
+}
+
+int omni_conv_dy_rows_layout(const omni_conv_desc *desc, int64_t *ld, int64_t *plane_pitch)
+{
+    if (ld == nullptr || plane_pitch == nullptr) return OMNI_INVALID_ARGUMENT;
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    BwdWeightsWs w;
+    plan_backward_weights(g, desc->dtype, &w);
+    return dy_rows_layout(desc, g, w, ld, plane_pitch) ? OMNI_OK : OMNI_UNSUPPORTED;
+}
+
+int omni_conv_backward_weights_rows(const omni_conv_desc *desc, const void *X, const void *dY_rows, const float *plane_sums,
+                                    float *dW, float *dbias, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (X == nullptr || dY_rows == nullptr || dW == nullptr || workspace == nullptr || (dbias != nullptr && plane_sums == nullptr))
+        return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(X) || !aligned16(dY_rows) || !aligned16(dW) || !aligned16(workspace) || (dbias && !aligned16(dbias)) ||
+        (plane_sums && !aligned16(plane_sums)))
+        return OMNI_MISALIGNED;
+    BwdWeightsWs w;
+    plan_backward_weights(g, desc->dtype, &w);
+    int64_t ld, pitch;
+    if (!dy_rows_layout(desc, g, w, &ld, &pitch)) return OMNI_UNSUPPORTED;
+    if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    float *partials = (float *)((char *)workspace + w.partials);
+    if (w.splits_patch > 0) {
+        st = launch_wgrad_patch(g, X, dY_rows, ld, partials, w.splits_patch, s);
+        if (st != OMNI_OK) return st;
+        return launch_wgrad_reduce(g, partials, w.splits_patch, dW, plane_sums, g.N, dbias, s);
+    }
+    return launch_wgrad_wide(g, X, dY_rows, ld, partials, w.splits_wide, dW, plane_sums, g.N, dbias, s);
+}
+
+int omni_conv_backward_data_rows(const omni_conv_desc *desc, const void *dY_rows, const void *packed, void *dX, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    int st = make_geom(desc, &g);
+    if (st != OMNI_OK) return st;
+    if (dY_rows == nullptr || packed == nullptr || dX == nullptr || workspace == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(dY_rows) || !aligned16(packed) || !aligned16(dX) || !aligned16(workspace)) return OMNI_MISALIGNED;
+    size_t pbytes;
+    if (!packed_weights_job(desc, g, OMNI_PASS_BACKWARD_DATA, nullptr, nullptr, nullptr, &pbytes)) return OMNI_UNSUPPORTED;
+    BwdWeightsWs ww;
+    plan_backward_weights(g, desc->dtype, &ww);
+    int64_t ld, pitch;
+    if (!dy_rows_layout(desc, g, ww, &ld, &pitch)) return OMNI_UNSUPPORTED;
+    BwdDataWs w;
+    plan_backward_data(g, desc->dtype, &w);
+    if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
+    if (fused_weight_bytes(g, true) > w.total) return OMNI_UNSUPPORTED;
+    return launch_fused_conv(g, true, dY_rows, nullptr, nullptr, 0, dX, workspace, (hipStream_t)hip_stream, -1, packed, ld);
+}
+
 int omni_sgd_momentum_step(int32_t n_tensors, float *const *W, float *const *V, const float *const *G,
                            const int64_t *counts, void *const *W_shadow, float lr, float momentum, float weight_decay,
                            void *hip_stream)
@@ -688,6 +757,19 @@ int omni_relu_backward(int32_t dtype, int64_t count, const void *y, const void *
     return launch_relu(dtype, true, count, y, dy, dx, (hipStream_t)hip_stream);
 }
 
+int omni_relu_backward_rows(int32_t dtype, int32_t N, int32_t C, int64_t plane, const void *y, const void *dy, void *dx_rows,
+                            int64_t ld, float *plane_sums, void *hip_stream)
+{
+    if (dtype != OMNI_BF16) return OMNI_UNSUPPORTED;
+    if (N < 0 || C <= 0 || plane <= 0) return OMNI_INVALID_ARGUMENT;
+    if (!relu_bwd_rows_supported(N, C, plane)) return OMNI_UNSUPPORTED;
+    if (ld % 8 != 0 || ld < (int64_t)N * ((plane + 7) / 8 * 8)) return OMNI_INVALID_ARGUMENT;
+    if (N == 0) return OMNI_OK;
+    if (y == nullptr || dy == nullptr || dx_rows == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(y) || !aligned16(dy) || !aligned16(dx_rows) || (plane_sums && !aligned16(plane_sums))) return OMNI_MISALIGNED;
+    return launch_relu_bwd_rows(N, C, plane, y, dy, dx_rows, ld, plane_sums, (hipStream_t)hip_stream);
+}
+
 int omni_pool_output_dim(int32_t in, int32_t k, int32_t stride, int32_t ceil_mode)
 {
     if (in <= 0 || k <= 0 || stride <= 0 || in < k) return OMNI_INVALID_ARGUMENT;
@@ -736,6 +818,23 @@ int omni_maxpool_relu_backward(int32_t dtype, int64_t planes, int32_t H, int32_t
     if (dy == nullptr || argmax == nullptr || y == nullptr || dx == nullptr) return OMNI_INVALID_ARGUMENT;
     if (!aligned16(dy) || !aligned16(y) || !aligned16(dx)) return OMNI_MISALIGNED;
     return launch_maxpool_bwd(dtype, planes, H, W, k, stride, ceil_mode, dy, argmax, y, dx, (hipStream_t)hip_stream);
+}
+
+int omni_maxpool_backward_rows(int32_t dtype, int32_t N, int32_t C, int32_t H, int32_t W, int32_t k, int32_t stride,
+                               int32_t ceil_mode, const void *dy, const uint8_t *argmax, const void *y, void *dx_rows,
+                               int64_t ld, float *plane_sums, void *hip_stream)
+{
+    if (N < 0 || C <= 0) return OMNI_INVALID_ARGUMENT;
+    int st = check_pool(dtype, (int64_t)N * C, H, W, k, stride);
+    if (st != OMNI_OK) return st;
+    if (dtype != OMNI_BF16 || !maxpool_bwd_rows_supported(N > 0 ? N : 1, C, H, W, k, stride, ceil_mode)) return OMNI_UNSUPPORTED;
+    if (ld % 8 != 0 || ld < (int64_t)N * (((int64_t)H * W + 7) / 8 * 8)) return OMNI_INVALID_ARGUMENT;
+    if (N == 0) return OMNI_OK;
+    if (dy == nullptr || argmax == nullptr || dx_rows == nullptr) return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(dy) || !aligned16(dx_rows) || (y && !aligned16(y)) || (plane_sums && !aligned16(plane_sums)))
+        return OMNI_MISALIGNED;
+    return launch_maxpool_bwd_rows(N, C, H, W, k, stride, ceil_mode, dy, argmax, y, dx_rows, ld, plane_sums,
+                                   (hipStream_t)hip_stream);
 }
 
 static int check_lrn(int32_t dtype, int64_t N, int32_t C, int64_t plane, int32_t size, float alpha, float beta, float k)

@@ -173,9 +173,11 @@ void gemm_split_tile(int rows, int cols, int *bm, int *bn);  // tile of a split 
 // repacked weights (fused_weight_bytes).
 bool fused_supported(const ConvGeom &g, int dtype, bool data_gradient);
 size_t fused_weight_bytes(const ConvGeom &g, bool data_gradient);
-// kid: kernel class the launch is timed under (-1: by data_gradient)
+// kid: kernel class the launch is timed under (-1: by data_gradient); in_ld > 0: the input is given in its rows
+// form [C][in_ld] (plane of image n at column n * (plane rounded up to 8)) instead of the dense tensor
 int launch_fused_conv(const ConvGeom &g, bool data_gradient, const void *X, const void *W, const float *bias,
-                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid = -1, const void *prepacked = nullptr);
+                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid = -1, const void *prepacked = nullptr,
+                      int64_t in_ld = 0);
 
 // strided.hip: the forward convolution of a layer with horizontal stride 4, no padding, at most 96 filters and
 // a short reduction (CaffeNet's conv1) without D-hat; bf16.  wt_scratch receives the repacked weights.
@@ -234,7 +236,16 @@ int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
                        const void *x, void *y, uint8_t *argmax, hipStream_t s);
 int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
                        const void *dy, const uint8_t *argmax, const void *y, void *dx, hipStream_t s);
-
+// The two producers of a layer's output gradient writing its "rows" form directly (bf16): a matrix [C][ld], plane
+// (n, c) at column n * pitch with pitch = the plane rounded up to 8 elements (the round-up zero), plus the sum of
+// every plane's values, plane_sums [C][N] (optional).  Columns from N * pitch to ld are not written.
+bool maxpool_bwd_rows_supported(int32_t N, int32_t C, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode);
+int launch_maxpool_bwd_rows(int32_t N, int32_t C, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
+                            const void *dy, const uint8_t *argmax, const void *y, void *dx_rows, int64_t ld, float *plane_sums,
+                            hipStream_t s);
+bool relu_bwd_rows_supported(int32_t N, int32_t C, int64_t plane);
+int launch_relu_bwd_rows(int32_t N, int32_t C, int64_t plane, const void *y, const void *dy, void *dx_rows, int64_t ld,
+                         float *plane_sums, hipStream_t s);
 
 // normdrop.hip: normalisation across channels (x, dy, out [N][C][plane]; scale fp32, same shape) and dropout
 int launch_lrn(int dtype, bool backward, int64_t N, int32_t C, int64_t plane, int32_t size, float alpha, float beta, float k,

@@ -180,6 +180,16 @@ struct PoolGeom {
     FastDiv div_rp, div_xb;  // row pairs per plane, 8-pixel blocks per row (backward, 3 x 3 / stride 2)
 };
 
+// Output as the "rows" form of a gradient [N][C][plane] that the model-gradient kernels read: a matrix
+// [C][ld] in which plane (n, c) starts at column n * pitch (pitch = the plane's size rounded up to 8
+// elements, the round-up zero).  sums (optional): [C][N], the sum of every plane's stored values.
+struct RowsOut {
+    int64_t ld;
+    int32_t pitch, N;
+    FastDiv div_C;
+    float *sums;
+};
+
 template <typename T>
 __global__ __launch_bounds__(256) void maxpool_fwd_kernel(PoolGeom g, int64_t plane0, uint32_t count,
                                                           const T *__restrict__ x, T *__restrict__ y,
@@ -402,12 +412,28 @@ __device__ __forceinline__ void store_packed(T *dst, const T *src)
 // are output rows t-1, t x columns 4b-1 .. 4b+3: ten (winner, gradient) pairs read once, and for
 // every pixel the candidate windows and the winner code each would have follow from the pixel's
 // parities, known at compile time.  Contributions are added in ascending (oy, ox).
-template <typename T>
+// ROWS: `out` is the rows matrix, the group's first plane is plane0 (plane = n * C + c), every task leaves the
+// sum of what it stored in tsum[task], and the planes' zero round-ups are written as well.
+template <typename T, bool ROWS = false>
 __device__ __forceinline__ void pool_bwd_k3s2_tasks(const PoolGeom &g, int np, const T *gdy, const uint8_t *gam,
-                                                    T *__restrict__ out, int hw, int howo)
+                                                    T *__restrict__ out, int hw, int howo, const RowsOut *ro = nullptr,
+                                                    int64_t plane0 = 0, float *tsum = nullptr)
 {
     const int rp = (g.H + 1) >> 1, xb = (g.W + 7) >> 3;
     const int tasks = np * rp * xb;
+    auto plane_ptr = [&](int pl) -> T * {
+        if constexpr (ROWS) {
+            uint32_t n, c;
+            ro->div_C.divmod((uint32_t)(plane0 + pl), n, c);
+            return out + (int64_t)c * ro->ld + (int64_t)n * ro->pitch;
+        } else {
+            return out + pl * hw;
+        }
+    };
+    if constexpr (ROWS) {
+        const int tail = ro->pitch - hw;
+        for (int i = threadIdx.x; i < np * tail; i += 256) plane_ptr(i / tail)[hw + i % tail] = (T)0;
+    }
     for (int task = threadIdx.x; task < tasks; task += 256) {
         uint32_t rest, b, pl, t;
         g.div_xb.divmod((uint32_t)task, rest, b);
@@ -446,11 +472,21 @@ __device__ __forceinline__ void pool_bwd_k3s2_tasks(const PoolGeom &g, int np, c
             res[1][e] = Elem<T>::from_f32(bot);
         }
         const int x0 = 8 * (int)b, nv = g.W - x0 < 8 ? g.W - x0 : 8;
+        if constexpr (ROWS) {
+            float ts = 0.f;  // of the stored (rounded) values, in the order row, pixel
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (2 * (int)t + r < g.H && e < nv) ts += Elem<T>::to_f32(res[r][e]);
+            tsum[task] = ts;
+        }
+        T *plane = plane_ptr((int)pl);
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int iy = 2 * (int)t + r;
             if (iy >= g.H) break;
-            T *row = out + (int)pl * hw + iy * g.W + x0;
+            T *row = plane + iy * g.W + x0;
             if (nv == 8) {
                 store_packed<8>(row, res[r]);  // element-aligned stores
             } else {
@@ -471,10 +507,10 @@ __device__ __forceinline__ void pool_bwd_k3s2_tasks(const PoolGeom &g, int np, c
 // registers) are issued before the current group is computed and stored, so every resident workgroup has
 // reads in flight all the time instead of only during its load phase.  Requires 16 <= pb * Ho*Wo <= 4096
 // for every group (the host checks, also for the last, smaller group).
-template <typename T, bool RELU>
+template <typename T, bool RELU, bool ROWS = false>
 __global__ __launch_bounds__(256) void maxpool_bwd_k3s2_kernel(PoolGeom g, int64_t planes, int pb,
                                                                const T *__restrict__ dy, const uint8_t *__restrict__ argmax,
-                                                               const T *__restrict__ y, T *__restrict__ dx)
+                                                               const T *__restrict__ y, T *__restrict__ dx, RowsOut ro)
 {
     extern __shared__ __align__(16) unsigned char pool_smem[];
     constexpr int VEC = 16 / (int)sizeof(T);
@@ -483,6 +519,7 @@ __global__ __launch_bounds__(256) void maxpool_bwd_k3s2_kernel(PoolGeom g, int64
     const int64_t groups = (planes + pb - 1) / pb;
     T *gdy = reinterpret_cast<T *>(pool_smem);
     uint8_t *gam = pool_smem + (((size_t)pb * howo * sizeof(T) + 15) / 16) * 16;
+    float *tsum = reinterpret_cast<float *>(gam + (((size_t)pb * howo + 15) / 16) * 16);  // ROWS: one float per task
     T d[MAXC][VEC], v[MAXC][VEC];
     uint8_t a[16];
     int at[MAXC], aat = 0, n = 0;
@@ -535,9 +572,26 @@ __global__ __launch_bounds__(256) void maxpool_bwd_k3s2_kernel(PoolGeom g, int64
         __syncthreads();
         const int64_t next = grp + gridDim.x;
         if (next < groups) load(next);
-        pool_bwd_k3s2_tasks<T>(g, np, gdy, gam, dx + grp * pb * hw, hw, howo);
-        if (next >= groups) break;
-        __syncthreads();  // the staged group has been read by everyone
+        if constexpr (ROWS) {
+            pool_bwd_k3s2_tasks<T, true>(g, np, gdy, gam, dx, hw, howo, &ro, grp * pb, tsum);
+            __syncthreads();  // the staged group has been read by everyone, and every task's sum is there
+            if (ro.sums != nullptr) {
+                const int per = ((g.H + 1) >> 1) * ((g.W + 7) >> 3);
+                for (int pl = threadIdx.x; pl < np; pl += 256) {
+                    float acc = 0.f;
+                    for (int j = 0; j < per; ++j) acc += tsum[pl * per + j];
+                    uint32_t nn, c;
+                    ro.div_C.divmod((uint32_t)(grp * pb + pl), nn, c);
+                    ro.sums[(int64_t)c * ro.N + nn] = acc;
+                }
+            }
+            // tsum is next written after the next group's staging barrier, which the summing threads join
+            if (next >= groups) break;
+        } else {
+            pool_bwd_k3s2_tasks<T>(g, np, gdy, gam, dx + grp * pb * hw, hw, howo);
+            if (next >= groups) break;
+            __syncthreads();  // the staged group has been read by everyone
+        }
         grp = next;
     }
 }
@@ -775,11 +829,11 @@ int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
                 const unsigned resident = 256u * 6u;
                 dim3 pgrid(grid.x < resident ? grid.x : resident);
                 if (dtype == OMNI_BF16) {
-                    if (y) hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<bf16_t, true>), pgrid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)dy, argmax, (const bf16_t *)y, (bf16_t *)dx);
-                    else hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<bf16_t, false>), pgrid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)dy, argmax, (const bf16_t *)nullptr, (bf16_t *)dx);
+                    if (y) hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<bf16_t, true>), pgrid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)dy, argmax, (const bf16_t *)y, (bf16_t *)dx, RowsOut{});
+                    else hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<bf16_t, false>), pgrid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)dy, argmax, (const bf16_t *)nullptr, (bf16_t *)dx, RowsOut{});
                 } else {
-                    if (y) hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<float, true>), pgrid, dim3(256), lds, s, g, planes, pb, (const float *)dy, argmax, (const float *)y, (float *)dx);
-                    else hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<float, false>), pgrid, dim3(256), lds, s, g, planes, pb, (const float *)dy, argmax, (const float *)nullptr, (float *)dx);
+                    if (y) hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<float, true>), pgrid, dim3(256), lds, s, g, planes, pb, (const float *)dy, argmax, (const float *)y, (float *)dx, RowsOut{});
+                    else hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<float, false>), pgrid, dim3(256), lds, s, g, planes, pb, (const float *)dy, argmax, (const float *)nullptr, (float *)dx, RowsOut{});
                 }
                 OMNI_LAUNCH_CHECK();
                 return OMNI_OK;
@@ -818,6 +872,113 @@ int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
         }
         OMNI_LAUNCH_CHECK();
     }
+    return OMNI_OK;
+}
+
+
+// The same backward pass writing the rows form (RowsOut) instead of the dense tensor: bf16, 3 x 3 / stride 2
+// windows on planes the persistent kernel can stage; anything else is reported as unsupported.
+bool maxpool_bwd_rows_supported(int32_t N, int32_t C, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode)
+{
+    if (k != 3 || stride != 2 || H < k || W < k || (int64_t)N * C > 0x7fffffffll) return false;
+    PoolGeom g = make_pool_geom(H, W, k, stride, ceil_mode);
+    const int64_t howo = (int64_t)g.Ho * g.Wo, per = (int64_t)H * W, planes = (int64_t)N * C;
+    if (howo * 3 > 32 * 1024 || per > 0x7fffffffll - 4096) return false;
+    int pb = pool_planes_per_block(howo * 3, per);
+    if (pb > 0) pb = pool_bwd_planes_k3s2(H, W, howo * 3, howo);
+    if (pb <= 0) return false;
+    const int64_t last = planes % pb == 0 ? pb : planes % pb;
+    const int64_t tasks = (int64_t)pb * ((H + 1) / 2) * ((W + 7) / 8);
+    return (int64_t)pb * howo <= 4096 && last * howo >= 16 && tasks <= 1024;
+}
+
+int launch_maxpool_bwd_rows(int32_t N, int32_t C, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
+                            const void *dy, const uint8_t *argmax, const void *y, void *dx_rows, int64_t ld, float *plane_sums,
+                            hipStream_t s)
+{
+    if (!maxpool_bwd_rows_supported(N, C, H, W, k, stride, ceil_mode)) return OMNI_UNSUPPORTED;
+    PoolGeom g = make_pool_geom(H, W, k, stride, ceil_mode);
+    const int64_t howo = (int64_t)g.Ho * g.Wo, per = (int64_t)H * W, planes = (int64_t)N * C;
+    const int pb = pool_bwd_planes_k3s2(H, W, howo * 3, howo);
+    RowsOut ro;
+    ro.ld = ld, ro.pitch = (int32_t)((per + 7) / 8 * 8), ro.N = N, ro.div_C = FastDiv((uint32_t)C), ro.sums = plane_sums;
+    const int64_t groups = (planes + pb - 1) / pb;
+    const int tasks = pb * ((H + 1) / 2) * ((W + 7) / 8);
+    size_t lds = (((size_t)pb * howo * 2 + 15) / 16) * 16 + (((size_t)pb * howo + 15) / 16) * 16 + (size_t)tasks * sizeof(float) + 16;
+    ProfScope prof(KID_POOL_BWD, s, 0.0,
+                   (double)planes * ((double)ro.pitch + (y ? 2.0 : 1.0) * (double)howo) * 2.0 + (double)planes * (howo + 4.0));
+    const unsigned resident = 256u * 6u;
+    dim3 pgrid((unsigned)(groups < resident ? groups : resident));
+    if (y)
+        hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<bf16_t, true, true>), pgrid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)dy,
+                           argmax, (const bf16_t *)y, (bf16_t *)dx_rows, ro);
+    else
+        hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<bf16_t, false, true>), pgrid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)dy,
+                           argmax, (const bf16_t *)nullptr, (bf16_t *)dx_rows, ro);
+    OMNI_LAUNCH_CHECK();
+    return OMNI_OK;
+}
+
+// ReLU backward from dense [N][C][hw] tensors into the rows form: out[c][n * 8 p8 + j] = y > 0 ? dy : 0 for
+// j < hw and zero up to 8 p8 = the plane rounded up to 8 elements.  A workgroup takes pp consecutive images of one
+// channel (pp * p8 <= 256 threads, one 8-element pack each); plane sums as in RowsOut.
+__global__ __launch_bounds__(256) void relu_bwd_rows_kernel(int hw, int p8, int pp, int N, int C, FastDiv div_p8,
+                                                            const bf16_t *__restrict__ y, const bf16_t *__restrict__ dy,
+                                                            uint16_t *__restrict__ out, int64_t ld, float *__restrict__ sums)
+{
+    __shared__ float psum[256];
+    const int c = blockIdx.y, n0 = blockIdx.x * pp;
+    uint32_t pl, i;
+    div_p8.divmod(threadIdx.x, pl, i);
+    const int n = n0 + (int)pl;
+    const bool live = (int)pl < pp && n < N;
+    float sum = 0.f;
+    if (live) {
+        const int valid = hw - 8 * (int)i, back = valid < 8 ? 8 - valid : 0;
+        // a plane's ragged last pack is read so that its 16 bytes END at the plane's end and shifted down
+        // afterwards, which zeroes the round-up
+        const int64_t at = ((int64_t)n * C + c) * hw + 8 * (int)i - back;
+        struct alignas(16) Pack8 { uint16_t v[8]; } d, v;
+        __builtin_memcpy(&d, dy + at, 16);
+        __builtin_memcpy(&v, y + at, 16);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) d.v[e] = bf16_to_f32(v.v[e]) > 0.f ? d.v[e] : (uint16_t)0;
+        if (back) {
+            unsigned __int128 x;
+            __builtin_memcpy(&x, &d, 16);
+            x >>= 16 * back;
+            __builtin_memcpy(&d, &x, 16);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum += bf16_to_f32(d.v[e]);
+        __builtin_memcpy(__builtin_assume_aligned(out + (int64_t)c * ld + ((int64_t)n * p8 + i) * 8, 16), &d, 16);
+    }
+    if (sums != nullptr) {
+        psum[threadIdx.x] = sum;
+        __syncthreads();
+        if ((int)threadIdx.x < pp && n0 + (int)threadIdx.x < N) {
+            float acc = 0.f;
+            for (int j = 0; j < p8; ++j) acc += psum[threadIdx.x * p8 + j];
+            sums[(int64_t)c * N + n0 + threadIdx.x] = acc;
+        }
+    }
+}
+
+bool relu_bwd_rows_supported(int32_t N, int32_t C, int64_t plane)
+{
+    return plane >= 8 && plane <= 2048 && C <= 65535 && (int64_t)N * C <= 0x7fffffffll;
+}
+
+int launch_relu_bwd_rows(int32_t N, int32_t C, int64_t plane, const void *y, const void *dy, void *dx_rows, int64_t ld,
+                         float *plane_sums, hipStream_t s)
+{
+    if (!relu_bwd_rows_supported(N, C, plane)) return OMNI_UNSUPPORTED;
+    const int p8 = (int)((plane + 7) / 8), pp = 256 / p8;
+    dim3 grid((unsigned)((N + pp - 1) / pp), (unsigned)C, 1);
+    ProfScope prof(KID_RELU, s, 0.0, (double)N * C * (2.0 * plane + 8.0 * p8) * 2.0 + 4.0 * N * C);
+    hipLaunchKernelGGL(relu_bwd_rows_kernel, grid, dim3(256), 0, s, (int)plane, p8, pp, N, C, FastDiv((uint32_t)p8),
+                       (const bf16_t *)y, (const bf16_t *)dy, (uint16_t *)dx_rows, ld, plane_sums);
+    OMNI_LAUNCH_CHECK();
     return OMNI_OK;
 }
 

@@ -56,6 +56,7 @@ struct Geom {
     int32_t kh, kw, ph, pw;  // window, zero padding
     int32_t Wp;              // row pitch of the patch: at least W + 2*pw, the width of a padded row
     int32_t HW, HoWo, M, KK;
+    uint32_t sn, sc;         // elements from an input image to the next and from a channel's plane to the next
     int32_t n_chunks;        // C / CH
     int32_t Fp;              // F rounded up to the row tile
     int32_t tiles_f, tiles_m, n_items, per_xcd;
@@ -109,7 +110,8 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
 // exist (small batches): the reduction's chunks are then split over `g.splits` workgroups per tile, each
 // leaving its raw fp32 sums in a slice [F][M] of the scratch, which reduce_store_kernel adds in split order
 // and hands to the forward epilogue.
-template <int BM, int WM, int WN, int BN, int PATCH_PIX, typename Epi>
+// RIN: the input is read with the strides g.sn, g.sc (its rows form) instead of as the dense tensor.
+template <int BM, int WM, int WN, int BN, int PATCH_PIX, typename Epi, bool RIN = false>
 __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Wt,
                                                         Geom g, Epi epi)
 {
@@ -178,7 +180,8 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
         int ea = slot_ya[i] * g.W, eb = ea + slot_len[i];
         int e0 = ea + 8 * (jj - slot_p0[i]);
         e0 = e0 < g.HW - 8 ? e0 : g.HW - 8;  // stay inside the plane: the overlap rewrites equal values
-        goff = ((uint32_t)((n0 + i) * g.C + 8 * tg) * (uint32_t)g.HW + (uint32_t)e0) * 2u;
+        if constexpr (RIN) goff = ((uint32_t)(n0 + i) * g.sn + (uint32_t)(8 * tg) * g.sc + (uint32_t)e0) * 2u;
+        else goff = ((uint32_t)((n0 + i) * g.C + 8 * tg) * (uint32_t)g.HW + (uint32_t)e0) * 2u;
         uint32_t l[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -193,7 +196,7 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
 
     u32x4 r0, r1, r2, r3, r4, r5, r6, r7;  // 8 channels x 8 elements
     const char *xb = reinterpret_cast<const char *>(X);
-    const uint32_t plane_b = (uint32_t)g.HW * 2u, chunk_b = plane_b * CH;
+    const uint32_t plane_b = (RIN ? g.sc : (uint32_t)g.HW) * 2u, chunk_b = plane_b * CH;
     auto issue_patch = [&](int chunk) {
         const char *p = xb + (goff + (uint32_t)chunk * chunk_b);  // threads without a task read a valid address too
         __builtin_memcpy(&r0, p, 16);
@@ -377,6 +380,7 @@ static bool make_fused_geom(const ConvGeom &c, bool data_gradient, Geom *g)
     g->kh = c.kh, g->kw = c.kw;
     g->Wp = g->W + 2 * g->pw;  // replaced below by the pitch chosen with the tile
     g->HW = g->H * g->W, g->HoWo = g->Ho * g->Wo, g->KK = c.kh * c.kw;
+    g->sn = (uint32_t)g->C * (uint32_t)g->HW, g->sc = (uint32_t)g->HW;  // dense [N][C][H][W]; launch_fused_conv may replace them
     int64_t M = (int64_t)g->N * g->HoWo;
     if (g->C % CH != 0 || g->HW < 8 || M > 0x7fffffffll - 4096) return false;
     if ((double)g->N * g->C * g->HW * 2.0 >= 4.0e9 || (double)M * g->F * 2.0 >= 4.0e9) return false;
@@ -537,13 +541,20 @@ int launch_pack_jobs(const PackJobTable &t, hipStream_t s)
     return OMNI_OK;
 }
 
-// `prepacked` != null: the repacked weights already exist there (fused_pack_job) and W is not read
+// `prepacked` != null: the repacked weights already exist there (fused_pack_job) and W is not read.
+// in_ld > 0: the input is not the dense tensor but its rows form, a matrix [C][in_ld] with image n's plane of
+// channel c at column n * (the plane rounded up to 8 elements).
 int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, const void *W, const float *bias,
-                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid, const void *prepacked)
+                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid, const void *prepacked, int64_t in_ld)
 {
     using namespace fused;
     Geom g;
     if (!make_fused_geom(c, data_gradient, &g)) return OMNI_UNSUPPORTED;
+    if (in_ld > 0) {
+        const int64_t pitch = ((int64_t)g.HW + 7) / 8 * 8;
+        if (in_ld < g.N * pitch || (double)in_ld * g.C * 2.0 >= 4.0e9) return OMNI_UNSUPPORTED;
+        g.sn = (uint32_t)pitch, g.sc = (uint32_t)in_ld;
+    }
     if (prepacked == nullptr) {
         PackJobTable t;
         fill_fused_job(g, data_gradient, W, wt_scratch, &t.job[0]);
@@ -557,20 +568,26 @@ int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, cons
     dim3 grid((unsigned)(g.per_xcd * 8)), block(NT);
     float *partials = reinterpret_cast<float *>(reinterpret_cast<char *>(wt_scratch) + fused_packed_bytes(g));
     PartialEpilogue pe{partials, g.F, g.M};
-#define OMNI_FUSED_LAUNCH(BM_, WM_, WN_, BN_, PATCH_)                                                                       \
+#define OMNI_FUSED_LAUNCH_IN(BM_, WM_, WN_, BN_, PATCH_, RIN_)                                                               \
     do {                                                                                                                    \
         if (g.splits > 1)                                                                                                   \
-            hipLaunchKernelGGL((fused_conv_kernel<BM_, WM_, WN_, BN_, PATCH_, PartialEpilogue>), grid, block, 0, s,          \
-                               (const bf16_t *)X, wt, g, pe);                                       \
+            hipLaunchKernelGGL((fused_conv_kernel<BM_, WM_, WN_, BN_, PATCH_, PartialEpilogue, RIN_>), grid, block, 0, s,    \
+                               (const bf16_t *)X, wt, g, pe);                                                               \
         else                                                                                                                \
-            hipLaunchKernelGGL((fused_conv_kernel<BM_, WM_, WN_, BN_, PATCH_, FwdEpilogue<bf16_t>>), grid, block, 0, s,      \
-                               (const bf16_t *)X, wt, g, epi);                                      \
+            hipLaunchKernelGGL((fused_conv_kernel<BM_, WM_, WN_, BN_, PATCH_, FwdEpilogue<bf16_t>, RIN_>), grid, block, 0,  \
+                               s, (const bf16_t *)X, wt, g, epi);                                                           \
+    } while (0)
+#define OMNI_FUSED_LAUNCH(BM_, WM_, WN_, BN_, PATCH_)                                                                       \
+    do {                                                                                                                    \
+        if (in_ld > 0) OMNI_FUSED_LAUNCH_IN(BM_, WM_, WN_, BN_, PATCH_, true);                                              \
+        else OMNI_FUSED_LAUNCH_IN(BM_, WM_, WN_, BN_, PATCH_, false);                                                       \
     } while (0)
     if (g.bm == 96) OMNI_FUSED_LAUNCH(96, 1, 8, BN_WIDE, PATCH_WIDE);
     else if (g.bn == BN_WIDE) OMNI_FUSED_LAUNCH(128, 2, 4, BN_WIDE, PATCH_WIDE);
     else if (g.bn == BN_MID) OMNI_FUSED_LAUNCH(128, 2, 4, BN_MID, PATCH_MID);
     else OMNI_FUSED_LAUNCH(128, 2, 4, BN_NARROW, PATCH_NARROW);
 #undef OMNI_FUSED_LAUNCH
+#undef OMNI_FUSED_LAUNCH_IN
     OMNI_LAUNCH_CHECK();
     if (g.splits > 1) {
         const int64_t count = (int64_t)g.F * g.M;

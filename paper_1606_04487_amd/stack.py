@@ -23,7 +23,7 @@ from .workloads import ConvLayer
 class ConvStack:
     def __init__(self, layers: Sequence[ConvLayer], dtype: int = B.F32, ceil_mode: bool = True,
                  skip_first_dgrad: bool = True, device: str = "cuda", fused: bool = True,
-                 overlap_wgrad: bool = False):
+                 overlap_wgrad: bool = False, dy_rows: bool = True):
         self.layers = list(layers)
         self.dtype = dtype
         self.tdtype = B.torch_dtype(dtype)
@@ -75,12 +75,24 @@ class ConvStack:
             self.packed_bwd.append(torch.empty(nb, dtype=torch.uint8, device=device) if nb else None)
         # activations
         self.X: List[Optional[torch.Tensor]] = [None] * len(self.layers)
-        self.Y, self.P, self.A, self.dYc, self.dXl = [], [], [], [], []
+        self.Y, self.P, self.A, self._dYd, self.dXl = [], [], [], [], []
+        # dY of a layer whose model gradient multiplies the "rows" matrix [F][N * pitch]: written in that form by
+        # the pooling / ReLU backward pass behind it (with the planes' sums for the bias gradient) and read as it
+        # is by both backward passes of the convolution, instead of a dense tensor that the library would repack
+        self.dYr, self.dYs, self.rows_ld = [], [], []
         self.Nrm, self.Sc, self.Dr, self.gN, self.gD = [], [], [], [], []   # normalised / scale / dropped; their gradients
         for i, (L, d) in enumerate(zip(self.layers, self.desc)):
             ho, wo = B.conv_output_dims(d)
             self.Y.append(torch.empty((L.N, L.F, ho, wo), dtype=self.tdtype, device=device))
-            self.dYc.append(torch.empty((L.N, L.F, ho, wo), dtype=self.tdtype, device=device))
+            layout = B.conv_dy_rows_layout(self.desc_wgrad[i]) if (dy_rows and dtype == B.BF16) else None
+            need_dx = not (i == 0 and skip_first_dgrad)
+            if layout is not None and ((need_dx and self.packed_bwd[i] is None) or not (L.pool_after or L.relu)
+                                       or (not L.pool_after and ho * wo > 2048)):
+                layout = None
+            self.rows_ld.append(layout[0] if layout else 0)
+            self.dYr.append(torch.zeros((L.F, layout[0]), dtype=self.tdtype, device=device) if layout else None)
+            self.dYs.append(torch.empty((L.F, L.N), dtype=torch.float32, device=device) if layout else None)
+            self._dYd.append(None if layout else torch.empty((L.N, L.F, ho, wo), dtype=self.tdtype, device=device))
             if L.pool_after:
                 po, pw = B.pool_output_dim(ho, 3, 2, ceil_mode), B.pool_output_dim(wo, 3, 2, ceil_mode)
                 self.P.append(torch.empty((L.N, L.F, po, pw), dtype=self.tdtype, device=device))
@@ -94,8 +106,20 @@ class ConvStack:
             self.gN.append(torch.empty_like(out) if L.lrn_after else None)
             self.Dr.append(torch.empty_like(out) if L.dropout_after > 0 else None)
             self.gD.append(torch.empty_like(out) if L.dropout_after > 0 else None)
-            need_dx = not (i == 0 and skip_first_dgrad)
             self.dXl.append(torch.empty((L.N, L.C, L.H, L.W), dtype=self.tdtype, device=device) if need_dx else None)
+
+    @property
+    def dYc(self) -> List[torch.Tensor]:
+        """Every layer's output gradient as a dense [N][F][Ho][Wo] tensor (a copy where the layer keeps the rows form)."""
+        out = []
+        for i, L in enumerate(self.layers):
+            if self.dYr[i] is None:
+                out.append(self._dYd[i])
+                continue
+            ho, wo = self.Y[i].shape[-2:]
+            planes = self.dYr[i].view(L.F, L.N, -1)[:, :, :ho * wo]
+            out.append(planes.permute(1, 0, 2).reshape(L.N, L.F, ho, wo).contiguous())
+        return out
 
     # ------------------------------------------------------------------ parameters
     def set_parameters(self, Ws, bs) -> None:
@@ -153,30 +177,44 @@ class ConvStack:
             if L.lrn_after:
                 B.lrn_backward(self.P[i] if L.pool_after else Y, g, self.Sc[i], *self.LRN, dx=self.gN[i])
                 g = self.gN[i]
-            if L.pool_after and L.relu:
+            rows = self.dYr[i]
+            if rows is not None and L.pool_after:
+                B.maxpool_backward_rows(g, self.A[i], self.P[i] if L.relu else None, Y.shape[-2], Y.shape[-1], 3, 2,
+                                        self.ceil_mode, dx_rows=rows, plane_sums=self.dYs[i], ld=self.rows_ld[i])
+            elif rows is not None:
+                B.relu_backward_rows(Y, g, dx_rows=rows, plane_sums=self.dYs[i], ld=self.rows_ld[i])
+            elif L.pool_after and L.relu:
                 B.maxpool_relu_backward(g, self.A[i], self.P[i], Y.shape[-2], Y.shape[-1], 3, 2, self.ceil_mode,
-                                        self.dYc[i])
+                                        self._dYd[i])
             elif L.pool_after:
-                B.maxpool_backward(g, self.A[i], Y.shape[-2], Y.shape[-1], 3, 2, self.ceil_mode, dx=self.dYc[i])
+                B.maxpool_backward(g, self.A[i], Y.shape[-2], Y.shape[-1], 3, 2, self.ceil_mode, dx=self._dYd[i])
             elif L.relu:
-                B.relu_backward(Y, g, self.dYc[i])
+                B.relu_backward(Y, g, self._dYd[i])
             else:
-                self.dYc[i] = g     # no layer between the convolution and the incoming gradient
+                self._dYd[i] = g     # no layer between the convolution and the incoming gradient
+
+            def model_gradient():
+                if rows is not None:
+                    B.conv_backward_weights_rows(self.desc_wgrad[i], self.X[i], rows, self.dYs[i], self.dW[i], self.db[i],
+                                                 self.ws_layer[i])
+                else:
+                    B.conv_backward_weights(self.desc_wgrad[i], self.X[i], self._dYd[i], self.dW[i], self.db[i],
+                                            self.ws_layer[i])
             if self.side is not None:
                 self.side.wait_stream(torch.cuda.current_stream())
                 with torch.cuda.stream(self.side):
-                    B.conv_backward_weights(self.desc_wgrad[i], self.X[i], self.dYc[i], self.dW[i], self.db[i],
-                                            self.ws_layer[i])
+                    model_gradient()
             else:
-                B.conv_backward_weights(self.desc_wgrad[i], self.X[i], self.dYc[i], self.dW[i], self.db[i],
-                                        self.ws_layer[i])
+                model_gradient()
             if self.dXl[i] is None:
                 g = None
                 break
-            if self.packed_bwd[i] is not None:
-                B.conv_backward_data_packed(self.desc[i], self.dYc[i], self.packed_bwd[i], self.dXl[i], self.ws_bwd)
+            if rows is not None:
+                B.conv_backward_data_rows(self.desc[i], rows, self.packed_bwd[i], self.dXl[i], self.ws_bwd)
+            elif self.packed_bwd[i] is not None:
+                B.conv_backward_data_packed(self.desc[i], self._dYd[i], self.packed_bwd[i], self.dXl[i], self.ws_bwd)
             else:
-                B.conv_backward_data(self.desc[i], self.dYc[i], self.Wc[i], self.dXl[i], self.ws_bwd)
+                B.conv_backward_data(self.desc[i], self._dYd[i], self.Wc[i], self.dXl[i], self.ws_bwd)
             g = self.dXl[i]
         if self.side is not None:
             torch.cuda.current_stream().wait_stream(self.side)

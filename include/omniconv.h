@@ -280,10 +280,19 @@ int omni_maxpool_relu_backward(int32_t dtype, int64_t planes, int32_t H, int32_t
  *       values) writing dx in the rows form of the [N][C][H][W] gradient, same plane_sums; bf16, 3 x 3 windows at
  *       stride 2 on planes of at most about 100 x 100, OMNI_UNSUPPORTED otherwise.
  *   omni_conv_backward_weights_rows: omni_conv_backward_weights reading dY_rows (not modified); dbias, if wanted, is
- *       the ordered sum of plane_sums over the images, so plane_sums must then be given.  dW is bit-identical to the
- *       plain entry point's.  Workspace as for OMNI_PASS_BACKWARD_WEIGHTS.
+ *       the ordered sum of the partial sums plane_sums [F][sums_per_filter] (any partition of a filter's row of
+ *       dY_rows into partial sums: the producers' N plane sums, or the column sums of the call below), which must
+ *       then be given.  dW is bit-identical to the plain entry point's.  Workspace as for OMNI_PASS_BACKWARD_WEIGHTS.
  *   omni_conv_backward_data_rows: omni_conv_backward_data_packed reading dY_rows; dX is bit-identical.  Workspace as
  *       for OMNI_PASS_BACKWARD_DATA.
+ *   omni_conv_backward_data_relu_rows: the same data gradient when the layer in front is convolution + ReLU with
+ *       nothing between: its result dX [N][C][H][W] IS that layer's output gradient once the ReLU's mask is applied,
+ *       so it is stored as dX_rows [C][ld_out] = rows form of (y_front > 0 ? dX : 0), y_front [N][C][H][W] (bf16)
+ *       being the front layer's output; ld_out a multiple of 8, >= N * (H*W rounded up to 8).  Only the planes'
+ *       H*W real columns are written: the round-up columns must be zero already (zero the buffer once).  col_sums
+ *       (nullable) is fp32 [C][sums_per_channel] and receives partial sums of every row's stored values
+ *       (sums_per_channel from omni_conv_backward_data_relu_rows_sums, host only; OMNI_UNSUPPORTED when this layer's
+ *       data gradient cannot store this way, e.g. at batches so small that its reduction is split).
  * Columns of dx_rows beyond N * plane_pitch are never written.  All pointers 16-byte aligned.
  */
 int omni_conv_dy_rows_layout(const omni_conv_desc *desc, int64_t *ld, int64_t *plane_pitch);
@@ -293,10 +302,14 @@ int omni_maxpool_backward_rows(int32_t dtype, int32_t N, int32_t C, int32_t H, i
                                int32_t ceil_mode, const void *dy, const uint8_t *argmax, const void *y, void *dx_rows,
                                int64_t ld, float *plane_sums, void *hip_stream);
 int omni_conv_backward_weights_rows(const omni_conv_desc *desc, const void *X, const void *dY_rows,
-                                    const float *plane_sums, float *dW, float *dbias, void *workspace,
-                                    size_t workspace_bytes, void *hip_stream);
+                                    const float *plane_sums, int32_t sums_per_filter, float *dW, float *dbias,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
 int omni_conv_backward_data_rows(const omni_conv_desc *desc, const void *dY_rows, const void *packed, void *dX,
                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+int omni_conv_backward_data_relu_rows_sums(const omni_conv_desc *desc, int32_t *sums_per_channel);
+int omni_conv_backward_data_relu_rows(const omni_conv_desc *desc, const void *dY_rows, const void *packed,
+                                      const void *y_front, void *dX_rows, int64_t ld_out, float *col_sums,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Normalisation across channels and dropout: the other two non-GEMM layers of the paper's CaffeNet runs (App. C,

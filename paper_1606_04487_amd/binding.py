@@ -34,7 +34,7 @@ SYMBOLS = [
     "omni_col2im", "omni_relu_forward", "omni_relu_backward", "omni_pool_output_dim",
     "omni_maxpool_forward", "omni_maxpool_backward", "omni_maxpool_relu_backward",
     "omni_conv_dy_rows_layout", "omni_relu_backward_rows", "omni_maxpool_backward_rows", "omni_conv_backward_weights_rows",
-    "omni_conv_backward_data_rows",
+    "omni_conv_backward_data_rows", "omni_conv_backward_data_relu_rows_sums", "omni_conv_backward_data_relu_rows",
     "omni_lrn_forward", "omni_lrn_backward", "omni_dropout_forward", "omni_dropout_backward", "omni_status_string", "omni_version", "omni_tuning_set",
     "omni_profile_enable", "omni_profile_select", "omni_profile_select_mask", "omni_profile_kernel_count", "omni_profile_kernel_name", "omni_profile_summary",
 ]
@@ -80,7 +80,9 @@ _lib.omni_conv_backward_data_packed.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _v
 _lib.omni_conv_dy_rows_layout.argtypes = [_dp, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
 _lib.omni_relu_backward_rows.argtypes = [_i32, _i32, _i32, _i64, _vp, _vp, _vp, _i64, _vp, _vp]
 _lib.omni_maxpool_backward_rows.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i64, _vp, _vp]
-_lib.omni_conv_backward_weights_rows.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.omni_conv_backward_weights_rows.argtypes = [_dp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
+_lib.omni_conv_backward_data_relu_rows_sums.argtypes = [_dp, ctypes.POINTER(_i32)]
+_lib.omni_conv_backward_data_relu_rows.argtypes = [_dp, _vp, _vp, _vp, _vp, _i64, _vp, _vp, _sz, _vp]
 _lib.omni_conv_backward_data_rows.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.omni_sgd_momentum_step.argtypes = [_i32, _vp, _vp, _vp, _vp, _vp, ctypes.c_float, ctypes.c_float,
                                         ctypes.c_float, _vp]
@@ -441,14 +443,16 @@ def maxpool_backward_rows(dy, argmax, y_pooled, H: int, W: int, k: int = 3, stri
 
 
 def conv_backward_weights_rows(desc: ConvDesc, X, dY_rows, plane_sums, dW=None, dbias=None, workspace=None, want_dbias=True):
-    """omni_conv_backward_weights_rows: omni_conv_backward_weights reading dY in its rows form."""
+    """omni_conv_backward_weights_rows: omni_conv_backward_weights reading dY in its rows form; plane_sums [F][any] are
+    partial sums of every filter's row (for the bias gradient)."""
     if dW is None:
         dW = torch.empty((desc.F, desc.C, desc.kh, desc.kw), dtype=torch.float32, device=X.device)
     if dbias is None and want_dbias:
         dbias = torch.empty((desc.F,), dtype=torch.float32, device=X.device)
     if workspace is None:
         workspace = alloc_workspace(desc, PASS_BACKWARD_WEIGHTS, X.device)
-    _check(_lib.omni_conv_backward_weights_rows(ctypes.byref(desc), _p(X), _p(dY_rows), _p(plane_sums), _p(dW), _p(dbias),
+    per = plane_sums.shape[1] if plane_sums is not None else 0
+    _check(_lib.omni_conv_backward_weights_rows(ctypes.byref(desc), _p(X), _p(dY_rows), _p(plane_sums), per, _p(dW), _p(dbias),
                                                 _p(workspace), workspace.numel(), _stream()))
     return dW, dbias
 
@@ -462,6 +466,35 @@ def conv_backward_data_rows(desc: ConvDesc, dY_rows, packed, dX=None, workspace=
     _check(_lib.omni_conv_backward_data_rows(ctypes.byref(desc), _p(dY_rows), _p(packed), _p(dX), _p(workspace),
                                              workspace.numel(), _stream()))
     return dX
+
+
+def conv_backward_data_relu_rows_sums(desc: ConvDesc):
+    """omni_conv_backward_data_relu_rows_sums: partial sums per channel that conv_backward_data_relu_rows writes, or
+    None when this layer's data gradient cannot store the masked rows form."""
+    n = _i32(0)
+    st = _lib.omni_conv_backward_data_relu_rows_sums(ctypes.byref(desc), ctypes.byref(n))
+    if st == -2:
+        return None
+    _check(st)
+    return n.value
+
+
+def conv_backward_data_relu_rows(desc: ConvDesc, dY_rows, packed, y_front, dX_rows=None, col_sums=None, ld_out=None,
+                                 workspace=None, want_sums=True):
+    """omni_conv_backward_data_relu_rows: the data gradient stored as the rows form of (y_front > 0 ? dX : 0), the
+    output gradient of the convolution + ReLU layer in front; returns (dX_rows [C][ld_out], col_sums)."""
+    pitch = (desc.H * desc.W + 7) // 8 * 8
+    if ld_out is None:
+        ld_out = desc.N * pitch
+    if dX_rows is None:
+        dX_rows = torch.zeros((desc.C, ld_out), dtype=torch.bfloat16, device=dY_rows.device)
+    if col_sums is None and want_sums:
+        col_sums = torch.empty((desc.C, conv_backward_data_relu_rows_sums(desc)), dtype=torch.float32, device=dY_rows.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, PASS_BACKWARD_DATA, dY_rows.device)
+    _check(_lib.omni_conv_backward_data_relu_rows(ctypes.byref(desc), _p(dY_rows), _p(packed), _p(y_front), _p(dX_rows), ld_out,
+                                                  _p(col_sums), _p(workspace), workspace.numel(), _stream()))
+    return dX_rows, col_sums
 
 
 def lrn_forward(x, size: int = 5, alpha: float = 1e-4, beta: float = 0.75, k: float = 1.0, y=None, scale=None,

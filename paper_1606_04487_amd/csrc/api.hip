@@ -652,12 +652,14 @@ int omni_conv_dy_rows_layout(const omni_conv_desc *desc, int64_t *ld, int64_t *p
 }
 
 int omni_conv_backward_weights_rows(const omni_conv_desc *desc, const void *X, const void *dY_rows, const float *plane_sums,
-                                    float *dW, float *dbias, void *workspace, size_t workspace_bytes, void *hip_stream)
+                                    int32_t sums_per_filter, float *dW, float *dbias, void *workspace, size_t workspace_bytes,
+                                    void *hip_stream)
 {
     ConvGeom g;
     int st = make_geom(desc, &g);
     if (st != OMNI_OK) return st;
-    if (X == nullptr || dY_rows == nullptr || dW == nullptr || workspace == nullptr || (dbias != nullptr && plane_sums == nullptr))
+    if (X == nullptr || dY_rows == nullptr || dW == nullptr || workspace == nullptr ||
+        (dbias != nullptr && (plane_sums == nullptr || sums_per_filter <= 0)))
         return OMNI_INVALID_ARGUMENT;
     if (!aligned16(X) || !aligned16(dY_rows) || !aligned16(dW) || !aligned16(workspace) || (dbias && !aligned16(dbias)) ||
         (plane_sums && !aligned16(plane_sums)))
@@ -672,30 +674,72 @@ int omni_conv_backward_weights_rows(const omni_conv_desc *desc, const void *X, c
     if (w.splits_patch > 0) {
         st = launch_wgrad_patch(g, X, dY_rows, ld, partials, w.splits_patch, s);
         if (st != OMNI_OK) return st;
-        return launch_wgrad_reduce(g, partials, w.splits_patch, dW, plane_sums, g.N, dbias, s);
+        return launch_wgrad_reduce(g, partials, w.splits_patch, dW, plane_sums, sums_per_filter, dbias, s);
     }
-    return launch_wgrad_wide(g, X, dY_rows, ld, partials, w.splits_wide, dW, plane_sums, g.N, dbias, s);
+    return launch_wgrad_wide(g, X, dY_rows, ld, partials, w.splits_wide, dW, plane_sums, sums_per_filter, dbias, s);
+}
+
+// the rows forms of both ends of a data gradient: checks shared by the two entry points below
+static int backward_data_rows_checks(const omni_conv_desc *desc, ConvGeom *g, int64_t *ld, size_t workspace_bytes)
+{
+    int st = make_geom(desc, g);
+    if (st != OMNI_OK) return st;
+    size_t pbytes;
+    if (!packed_weights_job(desc, *g, OMNI_PASS_BACKWARD_DATA, nullptr, nullptr, nullptr, &pbytes)) return OMNI_UNSUPPORTED;
+    BwdWeightsWs ww;
+    plan_backward_weights(*g, desc->dtype, &ww);
+    int64_t pitch;
+    if (!dy_rows_layout(desc, *g, ww, ld, &pitch)) return OMNI_UNSUPPORTED;
+    BwdDataWs w;
+    plan_backward_data(*g, desc->dtype, &w);
+    if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
+    if (fused_weight_bytes(*g, true) > w.total) return OMNI_UNSUPPORTED;
+    return OMNI_OK;
 }
 
 int omni_conv_backward_data_rows(const omni_conv_desc *desc, const void *dY_rows, const void *packed, void *dX, void *workspace,
                                  size_t workspace_bytes, void *hip_stream)
 {
-    ConvGeom g;
-    int st = make_geom(desc, &g);
-    if (st != OMNI_OK) return st;
     if (dY_rows == nullptr || packed == nullptr || dX == nullptr || workspace == nullptr) return OMNI_INVALID_ARGUMENT;
     if (!aligned16(dY_rows) || !aligned16(packed) || !aligned16(dX) || !aligned16(workspace)) return OMNI_MISALIGNED;
-    size_t pbytes;
-    if (!packed_weights_job(desc, g, OMNI_PASS_BACKWARD_DATA, nullptr, nullptr, nullptr, &pbytes)) return OMNI_UNSUPPORTED;
-    BwdWeightsWs ww;
-    plan_backward_weights(g, desc->dtype, &ww);
-    int64_t ld, pitch;
-    if (!dy_rows_layout(desc, g, ww, &ld, &pitch)) return OMNI_UNSUPPORTED;
-    BwdDataWs w;
-    plan_backward_data(g, desc->dtype, &w);
-    if (workspace_bytes < w.total) return OMNI_WORKSPACE_TOO_SMALL;
-    if (fused_weight_bytes(g, true) > w.total) return OMNI_UNSUPPORTED;
-    return launch_fused_conv(g, true, dY_rows, nullptr, nullptr, 0, dX, workspace, (hipStream_t)hip_stream, -1, packed, ld);
+    ConvGeom g;
+    int64_t ld;
+    int st = backward_data_rows_checks(desc, &g, &ld, workspace_bytes);
+    if (st != OMNI_OK) return st;
+    FusedIO io{ld, nullptr, 0, nullptr};
+    return launch_fused_conv(g, true, dY_rows, nullptr, nullptr, 0, dX, workspace, (hipStream_t)hip_stream, -1, packed, &io);
+}
+
+int omni_conv_backward_data_relu_rows_sums(const omni_conv_desc *desc, int32_t *sums_per_channel)
+{
+    if (sums_per_channel == nullptr) return OMNI_INVALID_ARGUMENT;
+    ConvGeom g;
+    int64_t ld;
+    int st = backward_data_rows_checks(desc, &g, &ld, (size_t)-1);
+    if (st != OMNI_OK) return st;
+    const int tiles = fused_column_tiles(g, true);
+    if (tiles <= 0) return OMNI_UNSUPPORTED;
+    *sums_per_channel = tiles;
+    return OMNI_OK;
+}
+
+int omni_conv_backward_data_relu_rows(const omni_conv_desc *desc, const void *dY_rows, const void *packed, const void *y_front,
+                                      void *dX_rows, int64_t ld_out, float *col_sums, void *workspace, size_t workspace_bytes,
+                                      void *hip_stream)
+{
+    if (dY_rows == nullptr || packed == nullptr || y_front == nullptr || dX_rows == nullptr || workspace == nullptr)
+        return OMNI_INVALID_ARGUMENT;
+    if (!aligned16(dY_rows) || !aligned16(packed) || !aligned16(y_front) || !aligned16(dX_rows) || !aligned16(workspace) ||
+        (col_sums && !aligned16(col_sums)))
+        return OMNI_MISALIGNED;
+    ConvGeom g;
+    int64_t ld;
+    int st = backward_data_rows_checks(desc, &g, &ld, workspace_bytes);
+    if (st != OMNI_OK) return st;
+    if (fused_column_tiles(g, true) <= 0) return OMNI_UNSUPPORTED;
+    if (ld_out % 8 != 0 || ld_out < (int64_t)g.N * (((int64_t)g.H * g.W + 7) / 8 * 8)) return OMNI_INVALID_ARGUMENT;
+    FusedIO io{ld, y_front, ld_out, col_sums};
+    return launch_fused_conv(g, true, dY_rows, nullptr, nullptr, 0, dX_rows, workspace, (hipStream_t)hip_stream, -1, packed, &io);
 }
 
 int omni_sgd_momentum_step(int32_t n_tensors, float *const *W, float *const *V, const float *const *G,

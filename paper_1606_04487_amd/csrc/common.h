@@ -173,11 +173,16 @@ void gemm_split_tile(int rows, int cols, int *bm, int *bn);  // tile of a split 
 // repacked weights (fused_weight_bytes).
 bool fused_supported(const ConvGeom &g, int dtype, bool data_gradient);
 size_t fused_weight_bytes(const ConvGeom &g, bool data_gradient);
-// kid: kernel class the launch is timed under (-1: by data_gradient); in_ld > 0: the input is given in its rows
-// form [C][in_ld] (plane of image n at column n * (plane rounded up to 8)) instead of the dense tensor
+// Optional forms of the fused kernel's operands: in_ld > 0 = the input is given in its rows form [C][in_ld] (plane of
+// image n at column n * (plane rounded up to 8)) instead of the dense tensor; mask != null = the output goes out in
+// the rows form as well (leading dimension out_ld), zero where the dense tensor mask [N][F][Ho][Wo] is not positive,
+// and col_sums [F][fused_column_tiles] (nullable) receives the sums of what every column tile stored per row.
+struct FusedIO { int64_t in_ld; const void *mask; int64_t out_ld; float *col_sums; };
+int fused_column_tiles(const ConvGeom &g, bool data_gradient);  // 0: not fused, or the reduction is split
+// kid: kernel class the launch is timed under (-1: by data_gradient)
 int launch_fused_conv(const ConvGeom &g, bool data_gradient, const void *X, const void *W, const float *bias,
                       int relu, void *Y, void *wt_scratch, hipStream_t s, int kid = -1, const void *prepacked = nullptr,
-                      int64_t in_ld = 0);
+                      const FusedIO *io = nullptr);
 
 // strided.hip: the forward convolution of a layer with horizontal stride 4, no padding, at most 96 filters and
 // a short reduction (CaffeNet's conv1) without D-hat; bf16.  wt_scratch receives the repacked weights.

@@ -348,8 +348,23 @@ __global__ __launch_bounds__(NT) void fused_conv_kernel(const bf16_t *__restrict
     // every wavefront is past the loop's last barrier: the weight tiles become staging space
     constexpr int STRIP = 16 * staged_pitch(TJ);
     static_assert((NT / 64) * STRIP <= (int)sizeof(atile), "staging strips fit in the weight tiles");
-    store_tile_staged<TI, TJ, 16>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, z, epi,
-                                  reinterpret_cast<char *>(atile) + wave * STRIP, lds_add, row0);
+    if constexpr (epilogue_is_masked<Epi>::value) {
+        // the patch is free as well: [BM][WN] sums of what each wavefront stored per row, added in wavefront order
+        float *wave_sums = reinterpret_cast<float *>(patch);
+        static_assert(BM * WN * 4 <= (int)sizeof(patch), "row sums fit in the patch");
+        store_tile_staged<TI, TJ, 16>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, z, epi,
+                                      reinterpret_cast<char *>(atile) + wave * STRIP, lds_add, row0, wave_sums, WN, wn);
+        __syncthreads();
+        if (epi.sums != nullptr && tid < BM && row0 + tid < g.F) {
+            float total = 0.f;
+#pragma unroll
+            for (int w = 0; w < WN; ++w) total += wave_sums[tid * WN + w];
+            epi.sums[(int64_t)(row0 + tid) * g.tiles_m + tm] = total;
+        }
+    } else {
+        store_tile_staged<TI, TJ, 16>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, z, epi,
+                                      reinterpret_cast<char *>(atile) + wave * STRIP, lds_add, row0);
+    }
 }
 
 // Weights [out][in][kh][kw] (forward) or [in][out][kh][kw] read flipped (data gradient) -> the kernel's
@@ -541,15 +556,30 @@ int launch_pack_jobs(const PackJobTable &t, hipStream_t s)
     return OMNI_OK;
 }
 
+int fused_column_tiles(const ConvGeom &c, bool data_gradient)
+{
+    fused::Geom g;
+    if (!fused::make_fused_geom(c, data_gradient, &g) || g.splits > 1) return 0;
+    return g.tiles_m;
+}
+
 // `prepacked` != null: the repacked weights already exist there (fused_pack_job) and W is not read.
-// in_ld > 0: the input is not the dense tensor but its rows form, a matrix [C][in_ld] with image n's plane of
-// channel c at column n * (the plane rounded up to 8 elements).
+// io (optional): in_ld > 0 = the input is not the dense tensor but its rows form, a matrix [C][in_ld] with image n's
+// plane of channel c at column n * (the plane rounded up to 8 elements); mask != null = the output is written in
+// the rows form too (leading dimension out_ld), zero where the dense tensor `mask` [N][F][Ho][Wo] is not positive,
+// with col_sums [F][fused_column_tiles] (nullable) receiving every column tile's sums of the stored values.
 int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, const void *W, const float *bias,
-                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid, const void *prepacked, int64_t in_ld)
+                      int relu, void *Y, void *wt_scratch, hipStream_t s, int kid, const void *prepacked, const FusedIO *io)
 {
     using namespace fused;
     Geom g;
     if (!make_fused_geom(c, data_gradient, &g)) return OMNI_UNSUPPORTED;
+    const int64_t in_ld = io != nullptr ? io->in_ld : 0;
+    const bool masked = io != nullptr && io->mask != nullptr;
+    const int64_t out_pitch = ((int64_t)g.HoWo + 7) / 8 * 8;
+    if (masked && (in_ld <= 0 || g.splits > 1 || bias != nullptr || relu || io->out_ld < g.N * out_pitch ||
+                   (double)io->out_ld * g.F * 2.0 >= 4.0e9))
+        return OMNI_UNSUPPORTED;
     if (in_ld > 0) {
         const int64_t pitch = ((int64_t)g.HW + 7) / 8 * 8;
         if (in_ld < g.N * pitch || (double)in_ld * g.C * 2.0 >= 4.0e9) return OMNI_UNSUPPORTED;
@@ -568,6 +598,8 @@ int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, cons
     dim3 grid((unsigned)(g.per_xcd * 8)), block(NT);
     float *partials = reinterpret_cast<float *>(reinterpret_cast<char *>(wt_scratch) + fused_packed_bytes(g));
     PartialEpilogue pe{partials, g.F, g.M};
+    RowsMaskEpilogue me{(bf16_t *)Y, masked ? (const bf16_t *)io->mask : nullptr, masked ? io->col_sums : nullptr, g.F, g.M, g.HoWo,
+                        g.div_HoWo, (uint32_t)out_pitch, masked ? (uint32_t)io->out_ld : 0u};
 #define OMNI_FUSED_LAUNCH_IN(BM_, WM_, WN_, BN_, PATCH_, RIN_)                                                               \
     do {                                                                                                                    \
         if (g.splits > 1)                                                                                                   \
@@ -579,7 +611,10 @@ int launch_fused_conv(const ConvGeom &c, bool data_gradient, const void *X, cons
     } while (0)
 #define OMNI_FUSED_LAUNCH(BM_, WM_, WN_, BN_, PATCH_)                                                                       \
     do {                                                                                                                    \
-        if (in_ld > 0) OMNI_FUSED_LAUNCH_IN(BM_, WM_, WN_, BN_, PATCH_, true);                                              \
+        if (masked)                                                                                                         \
+            hipLaunchKernelGGL((fused_conv_kernel<BM_, WM_, WN_, BN_, PATCH_, RowsMaskEpilogue, true>), grid, block, 0, s,   \
+                               (const bf16_t *)X, wt, g, me);                                                               \
+        else if (in_ld > 0) OMNI_FUSED_LAUNCH_IN(BM_, WM_, WN_, BN_, PATCH_, true);                                         \
         else OMNI_FUSED_LAUNCH_IN(BM_, WM_, WN_, BN_, PATCH_, false);                                                       \
     } while (0)
     if (g.bm == 96) OMNI_FUSED_LAUNCH(96, 1, 8, BN_WIDE, PATCH_WIDE);

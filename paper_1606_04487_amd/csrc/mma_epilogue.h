@@ -88,6 +88,49 @@ template <typename T> struct FwdEpilogue {
     bool fits32() const { return (double)M * F * sizeof(T) < 4.0e9; }
 };
 
+// data gradient handed to the layer in front in the form its model gradient multiplies: i = channel c, j = column
+// m = (n, pixel); element (i, j) goes to out[i * ld + n * pitch + pixel] (the rows matrix) if mask[n][i][pixel] > 0
+// (the ReLU of that layer, mask = its dense output [N][F][HoWo]), else zero goes there.
+struct RowsMaskEpilogue {
+    bf16_t *out;
+    const bf16_t *mask;
+    float *sums;  // [F][column tiles]: sum of what each column tile stored per row (nullable)
+    int F, M, HoWo;
+    FastDiv div_HoWo;
+    uint32_t pitch, ld;
+    typedef bf16_t Out;
+    static constexpr bool MASKED = true;
+    static constexpr bool HAS_ROW_ADD = false;
+    __device__ __forceinline__ float row_add(int) const { return 0.f; }
+    __device__ __forceinline__ char *base32(int) const { return reinterpret_cast<char *>(out); }
+    __device__ __forceinline__ uint32_t row_stride32() const { return ld * 2u; }
+    __device__ __forceinline__ int n_rows() const { return F; }
+    __device__ __forceinline__ uint32_t col_off32(int j, bool &ok) const
+    {
+        ok = j < M;
+        uint32_t n, r;
+        div_HoWo.divmod(ok ? (uint32_t)j : 0u, n, r);
+        return (n * pitch + r) * 2u;
+    }
+    __device__ __forceinline__ const char *mask_base() const { return reinterpret_cast<const char *>(mask); }
+    __device__ __forceinline__ uint32_t mask_row_stride32() const { return (uint32_t)HoWo * 2u; }
+    __device__ __forceinline__ uint32_t mask_col_off32(int j, bool &ok) const
+    {
+        ok = j < M;
+        uint32_t n, r;
+        div_HoWo.divmod(ok ? (uint32_t)j : 0u, n, r);
+        return (n * (uint32_t)F * (uint32_t)HoWo + r) * 2u;
+    }
+    // columns from j to the end of j's image (j < M)
+    __device__ __forceinline__ int columns_left_in_image(int j) const
+    {
+        uint32_t n, r;
+        div_HoWo.divmod((uint32_t)j, n, r);
+        return HoWo - (int)r;
+    }
+    __device__ __forceinline__ float apply(float v, float) const { return v; }
+};
+
 // dgrad: i = row k of dD-hat, j = column m; row-major with leading dimension ld.
 template <typename T> struct RowMajorEpilogue {
     T *out;
@@ -185,10 +228,18 @@ __device__ __forceinline__ void store_tile32(f32x16 (&acc)[TI][TJ], int i_wave, 
 // The pitch makes the two half-waves (rows r and r + 4) land 32 banks apart.
 constexpr int staged_pitch(int TJ) { return 32 * TJ * 4 + 32; }
 
+// An epilogue with Epi::MASKED (RowsMaskEpilogue) also zeroes every result whose entry in a second tensor is not
+// positive and leaves, in wave_sums[(row - i_tile) * wave_cols + wave_col], the sum of the values this wavefront
+// stored to that row (as rounded; fixed order: per 16-byte piece, then the row's pieces left to right).
+template <typename Epi, typename = void> struct epilogue_is_masked : std::false_type {};
+template <typename Epi> struct epilogue_is_masked<Epi, std::enable_if_t<Epi::MASKED>> : std::true_type {};
+
 template <int TI, int TJ, int SR, typename Epi>
 __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][TJ], int i_wave, int j_wave, int lane, int z,
-                                                  const Epi &epi, char *strip, const float *row_add, int i_tile)
+                                                  const Epi &epi, char *strip, const float *row_add, int i_tile,
+                                                  float *wave_sums = nullptr, int wave_cols = 1, int wave_col = 0)
 {
+    constexpr bool MASKED = epilogue_is_masked<Epi>::value;
     typedef typename Epi::Out Out;
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -211,6 +262,43 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][TJ], int i_w
     const uint32_t off_first = epi.col_off32(j_wave + cg * VEC, ok_first);
     const uint32_t off_last = epi.col_off32(j_wave + cg * VEC + VEC - 1, ok_last);
     const bool whole = ok_first && ok_last && off_last - off_first == (uint32_t)((VEC - 1) * sizeof(Out));
+    // MASKED: the mask entries of a piece are fetched as 16 bytes starting at its first column; a piece that runs
+    // from image n into image n + 1 (its first `mk_first` columns in n) takes a second fetch that ends where the
+    // piece ends, and picks per element.  Both stay inside the mask tensor because all the piece's columns exist;
+    // a piece with columns past the end (last column tile only) reads its mask element by element instead.
+    uint32_t moff_first = 0, moff_second = 0, mrs = 0;
+    int mk_first = VEC;
+    bool mask_vec = false;
+    const char *mbase = nullptr;
+    if constexpr (MASKED) {
+        static_assert(sizeof(Out) == 2, "masked stores are bf16");
+        bool ok;
+        moff_first = epi.mask_col_off32(j_wave + cg * VEC, ok);
+        mrs = epi.mask_row_stride32();
+        mbase = epi.mask_base();
+        mask_vec = ok_first && ok_last;
+        if (mask_vec && !whole) {
+            mk_first = epi.columns_left_in_image(j_wave + cg * VEC);  // 1 .. VEC - 1 here
+            moff_second = epi.mask_col_off32(j_wave + cg * VEC + mk_first, ok) - (uint32_t)(mk_first * 2);
+        }
+    }
+    // MASKED: the mask fetches of a group of passes (one strip) go out one group ahead, so that their latency passes
+    // under the previous group's work; two sets of registers take turns
+    u32x4 mask_a[2][MASKED ? PASSES : 1], mask_b[2][MASKED ? PASSES : 1];
+    auto fetch_masks = [&](int gi, u32x4 *ma, u32x4 *mb) {
+        if constexpr (MASKED) {
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                const int r = p * RPP + rr;
+                const int i = i_wave + gi * SR + r;   // gi * SR = t * 32 + half * SR
+                ma[p] = mb[p] = u32x4{0, 0, 0, 0};
+                if ((!EXACT && (rr >= RPP || r >= SR)) || i >= rows || !mask_vec) continue;
+                __builtin_memcpy(&ma[p], mbase + ((uint32_t)i * mrs + moff_first), 16);
+                if (!whole) __builtin_memcpy(&mb[p], mbase + ((uint32_t)i * mrs + moff_second), 16);
+            }
+        }
+    };
+    fetch_masks(0, mask_a[0], mask_b[0]);
 #pragma unroll
     for (int t = 0; t < TI; ++t) {
 #pragma unroll
@@ -222,6 +310,10 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][TJ], int i_w
                 float *row = reinterpret_cast<float *>(strip + r * PITCH);
 #pragma unroll
                 for (int u = 0; u < TJ; ++u) row[u * 32 + li] = acc[t][u][v];
+            }
+            if constexpr (MASKED) {
+                const int gi = t * (32 / SR) + half;          // compile-time after unrolling
+                if (gi + 1 < TI * (32 / SR)) fetch_masks(gi + 1, mask_a[(gi + 1) & 1], mask_b[(gi + 1) & 1]);
             }
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -239,7 +331,19 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][TJ], int i_w
                 if constexpr (Epi::HAS_ROW_ADD) add = row_add[i - i_tile];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) x[e] = epi.apply(x[e], add);
+                float stored = 0.f;  // MASKED: sum of this piece's stored values
                 if (i < rows) {
+                    if constexpr (MASKED) {
+                        if (mask_vec) {
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e) {
+                                const int cur = (t * (32 / SR) + half) & 1;
+                                const uint32_t word = e < mk_first ? mask_a[cur][p][e / 2] : mask_b[cur][p][e / 2];
+                                const uint32_t bits = (e & 1) ? (word & 0xffff0000u) : (word << 16);
+                                x[e] = __uint_as_float(bits) > 0.f ? x[e] : 0.f;
+                            }
+                        }
+                    }
                     if (whole) {
                         u32x4 piece;
                         if constexpr (sizeof(Out) == 4)
@@ -248,14 +352,47 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[TI][TJ], int i_w
                             piece = u32x4{f32x2_to_bf16x2(x[0], x[1]), f32x2_to_bf16x2(x[2], x[3]),
                                           f32x2_to_bf16x2(x[4], x[5]), f32x2_to_bf16x2(x[6], x[7])};
                         __builtin_memcpy(base + ((uint32_t)i * rs + off_first), &piece, 16);  // element-aligned 16-byte store
+                        if constexpr (MASKED) {
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e)
+                                stored += __uint_as_float((e & 1) ? (piece[e / 2] & 0xffff0000u) : (piece[e / 2] << 16));
+                        }
                     } else {
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) {
                             bool ok;
                             uint32_t off = epi.col_off32(j_wave + cg * VEC + e, ok);
-                            if (ok) *reinterpret_cast<Out *>(base + ((uint32_t)i * rs + off)) = Elem<Out>::from_f32(x[e]);
+                            if constexpr (MASKED) {
+                                if (ok) {
+                                    float xv = x[e];  // masked above unless the piece has columns past the end
+                                    if (!mask_vec) {
+                                        bool mok;
+                                        const uint32_t moff = epi.mask_col_off32(j_wave + cg * VEC + e, mok);
+                                        const bf16_t mbits = *reinterpret_cast<const bf16_t *>(mbase + ((uint32_t)i * mrs + moff));
+                                        xv = bf16_to_f32(mbits) > 0.f ? xv : 0.f;
+                                    }
+                                    const Out o = Elem<Out>::from_f32(xv);
+                                    *reinterpret_cast<Out *>(base + ((uint32_t)i * rs + off)) = o;
+                                    stored += Elem<Out>::to_f32(o);
+                                }
+                            } else {
+                                if (ok) *reinterpret_cast<Out *>(base + ((uint32_t)i * rs + off)) = Elem<Out>::from_f32(x[e]);
+                            }
                         }
                     }
+                }
+                // the row's raw results have been read by all its lanes (same instructions, LDS in order): its
+                // first floats now hold the pieces' sums
+                if constexpr (MASKED) reinterpret_cast<float *>(strip + r * PITCH)[cg] = stored;
+            }
+            if constexpr (MASKED) {
+                __builtin_amdgcn_wave_barrier();
+                if (lane < SR) {
+                    const float *ps = reinterpret_cast<const float *>(strip + lane * PITCH);
+                    float acc_row = 0.f;
+#pragma unroll
+                    for (int c = 0; c < GPR; ++c) acc_row += ps[c];
+                    wave_sums[(i_wave + t * 32 + half * SR + lane - i_tile) * wave_cols + wave_col] = acc_row;
                 }
             }
             __builtin_amdgcn_wave_barrier();

@@ -23,7 +23,8 @@ from .workloads import ConvLayer
 class ConvStack:
     def __init__(self, layers: Sequence[ConvLayer], dtype: int = B.F32, ceil_mode: bool = True,
                  skip_first_dgrad: bool = True, device: str = "cuda", fused: bool = True,
-                 overlap_wgrad: bool = False, dy_rows: bool = True):
+                 overlap_wgrad: bool = False, dy_rows: bool = True,
+                 fuse_relu_dgrad: bool = True):
         self.layers = list(layers)
         self.dtype = dtype
         self.tdtype = B.torch_dtype(dtype)
@@ -107,6 +108,21 @@ class ConvStack:
             self.Dr.append(torch.empty_like(out) if L.dropout_after > 0 else None)
             self.gD.append(torch.empty_like(out) if L.dropout_after > 0 else None)
             self.dXl.append(torch.empty((L.N, L.C, L.H, L.W), dtype=self.tdtype, device=device) if need_dx else None)
+        # A convolution + ReLU layer directly in front of another rows-form layer: that layer's data gradient applies
+        # the ReLU's mask and stores the result as this layer's rows matrix itself (with partial sums per column
+        # tile instead of per plane), so neither a dense dX nor a separate ReLU backward pass exists for the pair.
+        self.fused_front = [False] * len(self.layers)
+        for i in range(len(self.layers) - 1):
+            L = self.layers[i]
+            if not (fuse_relu_dgrad and self.dYr[i] is not None and self.dYr[i + 1] is not None and L.relu
+                    and not L.pool_after and not L.lrn_after and L.dropout_after == 0):
+                continue
+            per = B.conv_backward_data_relu_rows_sums(self.desc[i + 1])
+            if per is None:
+                continue
+            self.fused_front[i] = True
+            self.dYs[i] = torch.empty((L.F, per), dtype=torch.float32, device=device)
+            self.dXl[i + 1] = None
 
     @property
     def dYc(self) -> List[torch.Tensor]:
@@ -178,7 +194,9 @@ class ConvStack:
                 B.lrn_backward(self.P[i] if L.pool_after else Y, g, self.Sc[i], *self.LRN, dx=self.gN[i])
                 g = self.gN[i]
             rows = self.dYr[i]
-            if rows is not None and L.pool_after:
+            if self.fused_front[i]:
+                pass                 # written by the data gradient of the layer behind
+            elif rows is not None and L.pool_after:
                 B.maxpool_backward_rows(g, self.A[i], self.P[i] if L.relu else None, Y.shape[-2], Y.shape[-1], 3, 2,
                                         self.ceil_mode, dx_rows=rows, plane_sums=self.dYs[i], ld=self.rows_ld[i])
             elif rows is not None:
@@ -206,6 +224,11 @@ class ConvStack:
                     model_gradient()
             else:
                 model_gradient()
+            if i > 0 and self.fused_front[i - 1]:
+                B.conv_backward_data_relu_rows(self.desc[i], rows, self.packed_bwd[i], self.Y[i - 1], dX_rows=self.dYr[i - 1],
+                                               col_sums=self.dYs[i - 1], ld_out=self.rows_ld[i - 1], workspace=self.ws_bwd)
+                g = None
+                continue
             if self.dXl[i] is None:
                 g = None
                 break

@@ -193,7 +193,7 @@ def run_stack(B, layers, dtype, ceil_mode, x_dist, seed, skip_first_dgrad, lr=0.
          "X": [host32(x) for x in st.X], "Wc": [host32(w) for w in st.Wc], "Y": [host32(y) for y in st.Y],
          "P": [None if p is None else host32(p) for p in st.P], "dYc": [host32(g) for g in st.dYc],
          "dW": [host32(g) for g in st.dW], "db": [host32(g) for g in st.db],
-         "dX": [None if g is None else host32(g) for g in st.dXl],
+         "dX": [None if g is None else host32(g) for g in st.dXl], "fused_front": list(st.fused_front),
          "W0": [host32(w) for w in st.W], "b0": [host32(b) for b in st.b]}
     st.sgd_step(lr, mu)
     torch.cuda.synchronize()
@@ -211,7 +211,10 @@ def check_stack_layer(r, i, whole, rng=None):
     L, s, tol, rounded = layers[i], oshape(layers[i]), TOL[dtype], dtype == 1
     Xi, Wi, bi, Yg, Gg = r["X"][i], r["Wc"][i], r["bias"][i], r["Y"][i], r["dYc"][i]
     aX, aW, ab, aG = np.abs(Xi), np.abs(Wi), np.abs(bi), np.abs(Gg)
-    g_in = r["dOut"] if i == len(layers) - 1 else r["dX"][i + 1]
+    # fused_front[i]: this layer's dY came straight out of the data gradient of the layer behind (no dense dX
+    # exists); that pair is checked with layer i + 1
+    fused_front = r["fused_front"][i]
+    g_in = r["dOut"] if i == len(layers) - 1 else (None if fused_front else r["dX"][i + 1])
     tag = f"stack {L.name} N={L.N} {'bf16' if dtype else 'fp32'}"
     rng = rng or np.random.default_rng(1000 + i)
     if whole:
@@ -226,14 +229,15 @@ def check_stack_layer(r, i, whole, rng=None):
         assert np.array_equal(r["P"][i].astype(np.float64), Pref), ("pool", L.name)
         dYr = oracle.maxpool_backward(g_in, Aref, L.Ho, L.Wo)
         dYa = oracle.maxpool_backward(np.abs(g_in), Aref, L.Ho, L.Wo)
-    else:
+    elif not fused_front:
         dYr = g_in.astype(np.float64)
         dYa = np.abs(dYr)
     # each pixel sums the gradients of the (at most four) windows it won: fp32 on the GPU, rounded once on store;
     # elementwise against the sum of the absolute terms
     mask = oracle.relu_backward(Yg, np.ones_like(Yg))
     tol_g = 1e-6 if dtype == 0 else 2.0 ** -8
-    assert np.all(np.abs(Gg - mask * dYr) <= tol_g * mask * dYa), ("relu/pool backward, elementwise", L.name)
+    if not fused_front:
+        assert np.all(np.abs(Gg - mask * dYr) <= tol_g * mask * dYa), ("relu/pool backward, elementwise", L.name)
     assert np.all(Gg[Yg <= 0] == 0)
     if whole:
         check_errors(f"{tag} backward_weights (whole)", r["dW"][i], oracle.conv_backward_weights(s, Xi, Gg),
@@ -243,7 +247,19 @@ def check_stack_layer(r, i, whole, rng=None):
         check_errors(f"{tag} backward_weights (sampled)", r["dW"][i].reshape(-1)[idx], oracle.conv_backward_weights_at(s, Xi, Gg, idx),
                      oracle.conv_backward_weights_at(s, aX, aG, idx), 1e-4, False)
     check_errors(f"{tag} bias gradient", r["db"][i], oracle.bias_grad(s, Gg), oracle.bias_grad(s, aG), 1e-4, False)
-    if r["dX"][i] is not None:
+    if i > 0 and r["fused_front"][i - 1]:
+        # the data gradient went out as the front layer's dY, that layer's ReLU mask applied on the way
+        front = r["dYc"][i - 1]
+        fmask = (r["Y"][i - 1] > 0).astype(np.float64)
+        if whole:
+            check_errors(f"{tag} backward_data + ReLU backward (whole)", front, fmask * oracle.conv_backward_data(s, Gg, Wi),
+                         fmask * oracle.conv_backward_data(s, aG, aW), tol, rounded)
+        else:
+            idx = np.unique(np.concatenate([rng.integers(0, front.size, size=N_SAMPLES), boundary_indices(L.N, L.C, L.H * L.W)]))
+            m = fmask.reshape(-1)[idx]
+            check_errors(f"{tag} backward_data + ReLU backward (sampled)", front.reshape(-1)[idx],
+                         m * oracle.conv_backward_data_at(s, Gg, Wi, idx), m * oracle.conv_backward_data_at(s, aG, aW, idx), tol, rounded)
+    elif r["dX"][i] is not None:
         if whole:
             check_errors(f"{tag} backward_data (whole)", r["dX"][i], oracle.conv_backward_data(s, Gg, Wi),
                          oracle.conv_backward_data(s, aG, aW), tol, rounded)

@@ -147,7 +147,7 @@ def test_whole_caffenet_iteration_small_batch_stage_by_stage(B):
             assert np.array_equal((h32(st.Dr[i]) != 0)[cur != 0], keep[cur != 0] == 1), ("dropout mask", L.name)
             close(st.Dr[i], oracle.dropout_apply(cur, L.dropout_after, st.dropout_seed, i), ("dropout", L.name), 2.0 ** -8)
         # backward, in reverse order of the forward stages
-        gh = h32(g)
+        gh = h32(g) if not st.fused_front[i] else None
         if L.dropout_after > 0:
             close(st.gD[i], oracle.dropout_apply(gh, L.dropout_after, st.dropout_seed, i), ("dropout backward", L.name), 2.0 ** -8)
             gh = h32(st.gD[i])
@@ -156,11 +156,18 @@ def test_whole_caffenet_iteration_small_batch_stage_by_stage(B):
             gh = h32(st.gN[i])
         if L.pool_after:
             gh = oracle.maxpool_backward(gh, Aref, L.Ho, L.Wo)
-        ref_g = oracle.relu_backward(Yg, np.ones_like(Yg)) * gh if L.relu else gh.astype(np.float64)
-        close(st.dYc[i], ref_g, ("relu/pool backward", L.name), 2.0 ** -8)
+        if not st.fused_front[i]:    # else: checked below, together with the data gradient of the layer behind
+            ref_g = oracle.relu_backward(Yg, np.ones_like(Yg)) * gh if L.relu else gh.astype(np.float64)
+            close(st.dYc[i], ref_g, ("relu/pool backward", L.name), 2.0 ** -8)
         Gg = h32(st.dYc[i])
+        assert np.all(Gg[Yg <= 0] == 0) or not L.relu
         close(st.dW[i], oracle.conv_backward_weights(s, Xi, Gg), ("backward_weights", L.name), 1e-4)
         close(st.db[i], oracle.bias_grad(s, Gg), ("bias gradient", L.name), 1e-4)
+        if i > 0 and st.fused_front[i - 1]:
+            # this data gradient went out as the front layer's output gradient, its ReLU's mask applied
+            Yf = h32(st.Y[i - 1])
+            close(st.dYc[i - 1], oracle.conv_backward_data(s, Gg, Wi) * (Yf > 0), ("backward_data + ReLU backward", L.name))
+            continue
         if st.dXl[i] is None:
             break
         close(st.dXl[i], oracle.conv_backward_data(s, Gg, Wi), ("backward_data", L.name))

@@ -173,3 +173,70 @@ def test_rows_layout_declines(B):
         N, C, H, W, F, kh, kw, ph, pw = cfg
         d = B.conv_desc(N, C, H, W, F, kh, kw, (st, st), (ph, pw), B.BF16, flags)
         assert B.conv_dy_rows_layout(d) is None
+
+
+# (N, C, H, W, F, kh, kw, ph, pw) of the layer whose data gradient is taken, forced column tile (0: the library's
+# choice); N large enough that the data gradient's reduction is not split over workgroups
+RELU_ROWS_SHAPES = [((392, 64, 13, 13, 128, 3, 3, 1, 1), 0), ((392, 128, 13, 13, 128, 3, 3, 1, 1), 0),
+                    ((96, 96, 27, 27, 128, 5, 5, 2, 2), 0), ((392, 192, 13, 13, 128, 3, 3, 1, 1), 0),
+                    ((392, 128, 13, 13, 128, 3, 3, 1, 1), 256), ((392, 128, 13, 13, 128, 3, 3, 1, 1), 512),
+                    ((392, 64, 13, 13, 128, 3, 3, 1, 1), 512)]
+
+
+@pytest.mark.parametrize("cfg,bn", RELU_ROWS_SHAPES)
+def test_conv_backward_data_relu_rows(B, cfg, bn):
+    """The data gradient that stores (y_front > 0 ? dX : 0) as the front layer's rows matrix: bit-identical to the
+    dense data gradient followed by relu_backward_rows; its column-tile sums add up to the rows' sums; the model
+    gradient of the front layer takes them for its bias gradient.  Row tiles of 96 and 128 channels, a second row
+    tile that is half empty, all three column tiles, pieces that straddle images, a ragged last column tile."""
+    print("dgrad relu rows", cfg, bn, flush=True)
+    N, C, H, W, F, kh, kw, ph, pw = cfg
+    rng = np.random.default_rng(41)
+    Wt = gpu(0.05 * rng.standard_normal((F, C, kh, kw)))
+    dY = gpu(rng.standard_normal((N, F, H, W)))
+    y_front = gpu(np.maximum(rng.standard_normal((N, C, H, W)), 0.0))
+    d = B.conv_desc(N, C, H, W, F, kh, kw, (1, 1), (ph, pw), B.BF16, B.FLAG_FUSED)
+    ld, pitch = B.conv_dy_rows_layout(d)
+    rows, _ = B.relu_backward_rows(torch.ones_like(dY), dY, ld=ld)
+    buf = torch.empty(B.conv_packed_weights_bytes(d, B.PASS_BACKWARD_DATA), dtype=torch.uint8, device="cuda")
+    B.conv_pack_weights([d], [B.PASS_BACKWARD_DATA], [Wt], [buf])
+    B.tuning_set(B.TUNE_FUSED_BN, bn)
+    try:
+        per = B.conv_backward_data_relu_rows_sums(d)
+        assert per is not None and per >= 1
+        dX = B.conv_backward_data_rows(d, rows, buf)
+        got, sums = B.conv_backward_data_relu_rows(d, rows, buf, y_front)
+        again, sums2 = B.conv_backward_data_relu_rows(d, rows, buf, y_front)
+    finally:
+        B.tuning_set(B.TUNE_FUSED_BN, 0)
+    expect, plane_sums = B.relu_backward_rows(y_front, dX)
+    assert torch.equal(got, expect)
+    assert torch.equal(got, again) and torch.equal(sums, sums2)
+    total = host(expect).sum(axis=1)
+    scale = np.abs(host(expect)).sum(axis=1) + 1e-30
+    assert np.max(np.abs(host(sums).sum(axis=1) - total) / scale) <= 1e-5
+    assert tuple(sums.shape) == (C, per)
+    if cfg == RELU_ROWS_SHAPES[1][0] and bn == 0:
+        s = oracle.shape(N, C, H, W, F, kh, kw, (1, 1), (ph, pw))
+        ref = oracle.conv_backward_data(s, host(dY), host(Wt)) * (host(y_front) > 0)
+        assert np.max(np.abs(host(got) - rows_of(ref))) <= 2e-2 * np.max(np.abs(ref))
+        # the front layer (a 3 x 3 layer of C filters on these planes) takes the column-tile sums for its bias gradient
+        Cf = 64
+        df = B.conv_desc(N, Cf, H, W, C, 3, 3, (1, 1), (1, 1), B.BF16, B.FLAG_FUSED)
+        assert B.conv_dy_rows_layout(df) == (ld, pitch)
+        Xf = gpu(rng.standard_normal((N, Cf, H, W)))
+        dW_a, db_a = B.conv_backward_weights_rows(df, Xf, got, sums)
+        dW_b, db_b = B.conv_backward_weights_rows(df, Xf, got, plane_sums)
+        assert torch.equal(dW_a, dW_b)
+        sf = oracle.shape(N, Cf, H, W, C, 3, 3, (1, 1), (1, 1))
+        dense = host(got).reshape(C, N, pitch)[:, :, :H * W].transpose(1, 0, 2).reshape(N, C, H, W)
+        ref_b = oracle.bias_grad(sf, dense)
+        assert np.max(np.abs(host(db_a) - ref_b)) <= 1e-4 * np.max(np.abs(ref_b))
+        assert np.max(np.abs(host(db_b) - ref_b)) <= 1e-4 * np.max(np.abs(ref_b))
+
+
+def test_conv_backward_data_relu_rows_declines_split_reductions(B):
+    """Few column tiles (a small batch): the data gradient splits its reduction and cannot store the masked rows."""
+    d = B.conv_desc(4, 64, 13, 13, 128, 3, 3, (1, 1), (1, 1), B.BF16, B.FLAG_FUSED)
+    assert B.conv_dy_rows_layout(d) is not None
+    assert B.conv_backward_data_relu_rows_sums(d) is None

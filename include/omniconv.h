@@ -368,10 +368,12 @@ int omni_profile_summary(int kernel_id, int64_t *launches, double *total_ms, dou
  *                           pitch that keeps fragment reads free of bank conflicts where the patch still fits
  *   OMNI_TUNE_WGRAD_SPLITS: most ranges the LDS-patch model gradients split their reduction into (0: choose)
  *   OMNI_TUNE_WGRAD_PATCH : 1 switches the LDS-patch model gradients off (their layers take the direct loader), 0 on
+ *   OMNI_TUNE_POOL_LDS    : 1 sends the bf16 3 x 3 / stride 2 pools through the kernels that stage planes in LDS, 0 lets
+ *                           them take the kernels that read the planes directly
  * An override that does not fit a layer is ignored for that layer.
  */
 enum { OMNI_TUNE_GEMM_TILE = 0, OMNI_TUNE_FUSED_BN = 1, OMNI_TUNE_FUSED_BM = 2, OMNI_TUNE_WGRAD_SPLITS = 3, OMNI_TUNE_WGRAD_PATCH = 4,
-       OMNI_TUNE_FUSED_PITCH = 5 };
+       OMNI_TUNE_FUSED_PITCH = 5, OMNI_TUNE_POOL_LDS = 6 };
 int omni_tuning_set(int knob, int value);
 
 /* Host only.  Static string for a status code. */

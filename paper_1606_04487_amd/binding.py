@@ -114,7 +114,7 @@ def raw():
     return _lib
 
 
-TUNE_GEMM_TILE, TUNE_FUSED_BN, TUNE_FUSED_BM, TUNE_WGRAD_SPLITS, TUNE_WGRAD_PATCH, TUNE_FUSED_PITCH = 0, 1, 2, 3, 4, 5
+TUNE_GEMM_TILE, TUNE_FUSED_BN, TUNE_FUSED_BM, TUNE_WGRAD_SPLITS, TUNE_WGRAD_PATCH, TUNE_FUSED_PITCH, TUNE_POOL_LDS = 0, 1, 2, 3, 4, 5, 6
 
 
 def tuning_set(knob: int, value: int) -> None:

@@ -219,6 +219,10 @@ int omni_tuning_set(int knob, int value)
         if (value != 0 && value != 1) return OMNI_INVALID_ARGUMENT;
         set_fused_pitch_override(value);
         return OMNI_OK;
+    case OMNI_TUNE_POOL_LDS:
+        if (value != 0 && value != 1) return OMNI_INVALID_ARGUMENT;
+        set_pool_override(value);
+        return OMNI_OK;
     case OMNI_TUNE_WGRAD_SPLITS:
         if (value < 0) return OMNI_INVALID_ARGUMENT;
         set_wgrad_patch_override(value, -1);

@@ -241,6 +241,7 @@ int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
                        const void *x, void *y, uint8_t *argmax, hipStream_t s);
 int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t k, int32_t stride, int32_t ceil_mode,
                        const void *dy, const uint8_t *argmax, const void *y, void *dx, hipStream_t s);
+void set_pool_override(int lds);  // omni_tuning_set(OMNI_TUNE_POOL_LDS)
 // The two producers of a layer's output gradient writing its "rows" form directly (bf16): a matrix [C][ld], plane
 // (n, c) at column n * pitch with pitch = the plane rounded up to 8 elements (the round-up zero), plus the sum of
 // every plane's values, plane_sums [C][N] (optional).  Columns from N * pitch to ld are not written.

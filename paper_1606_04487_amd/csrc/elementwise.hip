@@ -174,6 +174,10 @@ int launch_relu(int dtype, bool backward, int64_t count, const void *ref, const 
 // ------------------------------------------------------------------------------------------------
 // Max-pool, k x k window, stride s, no padding, last window clipped at the border in ceil mode.
 // ------------------------------------------------------------------------------------------------
+static int g_pool_fwd_direct = 1;  // 0: the LDS kernel also for bf16 3 x 3 / stride 2 (tuning knob, for comparisons)
+
+void set_pool_override(int lds) { g_pool_fwd_direct = lds ? 0 : 1; }
+
 struct PoolGeom {
     int32_t H, W, Ho, Wo, k, s;
     FastDiv div_Wo, div_HoWo, div_W, div_HW, div_s;
@@ -378,6 +382,103 @@ __global__ __launch_bounds__(256) void maxpool_fwd_lds_kernel(PoolGeom g, int64_
         }
         y[p0 * howo + o] = braw;
         if (argmax != nullptr) argmax[p0 * howo + o] = (uint8_t)best;
+    }
+}
+
+// 3 x 3 / stride 2 forward pool on bf16 planes without LDS.  One thread = 2 output rows x 3 output columns of a
+// plane: the 5 input rows x 7 input columns under them arrive as five element-aligned 16-byte loads (all issued
+// before the first is used; neighbouring threads' loads overlap in the cache, not in memory), positions outside the
+// plane (clipped last windows, missing rows) become -inf, every value is widened once, and each window is scanned
+// in window order with a strict comparison, so the first maximum wins as in the definition.  A fifth of the vector
+// instructions of the LDS kernel, which those bound.
+__global__ __launch_bounds__(256) void maxpool_fwd_k3s2_bf16_kernel(PoolGeom g, FastDiv div_tasks, FastDiv div_tx, uint32_t total_tasks,
+                                                                    int64_t total_elems, const bf16_t *__restrict__ x,
+                                                                    bf16_t *__restrict__ y, uint8_t *__restrict__ argmax)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const uint32_t task = blockIdx.x * 256u + threadIdx.x;
+    if (task >= total_tasks) return;
+    uint32_t pl, rest, ty, tx;
+    div_tasks.divmod(task, pl, rest);
+    div_tx.divmod(rest, ty, tx);
+    const int iy0 = 4 * (int)ty, ix0 = 6 * (int)tx;
+    const int64_t base = (int64_t)pl * g.H * g.W + (int64_t)iy0 * g.W + ix0;
+    // loads; a piece that would run past the end of the tensor is moved back to end there and shifted down afterwards
+    u32x4 w[5];
+    int shift[5];
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        int64_t at = base + (int64_t)j * g.W;
+        const bool row_ok = iy0 + j < g.H;
+        if (!row_ok) at = base;
+        const int64_t last = total_elems - 8;
+        shift[j] = at > last ? (int)(at - last) : 0;
+        at = at > last ? last : at;
+        __builtin_memcpy(&w[j], x + at, 16);
+    }
+    // 16-bit lanes of columns inside the plane
+    uint32_t keep[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        keep[q] = (ix0 + 2 * q < g.W ? 0x0000ffffu : 0u) | (ix0 + 2 * q + 1 < g.W && 2 * q + 1 < 7 ? 0xffff0000u : 0u);
+    constexpr uint32_t NINF2 = 0xff80ff80u;  // two bf16 -inf
+    float v[5][7];
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        if (shift[j] != 0) {  // last rows of the last plane only
+            unsigned __int128 t;
+            __builtin_memcpy(&t, &w[j], 16);
+            t >>= 16 * shift[j];
+            __builtin_memcpy(&w[j], &t, 16);
+        }
+        const bool row_ok = iy0 + j < g.H;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t m = row_ok ? keep[q] : 0u;
+            const uint32_t word = (w[j][q] & m) | (NINF2 & ~m);
+            v[j][2 * q] = __uint_as_float(word << 16);
+            if (2 * q + 1 < 7) v[j][2 * q + 1] = __uint_as_float(word & 0xffff0000u);
+        }
+    }
+    const int howo = g.Ho * g.Wo;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int oy = 2 * (int)ty + r;
+        if (oy >= g.Ho) break;
+        uint32_t bits[3], code[3];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            float bv = v[2 * r][2 * c];
+            int best = 0;
+#pragma unroll
+            for (int k = 1; k < 9; ++k) {
+                const float cand = v[2 * r + k / 3][2 * c + k % 3];
+                const bool take = cand > bv;  // strict: the first maximum in scan order wins; -inf is never taken
+                best = take ? k : best;
+                bv = take ? cand : bv;
+            }
+            bits[c] = __float_as_uint(bv) >> 16;
+            code[c] = (uint32_t)best;
+        }
+        const int ox0 = 3 * (int)tx, n = g.Wo - ox0 < 3 ? g.Wo - ox0 : 3;
+        bf16_t *yo = y + (int64_t)pl * howo + oy * g.Wo + ox0;
+        if (n >= 2) {
+            const uint32_t two = bits[0] | (bits[1] << 16);
+            __builtin_memcpy(yo, &two, 4);
+            if (n == 3) yo[2] = (bf16_t)bits[2];
+        } else {
+            yo[0] = (bf16_t)bits[0];
+        }
+        if (argmax != nullptr) {
+            uint8_t *ao = argmax + (int64_t)pl * howo + oy * g.Wo + ox0;
+            if (n >= 2) {
+                const uint16_t two = (uint16_t)(code[0] | (code[1] << 8));
+                __builtin_memcpy(ao, &two, 2);
+                if (n == 3) ao[2] = (uint8_t)code[2];
+            } else {
+                ao[0] = (uint8_t)code[0];
+            }
+        }
     }
 }
 
@@ -777,6 +878,16 @@ int launch_maxpool_fwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
     int64_t planes_per_launch = (0x7fffffffll - 4096) / per;
     ProfScope prof(KID_POOL_FWD, s, 0.0, (double)planes * ((double)H * W + per) * elem_size(dtype) + (argmax ? (double)planes * per : 0.0));
     const int64_t hw = (int64_t)H * W;
+    if (dtype == OMNI_BF16 && k == 3 && stride == 2 && g_pool_fwd_direct) {
+        const int64_t txn = (g.Wo + 2) / 3, tasks = txn * ((g.Ho + 1) / 2), total = planes * tasks;
+        if (total <= 0x7fffffffll && planes * hw >= 8) {
+            hipLaunchKernelGGL(maxpool_fwd_k3s2_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, g,
+                               FastDiv((uint32_t)tasks), FastDiv((uint32_t)txn), (uint32_t)total, planes * hw, (const bf16_t *)x,
+                               (bf16_t *)y, argmax);
+            OMNI_LAUNCH_CHECK();
+            return OMNI_OK;
+        }
+    }
     // about 16 KB of input per workgroup (measured best on the 55 x 55 planes: 8192 elements 60 us, 4096 72 us)
     int pb = pool_planes_per_block(hw * (int64_t)elem_size(dtype), hw, 8192);
     if (pb > 0 && (planes + pb - 1) / pb <= 0x7fffffffll) {

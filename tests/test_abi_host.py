@@ -272,6 +272,7 @@ def test_tuning_overrides_are_checked(B):
     assert L.omni_tuning_set(9, 0) == -1
     assert L.omni_tuning_set(B.TUNE_FUSED_PITCH, 2) == -1 and L.omni_tuning_set(B.TUNE_WGRAD_SPLITS, -1) == -1
     assert L.omni_tuning_set(B.TUNE_WGRAD_PATCH, 2) == -1
+    assert L.omni_tuning_set(B.TUNE_POOL_LDS, 2) == -1 and L.omni_tuning_set(B.TUNE_POOL_LDS, 0) == 0
     # a forced column tile changes which layers run fused, and resetting restores the library's choice
     d = B.conv_desc(4, 256, 13, 13, 384, 3, 3, 1, 1, B.BF16, B.FLAG_FUSED)
     assert B.conv_fused_supported(d, B.PASS_FORWARD)
@@ -280,3 +281,63 @@ def test_tuning_overrides_are_checked(B):
         assert B.conv_fused_supported(d, B.PASS_FORWARD)
     B.tuning_set(B.TUNE_GEMM_TILE, 3)
     B.tuning_set(B.TUNE_GEMM_TILE, -1)
+
+
+def test_dy_rows_argument_checks(B):
+    """Layout and error paths of the rows form of the output gradient (host code only: nothing is launched)."""
+    L = B.raw()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    conv4 = B.conv_desc(256, 384, 13, 13, 384, 3, 3, 1, 1, B.BF16, B.FLAG_FUSED)
+    conv2 = B.conv_desc(256, 96, 27, 27, 256, 5, 5, 1, 2, B.BF16, B.FLAG_FUSED)
+    small = B.conv_desc(4, 384, 13, 13, 384, 3, 3, 1, 1, B.BF16, B.FLAG_FUSED)
+    ragged = B.conv_desc(3, 384, 13, 13, 384, 3, 3, 1, 1, B.BF16, B.FLAG_FUSED)
+    plain = B.conv_desc(256, 384, 13, 13, 384, 3, 3, 1, 1, B.BF16, 0)
+    conv1 = B.conv_desc(256, 3, 227, 227, 96, 11, 11, 4, 0, B.BF16, B.FLAG_FUSED)
+    # planes rounded up to 8 elements, one after the other, no round-up at the rows' ends
+    assert B.conv_dy_rows_layout(conv4) == (256 * 176, 176)
+    assert B.conv_dy_rows_layout(conv2) == (256 * 736, 736)
+    assert B.conv_dy_rows_layout(small) == (4 * 176, 176)
+    for d in (ragged, plain, conv1):
+        assert B.conv_dy_rows_layout(d) is None
+    n64 = ctypes.c_int64()
+    assert L.omni_conv_dy_rows_layout(ctypes.byref(conv4), None, ctypes.byref(n64)) == -1
+    # partial sums per channel of the masked data gradient: its column tiles; none where its reduction is split
+    assert B.conv_backward_data_relu_rows_sums(conv4) == (256 * 169 + 511) // 512
+    assert B.conv_backward_data_relu_rows_sums(small) is None
+    assert B.conv_backward_data_relu_rows_sums(plain) is None
+    assert L.omni_conv_backward_data_relu_rows_sums(ctypes.byref(conv4), None) == -1
+    # producers: dtype, extents, leading dimension, pointers
+    assert L.omni_relu_backward_rows(B.F32, 4, 8, 169, fake, fake, fake, 4 * 176, None, None) == -2
+    assert L.omni_relu_backward_rows(B.BF16, 4, 8, 4, fake, fake, fake, 32, None, None) == -2        # plane under 8 elements
+    assert L.omni_relu_backward_rows(B.BF16, 4, 8, 4096, fake, fake, fake, 4 * 4096, None, None) == -2
+    assert L.omni_relu_backward_rows(B.BF16, 4, 0, 169, fake, fake, fake, 4 * 176, None, None) == -1
+    assert L.omni_relu_backward_rows(B.BF16, 4, 8, 169, fake, fake, fake, 4 * 176 - 8, None, None) == -1
+    assert L.omni_relu_backward_rows(B.BF16, 4, 8, 169, fake, fake, fake, 4 * 176 + 4, None, None) == -1
+    assert L.omni_relu_backward_rows(B.BF16, 0, 8, 169, None, None, None, 0, None, None) == 0
+    assert L.omni_relu_backward_rows(B.BF16, 4, 8, 169, fake, None, fake, 4 * 176, None, None) == -1
+    assert L.omni_relu_backward_rows(B.BF16, 4, 8, 169, fake, fake, odd, 4 * 176, None, None) == -4
+    assert L.omni_maxpool_backward_rows(B.F32, 4, 8, 13, 13, 3, 2, 1, fake, fake, None, fake, 4 * 176, None, None) == -2
+    assert L.omni_maxpool_backward_rows(B.BF16, 4, 8, 13, 13, 2, 2, 1, fake, fake, None, fake, 4 * 176, None, None) == -2
+    assert L.omni_maxpool_backward_rows(B.BF16, 4, 8, 13, 13, 3, 2, 1, fake, fake, None, fake, 4 * 176 - 8, None, None) == -1
+    assert L.omni_maxpool_backward_rows(B.BF16, 4, 8, 13, 13, 3, 2, 1, fake, None, None, fake, 4 * 176, None, None) == -1
+    assert L.omni_maxpool_backward_rows(B.BF16, 4, 8, 13, 13, 3, 2, 1, fake, fake, None, odd, 4 * 176, None, None) == -4
+    assert L.omni_maxpool_backward_rows(B.BF16, 0, 8, 13, 13, 3, 2, 1, None, None, None, None, 0, None, None) == 0
+    # consumers: layers without the rows form, missing sums, workspace, alignment
+    big = 1 << 40
+    assert L.omni_conv_backward_weights_rows(ctypes.byref(plain), fake, fake, fake, 256, fake, fake, fake, big, None) == -2
+    assert L.omni_conv_backward_weights_rows(ctypes.byref(ragged), fake, fake, fake, 3, fake, fake, fake, big, None) == -2
+    assert L.omni_conv_backward_weights_rows(ctypes.byref(conv4), fake, fake, None, 0, fake, fake, fake, big, None) == -1   # dbias without sums
+    assert L.omni_conv_backward_weights_rows(ctypes.byref(conv4), fake, fake, fake, 0, fake, fake, fake, big, None) == -1
+    assert L.omni_conv_backward_weights_rows(ctypes.byref(conv4), fake, None, fake, 256, fake, fake, fake, big, None) == -1
+    assert L.omni_conv_backward_weights_rows(ctypes.byref(conv4), fake, odd, fake, 256, fake, fake, fake, big, None) == -4
+    assert L.omni_conv_backward_weights_rows(ctypes.byref(conv4), fake, fake, fake, 256, fake, fake, fake, 16, None) == -3
+    assert L.omni_conv_backward_data_rows(ctypes.byref(plain), fake, fake, fake, fake, big, None) == -2
+    assert L.omni_conv_backward_data_rows(ctypes.byref(conv4), fake, None, fake, fake, big, None) == -1
+    assert L.omni_conv_backward_data_rows(ctypes.byref(conv4), fake, fake, odd, fake, big, None) == -4
+    assert L.omni_conv_backward_data_rows(ctypes.byref(conv4), fake, fake, fake, fake, 16, None) == -3
+    assert L.omni_conv_backward_data_relu_rows(ctypes.byref(small), fake, fake, fake, fake, 4 * 176, None, fake, big, None) == -2
+    assert L.omni_conv_backward_data_relu_rows(ctypes.byref(conv4), fake, fake, None, fake, 256 * 176, None, fake, big, None) == -1
+    assert L.omni_conv_backward_data_relu_rows(ctypes.byref(conv4), fake, fake, fake, fake, 256 * 176 - 8, None, fake, big, None) == -1
+    assert L.omni_conv_backward_data_relu_rows(ctypes.byref(conv4), fake, fake, fake, fake, 256 * 176, odd, fake, big, None) == -4
+    assert L.omni_conv_backward_data_relu_rows(ctypes.byref(conv4), fake, fake, fake, fake, 256 * 176, None, fake, 16, None) == -3

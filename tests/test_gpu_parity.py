@@ -296,6 +296,29 @@ def test_maxpool(B, dtype, H, W, ceil_mode):
     assert np.array_equal(host(fused) != 0, (oracle.relu_backward(x, np.ones_like(x)) * ref) != 0) or dtype == 1
 
 
+@pytest.mark.parametrize("H,W,ceil_mode", [(55, 55, True), (27, 27, True), (13, 13, False), (7, 9, True), (3, 3, True),
+                                            (6, 20, True), (5, 14, False), (12, 29, True), (4, 4, True)])
+def test_maxpool_forward_kernels_agree(B, H, W, ceil_mode):
+    """bf16 3 x 3 / stride 2 forward pool: the kernel that reads the planes directly (the default) and the one that
+    stages them in LDS give the same values and winners, also where -0 and +0 tie and at the tensor's last rows
+    (where the direct kernel's loads are moved back to stay inside the tensor); both equal the oracle."""
+    rng = np.random.default_rng(H * 37 + W)
+    x = prep(np.round(rng.standard_normal((2, 3, H, W)) * 2) / 2, 1)
+    xg = gpu(x, 1)
+    try:
+        B.tuning_set(B.TUNE_POOL_LDS, 1)
+        y_lds, am_lds = B.maxpool_forward(xg, 3, 2, ceil_mode)
+        B.tuning_set(B.TUNE_POOL_LDS, 0)
+        y_dir, am_dir = B.maxpool_forward(xg, 3, 2, ceil_mode)
+    finally:
+        B.tuning_set(B.TUNE_POOL_LDS, 0)
+    assert torch.equal(y_lds.view(torch.int16), y_dir.view(torch.int16)) and torch.equal(am_lds, am_dir)
+    y_ref, am_ref = oracle.maxpool_forward(x, 3, 2, ceil_mode)
+    assert np.array_equal(host(y_dir), y_ref)
+    no_winners = B.maxpool_forward(xg, 3, 2, ceil_mode, argmax=None)[0]
+    assert torch.equal(no_winners, y_dir)
+
+
 # ------------------------------------------------------------------------------------ chained stack
 
 @pytest.mark.parametrize("dtype", [0, 1])

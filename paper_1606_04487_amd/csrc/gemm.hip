@@ -1023,6 +1023,44 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     }
 }
 
+// The same ordered sum for element counts that are a multiple of 4: a thread owns four consecutive elements and adds
+// the splits in ascending order, eight 16-byte loads in flight (the 4-byte loads of the kernel above keep too few
+// bytes in flight to reach the memory system's rate).  Extra workgroups finish the bias gradient as above.
+__global__ __launch_bounds__(256) void reduce_partials_vec_kernel(const float4 *__restrict__ partials, int splits, int64_t count4,
+                                                                  float4 *__restrict__ out, unsigned main_blocks,
+                                                                  const float *__restrict__ bias_partials, int bias_blocks,
+                                                                  int F, float *__restrict__ dbias)
+{
+    if (blockIdx.x >= main_blocks) {
+        const int c = threadIdx.x % 64, f = (int)(blockIdx.x - main_blocks) * 4 + threadIdx.x / 64;
+        if (f < F) {
+            float acc = 0.f;
+            for (int b = c; b < bias_blocks; b += 64) acc += bias_partials[(int64_t)f * bias_blocks + b];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+            if (c == 0) dbias[f] = acc;
+        }
+        return;
+    }
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count4) return;
+    const float4 *p = partials + i;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    int z = 0;
+    for (; z + 8 <= splits; z += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(z + u) * count4];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc.x += v[u].x, acc.y += v[u].y, acc.z += v[u].z, acc.w += v[u].w;
+    }
+    for (; z < splits; ++z) {
+        const float4 v = p[(int64_t)z * count4];
+        acc.x += v.x, acc.y += v.y, acc.z += v.z, acc.w += v.w;
+    }
+    out[i] = acc;
+}
+
 static GemmShape make_shape(int rows, int cols, int64_t red, int64_t chunk, int bm, int bn, int splits)
 {
     GemmShape s;
@@ -1307,8 +1345,15 @@ int launch_wgrad_reduce(const ConvGeom &g, const float *partials, int splits, fl
 {
     int64_t count = (int64_t)g.F * g.K;
     ProfScope prof(KID_REDUCE_PARTIALS, s, 0.0, 4.0 * count * (splits + 1));
-    const unsigned main_blocks = (unsigned)((count + 63) / 64);
     const unsigned bias_wgs = dbias != nullptr ? (unsigned)((g.F + 3) / 4) : 0u;
+    if (count % 4 == 0) {
+        const unsigned vec_blocks = (unsigned)((count / 4 + 255) / 256);
+        hipLaunchKernelGGL(reduce_partials_vec_kernel, dim3(vec_blocks + bias_wgs), dim3(256), 0, s, (const float4 *)partials, splits,
+                           count / 4, (float4 *)dW, vec_blocks, bias_partials, bias_blocks, g.F, dbias);
+        OMNI_LAUNCH_CHECK();
+        return OMNI_OK;
+    }
+    const unsigned main_blocks = (unsigned)((count + 63) / 64);
     hipLaunchKernelGGL(reduce_partials_kernel<false>, dim3(main_blocks + bias_wgs), dim3(256), 0, s, partials, splits, count, dW,
                        main_blocks, bias_partials, bias_blocks, g.F, dbias, PhaseMap{});
     OMNI_LAUNCH_CHECK();

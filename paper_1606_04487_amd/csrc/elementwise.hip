@@ -936,8 +936,10 @@ int launch_maxpool_bwd(int dtype, int64_t planes, int32_t H, int32_t W, int32_t 
             size_t lds = (((size_t)pb * howo * elem_size(dtype) + 15) / 16) * 16 + (size_t)pb * howo + 16;
             const int64_t last = planes % pb == 0 ? pb : planes % pb;
             if (k == 3 && stride == 2 && (int64_t)pb * howo <= 4096 && last * howo >= 16) {
-                // persistent: a few workgroups per compute unit, each walking the groups with the grid's stride
-                const unsigned resident = 256u * 6u;
+                // persistent: a few workgroups per compute unit, each walking the groups with the grid's stride (four:
+                // measured inside the training step, where the tensors come from memory, 3 / 4 / 6 / 8 per unit give
+                // 179 / 172 / 176 / 180 us for the step's three pools; back to back from a warm cache six are best)
+                const unsigned resident = 256u * 4u;
                 dim3 pgrid(grid.x < resident ? grid.x : resident);
                 if (dtype == OMNI_BF16) {
                     if (y) hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<bf16_t, true>), pgrid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)dy, argmax, (const bf16_t *)y, (bf16_t *)dx, RowsOut{});
@@ -1018,7 +1020,7 @@ int launch_maxpool_bwd_rows(int32_t N, int32_t C, int32_t H, int32_t W, int32_t 
     size_t lds = (((size_t)pb * howo * 2 + 15) / 16) * 16 + (((size_t)pb * howo + 15) / 16) * 16 + (size_t)tasks * sizeof(float) + 16;
     ProfScope prof(KID_POOL_BWD, s, 0.0,
                    (double)planes * ((double)ro.pitch + (y ? 2.0 : 1.0) * (double)howo) * 2.0 + (double)planes * (howo + 4.0));
-    const unsigned resident = 256u * 6u;
+    const unsigned resident = 256u * 4u;  // as in launch_maxpool_bwd
     dim3 pgrid((unsigned)(groups < resident ? groups : resident));
     if (y)
         hipLaunchKernelGGL((maxpool_bwd_k3s2_kernel<bf16_t, true, true>), pgrid, dim3(256), lds, s, g, planes, pb, (const bf16_t *)dy,

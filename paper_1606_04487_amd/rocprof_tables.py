@@ -10,6 +10,7 @@ Four sub-commands, each reading what one kind of rocprofv3 run wrote (`--output-
                                                    hbm_traffic.json beside this file, which bench.py reads for
                                                    `roofline.traffic`
     counters  <pmc csv> [<pmc csv> ...]            SQ counters of the matrix-core kernels
+    pools     <pool_bench stdout> <pmc csv> [...]  the pool kernels alone: pool_bench's table and their SQ counters
 
 Every table starts with the full command that produced its input.  Host-side text processing only.
 """
@@ -235,6 +236,40 @@ def cmd_counters(a) -> None:
     print(open(a.out).read())
 
 
+def cmd_pools(a) -> None:
+    """SQ counters of the pool kernels from runs of pool_bench, beside pool_bench's own table."""
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    for path in a.csv:
+        for r in csv.DictReader(open(path)):
+            if "maxpool" in r["Kernel_Name"]:
+                agg[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    table = [l.rstrip("\n") for l in open(a.bench_out) if l.startswith("|")]
+    with open(a.out, "w") as f:
+        f.write(f"# The 3 x 3 / stride 2 max-pool kernels on their own: {a.title}\n\n")
+        f.write("Commands (from /tmp with TMPDIR=/tmp on one MI355X; one counter set per rocprofv3 run):\n\n")
+        for c in a.command:
+            f.write(f"    {c}\n")
+        f.write("\nTimes by the library's HIP events (first command).  `back to back`: the same launch repeated, operands stay in the\n"
+                "last-level cache; `cold`: a 512 MiB fill between launches, operands come from memory as inside a training step.\n"
+                "Peak: 8000 GB/s.\n\n")
+        f.write("\n".join(table) + "\n\n")
+        f.write("SQ counters, averages per launch over the three layers (back-to-back launches only).  `VALU busy` = 4 x SQ_INSTS_VALU /\n"
+                "(32 x SQ_BUSY_CYCLES): a wave64 vector instruction occupies its SIMD for 4 cycles and SQ_BUSY_CYCLES adds up a shader\n"
+                "engine's 32 SIMDs.  `waiting` = SQ_WAIT_INST_ANY / SQ_WAVE_CYCLES.  `waves per SIMD` = 4.25 x SQ_WAVE_CYCLES / (32 x\n"
+                "SQ_BUSY_CYCLES): the counter ticks once per four cycles (a kernel with exactly two resident wavefronts per SIMD reads 0.47).\n\n")
+        f.write("| kernel | launches | wavefronts | VALU insts per wavefront | LDS insts per wavefront | VALU busy | waiting | waves per SIMD |\n"
+                "|---|---|---|---|---|---|---|---|\n")
+        for k, d in agg.items():
+            v = {c: sum(x) / len(x) for c, x in d.items()}
+            n = len(d["SQ_WAVES"])
+            f.write(f"| {short_name(k)} | {n} | {v['SQ_WAVES']:.0f} | {v['SQ_INSTS_VALU'] / v['SQ_WAVES']:.0f} | "
+                    f"{v['SQ_INSTS_LDS'] / v['SQ_WAVES']:.0f} | {4 * v['SQ_INSTS_VALU'] / (32 * v['SQ_BUSY_CYCLES']):.2f} | "
+                    f"{v['SQ_WAIT_INST_ANY'] / v['SQ_WAVE_CYCLES']:.2f} | {4.25 * v['SQ_WAVE_CYCLES'] / (32 * v['SQ_BUSY_CYCLES']):.1f} |\n")
+        if a.reading:
+            f.write("\n" + a.reading + "\n")
+    print(open(a.out).read())
+
+
 def main() -> None:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="what", required=True)
@@ -261,6 +296,11 @@ def main() -> None:
     m.add_argument("--out", required=True), m.add_argument("--title", required=True)
     m.add_argument("--command", action="append", required=True), m.add_argument("--reading", default="")
     m.set_defaults(fn=cmd_movement)
+    q = sub.add_parser("pools")
+    q.add_argument("bench_out"), q.add_argument("csv", nargs="+")
+    q.add_argument("--out", required=True), q.add_argument("--title", required=True)
+    q.add_argument("--command", action="append", required=True), q.add_argument("--reading", default="")
+    q.set_defaults(fn=cmd_pools)
     a = ap.parse_args()
     a.fn(a)
 

@@ -677,13 +677,23 @@ __global__ __launch_bounds__(256) void maxpool_bwd_k3s2_kernel(PoolGeom g, int64
             pool_bwd_k3s2_tasks<T, true>(g, np, gdy, gam, dx, hw, howo, &ro, grp * pb, tsum);
             __syncthreads();  // the staged group has been read by everyone, and every task's sum is there
             if (ro.sums != nullptr) {
+                // 16 lanes per plane: lane k adds the plane's tasks k, k + 16, ... in that order, then a fixed tree
+                // over the 16 lanes (the same order every run; one thread per plane would walk all tasks alone
+                // while the workgroup waits)
                 const int per = ((g.H + 1) >> 1) * ((g.W + 7) >> 3);
-                for (int pl = threadIdx.x; pl < np; pl += 256) {
+                const int k = threadIdx.x & 15;
+                for (int pl0 = 0; pl0 < np; pl0 += 16) {   // uniform trip count: the shuffles need every lane
+                    const int pl = pl0 + (int)(threadIdx.x >> 4);
                     float acc = 0.f;
-                    for (int j = 0; j < per; ++j) acc += tsum[pl * per + j];
-                    uint32_t nn, c;
-                    ro.div_C.divmod((uint32_t)(grp * pb + pl), nn, c);
-                    ro.sums[(int64_t)c * ro.N + nn] = acc;
+                    if (pl < np)
+                        for (int j = k; j < per; j += 16) acc += tsum[pl * per + j];
+#pragma unroll
+                    for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 16);
+                    if (pl < np && k == 0) {
+                        uint32_t nn, c;
+                        ro.div_C.divmod((uint32_t)(grp * pb + pl), nn, c);
+                        ro.sums[(int64_t)c * ro.N + nn] = acc;
+                    }
                 }
             }
             // tsum is next written after the next group's staging barrier, which the summing threads join

@@ -389,8 +389,8 @@ __global__ __launch_bounds__(256) void maxpool_fwd_lds_kernel(PoolGeom g, int64_
 // plane: the 5 input rows x 7 input columns under them arrive as five element-aligned 16-byte loads (all issued
 // before the first is used; neighbouring threads' loads overlap in the cache, not in memory), positions outside the
 // plane (clipped last windows, missing rows) become -inf, every value is widened once, and each window is scanned
-// in window order with a strict comparison, so the first maximum wins as in the definition.  A fifth of the vector
-// instructions of the LDS kernel, which those bound.
+// in window order with a strict comparison, so the first maximum wins as in the definition.  About 83 vector
+// instructions per output against 117 in the LDS kernel; both are bound by issuing them.
 __global__ __launch_bounds__(256) void maxpool_fwd_k3s2_bf16_kernel(PoolGeom g, FastDiv div_tasks, FastDiv div_tx, uint32_t total_tasks,
                                                                     int64_t total_elems, const bf16_t *__restrict__ x,
                                                                     bf16_t *__restrict__ y, uint8_t *__restrict__ argmax)

@@ -30,12 +30,29 @@ __device__ __forceinline__ void pack_one(const PackJob &j, int64_t p)
 {
     uint32_t v[8];
     if (j.kind == 0) {
-        // pack (chunk, tap, g, row) = input channels chunk*32 + 8g .. +7 of output channel `row` at window tap `tap`
-        const int row = (int)(p % j.Fp);
-        int64_t t = p / j.Fp;
-        const int gq = (int)(t % 4);
-        t /= 4;
-        const int tap = (int)(t % j.KK), chunk = (int)(t / j.KK);
+        // pack (chunk, tap, g, row) = input channels chunk*32 + 8g .. +7 of output channel `row` at window tap `tap`.
+        // Forward weights: a row's 8 channels x KK taps are contiguous in W, so the threads of a group of 4 rows x KK
+        // taps share the lines they read (thread order: row % 4 fastest, then tap, then the other row bits) and
+        // still write whole 64-byte lines; data-gradient weights are read with the row fastest as they are written
+        // (consecutive rows are KK elements apart in W there).
+        int row, gq, tap, chunk;
+        if (j.flip) {
+            row = (int)(p % j.Fp);
+            int64_t t = p / j.Fp;
+            gq = (int)(t % 4);
+            t /= 4;
+            tap = (int)(t % j.KK), chunk = (int)(t / j.KK);
+        } else {
+            const int row_lo = (int)(p % 4);
+            int64_t t = p / 4;
+            tap = (int)(t % j.KK);
+            t /= j.KK;
+            const int quads = j.Fp / 4;
+            row = (int)(t % quads) * 4 + row_lo;
+            t /= quads;
+            gq = (int)(t % 4), chunk = (int)(t / 4);
+            p = (((int64_t)chunk * j.KK + tap) * 4 + gq) * j.Fp + row;
+        }
         const int src_tap = j.flip ? j.KK - 1 - tap : tap;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
